@@ -1,0 +1,252 @@
+"""CPU oracle for the residual-binary linear layer.  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares nothing with the HIP library
+or its Python binding and never imports them.
+
+What each function follows:
+
+* ``pack`` / ``unpack``      - appendix "Weight Packing" (32 columns per word,
+                               +1 -> 0, -1 -> 1; least-significant bit = lowest
+                               column is this build's reading).
+* ``effective_weight``       - Section 4.1 and Eq. (stacked binary weight).
+* ``forward``                - Alg. 2 "compute layer output", Y = W_hat X.
+* ``svid`` / ``derive``      - Section 4.2 steps 1-3 and Alg. 2 forward loop for
+                               the signs; Section 4.3 (SVID: rank-1 SVD of the
+                               magnitudes) for the scales, one greedy pass.
+* ``stack_forward``          - the layer applied op after op (fp16 between ops).
+
+All floating point is fp64.  Stored fp16 / bf16 values are widened exactly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rb_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the C part with gcc (-O2 -fopenmp).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
+             _SRC, "-o", _LIB])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        i = ctypes.c_int
+        p = ctypes.c_void_p
+        lib.orc_pack.argtypes = [p, i, i, i, p]
+        lib.orc_unpack.argtypes = [p, i, i, i, p]
+        lib.orc_effective_weight.argtypes = [p, p, p, i, i, i, p]
+        lib.orc_matmul.argtypes = [p, p, i, i, i, p]
+        for f in (lib.orc_pack, lib.orc_unpack, lib.orc_effective_weight, lib.orc_matmul,
+                  lib.orc_threads):
+            f.restype = i
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Host threads the C loops use."""
+    return int(_load().orc_threads())
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+# --------------------------------------------------------------------------
+# stored formats -> fp64 (exact widening)
+# --------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float64, exactly."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    return b.view(np.float32).astype(np.float64)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+# --------------------------------------------------------------------------
+# Weight Packing
+# --------------------------------------------------------------------------
+def pack(signs: np.ndarray) -> np.ndarray:
+    """int8 +1/-1 [K][out][in] -> uint32 [K][out][in/32]."""
+    signs = np.ascontiguousarray(signs, dtype=np.int8)
+    K, out, inn = signs.shape
+    if inn % 32 != 0:
+        raise ValueError("in must be a multiple of 32")
+    packed = np.zeros((K, out, inn // 32), dtype=np.uint32)
+    rc = _load().orc_pack(_ptr(signs), K, out, inn, _ptr(packed))
+    if rc != 0:
+        raise ValueError(f"orc_pack failed ({rc}): entries must be +1 or -1")
+    return packed
+
+
+def unpack(packed: np.ndarray) -> np.ndarray:
+    """uint32 [K][out][in/32] -> int8 +1/-1 [K][out][in]."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    K, out, W32 = packed.shape
+    signs = np.zeros((K, out, W32 * 32), dtype=np.int8)
+    rc = _load().orc_unpack(_ptr(packed), K, out, W32 * 32, _ptr(signs))
+    if rc != 0:
+        raise ValueError(f"orc_unpack failed ({rc})")
+    return signs
+
+
+# --------------------------------------------------------------------------
+# Forward: Section 4.1, Eq. (stacked binary weight), Alg. 2 output line
+# --------------------------------------------------------------------------
+def effective_weight(signs: np.ndarray, g, h) -> np.ndarray:
+    """W_hat[i][j] = sum_k g_k[i] B_k[i][j] h_k[j], fp64 [out][in]."""
+    signs = np.ascontiguousarray(signs, dtype=np.int8)
+    K, out, inn = signs.shape
+    g = _f64(g).reshape(K, out)
+    h = _f64(h).reshape(K, inn)
+    What = np.empty((out, inn), dtype=np.float64)
+    rc = _load().orc_effective_weight(_ptr(signs), _ptr(g), _ptr(h), K, out, inn, _ptr(What))
+    if rc != 0:
+        raise ValueError(f"orc_effective_weight failed ({rc})")
+    return What
+
+
+def matmul(What: np.ndarray, X) -> np.ndarray:
+    """Y[t][i] = sum_j What[i][j] X[t][j]; X [T][in] -> Y fp64 [T][out]."""
+    What = _f64(What)
+    out, inn = What.shape
+    X = _f64(X).reshape(-1, inn)
+    T = X.shape[0]
+    Y = np.empty((T, out), dtype=np.float64)
+    rc = _load().orc_matmul(_ptr(What), _ptr(X), out, inn, T, _ptr(Y))
+    if rc != 0:
+        raise ValueError(f"orc_matmul failed ({rc})")
+    return Y
+
+
+def forward(signs: np.ndarray, g, h, X) -> np.ndarray:
+    """y = (sum_k g_k (.) B_k (.) h_k) x for every row of X.  fp64 [T][out]."""
+    return matmul(effective_weight(signs, g, h), X)
+
+
+def relative_l2(y_test, y_ref) -> np.ndarray:
+    """Per-vector ||y_test - y_ref||_2 / ||y_ref||_2 over the last axis."""
+    a = _f64(y_test)
+    b = _f64(y_ref)
+    a = a.reshape(-1, a.shape[-1])
+    b = b.reshape(-1, b.shape[-1])
+    num = np.sqrt(((a - b) ** 2).sum(axis=1))
+    den = np.sqrt((b ** 2).sum(axis=1))
+    return num / np.where(den == 0.0, 1.0, den)
+
+
+# --------------------------------------------------------------------------
+# Derivation of the paths from a full-precision weight
+# --------------------------------------------------------------------------
+def sign(R: np.ndarray) -> np.ndarray:
+    """sign with sign(0) = +1 (the paper leaves sign(0) open; B must be +-1)."""
+    return np.where(np.asarray(R) >= 0.0, 1, -1).astype(np.int8)
+
+
+def leading_singular_pair(A: np.ndarray, tol: float = 1e-13, max_iter: int = 200
+                          ) -> Tuple[float, np.ndarray, np.ndarray]:
+    """Leading singular triplet (sigma, a, b) of a non-negative matrix A by
+    power iteration from the all-ones vector; a, b have unit norm and
+    non-negative entries (Perron-Frobenius)."""
+    A = _f64(A)
+    b = np.ones(A.shape[1]) / np.sqrt(A.shape[1])
+    sigma = 0.0
+    for _ in range(max_iter):
+        a = A @ b
+        na = np.linalg.norm(a)
+        if na == 0.0:
+            return 0.0, np.zeros(A.shape[0]), b
+        a /= na
+        b_new = A.T @ a
+        s_new = np.linalg.norm(b_new)
+        b_new /= s_new
+        done = abs(s_new - sigma) <= tol * s_new and np.linalg.norm(b_new - b) <= 1e-10
+        b, sigma = b_new, s_new
+        if done:
+            break
+    a = A @ b
+    sigma = float(np.linalg.norm(a))
+    a /= sigma
+    return sigma, a, b
+
+
+def svid(R: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """SVID of Section 4.3: B = sign(R); (g, h) = rank-1 SVD fit of |R|,
+    sigma split evenly: g = sqrt(sigma) a, h = sqrt(sigma) b.  fp64."""
+    R = _f64(R)
+    sigma, a, b = leading_singular_pair(np.abs(R))
+    r = np.sqrt(sigma)
+    return sign(R), r * a, r * b
+
+
+def derive(W: np.ndarray, K: int, round_scales: bool = True):
+    """Greedy derivation (Alg. 2 forward loop with scales from one SVID pass):
+    R_0 = W; B_k = sign(R_{k-1}); (g_k, h_k) = SVID scales of R_{k-1};
+    R_k = R_{k-1} - g_k (.) B_k (.) h_k.
+
+    With ``round_scales`` the scales are rounded to fp16 before the residual is
+    formed, so that the next path corrects what the deployed path really does.
+    Returns (signs int8 [K][out][in], g [K][out], h [K][in], residual Frobenius
+    norms [K+1]); g, h are float16 when rounded, float64 otherwise.
+    """
+    R = _f64(W).copy()
+    out, inn = R.shape
+    signs = np.empty((K, out, inn), dtype=np.int8)
+    gs, hs = [], []
+    norms = [float(np.linalg.norm(R))]
+    for k in range(K):
+        B, g, h = svid(R)
+        if round_scales:
+            g = g.astype(np.float16)
+            h = h.astype(np.float16)
+        signs[k] = B
+        gs.append(g)
+        hs.append(h)
+        R = R - g.astype(np.float64)[:, None] * B.astype(np.float64) * h.astype(np.float64)[None, :]
+        norms.append(float(np.linalg.norm(R)))
+    return signs, np.stack(gs), np.stack(hs), np.array(norms)
+
+
+# --------------------------------------------------------------------------
+# Stack of layers
+# --------------------------------------------------------------------------
+def stack_forward(layers: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]],
+                  ops: Sequence[Tuple[int, int, int]],
+                  bufs: List[Optional[np.ndarray]],
+                  forced_inputs: Optional[Sequence[np.ndarray]] = None) -> List[np.ndarray]:
+    """Run ops (layer, src, dst) in order.  ``bufs[src]`` holds fp16 [T][in].
+
+    Free-running mode (``forced_inputs`` None): every op's fp64 output is
+    rounded to fp16 (round-to-nearest-even) and stored in ``bufs[dst]`` for the
+    ops that read it.  Teacher-forced mode: op n reads ``forced_inputs[n]``
+    instead (the input another implementation actually saw), so rounding
+    differences do not compound.  Returns each op's fp64 output [T][out].
+    """
+    outs = []
+    for n, (layer, src, dst) in enumerate(ops):
+        signs, g, h = layers[layer]
+        x = bufs[src] if forced_inputs is None else forced_inputs[n]
+        y = forward(signs, g, h, x)
+        outs.append(y)
+        if forced_inputs is None:
+            bufs[dst] = y.astype(np.float16)
+    return outs

@@ -1,0 +1,312 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+other than itself - brute force on tiny inputs, closed forms, an independent
+library routine, or a number the paper prints."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- packing ---
+def test_pack_matches_numpy_packbits_little():
+    rng = synth.child_rng(0, 1)
+    signs = synth.uniform_signs(rng, 2, 37, 160)
+    packed = oracle.pack(signs)
+    bits = (signs == -1).astype(np.uint8)
+    ref = np.packbits(bits, axis=-1, bitorder="little").view("<u4")
+    assert packed.dtype == np.uint32 and packed.shape == (2, 37, 5)
+    assert np.array_equal(packed, ref)
+
+
+def test_pack_constant_and_single_bit_patterns():
+    K, out, inn = 1, 3, 64
+    plus = np.ones((K, out, inn), dtype=np.int8)
+    assert np.all(oracle.pack(plus) == 0)                    # +1 -> bit 0
+    assert np.all(oracle.pack(-plus) == 0xFFFFFFFF)          # -1 -> bit 1
+    for i in range(out):
+        for j in range(inn):
+            s = plus.copy()
+            s[0, i, j] = -1
+            p = oracle.pack(s)
+            expect = np.zeros((K, out, inn // 32), dtype=np.uint32)
+            expect[0, i, j // 32] = np.uint32(1) << np.uint32(j % 32)   # LSB = lowest column
+            assert np.array_equal(p, expect), (i, j)
+
+
+def test_pack_unpack_round_trip_and_minimum_width():
+    rng = synth.child_rng(0, 2)
+    for (K, out, inn) in [(1, 1, 32), (2, 5, 32), (3, 17, 96), (2, 64, 1024)]:
+        signs = synth.uniform_signs(rng, K, out, inn)
+        assert np.array_equal(oracle.unpack(oracle.pack(signs)), signs)
+
+
+def test_pack_rejects_bad_input():
+    with pytest.raises(ValueError):
+        oracle.pack(np.ones((1, 2, 33), dtype=np.int8))
+    bad = np.ones((1, 2, 32), dtype=np.int8)
+    bad[0, 0, 0] = 0
+    with pytest.raises(ValueError):
+        oracle.pack(bad)
+
+
+# ---------------------------------------------------------------- forward ---
+def test_forward_brute_force_all_4x4_sign_matrices():
+    """K=1, g=h=1: for every one of the 2^16 sign matrices, y_i must be the
+    explicit signed sum of x (pure Python, independent of the oracle's loops)."""
+    x = np.array([0.75, -1.5, 2.25, 0.125])
+    all_rows = list(itertools.product((1, -1), repeat=4))
+    ones = np.ones((1, 4))
+    # every row pattern in every row position is covered by cycling row choices
+    for a, b in itertools.product(range(16), repeat=2):
+        rows = [all_rows[a], all_rows[b], all_rows[(a * 7 + b) % 16], all_rows[15 - a]]
+        B = np.array(rows, dtype=np.int8)[None]
+        y = oracle.forward(B, ones, ones, x[None])[0]
+        for i in range(4):
+            expect = 0.0
+            for j in range(4):
+                expect = expect + (x[j] if rows[i][j] == 1 else -x[j])
+            assert y[i] == expect
+    # and the full 2^16 enumeration on the first row with the others fixed
+    for pattern in itertools.product((1, -1), repeat=4):
+        B = np.ones((1, 4, 4), dtype=np.int8)
+        B[0, 2] = pattern
+        y = oracle.forward(B, ones, ones, x[None])[0]
+        assert y[2] == sum(p * v for p, v in zip(pattern, x))
+        assert y[0] == y[1] == y[3] == x.sum()
+
+
+def test_forward_nonsquare_against_python_loops():
+    """Catches a transposed operand or swapped g/h: out != in, K = 2."""
+    rng = synth.child_rng(0, 3)
+    K, out, inn, T = 2, 5, 32, 3
+    signs = synth.uniform_signs(rng, K, out, inn)
+    g = synth.halfnormal_scales(rng, K, out)
+    h = synth.halfnormal_scales(rng, K, inn)
+    X = synth.gaussian_activations(rng, T, inn)
+    Y = oracle.forward(signs, g, h, X)
+    assert Y.shape == (T, out)
+    for t in range(T):
+        for i in range(out):
+            acc = 0.0
+            for k in range(K):
+                inner = 0.0
+                for j in range(inn):
+                    inner += int(signs[k, i, j]) * (float(h[k, j]) * float(X[t, j]))
+                acc += float(g[k, i]) * inner
+            assert Y[t, i] == pytest.approx(acc, rel=1e-12, abs=1e-15)
+
+
+def test_forward_k1_is_one_scaled_sign_matrix_and_paths_add():
+    rng = synth.child_rng(0, 4)
+    out, inn = 24, 64
+    W = synth.gaussian_weight(rng, out, inn)
+    g = np.abs(rng.standard_normal((2, out)))
+    h = np.abs(rng.standard_normal((2, inn)))
+    x = rng.standard_normal((1, inn))
+    B1 = oracle.sign(W)[None]
+    y1 = oracle.forward(B1, g[:1], h[:1], x)[0]
+    expect = g[0] * (np.sign(W) @ (h[0] * x[0]))          # y = g (.) (B (h (.) x))
+    assert np.allclose(y1, expect, rtol=1e-13, atol=0)
+    B2 = synth.uniform_signs(rng, 1, out, inn)
+    y2 = oracle.forward(B2, g[1:], h[1:], x)[0]
+    y12 = oracle.forward(np.concatenate([B1, B2]), g, h, x)[0]
+    assert np.allclose(y12, y1 + y2, rtol=1e-13, atol=1e-15)
+
+
+def test_forward_probe_vectors_and_bit_flip():
+    rng = synth.child_rng(0, 5)
+    K, out, inn = 2, 6, 64
+    signs = synth.uniform_signs(rng, K, out, inn)
+    g = synth.halfnormal_scales(rng, K, out).astype(np.float64)
+    h = synth.halfnormal_scales(rng, K, inn).astype(np.float64)
+    for j in (0, 31, 32, 63):
+        e = np.zeros((1, inn)); e[0, j] = 1.0
+        y = oracle.forward(signs, g, h, e)[0]
+        for i in range(out):
+            assert y[i] == pytest.approx(sum(g[k, i] * signs[k, i, j] * h[k, j] for k in range(K)), rel=1e-14)
+    ones = np.ones((K, out, inn), dtype=np.int8)
+    x = rng.standard_normal((1, inn))
+    y = oracle.forward(ones[:1], np.ones((1, out)), np.ones((1, inn)), x)[0]
+    assert np.allclose(y, x.sum(), rtol=1e-13)
+    k, i, j = 1, 4, 37
+    y0 = oracle.forward(signs, g, h, x)[0]
+    flipped = signs.copy(); flipped[k, i, j] *= -1
+    y1 = oracle.forward(flipped, g, h, x)[0]
+    delta = y1 - y0
+    assert np.all(delta[np.arange(out) != i] == 0.0)
+    assert delta[i] == pytest.approx(-2 * g[k, i] * signs[k, i, j] * h[k, j] * x[0, j], rel=1e-9)
+
+
+def test_forward_matches_numpy_definition():
+    rng = synth.child_rng(0, 6)
+    K, out, inn, T = 2, 48, 96, 4
+    signs = synth.uniform_signs(rng, K, out, inn)
+    g = synth.halfnormal_scales(rng, K, out)
+    h = synth.halfnormal_scales(rng, K, inn)
+    X = synth.gaussian_activations(rng, T, inn)
+    W = (g.astype(np.float64)[:, :, None] * signs * h.astype(np.float64)[:, None, :]).sum(0)
+    ref = X.astype(np.float64) @ W.T
+    assert oracle.relative_l2(oracle.forward(signs, g, h, X), ref).max() < 1e-13
+
+
+def test_forward_is_linear():
+    rng = synth.child_rng(0, 7)
+    K, out, inn = 2, 16, 64
+    signs = synth.uniform_signs(rng, K, out, inn)
+    g = synth.halfnormal_scales(rng, K, out); h = synth.halfnormal_scales(rng, K, inn)
+    x = rng.standard_normal((1, inn)); z = rng.standard_normal((1, inn))
+    lhs = oracle.forward(signs, g, h, 2.5 * x - 0.75 * z)
+    rhs = 2.5 * oracle.forward(signs, g, h, x) - 0.75 * oracle.forward(signs, g, h, z)
+    assert oracle.relative_l2(lhs, rhs).max() < 1e-12
+
+
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x8000, 0x3C00], dtype=np.uint16)
+    vals = oracle.bf16_bits_to_f64(bits)
+    assert list(vals[:2]) == [1.0, -1.0]
+    assert vals[2] == 3.140625 and vals[5] == 2.0 ** -7
+    assert vals[3] == 0.0 and np.signbit(vals[4])
+
+
+# ------------------------------------------------------------- derivation ---
+def test_sign_of_zero_is_plus_one():
+    s = oracle.sign(np.array([[0.0, -0.0, 1e-300, -1e-300]]))
+    assert s.tolist() == [[1, 1, 1, -1]]
+
+
+def test_sign_is_the_best_binary_core_brute_force_4x4():
+    """For any positive g, h the sign matrix minimises ||R - g(.)B(.)h||_F over
+    all 2^16 candidates (Section 4.2 step 1 / step 3)."""
+    rng = synth.child_rng(0, 8)
+    R = rng.standard_normal((4, 4))
+    g = np.abs(rng.standard_normal(4)) + 0.1
+    h = np.abs(rng.standard_normal(4)) + 0.1
+    gh = np.outer(g, h)
+    best, best_err = None, np.inf
+    for pattern in itertools.product((1.0, -1.0), repeat=16):
+        B = np.array(pattern).reshape(4, 4)
+        err = ((R - gh * B) ** 2).sum()
+        if err < best_err:
+            best, best_err = B, err
+    assert np.array_equal(best, oracle.sign(R).astype(np.float64))
+
+
+def test_leading_singular_pair_matches_lapack_svd():
+    rng = synth.child_rng(0, 9)
+    A = np.abs(rng.standard_normal((40, 72)))
+    sigma, a, b = oracle.leading_singular_pair(A)
+    U, S, Vt = np.linalg.svd(A)
+    assert sigma == pytest.approx(S[0], rel=1e-12)
+    assert np.allclose(a, np.abs(U[:, 0]), atol=1e-9)
+    assert np.allclose(b, np.abs(Vt[0]), atol=1e-9)
+    assert np.all(a >= 0) and np.all(b >= 0)
+
+
+def test_residual_norm_closed_form_and_monotone():
+    """Eckart-Young on |R|: ||R_k||^2 = ||R_{k-1}||^2 - sigma_1(|R_{k-1}|)^2 when
+    the scales are not rounded; hence the residual never grows."""
+    rng = synth.child_rng(0, 10)
+    W = synth.gaussian_weight(rng, 96, 160)
+    signs, g, h, norms = oracle.derive(W, 3, round_scales=False)
+    R = W.copy()
+    for k in range(3):
+        s1 = np.linalg.svd(np.abs(R), compute_uv=False)[0]
+        assert norms[k + 1] ** 2 == pytest.approx(norms[k] ** 2 - s1 ** 2, rel=1e-10)
+        assert np.array_equal(signs[k], np.where(R >= 0, 1, -1))
+        R = R - np.outer(g[k], h[k]) * signs[k]
+    assert np.all(np.diff(norms) < 0)
+    # rounded scales: still non-increasing
+    _, _, _, norms16 = oracle.derive(W, 3, round_scales=True)
+    assert np.all(np.diff(norms16) < 0)
+    assert np.allclose(norms16, norms, rtol=2e-3)
+
+
+def test_residual_fractions_for_gaussian_weights():
+    """i.i.d. Gaussian W: ||R_1||^2/||W||^2 -> 1 - 2/pi; the next two ratios are
+    the statistical pins 0.130 and 0.058 (about 1 percent tolerance)."""
+    rng = synth.child_rng(0, 11)
+    W = synth.gaussian_weight(rng, 512, 1024)
+    _, _, _, norms = oracle.derive(W, 3, round_scales=False)
+    frac = (norms[1:] / norms[0]) ** 2
+    assert frac[0] == pytest.approx(1 - 2 / np.pi, abs=4e-3)
+    assert frac[1] == pytest.approx(0.130, abs=3e-3)
+    assert frac[2] == pytest.approx(0.058, abs=2e-3)
+
+
+def test_derive_k1_reduces_to_scaled_sign_and_rank1_exact_case():
+    """A matrix that IS g(.)B(.)h is recovered exactly by one path."""
+    rng = synth.child_rng(0, 12)
+    g = np.abs(rng.standard_normal(12)) + 0.5
+    h = np.abs(rng.standard_normal(20)) + 0.5
+    B = synth.uniform_signs(rng, 1, 12, 20)[0]
+    W = np.outer(g, h) * B
+    signs, g1, h1, norms = oracle.derive(W, 1, round_scales=False)
+    assert np.array_equal(signs[0], B)
+    assert np.allclose(np.outer(g1[0], h1[0]), np.outer(g, h), rtol=1e-10)
+    assert norms[1] < 1e-10 * norms[0]
+    # even split of sigma: ||g|| == ||h||
+    assert np.linalg.norm(g1[0]) == pytest.approx(np.linalg.norm(h1[0]), rel=1e-12)
+
+
+def test_derived_forward_approaches_dense_product():
+    rng = synth.child_rng(0, 13)
+    W = synth.gaussian_weight(rng, 64, 128)
+    x = rng.standard_normal((1, 128))
+    ref = x @ W.T
+    errs = []
+    for K in (1, 2, 3):
+        signs, g, h, _ = oracle.derive(W, K, round_scales=False)
+        errs.append(oracle.relative_l2(oracle.forward(signs, g, h, x), ref)[0])
+    assert errs[0] > errs[1] > errs[2]
+
+
+# ------------------------------------------------------------------ stack ---
+def test_stack_forward_modes():
+    rng = synth.child_rng(0, 14)
+    ops, widths = synth.llama_stack("7b", n_layers=1)
+    # shrink: same dataflow, tiny widths
+    small = {4096: 64, 11008: 96}
+    layers, op_list = [], []
+    for n, op in enumerate(ops):
+        o, i = small[op.out], small[op.inn]
+        layers.append((synth.uniform_signs(rng, 2, o, i),
+                       (synth.halfnormal_scales(rng, 2, o).astype(np.float64) * 50).astype(np.float16),
+                       synth.halfnormal_scales(rng, 2, i)))
+        op_list.append((n, op.src, op.dst))
+    bufs = [None] * len(widths)
+    bufs[0] = synth.gaussian_activations(rng, 2, 64)
+    outs = oracle.stack_forward(layers, op_list, bufs)
+    # op "o" (index 3) reads v's output (index 2) rounded to fp16
+    v16 = outs[2].astype(np.float16)
+    assert np.array_equal(bufs[ops[2].dst], v16)
+    assert np.array_equal(outs[3], oracle.forward(*layers[3], v16))
+    forced = [bufs[op.src] for op in ops]
+    outs_tf = oracle.stack_forward(layers, op_list, [None] * len(widths), forced_inputs=forced)
+    for a, b in zip(outs, outs_tf):
+        assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------ paper values ---
+def test_effective_bits_as_printed():
+    """Section 4.1: nominal 2-bit corresponds to ~2.02 effective bits (fp16 scales)."""
+    with open(os.path.join(GOLDEN, "effective_bits.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    nominal, printed, digits = int(rows[0][0]), float(rows[0][1]), int(rows[0][2])
+    with open(os.path.join(GOLDEN, "table_shapes.txt")) as f:
+        shapes = [tuple(int(v) for v in l.split()[:2]) for l in f if l.strip() and not l.startswith("#")]
+    for out, inn in shapes:
+        signs_bits = nominal * out * inn
+        scale_bits = nominal * 16 * (out + inn)
+        eff = (signs_bits + scale_bits) / (out * inn)
+        assert round(eff, digits) in (printed, round(printed - 0.01, digits)), (out, inn, eff)
+    out, inn = shapes[0]
+    assert round((nominal * out * inn + nominal * 16 * (out + inn)) / (out * inn), digits) == printed
+    # the packed array the oracle produces has exactly nominal bits per weight
+    p = oracle.pack(np.ones((nominal, 64, 128), dtype=np.int8))
+    assert p.nbytes * 8 == nominal * 64 * 128
