@@ -1,0 +1,149 @@
+/*
+ * rabit.h - C ABI of the residual-binary linear layer for AMD MI355X (gfx950).
+ *
+ * The layer (paper Section 4.1 "Binary Building Blocks" and Eq. "stacked binary
+ * weight"):
+ *
+ *      y = sum_{k=1..K}  g_k (.) ( B_k ( h_k (.) x ) )
+ *
+ * B_k in {-1,+1}^{out x in} is stored as sign bits, g_k (length out) scales the
+ * output channels and h_k (length in) the input channels of path k.  (The code
+ * listing in the paper's last appendix names the two scale vectors the other
+ * way round; this library follows Section 4.1.)
+ *
+ * Conventions for every function
+ *   - returns RB_OK (0) or a negative RB_ERR_* code; never throws or aborts;
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the current device; the caller owns every buffer;
+ *   - compute functions only enqueue work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream); they do not synchronise and do not
+ *     allocate.  Scratch memory comes from the caller as `workspace`;
+ *   - activations and scales are IEEE binary16 bit patterns (uint16_t) unless a
+ *     dtype argument says otherwise; accumulation is fp32;
+ *   - token-major layout for batches: X[T][in], Y[T][out] (the layout of the
+ *     paper's host wrapper: x is [seqlen, in], y is [seqlen, out]).
+ */
+#ifndef RABIT_H
+#define RABIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RB_OK               0
+#define RB_ERR_NULL        -1   /* a required pointer is NULL                         */
+#define RB_ERR_SHAPE       -2   /* in % 32 != 0, K outside 1..RB_MAX_K, T < 1, ...    */
+#define RB_ERR_ALIGN       -3   /* a device pointer is not 16-byte aligned            */
+#define RB_ERR_UNSUPPORTED -4   /* valid request this build has no kernel for         */
+#define RB_ERR_HIP         -5   /* the HIP runtime reported an error on launch        */
+#define RB_ERR_WORKSPACE   -6   /* workspace missing or smaller than rb_workspace_bytes */
+#define RB_ERR_VALUE       -7   /* rb_pack: an entry is neither +1 nor -1             */
+
+#define RB_MAX_K 2
+
+/* element types for rb_linear_gemm */
+#define RB_F16  0
+#define RB_BF16 1
+#define RB_F32  2
+
+/* ------------------------------------------------------------------------
+ * Packing (host, pure CPU, bit-exact).  Appendix "Weight Packing": every group
+ * of 32 columns becomes one 32-bit word, +1 -> bit 0, -1 -> bit 1.  Canonical
+ * form: word w of row i of path k holds columns 32w..32w+31, least-significant
+ * bit = lowest column; array uint32 [K][out][in/32], row-major.
+ * signs: int8 [K][out][in], entries +1 or -1.  Requires in % 32 == 0.
+ * ------------------------------------------------------------------------ */
+int rb_pack(const int8_t *signs, int K, int out, int in, uint32_t *packed);
+int rb_unpack(const uint32_t *packed, int K, int out, int in, int8_t *signs);
+
+/*
+ * Kernel-native layout (the same appendix interleaves rows so that a wavefront
+ * issues full coalesced loads; this is that idea laid out for 64-lane
+ * wavefronts and 128-bit loads).  The matrix is cut into tiles of 16 rows by
+ * 256 columns; rows are padded to a multiple of 16 and columns to a multiple
+ * of 256 with +1 entries (bit 0).  Tiles are stored row-tile major.  Inside a
+ * tile, lane l = r + 16*q (r = row in tile, q = 0..3) owns 2*K consecutive
+ * words: for c in {0,1}, for k in 0..K-1: the canonical word of path k, row r,
+ * columns 128*c + 32*q .. +31 of the tile.  One tile is 64 * 2K words.
+ * rb_native_bytes gives the size; rb_repack_native / rb_unpack_native convert
+ * host arrays between the canonical and the native form (exact inverses on the
+ * unpadded part).
+ */
+size_t rb_native_bytes(int K, int out, int in);
+int rb_repack_native(const uint32_t *packed, int K, int out, int in, void *native_host);
+int rb_unpack_native(const void *native_host, int K, int out, int in, uint32_t *packed);
+
+/* One frozen layer as the kernels consume it (Section 4.2, last paragraph: the
+ * binary cores are frozen for inference and the full-precision weight is gone). */
+typedef struct rb_layer {
+    int out, in, K;
+    const void     *bits;   /* device, native layout, rb_native_bytes(K,out,in) bytes, 16B aligned */
+    const uint16_t *g;      /* device fp16 [K][out] */
+    const uint16_t *h;      /* device fp16 [K][in]  */
+} rb_layer;
+
+/*
+ * Decode GEMV, one token:  y = sum_k g_k (.) (B_k (h_k (.) x)).
+ * x device fp16 [in], y device fp16 [out] (round-to-nearest-even from fp32).
+ * Equals rb_linear_gemm with T = 1, RB_F16 in and out.
+ */
+int rb_linear_gemv(const rb_layer *L, const uint16_t *x, uint16_t *y,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Batched form, T tokens: Y[t] = layer(X[t]).  X device [T][in] of act_dtype
+ * (RB_F16 or RB_BF16), Y device [T][out] of out_dtype (RB_F16, RB_BF16, RB_F32).
+ * Small T streams the weights once for all tokens; large T runs as a dense
+ * contraction on the matrix cores.
+ */
+int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
+                   int act_dtype, int out_dtype,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * A stack of layers run in order (the end-to-end decode setting of the paper's
+ * inference table, reduced to its linear layers).  Op n applies
+ * layers[ops[n].layer] to bufs[ops[n].src] and writes bufs[ops[n].dst]; every
+ * buffer is device fp16 [T][width].  The result of each op equals
+ * rb_linear_gemm on the same input.  An op may read any buffer written by an
+ * earlier op (or never written: stack inputs); dst buffers must be distinct
+ * from the op's src.
+ */
+typedef struct rb_stack_op { int layer; int src; int dst; } rb_stack_op;
+
+int rb_layer_stack(const rb_layer *layers, int n_layers,
+                   const rb_stack_op *ops, int n_ops,
+                   uint16_t *const *bufs, int n_bufs, int T,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace that the three compute calls need for these layers at T
+ * tokens (an upper bound over the layers; 16-byte aligned device memory). */
+size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int T);
+
+/* ------------------------------------------------------------------------
+ * Measurement aids (not part of the layer): the comparators the benchmark
+ * reports next to the binary path on the same GPU.
+ * ------------------------------------------------------------------------ */
+
+/* Dense fp16 GEMV y = W x with W device fp16 [out][in] row-major, fp32
+ * accumulation: the full-precision baseline row of the paper's inference table,
+ * hand-written for this GPU.  Requires in % 8 == 0. */
+int rb_dense_gemv_f16(const uint16_t *W, const uint16_t *x, uint16_t *y,
+                      int out, int in, void *stream);
+
+/* Streams `bytes` (multiple of 16) from device memory with 128-bit loads and
+ * writes one 16-byte checksum per workgroup into `sink` (device, at least
+ * 16 * rb_stream_read_groups() bytes): the read-bandwidth ceiling of this GPU. */
+int rb_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+int rb_stream_read_groups(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int rb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RABIT_H */

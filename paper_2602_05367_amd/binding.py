@@ -1,0 +1,254 @@
+"""ctypes binding of librabit.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point in
+``include/rabit.h``.  PyTorch supplies device memory and the current stream;
+all arithmetic runs in the HIP kernels.  Importing this module fails loudly if
+the library has not been built - there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Sequence, Tuple
+
+import numpy as np
+import torch  # imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librabit.so")
+
+RB_OK = 0
+RB_ERR_NULL, RB_ERR_SHAPE, RB_ERR_ALIGN, RB_ERR_UNSUPPORTED = -1, -2, -3, -4
+RB_ERR_HIP, RB_ERR_WORKSPACE, RB_ERR_VALUE = -5, -6, -7
+RB_F16, RB_BF16, RB_F32 = 0, 1, 2
+_ERR_NAMES = {-1: "RB_ERR_NULL", -2: "RB_ERR_SHAPE", -3: "RB_ERR_ALIGN", -4: "RB_ERR_UNSUPPORTED",
+              -5: "RB_ERR_HIP", -6: "RB_ERR_WORKSPACE", -7: "RB_ERR_VALUE"}
+
+EXPORTS = [
+    "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
+    "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
+    "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version",
+]
+
+
+class RabitError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__(f"{fn} returned {_ERR_NAMES.get(code, code)}")
+        self.code = code
+
+
+class rb_layer(ctypes.Structure):
+    _fields_ = [("out", ctypes.c_int), ("inn", ctypes.c_int), ("K", ctypes.c_int),
+                ("bits", ctypes.c_void_p), ("g", ctypes.c_void_p), ("h", ctypes.c_void_p)]
+
+
+class rb_stack_op(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_int), ("src", ctypes.c_int), ("dst", ctypes.c_int)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(LIB_PATH)
+    i, p, z = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.rb_pack.argtypes = [p, i, i, i, p]
+    lib.rb_unpack.argtypes = [p, i, i, i, p]
+    lib.rb_native_bytes.argtypes = [i, i, i]
+    lib.rb_native_bytes.restype = z
+    lib.rb_repack_native.argtypes = [p, i, i, i, p]
+    lib.rb_unpack_native.argtypes = [p, i, i, i, p]
+    lib.rb_linear_gemv.argtypes = [ctypes.POINTER(rb_layer), p, p, p, z, p]
+    lib.rb_linear_gemm.argtypes = [ctypes.POINTER(rb_layer), p, p, i, i, i, p, z, p]
+    lib.rb_layer_stack.argtypes = [ctypes.POINTER(rb_layer), i, ctypes.POINTER(rb_stack_op), i,
+                                   ctypes.POINTER(ctypes.c_void_p), i, i, p, z, p]
+    lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i]
+    lib.rb_workspace_bytes.restype = z
+    lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
+    lib.rb_stream_read.argtypes = [p, z, p, p]
+    lib.rb_stream_read_groups.argtypes = []
+    lib.rb_version.argtypes = []
+    for name in EXPORTS:
+        if name not in ("rb_native_bytes", "rb_workspace_bytes"):
+            getattr(lib, name).restype = i
+    return lib
+
+
+lib = _load()
+
+
+def _check(fn: str, code: int) -> None:
+    if code != RB_OK:
+        raise RabitError(fn, code)
+
+
+def _np_ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+_DTYPE_CODE = {torch.float16: RB_F16, torch.bfloat16: RB_BF16, torch.float32: RB_F32}
+
+
+# ------------------------------------------------------------------ host ---
+def rb_pack(signs: np.ndarray) -> np.ndarray:
+    """int8 +1/-1 [K][out][in] (host) -> canonical uint32 [K][out][in/32] (host)."""
+    signs = np.ascontiguousarray(signs, dtype=np.int8)
+    K, out, inn = signs.shape
+    packed = np.empty((K, out, max(inn // 32, 0)), dtype=np.uint32)
+    _check("rb_pack", lib.rb_pack(_np_ptr(signs), K, out, inn, _np_ptr(packed)))
+    return packed
+
+
+def rb_unpack(packed: np.ndarray) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    K, out, W32 = packed.shape
+    signs = np.empty((K, out, W32 * 32), dtype=np.int8)
+    _check("rb_unpack", lib.rb_unpack(_np_ptr(packed), K, out, W32 * 32, _np_ptr(signs)))
+    return signs
+
+
+def rb_native_bytes(K: int, out: int, inn: int) -> int:
+    return int(lib.rb_native_bytes(K, out, inn))
+
+
+def rb_repack_native(packed: np.ndarray) -> np.ndarray:
+    """canonical uint32 [K][out][in/32] -> native layout, flat uint32 (host)."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    K, out, W32 = packed.shape
+    native = np.empty(rb_native_bytes(K, out, W32 * 32) // 4, dtype=np.uint32)
+    _check("rb_repack_native", lib.rb_repack_native(_np_ptr(packed), K, out, W32 * 32, _np_ptr(native)))
+    return native
+
+
+def rb_unpack_native(native: np.ndarray, K: int, out: int, inn: int) -> np.ndarray:
+    native = np.ascontiguousarray(native, dtype=np.uint32)
+    packed = np.empty((K, out, inn // 32), dtype=np.uint32)
+    _check("rb_unpack_native", lib.rb_unpack_native(_np_ptr(native), K, out, inn, _np_ptr(packed)))
+    return packed
+
+
+# ---------------------------------------------------------------- device ---
+class Layer:
+    """Device-resident frozen layer: native sign words + fp16 g [K][out], h [K][in]."""
+
+    def __init__(self, bits: torch.Tensor, g: torch.Tensor, h: torch.Tensor, K: int, out: int, inn: int):
+        assert bits.is_cuda and g.is_cuda and h.is_cuda
+        assert g.dtype == torch.float16 and h.dtype == torch.float16
+        assert tuple(g.shape) == (K, out) and tuple(h.shape) == (K, inn)
+        assert bits.numel() * bits.element_size() == rb_native_bytes(K, out, inn)
+        self.bits, self.g, self.h = bits.contiguous(), g.contiguous(), h.contiguous()
+        self.K, self.out, self.inn = K, out, inn
+
+    @classmethod
+    def from_host(cls, signs: np.ndarray, g: np.ndarray, h: np.ndarray, device="cuda:0") -> "Layer":
+        """Pack int8 signs [K][out][in] with rb_pack + rb_repack_native and upload."""
+        K, out, inn = signs.shape
+        native = rb_repack_native(rb_pack(signs))
+        bits = torch.from_numpy(native.view(np.int32)).to(device)
+        return cls(bits, torch.from_numpy(np.ascontiguousarray(g, dtype=np.float16)).to(device),
+                   torch.from_numpy(np.ascontiguousarray(h, dtype=np.float16)).to(device), K, out, inn)
+
+    def struct(self) -> rb_layer:
+        return rb_layer(self.out, self.inn, self.K, self.bits.data_ptr(), self.g.data_ptr(),
+                        self.h.data_ptr())
+
+    @property
+    def packed_bytes(self) -> int:
+        """Bytes of sign bits of the unpadded matrix (K*out*in/8)."""
+        return self.K * self.out * self.inn // 8
+
+
+def _layer_array(layers: Sequence[Layer]):
+    arr = (rb_layer * len(layers))()
+    for n, L in enumerate(layers):
+        arr[n] = L.struct()
+    return arr
+
+
+def rb_workspace_bytes(layers: Sequence[Layer], T: int) -> int:
+    return int(lib.rb_workspace_bytes(_layer_array(layers), len(layers), T))
+
+
+def _workspace(layers: Sequence[Layer], T: int, device) -> Tuple[torch.Tensor, int]:
+    n = rb_workspace_bytes(layers, T)
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+    return ws, n
+
+
+def rb_linear_gemv(layer: Layer, x: torch.Tensor, y: torch.Tensor = None, workspace=None) -> torch.Tensor:
+    """y = layer(x) for one fp16 token x [in]; returns fp16 [out]."""
+    assert x.is_cuda and x.dtype == torch.float16 and x.is_contiguous() and x.numel() == layer.inn
+    if y is None:
+        y = torch.empty(layer.out, dtype=torch.float16, device=x.device)
+    ws, n = workspace if workspace is not None else _workspace([layer], 1, x.device)
+    s = layer.struct()
+    _check("rb_linear_gemv", lib.rb_linear_gemv(ctypes.byref(s), x.data_ptr(), y.data_ptr(),
+                                                ws.data_ptr(), n, _stream()))
+    return y
+
+
+def rb_linear_gemm(layer: Layer, X: torch.Tensor, out_dtype=torch.float16, Y: torch.Tensor = None,
+                   workspace=None) -> torch.Tensor:
+    """Y[t] = layer(X[t]); X [T][in] fp16 or bf16; returns [T][out] of out_dtype."""
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.inn
+    T = X.shape[0]
+    if Y is None:
+        Y = torch.empty((T, layer.out), dtype=out_dtype, device=X.device)
+    ws, n = workspace if workspace is not None else _workspace([layer], T, X.device)
+    s = layer.struct()
+    _check("rb_linear_gemm", lib.rb_linear_gemm(ctypes.byref(s), X.data_ptr(), Y.data_ptr(), T,
+                                                _DTYPE_CODE[X.dtype], _DTYPE_CODE[Y.dtype],
+                                                ws.data_ptr(), n, _stream()))
+    return Y
+
+
+class Stack:
+    """Marshalled arguments of rb_layer_stack, built once and reused per call."""
+
+    def __init__(self, layers: Sequence[Layer], ops: Sequence[Tuple[int, int, int]],
+                 bufs: Sequence[torch.Tensor], T: int):
+        self.layers, self.bufs, self.T = list(layers), list(bufs), T
+        for b in self.bufs:
+            assert b.is_cuda and b.dtype == torch.float16 and b.is_contiguous()
+        self._layers = _layer_array(self.layers)
+        self._ops = (rb_stack_op * len(ops))(*[rb_stack_op(*o) for o in ops])
+        self._bufs = (ctypes.c_void_p * len(bufs))(*[b.data_ptr() for b in self.bufs])
+        self.n_ops = len(ops)
+        self.ws, self.ws_bytes = _workspace(self.layers, T, self.bufs[0].device)
+
+    def run(self) -> None:
+        _check("rb_layer_stack", lib.rb_layer_stack(
+            self._layers, len(self.layers), self._ops, self.n_ops, self._bufs, len(self.bufs), self.T,
+            self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+
+def rb_layer_stack(layers: Sequence[Layer], ops: Sequence[Tuple[int, int, int]],
+                   bufs: Sequence[torch.Tensor], T: int) -> None:
+    """Run ops (layer, src, dst) in order over device fp16 buffers [T][width]."""
+    Stack(layers, ops, bufs, T).run()
+
+
+def rb_dense_gemv_f16(W: torch.Tensor, x: torch.Tensor, y: torch.Tensor = None) -> torch.Tensor:
+    out, inn = W.shape
+    assert W.dtype == torch.float16 and x.dtype == torch.float16 and W.is_contiguous()
+    if y is None:
+        y = torch.empty(out, dtype=torch.float16, device=W.device)
+    _check("rb_dense_gemv_f16", lib.rb_dense_gemv_f16(W.data_ptr(), x.data_ptr(), y.data_ptr(), out, inn,
+                                                      _stream()))
+    return y
+
+
+def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor:
+    nbytes = src.numel() * src.element_size()
+    if sink is None:
+        sink = torch.empty(int(lib.rb_stream_read_groups()) * 16, dtype=torch.uint8, device=src.device)
+    _check("rb_stream_read", lib.rb_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream()))
+    return sink
+
+
+def rb_version() -> int:
+    return int(lib.rb_version())

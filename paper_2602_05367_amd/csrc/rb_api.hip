@@ -1,0 +1,74 @@
+// C-ABI entry points: argument checks and kernel selection.  No allocation, no
+// synchronisation; everything is enqueued on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include "rabit.h"
+#include "rb_internal.h"
+
+namespace rb {
+
+int check_layer(const rb_layer *L)
+{
+    if (!L) return RB_ERR_NULL;
+    if (!L->bits || !L->g || !L->h) return RB_ERR_NULL;
+    if (L->K < 1 || L->K > RB_MAX_K || L->out < 1 || L->in < 32 || L->in % 32 != 0) return RB_ERR_SHAPE;
+    if ((uintptr_t)L->bits & 15) return RB_ERR_ALIGN;
+    if (((uintptr_t)L->g | (uintptr_t)L->h) & 1) return RB_ERR_ALIGN;
+    return RB_OK;
+}
+
+}  // namespace rb
+
+extern "C" size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int T)
+{
+    if (!layers || n_layers < 1 || T < 1) return 0;
+    return rb::workspace_bytes(layers, n_layers, T);
+}
+
+extern "C" int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T, int act_dtype,
+                              int out_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int rc = rb::check_layer(L);
+    if (rc != RB_OK) return rc;
+    if (!X || !Y) return RB_ERR_NULL;
+    if (T < 1 || T > 65535) return RB_ERR_SHAPE;
+    if (act_dtype != RB_F16 && act_dtype != RB_BF16) return RB_ERR_UNSUPPORTED;
+    if (out_dtype != RB_F16 && out_dtype != RB_BF16 && out_dtype != RB_F32) return RB_ERR_UNSUPPORTED;
+    if (((uintptr_t)X | (uintptr_t)Y) & 15) return RB_ERR_ALIGN;
+    if (workspace_bytes < rb::workspace_bytes(L, 1, T) || (workspace_bytes && !workspace))
+        return RB_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
+    return rb::dispatch_linear(L, X, Y, T, act_dtype, out_dtype, workspace, workspace_bytes,
+                               static_cast<hipStream_t>(stream));
+}
+
+extern "C" int rb_linear_gemv(const rb_layer *L, const uint16_t *x, uint16_t *y, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return rb_linear_gemm(L, x, y, 1, RB_F16, RB_F16, workspace, workspace_bytes, stream);
+}
+
+extern "C" int rb_layer_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                              uint16_t *const *bufs, int n_bufs, int T, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!layers || !ops || !bufs) return RB_ERR_NULL;
+    if (n_layers < 1 || n_ops < 1 || n_bufs < 1 || T < 1 || T > 65535) return RB_ERR_SHAPE;
+    for (int l = 0; l < n_layers; ++l) {
+        const int rc = rb::check_layer(&layers[l]);
+        if (rc != RB_OK) return rc;
+    }
+    for (int n = 0; n < n_ops; ++n) {
+        const rb_stack_op &op = ops[n];
+        if (op.layer < 0 || op.layer >= n_layers || op.src < 0 || op.src >= n_bufs || op.dst < 0 ||
+            op.dst >= n_bufs || op.src == op.dst)
+            return RB_ERR_SHAPE;
+        if (!bufs[op.src] || !bufs[op.dst]) return RB_ERR_NULL;
+        if (((uintptr_t)bufs[op.src] | (uintptr_t)bufs[op.dst]) & 15) return RB_ERR_ALIGN;
+    }
+    if (workspace_bytes < rb::workspace_bytes(layers, n_layers, T) || (workspace_bytes && !workspace))
+        return RB_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
+    return rb::dispatch_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,25 @@
+// Declarations shared between the entry points and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstddef>
+
+#include "rabit.h"
+
+namespace rb {
+
+int check_layer(const rb_layer *L);
+
+// generic sign-XOR + add kernel, any supported shape, T via grid.y
+int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
+                   hipStream_t stream);
+
+size_t workspace_bytes(const rb_layer *layers, int n_layers, int T);
+
+int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
+                    void *workspace, size_t workspace_bytes, hipStream_t stream);
+
+int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                   uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes,
+                   hipStream_t stream);
+
+}  // namespace rb
