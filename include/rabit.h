@@ -110,7 +110,8 @@ int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
  * buffer is device fp16 [T][width].  The result of each op equals
  * rb_linear_gemm on the same input.  An op may read any buffer written by an
  * earlier op (or never written: stack inputs); dst buffers must be distinct
- * from the op's src.
+ * from the op's src.  layers, ops and bufs are host arrays; bufs holds n_bufs
+ * device pointers.
  */
 typedef struct rb_stack_op { int layer; int src; int dst; } rb_stack_op;
 
@@ -119,9 +120,10 @@ int rb_layer_stack(const rb_layer *layers, int n_layers,
                    uint16_t *const *bufs, int n_bufs, int T,
                    void *workspace, size_t workspace_bytes, void *stream);
 
-/* Bytes of workspace that the three compute calls need for these layers at T
- * tokens (an upper bound over the layers; 16-byte aligned device memory). */
-size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int T);
+/* Bytes of workspace that a compute call over n_ops ops on these layers needs
+ * at T tokens (n_ops = 1 for rb_linear_gemv / rb_linear_gemm; 16-byte aligned
+ * device memory, contents owned by the library between calls). */
+size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 
 /* ------------------------------------------------------------------------
  * Measurement aids (not part of the layer): the comparators the benchmark
@@ -139,6 +141,15 @@ int rb_dense_gemv_f16(const uint16_t *W, const uint16_t *x, uint16_t *y,
  * 16 * rb_stream_read_groups() bytes): the read-bandwidth ceiling of this GPU. */
 int rb_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 int rb_stream_read_groups(void);
+
+/* Which kernel family the most recent compute call of this thread enqueued:
+ * RB_PATH_NONE, RB_PATH_SIGNADD (generic sign-XOR + add kernel, one launch per
+ * op) or RB_PATH_MX (matrix-core kernel, all ops of the call in one persistent
+ * launch).  For tests and benchmarks that must know what they measured. */
+#define RB_PATH_NONE    0
+#define RB_PATH_SIGNADD 1
+#define RB_PATH_MX      2
+int rb_last_path(void);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int rb_version(void);

@@ -27,7 +27,7 @@ _ERR_NAMES = {-1: "RB_ERR_NULL", -2: "RB_ERR_SHAPE", -3: "RB_ERR_ALIGN", -4: "RB
 EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
-    "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version",
+    "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
 
@@ -62,12 +62,13 @@ def _load() -> ctypes.CDLL:
     lib.rb_linear_gemm.argtypes = [ctypes.POINTER(rb_layer), p, p, i, i, i, p, z, p]
     lib.rb_layer_stack.argtypes = [ctypes.POINTER(rb_layer), i, ctypes.POINTER(rb_stack_op), i,
                                    ctypes.POINTER(ctypes.c_void_p), i, i, p, z, p]
-    lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i]
+    lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
     lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
     lib.rb_stream_read.argtypes = [p, z, p, p]
     lib.rb_stream_read_groups.argtypes = []
     lib.rb_version.argtypes = []
+    lib.rb_last_path.argtypes = []
     for name in EXPORTS:
         if name not in ("rb_native_bytes", "rb_workspace_bytes"):
             getattr(lib, name).restype = i
@@ -169,12 +170,12 @@ def _layer_array(layers: Sequence[Layer]):
     return arr
 
 
-def rb_workspace_bytes(layers: Sequence[Layer], T: int) -> int:
-    return int(lib.rb_workspace_bytes(_layer_array(layers), len(layers), T))
+def rb_workspace_bytes(layers: Sequence[Layer], n_ops: int, T: int) -> int:
+    return int(lib.rb_workspace_bytes(_layer_array(layers), len(layers), n_ops, T))
 
 
-def _workspace(layers: Sequence[Layer], T: int, device) -> Tuple[torch.Tensor, int]:
-    n = rb_workspace_bytes(layers, T)
+def _workspace(layers: Sequence[Layer], T: int, device, n_ops: int = 1) -> Tuple[torch.Tensor, int]:
+    n = rb_workspace_bytes(layers, n_ops, T)
     ws = torch.empty(max(n, 16), dtype=torch.uint8, device=device)
     return ws, n
 
@@ -218,7 +219,7 @@ class Stack:
         self._ops = (rb_stack_op * len(ops))(*[rb_stack_op(*o) for o in ops])
         self._bufs = (ctypes.c_void_p * len(bufs))(*[b.data_ptr() for b in self.bufs])
         self.n_ops = len(ops)
-        self.ws, self.ws_bytes = _workspace(self.layers, T, self.bufs[0].device)
+        self.ws, self.ws_bytes = _workspace(self.layers, T, self.bufs[0].device, n_ops=len(ops))
 
     def run(self) -> None:
         _check("rb_layer_stack", lib.rb_layer_stack(
@@ -248,6 +249,13 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
         sink = torch.empty(int(lib.rb_stream_read_groups()) * 16, dtype=torch.uint8, device=src.device)
     _check("rb_stream_read", lib.rb_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream()))
     return sink
+
+
+RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX = 0, 1, 2
+
+
+def rb_last_path() -> int:
+    return int(lib.rb_last_path())
 
 
 def rb_version() -> int:

@@ -19,10 +19,10 @@ int check_layer(const rb_layer *L)
 
 }  // namespace rb
 
-extern "C" size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int T)
+extern "C" size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
-    if (!layers || n_layers < 1 || T < 1) return 0;
-    return rb::workspace_bytes(layers, n_layers, T);
+    if (!layers || n_layers < 1 || n_ops < 1 || T < 1) return 0;
+    return rb::workspace_bytes(layers, n_layers, n_ops, T);
 }
 
 extern "C" int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T, int act_dtype,
@@ -35,7 +35,7 @@ extern "C" int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T, 
     if (act_dtype != RB_F16 && act_dtype != RB_BF16) return RB_ERR_UNSUPPORTED;
     if (out_dtype != RB_F16 && out_dtype != RB_BF16 && out_dtype != RB_F32) return RB_ERR_UNSUPPORTED;
     if (((uintptr_t)X | (uintptr_t)Y) & 15) return RB_ERR_ALIGN;
-    if (workspace_bytes < rb::workspace_bytes(L, 1, T) || (workspace_bytes && !workspace))
+    if (workspace_bytes < rb::workspace_bytes(L, 1, 1, T) || (workspace_bytes && !workspace))
         return RB_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
     return rb::dispatch_linear(L, X, Y, T, act_dtype, out_dtype, workspace, workspace_bytes,
@@ -66,7 +66,7 @@ extern "C" int rb_layer_stack(const rb_layer *layers, int n_layers, const rb_sta
         if (!bufs[op.src] || !bufs[op.dst]) return RB_ERR_NULL;
         if (((uintptr_t)bufs[op.src] | (uintptr_t)bufs[op.dst]) & 15) return RB_ERR_ALIGN;
     }
-    if (workspace_bytes < rb::workspace_bytes(layers, n_layers, T) || (workspace_bytes && !workspace))
+    if (workspace_bytes < rb::workspace_bytes(layers, n_layers, n_ops, T) || (workspace_bytes && !workspace))
         return RB_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
     return rb::dispatch_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,

@@ -6,17 +6,37 @@
 
 namespace rb {
 
-size_t workspace_bytes(const rb_layer *, int, int) { return 0; }
+thread_local int g_last_path = RB_PATH_NONE;
+
+size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
+{
+    if (T > 2) return 0;
+    return mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
+}
 
 int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
-                    void *, size_t, hipStream_t stream)
+                    void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    if (act_dtype == RB_F16 && out_dtype == RB_F16 && mx::layer_supported(L, T) && workspace &&
+        workspace_bytes >= mx::plan_workspace_bytes(L, 1, 1, T)) {
+        const rb_stack_op op{0, 0, 1};
+        uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};
+        const int rc = mx::run_plan(L, &op, 1, bufs, T, workspace, workspace_bytes, stream);
+        if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_MX; return rc; }
+    }
+    g_last_path = RB_PATH_SIGNADD;
     return launch_signadd(L, X, Y, T, act_dtype, out_dtype, stream);
 }
 
-int dispatch_stack(const rb_layer *layers, int, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs,
-                   int, int T, void *workspace, size_t workspace_bytes, hipStream_t stream)
+int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                   uint16_t *const *bufs, int, int T, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    bool fused = workspace && workspace_bytes >= mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
+    for (int n = 0; n < n_ops && fused; ++n) fused = mx::layer_supported(&layers[ops[n].layer], T);
+    if (fused) {
+        const int rc = mx::run_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes, stream);
+        if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_MX; return rc; }
+    }
     for (int n = 0; n < n_ops; ++n) {
         const rb_layer *L = &layers[ops[n].layer];
         const int rc = dispatch_linear(L, bufs[ops[n].src], bufs[ops[n].dst], T, RB_F16, RB_F16, workspace,
@@ -27,3 +47,5 @@ int dispatch_stack(const rb_layer *layers, int, const rb_stack_op *ops, int n_op
 }
 
 }  // namespace rb
+
+extern "C" int rb_last_path(void) { return rb::g_last_path; }

@@ -13,7 +13,7 @@ int check_layer(const rb_layer *L);
 int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
                    hipStream_t stream);
 
-size_t workspace_bytes(const rb_layer *layers, int n_layers, int T);
+size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 
 int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
                     void *workspace, size_t workspace_bytes, hipStream_t stream);
@@ -21,5 +21,13 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
 int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes,
                    hipStream_t stream);
+
+namespace mx {
+// matrix-core path (K = 2, T <= 2): whole op lists run as one persistent kernel
+bool layer_supported(const rb_layer *L, int T);
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
+int run_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,
+             void *workspace, size_t workspace_bytes, hipStream_t stream);
+}  // namespace mx
 
 }  // namespace rb

@@ -28,6 +28,7 @@ def test_config1_single_layer_2048():
     L = to_device_layer(signs, g, h)
     y = rb.rb_linear_gemv(L, torch.from_numpy(x[0]).cuda())
     torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX          # K=2, one fp16 token: the matrix-core kernel
     err = max_rel_l2(y, oracle.forward(signs, g, h, x))
     _say(f"  rel_l2={err:.3e}")
     assert err <= TOL
@@ -46,8 +47,9 @@ def test_gemv_shapes_and_tails(K, out, inn):
     L = to_device_layer(signs, g, h)
     y = rb.rb_linear_gemv(L, torch.from_numpy(x[0]).cuda())
     torch.cuda.synchronize()
+    assert rb.rb_last_path() == (rb.RB_PATH_MX if K == 2 else rb.RB_PATH_SIGNADD)
     err = max_rel_l2(y, oracle.forward(signs, g, h, x))
-    _say(f"  rel_l2={err:.3e}")
+    _say(f"  rel_l2={err:.3e} path={rb.rb_last_path()}")
     assert err <= TOL
 
 
