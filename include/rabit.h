@@ -120,6 +120,26 @@ int rb_layer_stack(const rb_layer *layers, int n_layers,
                    uint16_t *const *bufs, int n_bufs, int T,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same stack split for decode loops: rb_stack_prepare does everything that
+ * depends only on the frozen layers, the op list and the buffer addresses
+ * (uploads the op list into the workspace, derives per-layer constants from h,
+ * clears the scratch arrays) and rb_stack_run executes the prepared ops once
+ * on the current contents of the input buffers.  Between the two calls and
+ * between runs the caller must not write to the workspace nor change layers,
+ * buffers addresses or T; rb_stack_forget drops the library's host-side record
+ * of a workspace (call it before the memory is reused for something else).
+ * rb_stack_prepare returns RB_ERR_UNSUPPORTED for stacks that only
+ * rb_layer_stack's general path can run (K != 2, T > 2, an output read by more
+ * than three ops, more than 1024 ops fed from outside the stack).
+ */
+int rb_stack_prepare(const rb_layer *layers, int n_layers,
+                     const rb_stack_op *ops, int n_ops,
+                     uint16_t *const *bufs, int n_bufs, int T,
+                     void *workspace, size_t workspace_bytes, void *stream);
+int rb_stack_run(void *workspace, size_t workspace_bytes, void *stream);
+int rb_stack_forget(const void *workspace);
+
 /* Bytes of workspace that a compute call over n_ops ops on these layers needs
  * at T tokens (n_ops = 1 for rb_linear_gemv / rb_linear_gemm; 16-byte aligned
  * device memory, contents owned by the library between calls). */

@@ -27,6 +27,7 @@ _ERR_NAMES = {-1: "RB_ERR_NULL", -2: "RB_ERR_SHAPE", -3: "RB_ERR_ALIGN", -4: "RB
 EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
+    "rb_stack_prepare", "rb_stack_run", "rb_stack_forget",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -62,6 +63,9 @@ def _load() -> ctypes.CDLL:
     lib.rb_linear_gemm.argtypes = [ctypes.POINTER(rb_layer), p, p, i, i, i, p, z, p]
     lib.rb_layer_stack.argtypes = [ctypes.POINTER(rb_layer), i, ctypes.POINTER(rb_stack_op), i,
                                    ctypes.POINTER(ctypes.c_void_p), i, i, p, z, p]
+    lib.rb_stack_prepare.argtypes = lib.rb_layer_stack.argtypes
+    lib.rb_stack_run.argtypes = [p, z, p]
+    lib.rb_stack_forget.argtypes = [p]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
     lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
@@ -222,9 +226,23 @@ class Stack:
         self.ws, self.ws_bytes = _workspace(self.layers, T, self.bufs[0].device, n_ops=len(ops))
 
     def run(self) -> None:
+        """rb_layer_stack: set-up and execution in one call."""
         _check("rb_layer_stack", lib.rb_layer_stack(
             self._layers, len(self.layers), self._ops, self.n_ops, self._bufs, len(self.bufs), self.T,
             self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+    def prepare(self) -> None:
+        """rb_stack_prepare: everything that does not depend on the activations."""
+        _check("rb_stack_prepare", lib.rb_stack_prepare(
+            self._layers, len(self.layers), self._ops, self.n_ops, self._bufs, len(self.bufs), self.T,
+            self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+    def run_prepared(self) -> None:
+        """rb_stack_run: one pass of the prepared ops over the current buffer contents."""
+        _check("rb_stack_run", lib.rb_stack_run(self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+    def forget(self) -> None:
+        _check("rb_stack_forget", lib.rb_stack_forget(self.ws.data_ptr()))
 
 
 def rb_layer_stack(layers: Sequence[Layer], ops: Sequence[Tuple[int, int, int]],

@@ -48,9 +48,49 @@ extern "C" int rb_linear_gemv(const rb_layer *L, const uint16_t *x, uint16_t *y,
     return rb_linear_gemm(L, x, y, 1, RB_F16, RB_F16, workspace, workspace_bytes, stream);
 }
 
+static int check_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                       uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes);
+
+extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                                uint16_t *const *bufs, int n_bufs, int T, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    const int rc = check_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes);
+    if (rc != RB_OK) return rc;
+    if (!workspace) return RB_ERR_WORKSPACE;
+    for (int n = 0; n < n_ops; ++n)
+        if (!rb::mx::layer_supported(&layers[ops[n].layer], T)) return RB_ERR_UNSUPPORTED;
+    return rb::mx::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes,
+                                static_cast<hipStream_t>(stream));
+}
+
+extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return RB_ERR_NULL;
+    const int rc = rb::mx::launch_plan(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    if (rc == RB_OK) rb::set_last_path(RB_PATH_MX);
+    return rc;
+}
+
+extern "C" int rb_stack_forget(const void *workspace)
+{
+    if (!workspace) return RB_ERR_NULL;
+    rb::mx::forget_plan(workspace);
+    return RB_OK;
+}
+
 extern "C" int rb_layer_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
                               uint16_t *const *bufs, int n_bufs, int T, void *workspace,
                               size_t workspace_bytes, void *stream)
+{
+    const int rc = check_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes);
+    if (rc != RB_OK) return rc;
+    return rb::dispatch_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
+static int check_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
+                       uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes)
 {
     if (!layers || !ops || !bufs) return RB_ERR_NULL;
     if (n_layers < 1 || n_ops < 1 || n_bufs < 1 || T < 1 || T > 65535) return RB_ERR_SHAPE;
@@ -69,6 +109,5 @@ extern "C" int rb_layer_stack(const rb_layer *layers, int n_layers, const rb_sta
     if (workspace_bytes < rb::workspace_bytes(layers, n_layers, n_ops, T) || (workspace_bytes && !workspace))
         return RB_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
-    return rb::dispatch_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
-                              static_cast<hipStream_t>(stream));
+    return RB_OK;
 }

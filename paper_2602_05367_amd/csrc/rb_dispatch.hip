@@ -7,6 +7,7 @@
 namespace rb {
 
 thread_local int g_last_path = RB_PATH_NONE;
+void set_last_path(int path) { g_last_path = path; }
 
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {

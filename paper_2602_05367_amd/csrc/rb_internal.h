@@ -8,6 +8,7 @@
 namespace rb {
 
 int check_layer(const rb_layer *L);
+void set_last_path(int path);
 
 // generic sign-XOR + add kernel, any supported shape, T via grid.y
 int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
@@ -28,6 +29,12 @@ bool layer_supported(const rb_layer *L, int T);
 size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 int run_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,
              void *workspace, size_t workspace_bytes, hipStream_t stream);
+// the two halves of run_plan: set-up that depends only on the frozen layers and the buffer
+// addresses, and the per-token launch
+int prepare_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,
+                 void *workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_plan(void *workspace, size_t workspace_bytes, hipStream_t stream);
+void forget_plan(const void *workspace);
 }  // namespace mx
 
 }  // namespace rb

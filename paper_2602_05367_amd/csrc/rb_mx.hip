@@ -20,6 +20,8 @@
 
 #include <cmath>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "rabit.h"
@@ -35,6 +37,46 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 #define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+
+#ifdef RB_EXP_TRACE
+// experiment builds: per-stage timestamps of workgroup 0 (wavefronts 0 and CWAVES), printed at the end
+#define RB_TRACE(k)                                                                                        \
+    do {                                                                                                   \
+        if (grp == 0 && (wave == 0 || wave == CWAVES) && lane == 0 && st < 160)                            \
+            trace[(st * 8 + (k))] = __builtin_amdgcn_s_memtime();                                          \
+    } while (0)
+#define RB_TRACE_DUMP()                                                                                    \
+    do {                                                                                                   \
+        if (grp == 0 && wave == 0 && lane == 0)                                                            \
+            for (int q = 0; q < 128; ++q)                                                                  \
+                printf("S %d %llu %llu %llu %llu\n", q, trace[160 * 8 + q * 4], trace[160 * 8 + q * 4 + 1], \
+                       trace[160 * 8 + q * 4 + 2], trace[160 * 8 + q * 4 + 3]);                            \
+        if (grp == 0 && (wave == 0 || wave == CWAVES) && lane == 0)                                        \
+            for (int q = 0; q < n_stages && q < 160; ++q)                                                  \
+                printf("T w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu\n", wave, q, stages[q].nops,  \
+                       trace[q * 8 + 0], trace[q * 8 + 1], trace[q * 8 + 2], trace[q * 8 + 3],             \
+                       trace[q * 8 + 4], trace[q * 8 + 5], trace[q * 8 + 6]);                              \
+    } while (0)
+#define RB_TRACE_LDS (160 * 8 * 8 + 128 * 4 * 8)
+#define RB_STEP(k)                                                                                         \
+    do {                                                                                                   \
+        if (grp == 0 && wave == 0 && lane == 0 && step_no < 128)                                           \
+            trace[160 * 8 + step_no * 4 + (k)] = __builtin_amdgcn_s_memtime();                             \
+    } while (0)
+#define RB_STEP_NEXT() (++step_no)
+#else
+#define RB_TRACE_LDS 0
+#define RB_STEP(k) do { } while (0)
+#define RB_STEP_NEXT() do { } while (0)
+#define RB_TRACE(k) do { } while (0)
+#define RB_TRACE_DUMP() do { } while (0)
+#endif
+
+// Cache policy of the expanded-input loads.  They read what other compute units wrote earlier in
+// the same launch, so they must be coherent at device scope (sc1), not served from a stale line.
+#ifndef RB_OPERAND_POLICY
+#define RB_OPERAND_POLICY " sc1"
+#endif
 
 // ---------------------------------------------------------------- helpers ---
 __device__ __forceinline__ uint32_t lds_addr(const void *p)
@@ -63,19 +105,54 @@ __device__ __forceinline__ size_t up_offset(int CB, int tok, int p, int t, int j
     return ((size_t)((tok >> 1) * CB + cb) * 16 + (8 * (tok & 1) + 4 * p + t)) * 128 + operand_byte(j & 127);
 }
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt)
+__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, uint32_t &rt0, uint32_t &nrt)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+    rt0 = grp * RT / G;
+    nrt = (grp + 1) * RT / G - rt0;
 }
 
 // ------------------------------------------------------------ prep kernel ---
-// One workgroup per op: power-of-two scale of each path's input scales, and the
-// zero fill of the expanded-input array (padding columns and unused operand
-// columns must read as zero).  Workgroup 0 also resets the hand-over flags.
+// One workgroup per op: power-of-two scale of each path's input scales, the zero fill of the
+// expanded-input array (padding columns and unused operand columns must read as zero), and the
+// tables the stack kernel keeps in LDS.  Workgroup 0 also resets the hand-over flags.
 __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *flags, uint32_t *error,
-                                                   uint32_t *zero_page, int reset_flags)
+                                                   uint32_t *zero_page, OpInfo *info, WaveRec *rec,
+                                                   uint32_t epoch)
 {
-    Op &op = ops[blockIdx.x];
+    const int o = blockIdx.x;
+    Op &op = ops[o];
+    // Which tiles of this op every (workgroup, compute wavefront) pair streams: row tiles are dealt to
+    // the workgroups in contiguous, nearly equal shares, and a share (row tiles x column tiles,
+    // contiguous in the native layout) is cut into CWAVES contiguous runs.
+    {
+        const uint32_t G = (uint32_t)hdr->n_groups, RT = (uint32_t)op.RT, CT = (uint32_t)op.CT;
+        const uint32_t n_ops = (uint32_t)hdr->n_ops;
+        for (uint32_t idx = threadIdx.x; idx < G * CWAVES; idx += 256) {
+            const uint32_t grp = idx / CWAVES, wave = idx % CWAVES;
+            uint32_t rt0, nrt;
+            group_rows(RT, grp, G, rt0, nrt);
+            const uint32_t U = nrt * CT, u0 = wave * U / CWAVES, u1 = (wave + 1) * U / CWAVES;
+            uint32_t slot_base = 0;                       // row tiles of the earlier ops of the stage
+            for (int m = op.stage_op0; m < o; ++m) {
+                uint32_t a, b;
+                group_rows((uint32_t)ops[m].RT, grp, G, a, b);
+                slot_base += b;
+            }
+            WaveRec r;
+            r.tile0 = rt0 * CT + u0;
+            r.packed = (u1 - u0) | ((u0 % CT) << 16) | ((slot_base + u0 / CT) << 24);
+            rec[(size_t)idx * n_ops + o] = r;
+        }
+        if (threadIdx.x == 0) {
+            OpInfo inf;
+            inf.bits = (uint64_t)op.bits;
+            inf.up = (uint64_t)op.up;
+            inf.CT = CT;
+            inf.pad_[0] = inf.pad_[1] = inf.pad_[2] = 0;
+            info[o] = inf;
+        }
+    }
     __shared__ float red[256];
     for (int p = 0; p < 2; ++p) {
         float m = 0.f;
@@ -103,9 +180,8 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     const size_t n16 = up_bytes(op.in, hdr->T) / 16;
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
-    if (blockIdx.x == 0) {
-        if (reset_flags)
-            for (int i = threadIdx.x; i < hdr->n_groups; i += 256) flags[i] = hdr->epoch0 - 1u;
+    if (o == 0) {
+        for (int i = threadIdx.x; i < hdr->n_groups; i += 256) flags[i] = epoch;   // older than any launch to come
         if (threadIdx.x < 32) zero_page[threadIdx.x] = 0;
         if (threadIdx.x == 0) *error = 0;
     }
@@ -132,25 +208,6 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
 }
 
 // ---------------------------------------------------------- stack kernel ---
-struct Span { int u0, u1, rt0, nrt; };
-
-// share of workgroup `grp` (of G) and compute wavefront `wave` in an op
-__device__ __forceinline__ Span op_span(int RT, int CT, int grp, int G, int wave)
-{
-    // all inputs are wavefront-uniform; RT <= MAXSLOT * G keeps the products inside 32 bits
-    Span s;
-    s.rt0 = (int)((uint32_t)grp * (uint32_t)RT / (uint32_t)G);
-    s.nrt = (int)((uint32_t)(grp + 1) * (uint32_t)RT / (uint32_t)G) - s.rt0;
-    const uint32_t U = (uint32_t)(s.nrt * CT);
-    s.u0 = (int)((uint32_t)wave * U / CWAVES);
-    s.u1 = (int)((uint32_t)(wave + 1) * U / CWAVES);
-    s.rt0 = __builtin_amdgcn_readfirstlane(s.rt0);
-    s.nrt = __builtin_amdgcn_readfirstlane(s.nrt);
-    s.u0 = __builtin_amdgcn_readfirstlane(s.u0);
-    s.u1 = __builtin_amdgcn_readfirstlane(s.u1);
-    return s;
-}
-
 // workgroup barrier that orders LDS only: the weight prefetch of a compute wavefront stays in
 // flight across it (a full fence would wait for every outstanding global load)
 __device__ __forceinline__ void lds_barrier()
@@ -158,12 +215,10 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ const uint8_t *uniform_ptr(const void *p)
+__device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
 {
-    const uint64_t v = (uint64_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
 }
 
 __device__ __forceinline__ v4f mfma_signs(uint32_t w, v8i b, v4f acc, uint32_t c22, int scale_b)
@@ -178,6 +233,14 @@ __device__ __forceinline__ v4f mfma_signs(uint32_t w, v8i b, v4f acc, uint32_t c
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 1, 0, 0x7f7f7f7f, 0, scale_b);
 }
 
+// sum over the four lanes of a quad (the four terms of one path and token)
+__device__ __forceinline__ float quad_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));   // 1,0,3,2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));   // 2,3,0,1
+    return v;
+}
+
 struct BTile { v4i r[4]; };   // two 128-column blocks x 32 bytes per lane
 
 __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restrict__ hdr_p,
@@ -185,72 +248,105 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                                                            const Stage *__restrict__ stages,
                                                            uint32_t *__restrict__ flags,
                                                            uint32_t *__restrict__ error,
-                                                           const uint32_t *__restrict__ zero_page)
+                                                           const uint32_t *__restrict__ zero_page,
+                                                           const OpInfo *__restrict__ info_g,
+                                                           const WaveRec *__restrict__ rec_g,
+                                                           const uint32_t epoch0)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    float *part = reinterpret_cast<float *>(lds + LDS_RING_BYTES);
-    uint32_t *misc = reinterpret_cast<uint32_t *>(lds + LDS_RING_BYTES + LDS_PART_BYTES);
+    float *part = reinterpret_cast<float *>(lds + LDS_PART_OFF);
+    uint32_t *misc = reinterpret_cast<uint32_t *>(lds + LDS_MISC_OFF);
+#ifdef RB_EXP_TRACE
+    unsigned long long *trace = reinterpret_cast<unsigned long long *>(lds + LDS_BYTES);
+#endif
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x, G = gridDim.x;
     const int n_ops = hdr_p->n_ops, n_stages = hdr_p->n_stages, T = hdr_p->T;
-    const uint32_t epoch0 = hdr_p->epoch0;
 
+    // ---- LDS set-up: clear the partial sums, copy this workgroup's records and the op table
     for (int i = threadIdx.x; i < LDS_PART_BYTES / 4; i += THREADS) part[i] = 0.f;
+    {
+        const uint2 *src = reinterpret_cast<const uint2 *>(rec_g + (size_t)grp * CWAVES * n_ops);
+        uint2 *dst = reinterpret_cast<uint2 *>(lds + LDS_REC_OFF);
+        for (int i = threadIdx.x; i < CWAVES * n_ops; i += THREADS) dst[(i / n_ops) * MAX_OPS + (i % n_ops)] = src[i];
+        const uint4 *isrc = reinterpret_cast<const uint4 *>(info_g);
+        uint4 *idst = reinterpret_cast<uint4 *>(lds + LDS_INFO_OFF);
+        for (int i = threadIdx.x; i < 2 * n_ops; i += THREADS) idst[i] = isrc[i];
+    }
     if (threadIdx.x == 0) misc[0] = 0;
     __syncthreads();
 
     if (wave < CWAVES) {
         // ======================= compute wavefront ==========================
-        uint8_t *ring = lds + wave * (RING_D * 1024);
+        uint8_t *const ring = lds + LDS_RING_OFF + wave * (RING_D * 1024);
+        uint8_t *const ring_end = ring + RING_D * 1024;
         const int col = lane & 15, qd = lane >> 4;
         const int ncols = T > 1 ? 16 : 8;
         const int scale_b = (127 - 3 * (col & 3)) * 0x01010101;
+        // lanes beyond the used operand columns always read past the end of the buffer (zeros)
+        const uint32_t lane_off = col < ncols ? (uint32_t)(col * 128 + qd * 32) : 0x80000000u;
         uint32_t c22;
         asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c22));
         // A load that carries no data but keeps the number of vector-memory operations per
         // step constant (the in-order completion counter is what the ring relies on): four
         // bytes per lane from the zero page into a scratch corner of LDS.
-        uint8_t *dummy_dst = lds + LDS_RING_BYTES + LDS_PART_BYTES + 256 + wave * 256;
+        uint8_t *dummy_dst = lds + LDS_MISC_OFF + 256 + wave * 256;
         const uint32_t *dummy_src = zero_page;
+        auto issue_dummies = [&](int n) {
+            for (int i = 0; i < n; ++i) __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
+        };
+        // LDS tables are read with explicit instructions: a compiler-visible LDS read would make the
+        // compiler wait for every sign tile still in flight into the ring
+        const uint32_t rec_base = lds_addr(lds + LDS_REC_OFF) + (uint32_t)wave * MAX_OPS * 8;
+        const uint32_t info_base = lds_addr(lds + LDS_INFO_OFF);
+        auto read_rec = [&](int op, uint32_t &tile0, uint32_t &packed) {
+            uint2 v;
+            asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(rec_base + (uint32_t)op * 8) : "memory");
+            tile0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.x);
+            packed = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.y);
+        };
 
-        // ---- sign-tile stream cursor (runs RING_D tiles ahead of the MFMAs)
-        int a_op = -1, a_u = 0, a_u1 = 0;
-        const uint8_t *a_base = nullptr;
-        uint32_t a_count = 0;
+        // ---- sign-tile stream (runs RING_D tiles ahead of the MFMAs, across ops and stages)
+        int a_op = -1;
+        uint32_t a_n = 0;
+        const uint8_t *a_ptr = nullptr;
+        uint8_t *a_slot = ring;
         auto issue_a = [&]() {
-            while (a_u >= a_u1 && a_op < n_ops) {
-                a_op = __builtin_amdgcn_readfirstlane(a_op + 1);
-                if (a_op < n_ops) {
-                    const int CT = __builtin_amdgcn_readfirstlane(ops[a_op].CT);
-                    const Span s = op_span(__builtin_amdgcn_readfirstlane(ops[a_op].RT), CT, grp, G, wave);
-                    a_u = s.u0; a_u1 = s.u1;
-                    a_base = uniform_ptr(ops[a_op].bits) + (size_t)s.rt0 * CT * 1024;
+            while (a_n == 0 && a_op + 1 < n_ops) {
+                ++a_op;
+                uint32_t tile0, packed;
+                read_rec(a_op, tile0, packed);
+                a_n = packed & 0xffffu;
+                if (a_n != 0) {
+                    uint2 v;
+                    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(info_base + (uint32_t)a_op * 32) : "memory");
+                    a_ptr = reinterpret_cast<const uint8_t *>(uniform64(v.x, v.y)) + (size_t)tile0 * 1024;
                 }
             }
-            uint8_t *slot = ring + (a_count % RING_D) * 1024;
-            if (a_u < a_u1) {
-                __builtin_amdgcn_global_load_lds(a_base + ((size_t)a_u * 64 + lane) * 16, RB_LDS(slot), 16, 0, 0);
-                ++a_u;
+            if (a_n != 0) {
+                __builtin_amdgcn_global_load_lds(a_ptr + lane * 16, RB_LDS(a_slot), 16, 0, 0);
+                a_ptr += 1024;
+                --a_n;
             } else {
                 __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
             }
-            ++a_count;
-        };
-        auto issue_dummies = [&](int n) {
-            for (int i = 0; i < n; ++i) __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
+            a_slot += 1024;
+            if (a_slot == ring_end) a_slot = ring;
         };
 
 #pragma unroll 1
         for (int d = 0; d < RING_D; ++d) { issue_a(); issue_dummies(4); }
-        uint32_t c_count = 0;     // tiles consumed so far (ring slot = c_count % RING_D)
+        uint8_t *c_slot_ptr = ring;           // ring slot of the next tile to consume
+#ifdef RB_EXP_TRACE
+        int step_no = 0;
+#endif
         BTile B[NB];
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) B[i].r[r] = (v4i){0, 0, 0, 0};
-
         // Operand loads are written as instructions, so the compiler does not know that their
         // target registers stay busy until the data arrives.  Naming the registers here keeps
         // them allocated (never reused as temporaries) across the code between two stages.
@@ -262,99 +358,119 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 
         for (int st = 0; st < n_stages; ++st) {
             const Stage stage = stages[st];
+            const int stage_end = stage.op0 + stage.nops;
+            RB_TRACE(0);
             if (stage.wait_before) lds_barrier();        // released by the polling wavefront
+            RB_TRACE(1);
             keep_operands();
 
-            // ---- this wavefront's tiles of the stage, op after op
-            // B cursor: (op index in stage, tile) -> address of the expanded input
-            int b_op = stage.op0 - 1, b_u = 0, b_u1 = 0, b_CT = 1;
+            // ---- expanded-input stream of this stage (NB tiles ahead of the MFMAs).  What the
+            // consuming step needs to know about a tile travels with it in meta[]:
+            // bit 0: a tile (not the end of the stage), bit 1: last tile of its row tile for this
+            // wavefront (write the partial sums), bits 8..: partial-sum slot.
+            int b_op = stage.op0 - 1;
+            uint32_t b_n = 0, b_ct = 0, b_CT = 1, b_slot = 0;
             v4i b_rsrc = {0, 0, 0, 0x00020000};               // empty buffer: every load returns zero
-            auto issue_b = [&](BTile &dst) {
-                while (b_u >= b_u1 && b_op < stage.op0 + stage.nops) {
-                    b_op = __builtin_amdgcn_readfirstlane(b_op + 1);
-                    if (b_op < stage.op0 + stage.nops) {
-                        b_CT = __builtin_amdgcn_readfirstlane(ops[b_op].CT);
-                        const Span s = op_span(__builtin_amdgcn_readfirstlane(ops[b_op].RT), b_CT, grp, G, wave);
-                        b_u = s.u0; b_u1 = s.u1;
-                        const uint64_t up = (uint64_t)uniform_ptr(ops[b_op].up);
+            uint32_t meta[NB];
+            auto issue_b = [&](BTile &dst, uint32_t &m) {
+                while (b_n == 0 && b_op + 1 < stage_end) {
+                    ++b_op;
+                    uint32_t tile0, packed;
+                    read_rec(b_op, tile0, packed);
+                    b_n = packed & 0xffffu;
+                    if (b_n != 0) {
+                        b_ct = (packed >> 16) & 0xffu;
+                        b_slot = packed >> 24;
+                        uint4 v;
+                        asm volatile("ds_read_b128 %0, %1 offset:8\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(info_base + (uint32_t)b_op * 32) : "memory");
                         // raw buffer descriptor: base, stride 0, size of token pair 0, 32-bit untyped
-                        b_rsrc[0] = (int)(uint32_t)up;
-                        b_rsrc[1] = (int)((uint32_t)(up >> 32) & 0xffffu);
-                        b_rsrc[2] = 2 * b_CT * UP_BLOCK_BYTES;
+                        b_CT = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.z);
+                        b_rsrc[0] = __builtin_amdgcn_readfirstlane((int)v.x);
+                        b_rsrc[1] = __builtin_amdgcn_readfirstlane((int)v.y) & 0xffff;
+                        b_rsrc[2] = (int)(2 * b_CT * UP_BLOCK_BYTES);
                         b_rsrc[3] = 0x00020000;
                     }
                 }
                 // Always four loads, written as instructions so that their order and their number
                 // per step are exactly what the wait before the MFMAs counts on.  Without a tile
-                // left, and in lanes beyond the used operand columns, the offset lies past the end
-                // of the buffer: a bounds-checked zero, no memory access.
-                const bool valid = b_u < b_u1;
-                const int ct = valid ? b_u % b_CT : 0;
-                const uint32_t off0 = (valid && col < ncols)
-                                          ? (uint32_t)((2 * ct) * UP_BLOCK_BYTES + col * 128 + qd * 32)
-                                          : 0x80000000u;
-                asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen sc1\n\t"
-                             "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:16 sc1\n\t"
-                             "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048 sc1\n\t"
-                             "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:2064 sc1"
-                             : "=&v"(dst.r[0]), "=&v"(dst.r[1]), "=&v"(dst.r[2]), "=&v"(dst.r[3])
+                // left the offset lies past the end of the buffer: a bounds-checked zero, no access.
+                // The target registers are in-out operands on purpose: the compiler cannot see that
+                // a load issued here lands later, and the loads of the last steps of a stage are
+                // never waited for.  As in-out operands the registers stay allocated to the operand
+                // ring for the whole kernel, so no temporary is ever placed where a late load lands.
+#ifdef RB_EXP_SKIP_OPERANDS
+                const bool valid = false;
+#else
+                const bool valid = b_n != 0;
+#endif
+                const uint32_t off0 = valid ? b_ct * (2 * UP_BLOCK_BYTES) + lane_off : 0x80000000u;
+                asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:16" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:2064" RB_OPERAND_POLICY
+                             : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
                              : "v"(off0), "s"(b_rsrc)
                              : "memory");
-                b_u += valid ? 1 : 0;
+                m = 0;
+                if (b_n != 0) {
+                    --b_n;
+                    ++b_ct;
+                    const bool wrap = b_ct == b_CT;
+                    m = 1u | ((wrap || b_n == 0) ? 2u : 0u) | (b_slot << 8);
+                    if (wrap) { b_ct = 0; ++b_slot; }
+                }
             };
 
-            // consume cursor
-            int c_op = stage.op0 - 1, c_u = 0, c_u1 = 0, c_CT = 1, slot_base = 0, next_slot_base = 0;
             v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
             const int parity = st & 1;
-            auto flush = [&](int slot) {
-                float *dstp = part + (size_t)(parity * MAXSLOT + slot) * 512 + (4 * qd) * 16 + col;
-                const uint32_t a = lds_addr(dstp);
-                asm volatile("ds_add_f32 %0, %1\n\tds_add_f32 %0, %2 offset:64\n\tds_add_f32 %0, %3 offset:128\n\t"
-                             "ds_add_f32 %0, %4 offset:192\n\tds_add_f32 %0, %5 offset:1024\n\t"
-                             "ds_add_f32 %0, %6 offset:1088\n\tds_add_f32 %0, %7 offset:1152\n\t"
-                             "ds_add_f32 %0, %8 offset:1216\n\ts_waitcnt lgkmcnt(0)"
-                             :
-                             : "v"(a), "v"(acc0[0]), "v"(acc0[1]), "v"(acc0[2]), "v"(acc0[3]), "v"(acc1[0]),
-                               "v"(acc1[1]), "v"(acc1[2]), "v"(acc1[3])
-                             : "memory");
+            // a quad of lanes holds the four terms of (path = quad & 1, token = quad >> 1); its
+            // first lane writes rows 4*qd .. 4*qd+3 of that path and token
+            const int quad = col >> 2;
+            const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * LDS_PART_SLOT_BYTES +
+                                       (uint32_t)wave * 256 + (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
+            auto flush = [&](uint32_t slot) {
+                v4f v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float s0 = quad_sum(acc0[r]), s1 = quad_sum(acc1[r]);
+                    v[r] = (quad & 1) ? s1 : s0;
+                }
+                if ((col & 3) == 0)
+                    asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                 :
+                                 : "v"(part_lane + slot * LDS_PART_SLOT_BYTES), "v"(v)
+                                 : "memory");
                 acc0 = (v4f){0, 0, 0, 0};
                 acc1 = (v4f){0, 0, 0, 0};
             };
 
 #pragma unroll
-            for (int i = 0; i < NB; ++i) { issue_b(B[i]); issue_dummies(1); }
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i]); issue_dummies(1); }
 
             bool more = true;
             while (more) {
 #pragma unroll
                 for (int s = 0; s < NB; ++s) {
-                    // advance the consume cursor to the next tile of this wavefront in the stage
-                    while (c_u >= c_u1 && c_op < stage.op0 + stage.nops) {
-                        c_op = __builtin_amdgcn_readfirstlane(c_op + 1);
-                        slot_base = next_slot_base;
-                        if (c_op < stage.op0 + stage.nops) {
-                            c_CT = __builtin_amdgcn_readfirstlane(ops[c_op].CT);
-                            const Span sp = op_span(__builtin_amdgcn_readfirstlane(ops[c_op].RT), c_CT, grp, G, wave);
-                            c_u = sp.u0; c_u1 = sp.u1;
-                            next_slot_base = slot_base + sp.nrt;
-                        }
-                    }
-                    if (c_u >= c_u1) { more = false; break; }
+                    const uint32_t m = meta[s];
+                    if (!(m & 1u)) { more = false; break; }
                     // Every step issues exactly five vector-memory loads (four operand loads, one
                     // sign tile or its stand-in) and loads complete in order.  The operand of this
                     // tile was requested NB steps ago, followed by 5 * NB - 4 younger loads; the
                     // sign tile is older still (RING_D > NB).  So "at most 5 * NB - 4 outstanding"
                     // means both have arrived.
+                    RB_STEP(0);
                     uint4 w;
                     {
-                        const uint32_t addr = lds_addr(ring + (c_count % RING_D) * 1024 + lane * 16);
+                        const uint32_t addr = lds_addr(c_slot_ptr) + lane * 16;
                         asm volatile("s_waitcnt vmcnt(%6)\n\tds_read_b128 %0, %5\n\ts_waitcnt lgkmcnt(0)"
                                      : "=v"(w), "+v"(B[s].r[0]), "+v"(B[s].r[1]), "+v"(B[s].r[2]), "+v"(B[s].r[3])
                                      : "v"(addr), "n"(5 * NB - 4)
                                      : "memory");
                     }
-                    ++c_count;
+                    RB_STEP(1);
+                    c_slot_ptr += 1024;
+                    if (c_slot_ptr == ring_end) c_slot_ptr = ring;
                     const BTile bt = B[s];
                     v8i b0, b1;
 #pragma unroll
@@ -362,24 +478,35 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         b0[i] = bt.r[0][i]; b0[4 + i] = bt.r[1][i];
                         b1[i] = bt.r[2][i]; b1[4 + i] = bt.r[3][i];
                     }
+#ifndef RB_EXP_NO_MFMA
                     acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
                     acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
                     acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
                     acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
-                    const int local_rt = c_u / c_CT;
-                    ++c_u;
-                    if (c_u == c_u1 || c_u % c_CT == 0) flush(slot_base + local_rt);
-                    issue_b(B[s]);
+#else
+                    acc0[0] += __uint_as_float((w.x ^ w.y ^ w.z ^ w.w) & 0x007fffffu) + (float)b0[0] + (float)b1[0];
+#endif
+                    if (m & 2u) flush(m >> 8);
+                    RB_STEP(2);
+                    issue_b(B[s], meta[s]);
                     issue_a();
+                    RB_STEP(3);
+                    RB_STEP_NEXT();
                 }
             }
+            RB_TRACE(2);
             lds_barrier();                                    // partial sums of the stage are in LDS
+            RB_TRACE(3);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land in LDS after the end
         keep_operands();
+        RB_TRACE_DUMP();
     } else {
         // =================== finishing / hand-over wavefront ================
         const int ew = wave - CWAVES;
+        // lane -> (slot, row, token): a wavefront finishes two slots per stage, one per half
+        const int my_slot = ew + EWAVES * (lane >> 5);
+        const int row = lane & 15, tok = (lane >> 4) & 1;
         uint32_t sig = 0;                                     // signalling stages seen so far
         bool failed = false;                                  // a wait timed out: stop waiting, report
         for (int st = 0; st < n_stages; ++st) {
@@ -400,54 +527,82 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                             failed = true;
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(2);
+                        __builtin_amdgcn_s_sleep(1);
                     }
                 }
                 lds_barrier();
             }
+            // ---- before the partial sums are ready: find this lane's row and fetch everything
+            // that does not depend on them (output scales, the scales of the ops that read y next)
+            int my_op = -1, grow = 0;
+            {
+                int slot_base = 0;
+                for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+                    uint32_t rt0, nrt;
+                    group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, rt0, nrt);
+                    if (my_slot >= slot_base && my_slot < slot_base + (int)nrt) {
+                        my_op = o;
+                        grow = (int)(rt0 + (uint32_t)(my_slot - slot_base)) * 16 + row;
+                    }
+                    slot_base += (int)nrt;
+                }
+            }
+            const bool active = my_op >= 0 && tok < T && grow < ops[my_op >= 0 ? my_op : 0].out;
+            float gsc[2] = {0.f, 0.f};
+            __half *yp = nullptr;
+            int n_cons = 0;
+            float hh[MAX_CONS][2];
+            uint8_t *upp[MAX_CONS];
+            if (active) {
+                const Op &op = ops[my_op];
+                const __half *g = reinterpret_cast<const __half *>(op.g);
+                gsc[0] = __half2float(g[grow]) * op.inv_sc[0];
+                gsc[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
+                yp = reinterpret_cast<__half *>(op.y) + (size_t)tok * op.out + grow;
+                n_cons = op.n_cons;
+#pragma unroll
+                for (int c = 0; c < MAX_CONS; ++c) {
+                    hh[c][0] = hh[c][1] = 0.f;
+                    upp[c] = nullptr;
+                    if (c < n_cons) {
+                        const Op &m = ops[op.cons[c]];
+                        const __half *h = reinterpret_cast<const __half *>(m.h);
+                        hh[c][0] = __half2float(h[grow]) * m.sc[0];
+                        hh[c][1] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
+                        upp[c] = m.up + up_offset(col_tiles(m.in) * 2, tok, 0, 0, grow);
+                    }
+                }
+            }
+            RB_TRACE(4);
             lds_barrier();                                    // partial sums complete
-            const int parity = st & 1;
-            // slots of this workgroup in this stage, dealt round-robin to the four wavefronts
-            int slot = 0;
-            for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
-                const Op &op = ops[o];
-                const Span sp = op_span(op.RT, op.CT, grp, G, 0);
-                for (int r = 0; r < sp.nrt; ++r, ++slot) {
-                    if ((slot & (EWAVES - 1)) != ew) continue;
-                    float *P = part + (size_t)(parity * MAXSLOT + slot) * 512;
-                    const int row = lane & 15, tok = (lane >> 4) & 1;
-                    const int grow = (sp.rt0 + r) * 16 + row;
-                    float y = 0.f;
-                    if (lane < 32) {
+            RB_TRACE(5);
+            if (active) {
+                // sum the partial sums of the compute wavefronts, clear them for the next use
+                float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CWAVES) * 64 + tok * 16 + row;
+                float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                for (int w = 0; w < CWAVES; ++w) {
+                    s0 += P[w * 64];
+                    s1 += P[w * 64 + 32];
+                }
+#pragma unroll
+                for (int w = 0; w < CWAVES; ++w) {
+                    P[w * 64] = 0.f;
+                    P[w * 64 + 32] = 0.f;
+                }
+                const __half y16 = __float2half_rn(gsc[0] * s0 + gsc[1] * s1);
+                *yp = y16;
+                const float yf = __half2float(y16);
+#pragma unroll
+                for (int c = 0; c < MAX_CONS; ++c) {
+                    if (c < n_cons) {
 #pragma unroll
                         for (int p = 0; p < 2; ++p) {
-                            const float4 v = *reinterpret_cast<const float4 *>(P + (p * 16 + row) * 16 + 8 * tok + 4 * p);
-                            const float gsc = grow < op.out
-                                                  ? __half2float(reinterpret_cast<const __half *>(op.g)[(size_t)p * op.out + grow]) *
-                                                        op.inv_sc[p]
-                                                  : 0.f;
-                            y += gsc * ((v.x + v.y) + (v.z + v.w));
-                        }
-                    }
-                    // clear the slot for its next use
-                    reinterpret_cast<float4 *>(P)[lane] = make_float4(0, 0, 0, 0);
-                    reinterpret_cast<float4 *>(P)[lane + 64] = make_float4(0, 0, 0, 0);
-                    if (lane < 32 && tok < T && grow < op.out) {
-                        const __half y16 = __float2half_rn(y);
-                        reinterpret_cast<__half *>(op.y)[(size_t)tok * op.out + grow] = y16;
-                        const float yf = __half2float(y16);
-                        for (int c = 0; c < op.n_cons; ++c) {
-                            const Op &m = ops[op.cons[c]];
-                            const int CB = col_tiles(m.in) * 2;
+                            const uint32_t terms = expand4(hh[c][p] * yf);
 #pragma unroll
-                            for (int p = 0; p < 2; ++p) {
-                                const float h = __half2float(reinterpret_cast<const __half *>(m.h)[(size_t)p * m.in + grow]);
-                                const uint32_t terms = expand4(h * yf * m.sc[p]);
-#pragma unroll
-                                for (int t = 0; t < 4; ++t)
-                                    __hip_atomic_store(m.up + up_offset(CB, tok, p, t, grow), (uint8_t)(terms >> (8 * t)),
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            }
+                            for (int t = 0; t < 4; ++t)
+                                __hip_atomic_store(upp[c] + (4 * p + t) * 128, (uint8_t)(terms >> (8 * t)),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
                 }
@@ -463,7 +618,9 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     __hip_atomic_store(&flags[grp], epoch0 + sig, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ++sig;
             }
+            RB_TRACE(6);
         }
+        RB_TRACE_DUMP();
     }
 }
 
@@ -477,6 +634,9 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t up_total
     o = align_up(o, 128); L.flags = o; o += sizeof(uint32_t) * (size_t)n_groups;
     o = align_up(o, 128); L.error = o; o += 128;
     L.zero = o; o += 128;
+    L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
+    L.info = o; o += sizeof(OpInfo) * (size_t)n_ops;
+    o = align_up(o, 128); L.rec = o; o += sizeof(WaveRec) * (size_t)n_ops * (size_t)n_groups * CWAVES;
     o = align_up(o, 256); L.up = o; o += up_total;
     L.total = align_up(o, 256);
     return L;
@@ -496,7 +656,7 @@ static int device_groups()
 
 bool layer_supported(const rb_layer *L, int T)
 {
-    return L->K == 2 && T >= 1 && T <= MAX_T && L->in % 32 == 0;
+    return L->K == 2 && T >= 1 && T <= MAX_T && L->in % 32 == 0 && L->in <= 65536;
 }
 
 size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
@@ -508,10 +668,17 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
     return make_layout(n_ops, n_ops, G, align_up(up_max, 256) * (size_t)n_ops).total;
 }
 
-static uint32_t g_epoch = 1;
+// Host record of a prepared plan, keyed by the workspace that holds its device part.
+struct Prepared {
+    Layout lay;
+    int n_ops = 0, n_stages = 0, n_signals = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0;
+};
+static std::mutex g_mutex;
+static std::map<const void *, Prepared> g_prepared;
+static uint32_t g_epoch = 1;          // hand-over epochs grow monotonically over all launches
 
-int run_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
-             void *workspace, size_t workspace_bytes_, hipStream_t stream)
+int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
+                 void *workspace, size_t workspace_bytes_, hipStream_t stream)
 {
     const int G = device_groups();
     if (G <= 0) return RB_ERR_HIP;
@@ -547,6 +714,7 @@ int run_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_
             pr.cons[pr.n_cons++] = n;
         }
     }
+    if (expand_list.size() > MAX_EXPAND || n_ops > MAX_OPS) return RB_ERR_UNSUPPORTED;
     std::vector<Stage> stages;
     {
         int op0 = 0;
@@ -569,71 +737,103 @@ int run_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_
             stages.push_back(s);
             op0 += s.nops;
         }
-        // a stage signals if a later stage waits (the wait of stage s+1.. refers to the latest signal)
+        // A waiting stage polls for the most recent signal, so every stage that has a waiting
+        // stage anywhere after it signals (its flag then also covers all earlier stages).
         for (size_t s = 0; s + 1 < stages.size(); ++s)
             for (size_t r = s + 1; r < stages.size(); ++r)
                 if (stages[r].wait_before) { stages[s].signal_after = 1; break; }
-        // every waiting stage must follow a signalling stage that covers all earlier writes:
-        // make each stage before a waiting stage signal
-        for (size_t s = 1; s < stages.size(); ++s)
-            if (stages[s].wait_before) stages[s - 1].signal_after = 1;
     }
-    const int n_stages = (int)stages.size();
-    int n_signals = 0;
-    for (const Stage &s : stages) n_signals += s.signal_after;
-
-    const Layout lay = make_layout(n_ops, n_stages, G, up_total);
+    for (const Stage &st : stages)
+        for (int n = st.op0; n < st.op0 + st.nops; ++n) ops[(size_t)n].stage_op0 = st.op0;
+    Prepared pr;
+    pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T;
+    for (const Stage &s : stages) pr.n_signals += s.signal_after;
+    pr.n_expand = (int)expand_list.size();
+    for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
+    pr.lay = make_layout(n_ops, pr.n_stages, G, up_total);
+    const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     for (int n = 0; n < n_ops; ++n) ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
 
     Header hdr{};
-    hdr.n_ops = n_ops; hdr.n_stages = n_stages; hdr.T = T; hdr.n_groups = G;
-    hdr.epoch0 = g_epoch;
-    g_epoch += (uint32_t)n_signals + 2u;
+    hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G;
 
-    // ---- upload (stream-ordered copies from host memory that lives until they are staged)
+    // ---- upload: stream-ordered copies out of host memory that outlives the call
     static thread_local std::vector<uint8_t> blob;
-    blob.assign(lay.up, 0);
+    blob.assign(lay.flags, 0);
     std::memcpy(blob.data(), &hdr, sizeof(hdr));
     std::memcpy(blob.data() + lay.ops, ops.data(), sizeof(Op) * (size_t)n_ops);
-    std::memcpy(blob.data() + lay.stages, stages.data(), sizeof(Stage) * (size_t)n_stages);
-    std::vector<int> which = expand_list;
-    const size_t which_off = lay.error + 64;   // spare bytes after the error word hold the expand list
-    if (which.size() * sizeof(int) > 64) {
-        // long lists go behind the zero page instead of the spare bytes: not expected for decoder stacks
-        return RB_ERR_UNSUPPORTED;
-    }
-    std::memcpy(blob.data() + which_off, which.data(), which.size() * sizeof(int));
+    std::memcpy(blob.data() + lay.stages, stages.data(), sizeof(Stage) * (size_t)pr.n_stages);
+    static thread_local int which[MAX_EXPAND];
+    for (size_t i = 0; i < expand_list.size(); ++i) which[i] = expand_list[i];
     if (hipMemcpyAsync(ws, blob.data(), lay.flags, hipMemcpyHostToDevice, stream) != hipSuccess) return RB_ERR_HIP;
-    if (hipMemcpyAsync(ws + which_off, blob.data() + which_off, 64, hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (!expand_list.empty() &&
+        hipMemcpyAsync(ws + lay.which, which, sizeof(int) * expand_list.size(), hipMemcpyHostToDevice, stream) !=
+            hipSuccess)
         return RB_ERR_HIP;
 
+    uint32_t epoch;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        epoch = g_epoch;
+        g_epoch += 2u;
+        g_prepared[workspace] = pr;
+    }
+    hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
+                       reinterpret_cast<Op *>(ws + lay.ops), reinterpret_cast<uint32_t *>(ws + lay.flags),
+                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero),
+                       reinterpret_cast<OpInfo *>(ws + lay.info), reinterpret_cast<WaveRec *>(ws + lay.rec), epoch);
+    return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+}
+
+int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    Prepared pr;
+    uint32_t epoch;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        const auto it = g_prepared.find(workspace);
+        if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
+        pr = it->second;
+        epoch = g_epoch;
+        g_epoch += (uint32_t)pr.n_signals + 2u;
+    }
+    if (workspace_bytes_ < pr.lay.total) return RB_ERR_WORKSPACE;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const Layout &lay = pr.lay;
     Header *d_hdr = reinterpret_cast<Header *>(ws);
     Op *d_ops = reinterpret_cast<Op *>(ws + lay.ops);
-    Stage *d_stages = reinterpret_cast<Stage *>(ws + lay.stages);
-    uint32_t *d_flags = reinterpret_cast<uint32_t *>(ws + lay.flags);
-    uint32_t *d_error = reinterpret_cast<uint32_t *>(ws + lay.error);
-    uint32_t *d_zero = reinterpret_cast<uint32_t *>(ws + lay.zero);
-    const int *d_which = reinterpret_cast<const int *>(ws + which_off);
-
-    hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, d_hdr, d_ops, d_flags, d_error, d_zero, 1);
-    if (!expand_list.empty()) {
-        int max_in = 0;
-        for (int n : expand_list) max_in = std::max(max_in, ops[(size_t)n].in);
-        hipLaunchKernelGGL(expand_kernel, dim3((max_in + 255) / 256, T, (unsigned)expand_list.size()), dim3(256), 0,
-                           stream, d_hdr, d_ops, d_which);
-    }
+    if (pr.n_expand > 0)
+        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
+                           dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(stack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + RB_TRACE_LDS) != hipSuccess)
             return RB_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(stack_kernel, dim3(G), dim3(THREADS), LDS_BYTES, stream, d_hdr, d_ops, d_stages, d_flags,
-                       d_error, d_zero);
+    hipLaunchKernelGGL(stack_kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
+                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<uint32_t *>(ws + lay.flags),
+                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                       reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec),
+                       epoch);
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+}
+
+void forget_plan(const void *workspace)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_prepared.erase(workspace);
+}
+
+int run_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
+             void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    const int rc = prepare_plan(layers, sops, n_ops, bufs, T, workspace, workspace_bytes_, stream);
+    if (rc != RB_OK) return rc;
+    return launch_plan(workspace, workspace_bytes_, stream);
 }
 
 }  // namespace mx

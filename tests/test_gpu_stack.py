@@ -11,7 +11,7 @@ import torch
 import oracle
 import synth
 import paper_2602_05367_amd as rb
-from helpers import TOL, build_stack, to_device_layer
+from helpers import TOL, build_stack, to_device_layer, random_layer
 
 pytestmark = pytest.mark.gpu
 
@@ -66,3 +66,50 @@ def test_small_stack_batched_with_outliers(T):
 def test_one_13b_block_derived():
     ops, widths, layers, bufs = build_stack("13b", 1, 4, 1, derived=True)
     _run_and_check(ops, widths, layers, bufs, 1, "one 13B-shaped block, derived")
+
+
+def test_prepare_once_run_many_tokens():
+    """rb_stack_prepare + rb_stack_run: one set-up, then one run per token; every run must equal
+    rb_layer_stack on the same input bit for bit."""
+    shrink = {4096: 512, 11008: 1376}
+    ops, widths, layers, bufs = build_stack("7b", 2, 2, 1, derived=False, shrink=shrink, gain=100.0)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    dev_bufs = [torch.zeros((1, w), dtype=torch.float16, device="cuda") for w in widths]
+    ref_bufs = [torch.zeros((1, w), dtype=torch.float16, device="cuda") for w in widths]
+    op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
+    stack = rb.Stack(dev_layers, op_list, dev_bufs, 1)
+    stack.prepare()
+    for token in range(4):
+        x = synth.gaussian_activations(synth.child_rng(2, 50, token), 1, widths[0])
+        dev_bufs[0].copy_(torch.from_numpy(x)); ref_bufs[0].copy_(torch.from_numpy(x))
+        print(f"prepared stack, token {token}", flush=True)
+        stack.run_prepared()
+        rb.rb_layer_stack(dev_layers, op_list, ref_bufs, 1)
+        torch.cuda.synchronize()
+        for a, b in zip(dev_bufs, ref_bufs):
+            assert torch.equal(a, b)
+        last = oracle.forward(*layers[-1], dev_bufs[ops[-1].src].cpu().numpy())
+        assert oracle.relative_l2(dev_bufs[ops[-1].dst].cpu().numpy().astype(np.float64), last).max() <= TOL
+    stack.forget()
+    with pytest.raises(rb.RabitError):
+        stack.run_prepared()
+
+
+def test_independent_ops_need_no_hand_over():
+    """Ops that all read buffers nobody writes (the small-batch recipe: every op has its own
+    input) run in one launch without waiting on each other."""
+    rng = synth.child_rng(3, 77)
+    shapes = [(512, 512), (1376, 512), (512, 1376), (512, 512), (1376, 512)]
+    layers = [random_layer(rng, 2, o, i) for (o, i) in shapes]
+    xs = [synth.outlier_activations(rng, 2, i) for (_, i) in shapes]
+    dev_layers = [to_device_layer(*l) for l in layers]
+    bufs = [torch.from_numpy(x).cuda() for x in xs] + \
+           [torch.zeros((2, o), dtype=torch.float16, device="cuda") for (o, _) in shapes]
+    op_list = [(n, n, len(shapes) + n) for n in range(len(shapes))]
+    print("independent ops, T=2", flush=True)
+    rb.rb_layer_stack(dev_layers, op_list, bufs, 2)
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX
+    for n in range(len(shapes)):
+        ref = oracle.forward(*layers[n], xs[n])
+        assert oracle.relative_l2(bufs[len(shapes) + n].cpu().numpy().astype(np.float64), ref).max() <= TOL
