@@ -66,8 +66,9 @@ int rb_unpack(const uint32_t *packed, int K, int out, int in, int8_t *signs);
  * 256 columns; rows are padded to a multiple of 16 and columns to a multiple
  * of 256 with +1 entries (bit 0).  Tiles are stored row-tile major.  Inside a
  * tile, lane l = r + 16*q (r = row in tile, q = 0..3) owns 2*K consecutive
- * words: for c in {0,1}, for k in 0..K-1: the canonical word of path k, row r,
- * columns 128*c + 32*q .. +31 of the tile.  One tile is 64 * 2K words.
+ * words: for c in {0,1}, for k in 0..K-1: the word of path k, row r, columns
+ * 128*c + 32*q .. +31 of the tile, with its 32 columns bit-interleaved: native
+ * bit 4*e + s (e = 0..7, s = 0..3) is column 8*s + e.  One tile is 64 * 2K words.
  * rb_native_bytes gives the size; rb_repack_native / rb_unpack_native convert
  * host arrays between the canonical and the native form (exact inverses on the
  * unpadded part).

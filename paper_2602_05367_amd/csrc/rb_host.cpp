@@ -63,7 +63,7 @@ extern "C" int rb_repack_native(const uint32_t *packed, int K, int out, int in, 
                     for (int k = 0; k < K; ++k) {
                         const int w = rb::tile_word_column(ct, c, q);
                         uint32_t v = 0;                         // padding: +1 everywhere
-                        if (row < out && w < W32) v = packed[((size_t)k * out + row) * W32 + w];
+                        if (row < out && w < W32) v = rb::to_native_word(packed[((size_t)k * out + row) * W32 + w]);
                         tile[rb::lane_word(lane, c, k, K)] = v;
                     }
             }
@@ -83,7 +83,7 @@ extern "C" int rb_unpack_native(const void *native_host, int K, int out, int in,
                 const int rt = row / rb::TILE_ROWS, r = row % rb::TILE_ROWS;
                 const int ct = w / 8, c = (w % 8) / 4, q = w % 4;
                 const uint32_t *tile = src + ((size_t)rt * CT + ct) * rb::tile_words(K);
-                packed[((size_t)k * out + row) * W32 + w] = tile[rb::lane_word(r + 16 * q, c, k, K)];
+                packed[((size_t)k * out + row) * W32 + w] = rb::to_canonical_word(tile[rb::lane_word(r + 16 * q, c, k, K)]);
             }
     return RB_OK;
 }

@@ -39,7 +39,8 @@ constexpr int LDS_PART_SLOT_BYTES = CWAVES * 2 * 2 * 16 * 4;
 constexpr int LDS_PART_BYTES = 2 * MAXSLOT * LDS_PART_SLOT_BYTES;
 constexpr int LDS_REC_BYTES = CWAVES * MAX_OPS * 8;      // WaveRec per (wavefront, op)
 constexpr int LDS_INFO_BYTES = MAX_OPS * 32;             // OpInfo per op
-constexpr int LDS_MISC_BYTES = 256 + CWAVES * 256;       // counters + per-wavefront dummy-load target
+constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
+constexpr int LDS_MISC_BYTES = 256 + CWAVES * 256 + EWAVES * LDS_STAGE_BYTES;   // + per-wavefront dummy-load target
 constexpr int LDS_RING_OFF = 0;
 constexpr int LDS_PART_OFF = LDS_RING_OFF + LDS_RING_BYTES;
 constexpr int LDS_REC_OFF = LDS_PART_OFF + LDS_PART_BYTES;
@@ -55,14 +56,14 @@ static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 // canonical word j / 32 (see operand_byte).
 constexpr int UP_BLOCK_BYTES = 16 * 128;
 
-// byte offset inside a 128-byte operand column for input column jj (0..127)
+// byte offset inside a 128-byte operand column for input column jj (0..127).  The fp4 register s
+// of lane group q takes nibble e from native bit 4*e + s, which is column 32*q + 8*s + e, and the
+// matrix instruction gives that nibble the contraction index 32*q + 8*s + e: index == column.  Its
+// 8-bit operand keeps index k in lane group (k mod 64) / 16, byte (k mod 16) + 16 * (k / 64), so 16
+// consecutive columns are 16 consecutive bytes.
 __host__ __device__ inline int operand_byte(int jj)
 {
-    const int q = jj >> 5, o = jj & 31;        // lane group that owns the word, bit in word
-    const int s = o & 3, e = o >> 2;           // fp4 register s, nibble e  (bit = 4*e + s)
-    const int k = 32 * q + 8 * s + e;          // contraction index of that nibble
-    // the 8-bit operand keeps k in [16*q', 16*q'+16) and [64+16*q', 64+16*q'+16) in lane group q'
-    return k < 64 ? (k >> 4) * 32 + (k & 15) : ((k - 64) >> 4) * 32 + 16 + ((k - 64) & 15);
+    return ((jj & 63) >> 4) * 32 + (jj & 15) + ((jj >> 6) << 4);
 }
 
 struct Op {
@@ -109,9 +110,10 @@ struct Header {
 
 // workspace: [Header][Op x n_ops][Stage x n_stages][flags: n_groups x u32][error u32][zero page 128 B]
 //            [indices of the ops whose input is expanded by a kernel of its own]
+//            [indices of the ops whose input is written by another op of the launch]
 //            [OpInfo x n_ops][WaveRec x n_groups x CWAVES x n_ops][up arrays]
 struct Layout {
-    size_t ops, stages, flags, error, zero, which, info, rec, up, total;
+    size_t ops, stages, flags, error, zero, which, poison, info, rec, up, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

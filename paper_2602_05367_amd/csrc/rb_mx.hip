@@ -11,10 +11,15 @@
 //     current stage NB tiles ahead, and issues four MFMAs per tile;
 //   * partial sums of the wavefronts that share a row tile meet in LDS;
 //   * four more wavefronts finish rows: y = sum_k g_k * acc_k, fp16 rounding,
-//     the store, the four-term expansion of h (.) y for the ops that read y
-//     next, and the cross-CU hand-over (agent-scope stores, one flag per
-//     workgroup, agent-scope polling).  Keeping this traffic on wavefronts of
-//     their own means no wait on it ever drains a weight prefetch.
+//     the store, and the four-term expansion of h (.) y for the ops that read y
+//     next, written with device-scope 16-byte stores.  Keeping this traffic on
+//     wavefronts of their own means no wait on it ever drains a weight prefetch;
+//   * hand-over between compute units needs no flag and no barrier: before a
+//     launch every 16-byte group of an expanded input that a producer will write
+//     gets a poison byte (a bf8 NaN code no finite value converts to); a
+//     consumer checks that byte in the operand it has just loaded and, if it is
+//     still there, loads again.  One 16-byte store carries the 16 rows of one
+//     row tile, so the byte says the whole group has arrived.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -207,6 +212,20 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
     }
 }
 
+// Marks every 16-column group of the expanded input of the listed ops as "not yet written": the
+// first byte of the group, in every operand column in use, becomes POISON.
+constexpr uint8_t POISON = 0xff;     // bf8 NaN; the conversion of a finite value never yields it
+__global__ __launch_bounds__(256) void poison_kernel(const Header *hdr, const Op *ops, const int *which)
+{
+    const Op &op = ops[which[blockIdx.y]];
+    const int CB = col_tiles(op.in) * 2, T = hdr->T;
+    const int idx = blockIdx.x * 256 + threadIdx.x;           // (group, token, path, term)
+    const int group = idx / (8 * T), rest = idx % (8 * T);
+    if (group * 16 >= op.in) return;
+    const int tok = rest >> 3, p = (rest >> 2) & 1, t = rest & 3;
+    op.up[up_offset(CB, tok, p, t, group * 16)] = POISON;
+}
+
 // ---------------------------------------------------------- stack kernel ---
 // workgroup barrier that orders LDS only: the weight prefetch of a compute wavefront stays in
 // flight across it (a full fence would wait for every outstanding global load)
@@ -246,16 +265,13 @@ struct BTile { v4i r[4]; };   // two 128-column blocks x 32 bytes per lane
 __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
-                                                           uint32_t *__restrict__ flags,
                                                            uint32_t *__restrict__ error,
                                                            const uint32_t *__restrict__ zero_page,
                                                            const OpInfo *__restrict__ info_g,
-                                                           const WaveRec *__restrict__ rec_g,
-                                                           const uint32_t epoch0)
+                                                           const WaveRec *__restrict__ rec_g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     float *part = reinterpret_cast<float *>(lds + LDS_PART_OFF);
-    uint32_t *misc = reinterpret_cast<uint32_t *>(lds + LDS_MISC_OFF);
 #ifdef RB_EXP_TRACE
     unsigned long long *trace = reinterpret_cast<unsigned long long *>(lds + LDS_BYTES);
 #endif
@@ -275,7 +291,6 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         uint4 *idst = reinterpret_cast<uint4 *>(lds + LDS_INFO_OFF);
         for (int i = threadIdx.x; i < 2 * n_ops; i += THREADS) idst[i] = isrc[i];
     }
-    if (threadIdx.x == 0) misc[0] = 0;
     __syncthreads();
 
     if (wave < CWAVES) {
@@ -339,6 +354,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #pragma unroll 1
         for (int d = 0; d < RING_D; ++d) { issue_a(); issue_dummies(4); }
         uint8_t *c_slot_ptr = ring;           // ring slot of the next tile to consume
+        bool failed = false;                  // a producer never delivered: stop waiting, report
 #ifdef RB_EXP_TRACE
         int step_no = 0;
 #endif
@@ -360,8 +376,6 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             const Stage stage = stages[st];
             const int stage_end = stage.op0 + stage.nops;
             RB_TRACE(0);
-            if (stage.wait_before) lds_barrier();        // released by the polling wavefront
-            RB_TRACE(1);
             keep_operands();
 
             // ---- expanded-input stream of this stage (NB tiles ahead of the MFMAs).  What the
@@ -372,7 +386,22 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             uint32_t b_n = 0, b_ct = 0, b_CT = 1, b_slot = 0;
             v4i b_rsrc = {0, 0, 0, 0x00020000};               // empty buffer: every load returns zero
             uint32_t meta[NB];
-            auto issue_b = [&](BTile &dst, uint32_t &m) {
+            uint32_t s_off[NB];                               // where each operand in flight came from,
+            v4i s_rsrc[NB];                                   // in case it has to be fetched again
+            auto load_operand = [&](BTile &dst, uint32_t off0, v4i rsrc) {
+                // The target registers are in-out operands on purpose: the compiler cannot see that
+                // a load issued here lands later, and the loads of the last steps of a stage are
+                // never waited for.  As in-out operands the registers stay allocated to the operand
+                // ring for the whole kernel, so no temporary is ever placed where a late load lands.
+                asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:16" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048" RB_OPERAND_POLICY "\n\t"
+                             "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:2064" RB_OPERAND_POLICY
+                             : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
+                             : "v"(off0), "s"(rsrc)
+                             : "memory");
+            };
+            auto issue_b = [&](BTile &dst, uint32_t &m, uint32_t &keep_off, v4i &keep_rsrc) {
                 while (b_n == 0 && b_op + 1 < stage_end) {
                     ++b_op;
                     uint32_t tile0, packed;
@@ -395,23 +424,15 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 // Always four loads, written as instructions so that their order and their number
                 // per step are exactly what the wait before the MFMAs counts on.  Without a tile
                 // left the offset lies past the end of the buffer: a bounds-checked zero, no access.
-                // The target registers are in-out operands on purpose: the compiler cannot see that
-                // a load issued here lands later, and the loads of the last steps of a stage are
-                // never waited for.  As in-out operands the registers stay allocated to the operand
-                // ring for the whole kernel, so no temporary is ever placed where a late load lands.
 #ifdef RB_EXP_SKIP_OPERANDS
                 const bool valid = false;
 #else
                 const bool valid = b_n != 0;
 #endif
                 const uint32_t off0 = valid ? b_ct * (2 * UP_BLOCK_BYTES) + lane_off : 0x80000000u;
-                asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:16" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:2064" RB_OPERAND_POLICY
-                             : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
-                             : "v"(off0), "s"(b_rsrc)
-                             : "memory");
+                load_operand(dst, off0, b_rsrc);
+                keep_off = off0;
+                keep_rsrc = b_rsrc;
                 m = 0;
                 if (b_n != 0) {
                     --b_n;
@@ -446,7 +467,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             };
 
 #pragma unroll
-            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i]); issue_dummies(1); }
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], s_off[i], s_rsrc[i]); issue_dummies(1); }
 
             bool more = true;
             while (more) {
@@ -468,6 +489,29 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                                      : "v"(addr), "n"(5 * NB - 4)
                                      : "memory");
                     }
+                    // Hand-over: an operand written by another compute unit earlier in this launch is
+                    // valid once the poison byte of each of its 16-byte groups is gone.  If one is
+                    // still there the producer has not stored yet: fetch the operand again (all
+                    // older loads are waited for on the way, which keeps the wait counts valid).
+                    if (stage.wait_before && !failed) {
+                        int spins = 0;
+                        while (true) {
+                            const BTile &b = B[s];
+                            const bool poisoned = (b.r[0][0] & 0xff) == POISON || (b.r[1][0] & 0xff) == POISON ||
+                                                  (b.r[2][0] & 0xff) == POISON || (b.r[3][0] & 0xff) == POISON;
+                            if (!__any(poisoned)) break;
+                            if (++spins > (1 << 15)) {
+                                if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                failed = true;
+                                break;
+                            }
+                            load_operand(B[s], s_off[s], s_rsrc[s]);
+                            asm volatile("s_waitcnt vmcnt(0)"
+                                         : "+v"(B[s].r[0]), "+v"(B[s].r[1]), "+v"(B[s].r[2]), "+v"(B[s].r[3])
+                                         :
+                                         : "memory");
+                        }
+                    }
                     RB_STEP(1);
                     c_slot_ptr += 1024;
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
@@ -488,7 +532,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #endif
                     if (m & 2u) flush(m >> 8);
                     RB_STEP(2);
-                    issue_b(B[s], meta[s]);
+                    issue_b(B[s], meta[s], s_off[s], s_rsrc[s]);
                     issue_a();
                     RB_STEP(3);
                     RB_STEP_NEXT();
@@ -502,36 +546,16 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         keep_operands();
         RB_TRACE_DUMP();
     } else {
-        // =================== finishing / hand-over wavefront ================
+        // ========================= finishing wavefront ======================
         const int ew = wave - CWAVES;
         // lane -> (slot, row, token): a wavefront finishes two slots per stage, one per half
-        const int my_slot = ew + EWAVES * (lane >> 5);
+        const int half = lane >> 5;
+        const int my_slot = ew + EWAVES * half;
         const int row = lane & 15, tok = (lane >> 4) & 1;
-        uint32_t sig = 0;                                     // signalling stages seen so far
-        bool failed = false;                                  // a wait timed out: stop waiting, report
+        // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
+        uint8_t *stage_bytes = lds + LDS_MISC_OFF + 256 + CWAVES * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
         for (int st = 0; st < n_stages; ++st) {
             const Stage stage = stages[st];
-            if (stage.wait_before) {
-                // wait until every workgroup has published the previous signalling stage
-                if (ew == 0 && !failed) {
-                    const uint32_t target = epoch0 + sig - 1u;
-                    int spins = 0;
-                    while (true) {
-                        bool ok = true;
-                        for (int i = lane; i < G; i += 64)
-                            ok = ok && (int)(__hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                                             target) >= 0;
-                        if (__all(ok)) break;
-                        if (++spins > (1 << 17)) {
-                            if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            failed = true;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                }
-                lds_barrier();
-            }
             // ---- before the partial sums are ready: find this lane's row and fetch everything
             // that does not depend on them (output scales, the scales of the ops that read y next)
             int my_op = -1, grow = 0;
@@ -547,35 +571,41 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     slot_base += (int)nrt;
                 }
             }
-            const bool active = my_op >= 0 && tok < T && grow < ops[my_op >= 0 ? my_op : 0].out;
+            const bool have_slot = my_op >= 0;
+            const bool active = have_slot && tok < T && grow < ops[have_slot ? my_op : 0].out;
             float gsc[2] = {0.f, 0.f};
             __half *yp = nullptr;
             int n_cons = 0;
             float hh[MAX_CONS][2];
-            uint8_t *upp[MAX_CONS];
-            if (active) {
+            uint8_t *upp[MAX_CONS];                       // operand column 0 of token 0, first row of the slot
+#pragma unroll
+            for (int c = 0; c < MAX_CONS; ++c) { hh[c][0] = hh[c][1] = 0.f; upp[c] = nullptr; }
+            if (have_slot) {
                 const Op &op = ops[my_op];
-                const __half *g = reinterpret_cast<const __half *>(op.g);
-                gsc[0] = __half2float(g[grow]) * op.inv_sc[0];
-                gsc[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
-                yp = reinterpret_cast<__half *>(op.y) + (size_t)tok * op.out + grow;
                 n_cons = op.n_cons;
+                if (active) {
+                    const __half *g = reinterpret_cast<const __half *>(op.g);
+                    gsc[0] = __half2float(g[grow]) * op.inv_sc[0];
+                    gsc[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
+                    yp = reinterpret_cast<__half *>(op.y) + (size_t)tok * op.out + grow;
+                }
 #pragma unroll
                 for (int c = 0; c < MAX_CONS; ++c) {
-                    hh[c][0] = hh[c][1] = 0.f;
-                    upp[c] = nullptr;
                     if (c < n_cons) {
                         const Op &m = ops[op.cons[c]];
-                        const __half *h = reinterpret_cast<const __half *>(m.h);
-                        hh[c][0] = __half2float(h[grow]) * m.sc[0];
-                        hh[c][1] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
-                        upp[c] = m.up + up_offset(col_tiles(m.in) * 2, tok, 0, 0, grow);
+                        if (active) {
+                            const __half *h = reinterpret_cast<const __half *>(m.h);
+                            hh[c][0] = __half2float(h[grow]) * m.sc[0];
+                            hh[c][1] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
+                        }
+                        upp[c] = m.up + up_offset(col_tiles(m.in) * 2, 0, 0, 0, grow - row);
                     }
                 }
             }
             RB_TRACE(4);
             lds_barrier();                                    // partial sums complete
             RB_TRACE(5);
+            float yf = 0.f;
             if (active) {
                 // sum the partial sums of the compute wavefronts, clear them for the next use
                 float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CWAVES) * 64 + tok * 16 + row;
@@ -592,31 +622,49 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 }
                 const __half y16 = __float2half_rn(gsc[0] * s0 + gsc[1] * s1);
                 *yp = y16;
-                const float yf = __half2float(y16);
+                yf = __half2float(y16);
+            }
+            // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
+            // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
+            if (__any(n_cons > 0)) {
+                if (have_slot && tok < T) {
 #pragma unroll
-                for (int c = 0; c < MAX_CONS; ++c) {
-                    if (c < n_cons) {
+                    for (int c = 0; c < MAX_CONS; ++c) {
+                        if (c < n_cons) {
 #pragma unroll
-                        for (int p = 0; p < 2; ++p) {
-                            const uint32_t terms = expand4(hh[c][p] * yf);
+                            for (int p = 0; p < 2; ++p) {
+                                const uint32_t terms = active ? expand4(hh[c][p] * yf) : 0u;
+                                uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
 #pragma unroll
-                            for (int t = 0; t < 4; ++t)
-                                __hip_atomic_store(upp[c] + (4 * p + t) * 128, (uint8_t)(terms >> (8 * t)),
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
+                            }
                         }
                     }
                 }
-            }
-            if (stage.signal_after) {
-                // all stores of this wavefront have reached memory, then count in; the last of the
-                // four publishes the workgroup's flag
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                uint32_t old = 0;
-                if (lane == 0) old = atomicAdd(&misc[0], 1u);
-                old = __builtin_amdgcn_readfirstlane(old);
-                if (old == (uint32_t)EWAVES * (sig + 1) - 1u && lane == 0)
-                    __hip_atomic_store(&flags[grp], epoch0 + sig, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ++sig;
+                // lanes now act as (half, consumer, token, path, term): 96 vectors, two rounds
+#pragma unroll
+                for (int round = 0; round < 2; ++round) {
+                    const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
+                    const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vrest = v % 16;
+                    const int vtok = vrest >> 3, vpt = vrest & 7;
+                    // the slot's values live in the lanes of its half: take them from that half's lane 0
+                    const int src_lane = vh * 32;
+                    const int nc = __shfl(n_cons, src_lane);
+                    const bool has = __shfl((int)have_slot, src_lane) != 0;
+                    uint64_t base = 0;
+#pragma unroll
+                    for (int c = 0; c < MAX_CONS; ++c) {
+                        const uint64_t u = (uint64_t)upp[c];
+                        const uint32_t lo = __shfl((uint32_t)u, src_lane), hi = __shfl((uint32_t)(u >> 32), src_lane);
+                        if (c == vc) base = ((uint64_t)hi << 32) | lo;
+                    }
+                    if (v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T) {
+                        const v4i bytes = *reinterpret_cast<const v4i *>(
+                            stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 128;
+                        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
+                    }
+                }
             }
             RB_TRACE(6);
         }
@@ -635,6 +683,7 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t up_total
     o = align_up(o, 128); L.error = o; o += 128;
     L.zero = o; o += 128;
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
+    L.poison = o; o += align_up(sizeof(int) * MAX_OPS, 128);
     L.info = o; o += sizeof(OpInfo) * (size_t)n_ops;
     o = align_up(o, 128); L.rec = o; o += sizeof(WaveRec) * (size_t)n_ops * (size_t)n_groups * CWAVES;
     o = align_up(o, 256); L.up = o; o += up_total;
@@ -672,6 +721,7 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
 struct Prepared {
     Layout lay;
     int n_ops = 0, n_stages = 0, n_signals = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0;
+    int n_poison = 0, max_poison_in = 0;
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
@@ -750,6 +800,13 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     for (const Stage &s : stages) pr.n_signals += s.signal_after;
     pr.n_expand = (int)expand_list.size();
     for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
+    std::vector<int> poison_list;
+    for (int n = 0; n < n_ops; ++n)
+        if (!ops[(size_t)n].expand_x) {
+            poison_list.push_back(n);
+            pr.max_poison_in = std::max(pr.max_poison_in, ops[(size_t)n].in);
+        }
+    pr.n_poison = (int)poison_list.size();
     pr.lay = make_layout(n_ops, pr.n_stages, G, up_total);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
@@ -772,6 +829,12 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         hipMemcpyAsync(ws + lay.which, which, sizeof(int) * expand_list.size(), hipMemcpyHostToDevice, stream) !=
             hipSuccess)
         return RB_ERR_HIP;
+    static thread_local int which_poison[MAX_OPS];
+    for (size_t i = 0; i < poison_list.size(); ++i) which_poison[i] = poison_list[i];
+    if (!poison_list.empty() &&
+        hipMemcpyAsync(ws + lay.poison, which_poison, sizeof(int) * poison_list.size(), hipMemcpyHostToDevice,
+                       stream) != hipSuccess)
+        return RB_ERR_HIP;
 
     uint32_t epoch;
     {
@@ -790,14 +853,11 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
 int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
 {
     Prepared pr;
-    uint32_t epoch;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         const auto it = g_prepared.find(workspace);
         if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
         pr = it->second;
-        epoch = g_epoch;
-        g_epoch += (uint32_t)pr.n_signals + 2u;
     }
     if (workspace_bytes_ < pr.lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -807,6 +867,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (pr.n_expand > 0)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
+    if (pr.n_poison > 0)
+        hipLaunchKernelGGL(poison_kernel, dim3((pr.max_poison_in / 16 * 8 * pr.T + 255) / 256, (unsigned)pr.n_poison),
+                           dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.poison));
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(stack_kernel),
@@ -815,10 +878,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
         attr_set = true;
     }
     hipLaunchKernelGGL(stack_kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
-                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<uint32_t *>(ws + lay.flags),
+                       reinterpret_cast<const Stage *>(ws + lay.stages),
                        reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
-                       reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec),
-                       epoch);
+                       reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec));
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 

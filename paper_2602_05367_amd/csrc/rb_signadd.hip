@@ -26,15 +26,16 @@ constexpr int SIGNADD_WAVES = 4;
 
 __device__ __forceinline__ float signed_sum32(uint32_t word, const float *__restrict__ u)
 {
-    // sum_b (bit b of word ? -u[b] : +u[b]); u is 16-byte aligned LDS
+    // sum over the 32 columns b of (sign bit of column b ? -u[b] : +u[b]); the bit of column b
+    // sits at native_bit(b) of the word; u is 16-byte aligned LDS
     float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
 #pragma unroll
     for (int b = 0; b < 32; b += 4) {
         const float4 v = *reinterpret_cast<const float4 *>(u + b);
-        acc0 += __uint_as_float(__float_as_uint(v.x) ^ ((word << (31 - b)) & 0x80000000u));
-        acc1 += __uint_as_float(__float_as_uint(v.y) ^ ((word << (30 - b)) & 0x80000000u));
-        acc2 += __uint_as_float(__float_as_uint(v.z) ^ ((word << (29 - b)) & 0x80000000u));
-        acc3 += __uint_as_float(__float_as_uint(v.w) ^ ((word << (28 - b)) & 0x80000000u));
+        acc0 += __uint_as_float(__float_as_uint(v.x) ^ ((word << (31 - native_bit(b))) & 0x80000000u));
+        acc1 += __uint_as_float(__float_as_uint(v.y) ^ ((word << (31 - native_bit(b + 1))) & 0x80000000u));
+        acc2 += __uint_as_float(__float_as_uint(v.z) ^ ((word << (31 - native_bit(b + 2))) & 0x80000000u));
+        acc3 += __uint_as_float(__float_as_uint(v.w) ^ ((word << (31 - native_bit(b + 3))) & 0x80000000u));
     }
     return (acc0 + acc1) + (acc2 + acc3);
 }

@@ -59,7 +59,11 @@ def test_native_layout_places_words_as_documented():
     native = rb.rb_repack_native(packed).reshape(2, 2, 64, 2, K)   # [rt][ct][lane][c][k]
     for rt, ct, lane, c, k in [(0, 0, 0, 0, 0), (1, 1, 63, 1, 1), (0, 1, 17, 1, 0), (1, 0, 40, 0, 1)]:
         row, q = rt * 16 + lane % 16, lane // 16
-        assert native[rt, ct, lane, c, k] == packed[k, row, ct * 8 + c * 4 + q]
+        canonical = int(packed[k, row, ct * 8 + c * 4 + q])
+        word = int(native[rt, ct, lane, c, k])
+        for e in range(8):
+            for s in range(4):                       # native bit 4e+s is column 8s+e of the word
+                assert (word >> (4 * e + s)) & 1 == (canonical >> (8 * s + e)) & 1
 
 
 def test_pack_error_codes():
