@@ -23,14 +23,30 @@ namespace mx {
 constexpr int CWAVES = 8;          // wavefronts that stream weights and issue MFMAs
 constexpr int EWAVES = 4;          // wavefronts that finish rows and talk to other CUs
 constexpr int THREADS = (CWAVES + EWAVES) * 64;
-constexpr int RING_D = 10;         // sign tiles in flight per compute wavefront (1 KB each)
-constexpr int NB = 4;              // expanded-input operands in flight per compute wavefront (tiles)
+#ifndef RB_RING_D
+#define RB_RING_D 6
+#endif
+#ifndef RB_NB1
+#define RB_NB1 4
+#endif
+constexpr int RING_D = RB_RING_D;   // sign tiles requested ahead per compute wavefront (1 KB each)
+// expanded-input operands requested ahead per compute wavefront (tiles); each holds 8 registers per
+// lane for one token and 16 for two.  Measured on the 7B-shaped stack: depths 4 to 8 stream equally
+// fast, so the shallow one is used.
+constexpr int nb_of(int T) { return T == 1 ? RB_NB1 : 4; }
+// vector-memory loads per step: operand loads (16 bytes per lane each) and one sign tile
+constexpr int kop_of(int T) { return T == 1 ? 2 : 4; }
+// Loads complete in order.  The operand of a tile is requested nb steps before its use, the sign
+// tile RING_D > nb steps before; when at most this many loads are outstanding both have arrived.
+constexpr int wait_of(int T) { return (nb_of(T) - 1) * (kop_of(T) + 1) + 1; }
 constexpr int MAXSLOT = 8;         // (op, row tile) pairs one CU finishes per stage
 constexpr int MAX_CONS = 3;        // ops that read one op's output inside a fused stack
+constexpr int MAX_DEPS = 3;        // distinct ops of earlier stages whose output one stage reads
 constexpr int MAX_T = 2;           // tokens per call on this path
 constexpr int MAX_OPS = 320;       // ops per launch (their per-wavefront records live in LDS)
 constexpr size_t MAX_EXPAND = 1024;
-static_assert(RING_D > NB && 5 * NB - 4 <= 63, "the in-order wait counts on this");
+static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1) <= 63 && wait_of(2) <= 63,
+              "the in-order wait counts on this");
 
 // LDS map of the stack kernel
 constexpr int LDS_RING_BYTES = CWAVES * RING_D * 1024;
@@ -49,21 +65,26 @@ constexpr int LDS_MISC_OFF = LDS_INFO_OFF + LDS_INFO_BYTES;
 constexpr int LDS_BYTES = LDS_MISC_OFF + LDS_MISC_BYTES;
 static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 
-// Expanded input ("right operand") of one op: for every 128-column block cb
-// there are 16 operand columns of 128 bytes: column 8*(token&1) + 4*path + term.
-// Inside a column, the byte that multiplies input column j of the block sits
-// where the MFMA pairs it with the fp4 sign taken from bit (j % 32) of the
-// canonical word j / 32 (see operand_byte).
-constexpr int UP_BLOCK_BYTES = 16 * 128;
+// Expanded input ("right operand") of one op, stored as the register image the MFMA wants, so
+// that one load instruction of a wavefront reads 1 KB of consecutive bytes (16 per lane).
+// The 8-bit right operand of v_mfma_scale_f32_16x16x128_f8f6f4 keeps, in lane col + 16 * q
+// (col = operand column, q = 0..3), contraction indices 16q..16q+15 in its first four registers and
+// 64+16q..64+16q+15 in the next four.  Contraction index == input column inside a 128-column block
+// (see rb_layout.h), and the operand column is 8 * token + 4 * path + term.
+//   two tokens:  block b is 2 KB: [half j of the contraction][lane col + 16q][16 bytes]
+//   one token:   only columns 0..7 exist, so block b is 1 KB: [q][j][col][16 bytes]; lane
+//                col + 16q of the load gets (j = col / 8, column col % 8), i.e. lanes 0..7 of each
+//                row of 16 hold the first four registers of their column, and the next four
+//                registers come from eight lanes further on with one cross-lane move each.
+// A 16-byte group is the 16 input columns one row tile of the producing op writes.
+__host__ __device__ constexpr int up_block_bytes(int T) { return T == 1 ? 1024 : 2048; }
 
-// byte offset inside a 128-byte operand column for input column jj (0..127).  The fp4 register s
-// of lane group q takes nibble e from native bit 4*e + s, which is column 32*q + 8*s + e, and the
-// matrix instruction gives that nibble the contraction index 32*q + 8*s + e: index == column.  Its
-// 8-bit operand keeps index k in lane group (k mod 64) / 16, byte (k mod 16) + 16 * (k / 64), so 16
-// consecutive columns are 16 consecutive bytes.
-__host__ __device__ inline int operand_byte(int jj)
+// byte offset of the 16-byte group of (input column block of 16 starting at j0, operand column c)
+__host__ __device__ inline size_t up_group_offset(int T, int j0, int c)
 {
-    return ((jj & 63) >> 4) * 32 + (jj & 15) + ((jj >> 6) << 4);
+    const int b = j0 >> 7, jj = j0 & 127, q = (jj & 63) >> 4, j = jj >> 6;
+    return T == 1 ? (size_t)b * 1024 + (size_t)(q * 16 + j * 8 + c) * 16
+                  : (size_t)b * 2048 + (size_t)j * 1024 + (size_t)(q * 16 + c) * 16;
 }
 
 struct Op {
@@ -72,12 +93,15 @@ struct Op {
     const uint16_t *h;        // fp16 [K][in]
     const uint16_t *x;        // fp16 [T][in]  input buffer (read by the expansion kernel only)
     uint16_t *y;              // fp16 [T][out] output buffer
-    uint8_t *up;              // expanded input of this op: [pairs][CB][16][128] bytes
+    uint8_t *up;              // expanded input of this op (see up_group_offset)
     int out, in;
     int RT, CT;               // row tiles (16 rows), column tiles (256 columns)
     int n_cons;               // ops that read y inside this call
     int cons[MAX_CONS];
     int expand_x;             // 1: x comes from outside the fused ops and must be expanded first
+    int dep;                  // op of this launch that writes x (-1: none)
+    int dep_slot;             // position of dep in the list of its stage (-1: none)
+    uint8_t *ready;           // as a producer: one flag byte per row tile of y, 1 = final (null: no reader)
     int stage_op0;            // first op of the stage this op belongs to
     float sc[2];              // power-of-two input scale per path (max |h| * sc <= 1/2)
     float inv_sc[2];
@@ -88,7 +112,9 @@ struct OpInfo {
     uint64_t bits;            // address of the sign tiles
     uint64_t up;              // address of the expanded input
     uint32_t CT;
-    uint32_t pad_[3];
+    uint32_t in;
+    int32_t dep_slot;         // which entry of the stage's list writes the input during this launch (-1: none)
+    uint32_t pad_;
 };
 static_assert(sizeof(OpInfo) == 32, "LDS_INFO_BYTES");
 
@@ -98,30 +124,55 @@ struct WaveRec {
     uint32_t packed;          // n (tiles, bits 0..15) | ct0 (column tile of the first, 16..23) | slot0 (24..31)
 };
 
+// What a finishing wavefront needs for finishing slot `slot` of workgroup `grp` in stage `st`
+// (one row tile of one op), laid out flat so that its address follows from (st, grp, slot) alone:
+// nothing on the path from the partial sums to the stores waits for a chain of dependent loads.
+struct SlotRec {
+    uint64_t y;               // fp16 output: row 0 of token 0
+    uint64_t ready;           // hand-over flag byte of this row tile (0: no reader)
+    uint64_t up[MAX_CONS];    // per reading op: the 16-byte group of operand column 0 these rows fill
+    int out, n_cons;          // rows of the op; ops that read its output
+    int row0, op;             // first row of the row tile; op index (< 0: slot unused)
+    uint64_t pad_;
+};
+static_assert(sizeof(SlotRec) == 64, "four 16-byte loads");
+// per row of the slot: g_1 / sc_1, g_2 / sc_2 of the op (its output scales over the input scaling
+// it was fed with), then h_k * sc_k of each reading op (its input scales times its input scaling)
+struct SlotVals {
+    float v[16][2 + 2 * MAX_CONS];
+};
+static_assert(sizeof(SlotVals) == 512, "32 bytes per row");
+
 struct Stage {
     int op0, nops;            // ops [op0, op0 + nops) are independent of each other
-    int wait_before;          // 1: an op of this stage reads what an earlier stage wrote
-    int signal_after;         // 1: a later stage reads what this stage writes
+    int n_deps;               // ops of earlier stages whose output this stage reads
+    int dep[MAX_DEPS];
 };
+// Hand-over bits in LDS: [stage parity][entry of the stage's list][64-block window] x 64 bits, bit b
+// set = 256-row block 64 * window + b of that op's output is final.
+constexpr int READY_WINDOWS = 4;   // inputs of up to 65536 columns
+constexpr int LDS_READY_BYTES = 2 * MAX_DEPS * READY_WINDOWS * 8;
+static_assert(LDS_READY_BYTES <= 256, "the first 256 bytes of the miscellaneous LDS area");
 
 struct Header {
     int n_ops, n_stages, T, n_groups;
 };
 
-// workspace: [Header][Op x n_ops][Stage x n_stages][flags: n_groups x u32][error u32][zero page 128 B]
+// workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 128 B]
 //            [indices of the ops whose input is expanded by a kernel of its own]
-//            [indices of the ops whose input is written by another op of the launch]
-//            [OpInfo x n_ops][WaveRec x n_groups x CWAVES x n_ops][up arrays]
+//            [hand-over flags: one byte per row tile (padded to 16 per 256-row block) of every op that has a reader]
+//            [OpInfo x n_ops][WaveRec x n_groups x CWAVES x n_ops]
+//            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
 struct Layout {
-    size_t ops, stages, flags, error, zero, which, poison, info, rec, up, total;
+    size_t ops, stages, error, zero, which, ready, info, rec, slots, vals, up, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 __host__ __device__ inline size_t up_bytes(int in, int T)
 {
-    const int CB = (in + 255) / 256 * 2;
-    return (size_t)((T + 1) / 2) * CB * UP_BLOCK_BYTES;
+    const int CB = (in + 255) / 256 * 2;           // whole column tiles: two blocks each
+    return (size_t)CB * up_block_bytes(T);
 }
 
 }  // namespace mx

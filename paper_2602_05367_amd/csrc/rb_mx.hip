@@ -14,12 +14,15 @@
 //     the store, and the four-term expansion of h (.) y for the ops that read y
 //     next, written with device-scope 16-byte stores.  Keeping this traffic on
 //     wavefronts of their own means no wait on it ever drains a weight prefetch;
-//   * hand-over between compute units needs no flag and no barrier: before a
-//     launch every 16-byte group of an expanded input that a producer will write
-//     gets a poison byte (a bf8 NaN code no finite value converts to); a
-//     consumer checks that byte in the operand it has just loaded and, if it is
-//     still there, loads again.  One 16-byte store carries the 16 rows of one
-//     row tile, so the byte says the whole group has arrived.
+//   * hand-over between compute units: a finishing wavefront, once its stores
+//     are acknowledged, adds one to a device-scope counter of the 256-row block
+//     of y its row tile belongs to; a compute wavefront reads the counters of
+//     the op that writes its input (one load covers 64 blocks) before it
+//     requests the first expanded-input tile of a block, and only then touches
+//     those bytes.  Nothing reads a line before it is final, so the reads may be
+//     plain ones that the 32 compute units of an XCD share in its L2; device-
+//     coherent reads of every operand would put twice the weight traffic on the
+//     fabric that also carries the HBM stream.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -40,33 +43,41 @@ namespace mx {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 #define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+// Pointers read from the op table are generic; dereferencing them as such makes FLAT instructions,
+// which also count as LDS traffic: every LDS wait would then wait for global stores to be acknowledged.
+#define RB_GLOBAL(T, p) ((__attribute__((address_space(1))) T *)(p))
 
 #ifdef RB_EXP_TRACE
+#ifndef RB_TRACE_GRP
+#define RB_TRACE_GRP 0
+#endif
 // experiment builds: per-stage timestamps of workgroup 0 (wavefronts 0 and CWAVES), printed at the end
 #define RB_TRACE(k)                                                                                        \
     do {                                                                                                   \
-        if (grp == 0 && (wave == 0 || wave == CWAVES) && lane == 0 && st < 160)                            \
-            trace[(st * 8 + (k))] = __builtin_amdgcn_s_memtime();                                          \
+        if (grp == RB_TRACE_GRP && (wave == 0 || wave == CWAVES) && lane == 0 && st < 64)                             \
+            trace[((wave ? 64 : 0) + st) * 8 + (k)] = __builtin_amdgcn_s_memtime();                        \
     } while (0)
 #define RB_TRACE_DUMP()                                                                                    \
     do {                                                                                                   \
-        if (grp == 0 && wave == 0 && lane == 0)                                                            \
-            for (int q = 0; q < 128; ++q)                                                                  \
-                printf("S %d %llu %llu %llu %llu\n", q, trace[160 * 8 + q * 4], trace[160 * 8 + q * 4 + 1], \
-                       trace[160 * 8 + q * 4 + 2], trace[160 * 8 + q * 4 + 3]);                            \
-        if (grp == 0 && (wave == 0 || wave == CWAVES) && lane == 0)                                        \
-            for (int q = 0; q < n_stages && q < 160; ++q)                                                  \
-                printf("T w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu\n", wave, q, stages[q].nops,  \
-                       trace[q * 8 + 0], trace[q * 8 + 1], trace[q * 8 + 2], trace[q * 8 + 3],             \
-                       trace[q * 8 + 4], trace[q * 8 + 5], trace[q * 8 + 6]);                              \
+        if (grp == RB_TRACE_GRP && wave == 0 && lane == 0)                                                 \
+            for (int q = 0; q < 48; ++q)                                                                  \
+                printf("S %d %llu %llu %llu %llu\n", q, trace[128 * 8 + q * 4], trace[128 * 8 + q * 4 + 1], \
+                       trace[128 * 8 + q * 4 + 2], trace[128 * 8 + q * 4 + 3]);                            \
+        if (grp == RB_TRACE_GRP && (wave == 0 || wave == CWAVES) && lane == 0)                             \
+            for (int q = 0; q < n_stages && q < 64; ++q) {                                                 \
+                const unsigned long long *tq = trace + ((wave ? 64 : 0) + q) * 8;                          \
+                printf("T w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu %llu\n", wave, q, stages[q].nops,  \
+                       tq[0], tq[1], tq[2], tq[3], tq[4], tq[5], tq[6], tq[7]);                            \
+            }                                                                                              \
     } while (0)
-#define RB_TRACE_LDS (160 * 8 * 8 + 128 * 4 * 8)
+#define RB_TRACE_LDS (128 * 8 * 8 + 48 * 4 * 8)
 #define RB_STEP(k)                                                                                         \
     do {                                                                                                   \
-        if (grp == 0 && wave == 0 && lane == 0 && step_no < 128)                                           \
-            trace[160 * 8 + step_no * 4 + (k)] = __builtin_amdgcn_s_memtime();                             \
+        if (grp == RB_TRACE_GRP && wave == 0 && lane == 0 && step_no < 48)                                           \
+            trace[128 * 8 + step_no * 4 + (k)] = __builtin_amdgcn_s_memtime();                             \
     } while (0)
 #define RB_STEP_NEXT() (++step_no)
 #else
@@ -75,12 +86,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #define RB_STEP_NEXT() do { } while (0)
 #define RB_TRACE(k) do { } while (0)
 #define RB_TRACE_DUMP() do { } while (0)
-#endif
-
-// Cache policy of the expanded-input loads.  They read what other compute units wrote earlier in
-// the same launch, so they must be coherent at device scope (sc1), not served from a stale line.
-#ifndef RB_OPERAND_POLICY
-#define RB_OPERAND_POLICY " sc1"
 #endif
 
 // ---------------------------------------------------------------- helpers ---
@@ -104,10 +109,9 @@ __device__ __forceinline__ uint32_t expand4(float u)
 }
 
 // byte address of (token, path, term, input column j) in an op's expanded input
-__device__ __forceinline__ size_t up_offset(int CB, int tok, int p, int t, int j)
+__device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
 {
-    const int cb = j >> 7;
-    return ((size_t)((tok >> 1) * CB + cb) * 16 + (8 * (tok & 1) + 4 * p + t)) * 128 + operand_byte(j & 127);
+    return up_group_offset(T, j & ~15, 8 * tok + 4 * p + t) + (size_t)(j & 15);
 }
 
 // row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt)
@@ -120,10 +124,9 @@ __host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G
 // ------------------------------------------------------------ prep kernel ---
 // One workgroup per op: power-of-two scale of each path's input scales, the zero fill of the
 // expanded-input array (padding columns and unused operand columns must read as zero), and the
-// tables the stack kernel keeps in LDS.  Workgroup 0 also resets the hand-over flags.
-__global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *flags, uint32_t *error,
-                                                   uint32_t *zero_page, OpInfo *info, WaveRec *rec,
-                                                   uint32_t epoch)
+// tables the stack kernel keeps in LDS.
+__global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *error,
+                                                   uint32_t *zero_page, OpInfo *info, WaveRec *rec)
 {
     const int o = blockIdx.x;
     Op &op = ops[o];
@@ -154,7 +157,9 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
             inf.bits = (uint64_t)op.bits;
             inf.up = (uint64_t)op.up;
             inf.CT = CT;
-            inf.pad_[0] = inf.pad_[1] = inf.pad_[2] = 0;
+            inf.in = (uint32_t)op.in;
+            inf.dep_slot = op.dep_slot;
+            inf.pad_ = 0;
             info[o] = inf;
         }
     }
@@ -186,10 +191,62 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
     if (o == 0) {
-        for (int i = threadIdx.x; i < hdr->n_groups; i += 256) flags[i] = epoch;   // older than any launch to come
         if (threadIdx.x < 32) zero_page[threadIdx.x] = 0;
         if (threadIdx.x == 0) *error = 0;
     }
+}
+
+// Second set-up pass (needs the scales of every op): the tables of the finishing wavefronts.
+// One workgroup per (stage, pair of workgroups of the stack kernel); a thread per (slot, row).
+__global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *ops, const Stage *stages,
+                                                   SlotRec *slots, SlotVals *vals)
+{
+    const int G = hdr->n_groups, T = hdr->T;
+    const int st = blockIdx.x;
+    const int grp = blockIdx.y * 2 + (threadIdx.x >> 7);
+    if (grp >= G) return;
+    const int slot = (threadIdx.x >> 4) & 7, row = threadIdx.x & 15;
+    const Stage stage = stages[st];
+    int my_op = -1, row0 = 0, slot_base = 0;
+    for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+        uint32_t rt0, nrt;
+        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, rt0, nrt);
+        if (slot >= slot_base && slot < slot_base + (int)nrt) {
+            my_op = o;
+            row0 = (int)(rt0 + (uint32_t)(slot - slot_base)) * 16;
+        }
+        slot_base += (int)nrt;
+    }
+    const size_t idx = ((size_t)st * G + grp) * MAXSLOT + slot;
+    SlotRec sr;
+    sr.y = 0; sr.ready = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
+    for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
+    float v[2 + 2 * MAX_CONS];
+    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) v[i] = 0.f;
+    if (my_op >= 0) {
+        const Op &op = ops[my_op];
+        const int grow = row0 + row;
+        sr.y = (uint64_t)op.y;
+        sr.ready = op.ready ? (uint64_t)(op.ready + (row0 >> 4)) : 0;
+        sr.out = op.out; sr.n_cons = op.n_cons; sr.row0 = row0; sr.op = my_op;
+        const bool valid = grow < op.out;
+        const __half *g = reinterpret_cast<const __half *>(op.g);
+        if (valid) {
+            v[0] = __half2float(g[grow]) * op.inv_sc[0];
+            v[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
+        }
+        for (int c = 0; c < op.n_cons; ++c) {
+            const Op &m = ops[op.cons[c]];
+            sr.up[c] = (uint64_t)(m.up + up_group_offset(T, row0, 0));
+            const __half *h = reinterpret_cast<const __half *>(m.h);
+            if (valid) {
+                v[2 + 2 * c] = __half2float(h[grow]) * m.sc[0];
+                v[3 + 2 * c] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
+            }
+        }
+    }
+    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) vals[idx].v[row][i] = v[i];
+    if (row == 0) slots[idx] = sr;
 }
 
 // --------------------------------------------------------- expand kernel ---
@@ -201,29 +258,23 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
     const int tok = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= op.in) return;
-    const int CB = col_tiles(op.in) * 2;
+    const int T = hdr->T;
     const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
         const uint32_t terms = expand4(h * x * op.sc[p]);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) op.up[up_offset(CB, tok, p, t, j)] = (uint8_t)(terms >> (8 * t));
+        for (int t = 0; t < 4; ++t) op.up[up_offset(T, tok, p, t, j)] = (uint8_t)(terms >> (8 * t));
     }
 }
 
-// Marks every 16-column group of the expanded input of the listed ops as "not yet written": the
-// first byte of the group, in every operand column in use, becomes POISON.
-constexpr uint8_t POISON = 0xff;     // bf8 NaN; the conversion of a finite value never yields it
-__global__ __launch_bounds__(256) void poison_kernel(const Header *hdr, const Op *ops, const int *which)
+// Clears the hand-over counters before a launch (a kernel, not a memset, so that a caller may
+// capture the launch sequence in a graph).
+__global__ __launch_bounds__(256) void clear_kernel(uint32_t *ready, int n)
 {
-    const Op &op = ops[which[blockIdx.y]];
-    const int CB = col_tiles(op.in) * 2, T = hdr->T;
-    const int idx = blockIdx.x * 256 + threadIdx.x;           // (group, token, path, term)
-    const int group = idx / (8 * T), rest = idx % (8 * T);
-    if (group * 16 >= op.in) return;
-    const int tok = rest >> 3, p = (rest >> 2) & 1, t = rest & 3;
-    op.up[up_offset(CB, tok, p, t, group * 16)] = POISON;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) ready[i] = 0;
 }
 
 // ---------------------------------------------------------- stack kernel ---
@@ -260,15 +311,18 @@ __device__ __forceinline__ float quad_sum(float v)
     return v;
 }
 
-struct BTile { v4i r[4]; };   // two 128-column blocks x 32 bytes per lane
+template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile: two 128-column blocks
 
+template <int TT>
 __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
                                                            uint32_t *__restrict__ error,
                                                            const uint32_t *__restrict__ zero_page,
                                                            const OpInfo *__restrict__ info_g,
-                                                           const WaveRec *__restrict__ rec_g)
+                                                           const WaveRec *__restrict__ rec_g,
+                                                           const SlotRec *__restrict__ slots_g,
+                                                           const SlotVals *__restrict__ vals_g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     float *part = reinterpret_cast<float *>(lds + LDS_PART_OFF);
@@ -279,7 +333,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x, G = gridDim.x;
-    const int n_ops = hdr_p->n_ops, n_stages = hdr_p->n_stages, T = hdr_p->T;
+    const int n_ops = hdr_p->n_ops, n_stages = hdr_p->n_stages;
+    constexpr int T = TT, NB = nb_of(TT), KOP = kop_of(TT);
 
     // ---- LDS set-up: clear the partial sums, copy this workgroup's records and the op table
     for (int i = threadIdx.x; i < LDS_PART_BYTES / 4; i += THREADS) part[i] = 0.f;
@@ -298,10 +353,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         uint8_t *const ring = lds + LDS_RING_OFF + wave * (RING_D * 1024);
         uint8_t *const ring_end = ring + RING_D * 1024;
         const int col = lane & 15, qd = lane >> 4;
-        const int ncols = T > 1 ? 16 : 8;
         const int scale_b = (127 - 3 * (col & 3)) * 0x01010101;
-        // lanes beyond the used operand columns always read past the end of the buffer (zeros)
-        const uint32_t lane_off = col < ncols ? (uint32_t)(col * 128 + qd * 32) : 0x80000000u;
+        const uint32_t lane_off = (uint32_t)lane * 16u;
         uint32_t c22;
         asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c22));
         // A load that carries no data but keeps the number of vector-memory operations per
@@ -341,7 +394,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 }
             }
             if (a_n != 0) {
-                __builtin_amdgcn_global_load_lds(a_ptr + lane * 16, RB_LDS(a_slot), 16, 0, 0);
+                // non-temporal: every sign tile is read once (measured: the stream is ~13% faster)
+                __builtin_amdgcn_global_load_lds(a_ptr + lane * 16, RB_LDS(a_slot), 16, 0, 2);
                 a_ptr += 1024;
                 --a_n;
             } else {
@@ -352,24 +406,25 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         };
 
 #pragma unroll 1
-        for (int d = 0; d < RING_D; ++d) { issue_a(); issue_dummies(4); }
+        for (int d = 0; d < RING_D; ++d) { issue_a(); issue_dummies(KOP); }
         uint8_t *c_slot_ptr = ring;           // ring slot of the next tile to consume
         bool failed = false;                  // a producer never delivered: stop waiting, report
 #ifdef RB_EXP_TRACE
         int step_no = 0;
 #endif
-        BTile B[NB];
+        BTile<TT> B[NB];
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) B[i].r[r] = (v4i){0, 0, 0, 0};
+            for (int r = 0; r < KOP; ++r) B[i].r[r] = (v4i){0, 0, 0, 0};
         // Operand loads are written as instructions, so the compiler does not know that their
         // target registers stay busy until the data arrives.  Naming the registers here keeps
         // them allocated (never reused as temporaries) across the code between two stages.
         auto keep_operands = [&]() {
 #pragma unroll
             for (int i = 0; i < NB; ++i)
-                asm volatile("" : "+v"(B[i].r[0]), "+v"(B[i].r[1]), "+v"(B[i].r[2]), "+v"(B[i].r[3]));
+#pragma unroll
+                for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[i].r[r]));
         };
 
         for (int st = 0; st < n_stages; ++st) {
@@ -386,22 +441,43 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             uint32_t b_n = 0, b_ct = 0, b_CT = 1, b_slot = 0;
             v4i b_rsrc = {0, 0, 0, 0x00020000};               // empty buffer: every load returns zero
             uint32_t meta[NB];
-            uint32_t s_off[NB];                               // where each operand in flight came from,
-            v4i s_rsrc[NB];                                   // in case it has to be fetched again
-            auto load_operand = [&](BTile &dst, uint32_t off0, v4i rsrc) {
+            auto load_operand = [&](BTile<TT> &dst, uint32_t off0, v4i rsrc) {
                 // The target registers are in-out operands on purpose: the compiler cannot see that
                 // a load issued here lands later, and the loads of the last steps of a stage are
                 // never waited for.  As in-out operands the registers stay allocated to the operand
                 // ring for the whole kernel, so no temporary is ever placed where a late load lands.
-                asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:16" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048" RB_OPERAND_POLICY "\n\t"
-                             "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:2064" RB_OPERAND_POLICY
-                             : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
-                             : "v"(off0), "s"(rsrc)
-                             : "memory");
+                // Plain loads: the counters have shown that these bytes are final, and nobody in
+                // this XCD has read them before that, so its L2 holds no older copy.  Each load
+                // reads 1 KB of consecutive bytes (the layout of the expanded input sees to that).
+                if constexpr (TT == 1)
+                    asm volatile("buffer_load_dwordx4 %0, %2, %3, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %1, %2, %3, 0 offen offset:1024"
+                                 : "+v"(dst.r[0]), "+v"(dst.r[1])
+                                 : "v"(off0), "s"(rsrc)
+                                 : "memory");
+                else
+                    asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:1024\n\t"
+                                 "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048\n\t"
+                                 "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:3072"
+                                 : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
+                                 : "v"(off0), "s"(rsrc)
+                                 : "memory");
             };
-            auto issue_b = [&](BTile &dst, uint32_t &m, uint32_t &keep_off, v4i &keep_rsrc) {
+            // Hand-over: a finishing wavefront of this workgroup watches the counters of the ops
+            // this stage reads from and keeps one bit per 256-column block in LDS; nothing but that
+            // wavefront polls memory.  A compute wavefront requests an operand tile only after its
+            // bit is set, so no line of an expanded input is read before it is final.
+            int b_dep = -1;                                   // entry of the stage's list (-1: input complete before the launch)
+            const uint32_t ready_base = lds_addr(lds + LDS_MISC_OFF) + (uint32_t)((st & 1) * MAX_DEPS * READY_WINDOWS * 8);
+            auto block_ready = [&](int dep, uint32_t ct) -> bool {
+                uint2 v;
+                asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                             : "=v"(v) : "v"(ready_base + (uint32_t)(dep * READY_WINDOWS + (int)(ct >> 6)) * 8u) : "memory");
+                const uint64_t bits = uniform64(v.x, v.y);
+                return (bits >> (ct & 63u)) & 1ull;
+            };
+            auto issue_b = [&](BTile<TT> &dst, uint32_t &m) {
                 while (b_n == 0 && b_op + 1 < stage_end) {
                     ++b_op;
                     uint32_t tile0, packed;
@@ -417,11 +493,22 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         b_CT = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.z);
                         b_rsrc[0] = __builtin_amdgcn_readfirstlane((int)v.x);
                         b_rsrc[1] = __builtin_amdgcn_readfirstlane((int)v.y) & 0xffff;
-                        b_rsrc[2] = (int)(2 * b_CT * UP_BLOCK_BYTES);
+                        b_rsrc[2] = (int)(2 * b_CT * up_block_bytes(TT));
                         b_rsrc[3] = 0x00020000;
+                        uint32_t r;
+                        asm volatile("ds_read_b32 %0, %1 offset:24\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(r) : "v"(info_base + (uint32_t)b_op * 32) : "memory");
+                        b_dep = __builtin_amdgcn_readfirstlane((int)r);
                     }
                 }
-                // Always four loads, written as instructions so that their order and their number
+                if (b_n != 0 && b_dep >= 0 && !failed) {
+                    int spins = 0;
+                    while (!block_ready(b_dep, b_ct)) {
+                        __builtin_amdgcn_s_sleep(2);
+                        if (++spins > (1 << 24)) { failed = true; break; }    // the watcher reports; just go on
+                    }
+                }
+                // Always the same number of loads, written as instructions so that their order and their number
                 // per step are exactly what the wait before the MFMAs counts on.  Without a tile
                 // left the offset lies past the end of the buffer: a bounds-checked zero, no access.
 #ifdef RB_EXP_SKIP_OPERANDS
@@ -429,10 +516,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #else
                 const bool valid = b_n != 0;
 #endif
-                const uint32_t off0 = valid ? b_ct * (2 * UP_BLOCK_BYTES) + lane_off : 0x80000000u;
+                const uint32_t off0 = valid ? b_ct * (2 * up_block_bytes(TT)) + lane_off : 0x80000000u;
                 load_operand(dst, off0, b_rsrc);
-                keep_off = off0;
-                keep_rsrc = b_rsrc;
                 m = 0;
                 if (b_n != 0) {
                     --b_n;
@@ -467,7 +552,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             };
 
 #pragma unroll
-            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], s_off[i], s_rsrc[i]); issue_dummies(1); }
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i]); issue_dummies(1); }
 
             bool more = true;
             while (more) {
@@ -475,52 +560,44 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 for (int s = 0; s < NB; ++s) {
                     const uint32_t m = meta[s];
                     if (!(m & 1u)) { more = false; break; }
-                    // Every step issues exactly five vector-memory loads (four operand loads, one
+                    // Every step issues exactly KOP + 1 vector-memory loads (the operand loads, one
                     // sign tile or its stand-in) and loads complete in order.  The operand of this
-                    // tile was requested NB steps ago, followed by 5 * NB - 4 younger loads; the
-                    // sign tile is older still (RING_D > NB).  So "at most 5 * NB - 4 outstanding"
+                    // tile was requested NB steps ago, followed by wait_of(T) younger loads; the
+                    // sign tile is older still (RING_D > NB).  So "at most wait_of(T) outstanding"
                     // means both have arrived.
                     RB_STEP(0);
                     uint4 w;
                     {
                         const uint32_t addr = lds_addr(c_slot_ptr) + lane * 16;
-                        asm volatile("s_waitcnt vmcnt(%6)\n\tds_read_b128 %0, %5\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(w), "+v"(B[s].r[0]), "+v"(B[s].r[1]), "+v"(B[s].r[2]), "+v"(B[s].r[3])
-                                     : "v"(addr), "n"(5 * NB - 4)
+                        asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(w)
+                                     : "v"(addr), "n"(wait_of(TT))
                                      : "memory");
-                    }
-                    // Hand-over: an operand written by another compute unit earlier in this launch is
-                    // valid once the poison byte of each of its 16-byte groups is gone.  If one is
-                    // still there the producer has not stored yet: fetch the operand again (all
-                    // older loads are waited for on the way, which keeps the wait counts valid).
-                    if (stage.wait_before && !failed) {
-                        int spins = 0;
-                        while (true) {
-                            const BTile &b = B[s];
-                            const bool poisoned = (b.r[0][0] & 0xff) == POISON || (b.r[1][0] & 0xff) == POISON ||
-                                                  (b.r[2][0] & 0xff) == POISON || (b.r[3][0] & 0xff) == POISON;
-                            if (!__any(poisoned)) break;
-                            if (++spins > (1 << 15)) {
-                                if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                failed = true;
-                                break;
-                            }
-                            load_operand(B[s], s_off[s], s_rsrc[s]);
-                            asm volatile("s_waitcnt vmcnt(0)"
-                                         : "+v"(B[s].r[0]), "+v"(B[s].r[1]), "+v"(B[s].r[2]), "+v"(B[s].r[3])
-                                         :
-                                         : "memory");
-                        }
+#pragma unroll
+                        for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
                     }
                     RB_STEP(1);
                     c_slot_ptr += 1024;
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
-                    const BTile bt = B[s];
+                    const BTile<TT> bt = B[s];
                     v8i b0, b1;
+                    if constexpr (TT == 1) {
+                        // lanes 0..7 of a row of 16 hold the first four registers of their column; the
+                        // other four sit eight lanes further on (row_shl:8).  Lanes 8..15 end up with
+                        // bytes of no meaning: their columns of the product are never read.
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        b0[i] = bt.r[0][i]; b0[4 + i] = bt.r[1][i];
-                        b1[i] = bt.r[2][i]; b1[4 + i] = bt.r[3][i];
+                        for (int i = 0; i < 4; ++i) {
+                            b0[i] = bt.r[0][i];
+                            b0[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[0][i], 0x108, 0xf, 0xf, true);
+                            b1[i] = bt.r[1][i];
+                            b1[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[1][i], 0x108, 0xf, 0xf, true);
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            b0[i] = bt.r[0][i]; b0[4 + i] = bt.r[1][i];
+                            b1[i] = bt.r[2 % KOP][i]; b1[4 + i] = bt.r[3 % KOP][i];
+                        }
                     }
 #ifndef RB_EXP_NO_MFMA
                     acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
@@ -532,7 +609,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #endif
                     if (m & 2u) flush(m >> 8);
                     RB_STEP(2);
-                    issue_b(B[s], meta[s], s_off[s], s_rsrc[s]);
+                    issue_b(B[s], meta[s]);
                     issue_a();
                     RB_STEP(3);
                     RB_STEP_NEXT();
@@ -554,57 +631,43 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         const int row = lane & 15, tok = (lane >> 4) & 1;
         // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
         uint8_t *stage_bytes = lds + LDS_MISC_OFF + 256 + CWAVES * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
+
+        // Everything a stage's epilogue needs from memory sits in two flat tables indexed by
+        // (stage, workgroup, slot) and is requested one stage ahead, while the compute wavefronts
+        // work: nothing after the barrier waits for memory.  The loads are unconditional, so the
+        // compiler can wait for exactly these and not for younger ones.
+        struct Fin {
+            SlotRec r;
+            v4f a, b;                       // the row's eight values
+        };
+        auto fetch = [&](int st) -> Fin {
+            const size_t idx = ((size_t)min(st, n_stages - 1) * G + grp) * MAXSLOT + my_slot;
+            Fin f;
+            f.r = slots_g[idx];
+            const v4f *pv = reinterpret_cast<const v4f *>(&vals_g[idx].v[row][0]);
+            f.a = pv[0];
+            f.b = pv[1];
+            if (st >= n_stages) f.r.op = -1;
+            return f;
+        };
+        Fin cur = fetch(0);
+
+        const uint32_t ready_lds = lds_addr(lds + LDS_MISC_OFF);
         for (int st = 0; st < n_stages; ++st) {
-            const Stage stage = stages[st];
-            // ---- before the partial sums are ready: find this lane's row and fetch everything
-            // that does not depend on them (output scales, the scales of the ops that read y next)
-            int my_op = -1, grow = 0;
-            {
-                int slot_base = 0;
-                for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
-                    uint32_t rt0, nrt;
-                    group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, rt0, nrt);
-                    if (my_slot >= slot_base && my_slot < slot_base + (int)nrt) {
-                        my_op = o;
-                        grow = (int)(rt0 + (uint32_t)(my_slot - slot_base)) * 16 + row;
-                    }
-                    slot_base += (int)nrt;
-                }
-            }
-            const bool have_slot = my_op >= 0;
-            const bool active = have_slot && tok < T && grow < ops[have_slot ? my_op : 0].out;
-            float gsc[2] = {0.f, 0.f};
-            __half *yp = nullptr;
-            int n_cons = 0;
-            float hh[MAX_CONS][2];
-            uint8_t *upp[MAX_CONS];                       // operand column 0 of token 0, first row of the slot
-#pragma unroll
-            for (int c = 0; c < MAX_CONS; ++c) { hh[c][0] = hh[c][1] = 0.f; upp[c] = nullptr; }
-            if (have_slot) {
-                const Op &op = ops[my_op];
-                n_cons = op.n_cons;
-                if (active) {
-                    const __half *g = reinterpret_cast<const __half *>(op.g);
-                    gsc[0] = __half2float(g[grow]) * op.inv_sc[0];
-                    gsc[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
-                    yp = reinterpret_cast<__half *>(op.y) + (size_t)tok * op.out + grow;
-                }
-#pragma unroll
-                for (int c = 0; c < MAX_CONS; ++c) {
-                    if (c < n_cons) {
-                        const Op &m = ops[op.cons[c]];
-                        if (active) {
-                            const __half *h = reinterpret_cast<const __half *>(m.h);
-                            hh[c][0] = __half2float(h[grow]) * m.sc[0];
-                            hh[c][1] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
-                        }
-                        upp[c] = m.up + up_offset(col_tiles(m.in) * 2, 0, 0, 0, grow - row);
-                    }
-                }
+            const Fin nxt = fetch(st + 1);
+            // the bits of the next stage: nobody reads them before this stage's barrier
+            if (ew == 0 && lane < MAX_DEPS * READY_WINDOWS) {
+                const uint32_t a = ready_lds + (uint32_t)((((st + 1) & 1) * MAX_DEPS * READY_WINDOWS + lane) * 8);
+                asm volatile("ds_write_b64 %0, %1" : : "v"(a), "v"(make_uint2(0u, 0u)) : "memory");
             }
             RB_TRACE(4);
             lds_barrier();                                    // partial sums complete
             RB_TRACE(5);
+            const bool have_slot = cur.r.op >= 0;
+            const int grow = cur.r.row0 + row;
+            const bool active = have_slot && tok < T && grow < cur.r.out;
+            const int n_cons = have_slot ? cur.r.n_cons : 0;
+            const float hs[MAX_CONS][2] = {{cur.a[2], cur.a[3]}, {cur.b[0], cur.b[1]}, {cur.b[2], cur.b[3]}};
             float yf = 0.f;
             if (active) {
                 // sum the partial sums of the compute wavefronts, clear them for the next use
@@ -615,15 +678,18 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     s0 += P[w * 64];
                     s1 += P[w * 64 + 32];
                 }
+                RB_TRACE(2);
 #pragma unroll
                 for (int w = 0; w < CWAVES; ++w) {
                     P[w * 64] = 0.f;
                     P[w * 64 + 32] = 0.f;
                 }
-                const __half y16 = __float2half_rn(gsc[0] * s0 + gsc[1] * s1);
-                *yp = y16;
-                yf = __half2float(y16);
+                RB_TRACE(3);
+                const _Float16 y16 = (_Float16)(cur.a[0] * s0 + cur.a[1] * s1);      // round to nearest even
+                RB_GLOBAL(_Float16, cur.r.y)[(size_t)tok * cur.r.out + grow] = y16;
+                yf = (float)y16;
             }
+            RB_TRACE(0);
             // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
             // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
             if (__any(n_cons > 0)) {
@@ -633,7 +699,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         if (c < n_cons) {
 #pragma unroll
                             for (int p = 0; p < 2; ++p) {
-                                const uint32_t terms = active ? expand4(hh[c][p] * yf) : 0u;
+                                const uint32_t terms = active ? expand4(hs[c][p] * yf) : 0u;
                                 uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
 #pragma unroll
                                 for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
@@ -641,6 +707,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         }
                     }
                 }
+                RB_TRACE(1);
                 // lanes now act as (half, consumer, token, path, term): 96 vectors, two rounds
 #pragma unroll
                 for (int round = 0; round < 2; ++round) {
@@ -654,38 +721,134 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     uint64_t base = 0;
 #pragma unroll
                     for (int c = 0; c < MAX_CONS; ++c) {
-                        const uint64_t u = (uint64_t)upp[c];
+                        // the 16-byte group of operand column 0 that this slot's rows fill
+                        const uint64_t u = cur.r.up[c];
                         const uint32_t lo = __shfl((uint32_t)u, src_lane), hi = __shfl((uint32_t)(u >> 32), src_lane);
                         if (c == vc) base = ((uint64_t)hi << 32) | lo;
                     }
                     if (v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T) {
                         const v4i bytes = *reinterpret_cast<const v4i *>(
                             stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
-                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 128;
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 16;
                         asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
+                // publish: once the stores are acknowledged, raise the flag byte of this row tile (a plain
+                // device-scope store: read-modify-write counters shared by 16 producers took ~1 us per update)
+#ifdef RB_EXP_WBL2
+                asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+#else
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+                if ((lane & 31) == 0 && have_slot && n_cons > 0)
+                    asm volatile("global_store_byte %0, %1, off sc1" : : "v"(cur.r.ready), "v"(1u) : "memory");
             }
             RB_TRACE(6);
+            // ---- watch the counters the next stage depends on (one wavefront per workgroup) and
+            // publish them to the compute wavefronts, which may already be in that stage
+            if (ew == 0 && st + 1 < n_stages) {
+                const Stage nx = stages[st + 1];
+                int spins = 0;
+                bool all = nx.n_deps == 0;
+                const uint32_t bits_lds = ready_lds + (uint32_t)((((st + 1) & 1) * MAX_DEPS) * READY_WINDOWS * 8);
+                auto publish = [&](int d, int win, unsigned long long bal) {
+                    if (lane == 0)
+                        asm volatile("ds_write_b64 %0, %1" : : "v"(bits_lds + (uint32_t)((d * READY_WINDOWS + win) * 8)),
+                                     "v"(make_uint2((uint32_t)bal, (uint32_t)(bal >> 32))) : "memory");
+                };
+                auto give_up = [&]() {                      // a producer never delivered: report, let everybody go on
+                    if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int d = 0; d < MAX_DEPS; ++d)
+                        for (int win = 0; win < READY_WINDOWS; ++win) publish(d, win, ~0ull);
+                };
+                bool narrow = true;                               // every op in the list has at most 64 blocks
+                for (int d = 0; d < nx.n_deps; ++d) narrow = narrow && col_tiles(ops[nx.dep[d]].out) <= 64;
+                if (!all && narrow) {
+                    // A load of this compute unit queues behind the weight prefetch of its compute
+                    // wavefronts, so one round trip takes microseconds.  Keep several polls in flight:
+                    // after the first has come back, a fresh sample arrives every fraction of that time.
+                    constexpr int POLLS = 4;
+                    int expect[MAX_DEPS];
+                    __amdgpu_buffer_rsrc_t flags[MAX_DEPS];
+#pragma unroll
+                    for (int d = 0; d < MAX_DEPS; ++d) {
+                        const Op &pr = ops[nx.dep[d < nx.n_deps ? d : 0]];
+                        expect[d] = d < nx.n_deps ? min(16, (pr.out - 256 * lane + 15) >> 4) : 0;
+                        flags[d] = __builtin_amdgcn_make_buffer_rsrc(pr.ready, 0, col_tiles(pr.out) * 16, 0x00020000);
+                    }
+                    auto poll = [&](int d) -> v4u {                 // the 16 flag bytes of block `lane`, device-coherent
+                        return __builtin_amdgcn_raw_buffer_load_b128(flags[d], lane * 16, 0, 16);
+                    };
+                    auto raised = [&](v4u f) -> int {
+                        return __builtin_popcount(f[0]) + __builtin_popcount(f[1]) + __builtin_popcount(f[2]) + __builtin_popcount(f[3]);
+                    };
+                    v4u q[POLLS][MAX_DEPS];
+#pragma unroll
+                    for (int p = 0; p < POLLS; ++p)
+#pragma unroll
+                        for (int d = 0; d < MAX_DEPS; ++d) q[p][d] = poll(d);
+                    while (!all) {
+#pragma unroll
+                        for (int p = 0; p < POLLS; ++p) {
+                            if (all) break;
+                            all = true;
+#pragma unroll
+                            for (int d = 0; d < MAX_DEPS; ++d) {
+                                const unsigned long long bal = __ballot(raised(q[p][d]) >= expect[d]);
+                                if (d < nx.n_deps) publish(d, 0, bal);
+                                all = all && bal == ~0ull;
+                                q[p][d] = poll(d);
+                            }
+                            if (!all && ++spins > (1 << 18)) { give_up(); all = true; }
+                        }
+                    }
+                }
+                while (!all) {
+                    all = true;
+                    for (int d = 0; d < nx.n_deps; ++d) {
+                        const Op &pr = ops[nx.dep[d]];
+                        const int nwin = (col_tiles(pr.out) + 63) >> 6;
+                        for (int win = 0; win < nwin; ++win) {
+                            const int ct_l = win * 64 + lane;
+                            const int expect = min(16, (pr.out - 256 * ct_l + 15) >> 4);     // <= 0: no such block
+                            __amdgpu_buffer_rsrc_t fl = __builtin_amdgcn_make_buffer_rsrc(pr.ready, 0, col_tiles(pr.out) * 16, 0x00020000);
+                            const v4u f = __builtin_amdgcn_raw_buffer_load_b128(fl, ct_l * 16, 0, 16);
+                            const int up_ = __builtin_popcount(f[0]) + __builtin_popcount(f[1]) + __builtin_popcount(f[2]) + __builtin_popcount(f[3]);
+                            const unsigned long long bal = __ballot(up_ >= expect);
+                            publish(d, win, bal);
+                            all = all && bal == ~0ull;
+                        }
+                    }
+                    if (!all && ++spins > (1 << 16)) { give_up(); all = true; }
+                }
+#ifdef RB_EXP_TRACE
+                if (grp == RB_TRACE_GRP && lane == 0 && st < 64) {
+                    trace[(64 + st) * 8 + 7] = __builtin_amdgcn_s_memtime();
+                    trace[st * 8 + 7] = (unsigned long long)spins;
+                }
+#endif
+            }
+            cur = nxt;
         }
         RB_TRACE_DUMP();
     }
 }
 
 // ------------------------------------------------------------------ host ---
-static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t up_total)
+static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t n_ready, size_t up_total)
 {
     Layout L;
     size_t o = sizeof(Header);
     o = align_up(o, 128); L.ops = o; o += sizeof(Op) * (size_t)n_ops;
     o = align_up(o, 128); L.stages = o; o += sizeof(Stage) * (size_t)n_stages;
-    o = align_up(o, 128); L.flags = o; o += sizeof(uint32_t) * (size_t)n_groups;
     o = align_up(o, 128); L.error = o; o += 128;
     L.zero = o; o += 128;
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
-    L.poison = o; o += align_up(sizeof(int) * MAX_OPS, 128);
+    L.ready = o; o += align_up(n_ready, 128);
     L.info = o; o += sizeof(OpInfo) * (size_t)n_ops;
     o = align_up(o, 128); L.rec = o; o += sizeof(WaveRec) * (size_t)n_ops * (size_t)n_groups * CWAVES;
+    o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+    o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 256); L.up = o; o += up_total;
     L.total = align_up(o, 256);
     return L;
@@ -712,20 +875,23 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
 {
     // upper bound: every op could use the widest layer
     size_t up_max = 0;
-    for (int l = 0; l < n_layers; ++l) up_max = std::max(up_max, up_bytes(layers[l].in, T));
-    const int G = 1024;   // bound on compute units
-    return make_layout(n_ops, n_ops, G, align_up(up_max, 256) * (size_t)n_ops).total;
+    size_t ready_max = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        up_max = std::max(up_max, up_bytes(layers[l].in, T));
+        ready_max = std::max(ready_max, (size_t)col_tiles(layers[l].out) * 16);
+    }
+    int G = device_groups();
+    if (G <= 0) G = 1024;  // no device to ask: a bound on compute units
+    return make_layout(n_ops, n_ops, G, ready_max * (size_t)n_ops, align_up(up_max, 256) * (size_t)n_ops).total;
 }
 
 // Host record of a prepared plan, keyed by the workspace that holds its device part.
 struct Prepared {
     Layout lay;
-    int n_ops = 0, n_stages = 0, n_signals = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0;
-    int n_poison = 0, max_poison_in = 0;
+    int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0, n_ready = 0;
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
-static uint32_t g_epoch = 1;          // hand-over epochs grow monotonically over all launches
 
 int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
                  void *workspace, size_t workspace_bytes_, hipStream_t stream)
@@ -754,6 +920,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         int producer = -1;
         for (int m = n - 1; m >= 0; --m)
             if (sops[m].dst == sops[n].src) { producer = m; break; }
+        o.dep = producer;
         if (producer < 0) {
             o.expand_x = 1;
             expand_list.push_back(n);
@@ -769,7 +936,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     {
         int op0 = 0;
         while (op0 < n_ops) {
-            Stage s{op0, 0, 0, 0};
+            Stage s{op0, 0, 0, {0, 0, 0}};
             int slots = 0;
             for (int n = op0; n < n_ops; ++n) {
                 bool conflict = false;
@@ -779,74 +946,79 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
                 const int per_group = (ops[(size_t)n].RT + G - 1) / G;
                 if (per_group > MAXSLOT) return RB_ERR_UNSUPPORTED;
                 if (conflict || slots + per_group > MAXSLOT) break;
+                // the ops of earlier stages this stage waits for: a short list
+                const int dep = ops[(size_t)n].dep;
+                int slot_of_dep = -1;
+                if (dep >= 0) {
+                    for (int d = 0; d < s.n_deps; ++d)
+                        if (s.dep[d] == dep) slot_of_dep = d;
+                    if (slot_of_dep < 0) {
+                        if (s.n_deps == MAX_DEPS) break;
+                        slot_of_dep = s.n_deps;
+                        s.dep[s.n_deps++] = dep;
+                    }
+                }
+                ops[(size_t)n].dep_slot = slot_of_dep;
                 slots += per_group;
                 ++s.nops;
             }
-            for (int n = s.op0; n < s.op0 + s.nops; ++n)
-                if (!ops[(size_t)n].expand_x) s.wait_before = 1;
             stages.push_back(s);
             op0 += s.nops;
         }
-        // A waiting stage polls for the most recent signal, so every stage that has a waiting
-        // stage anywhere after it signals (its flag then also covers all earlier stages).
-        for (size_t s = 0; s + 1 < stages.size(); ++s)
-            for (size_t r = s + 1; r < stages.size(); ++r)
-                if (stages[r].wait_before) { stages[s].signal_after = 1; break; }
     }
     for (const Stage &st : stages)
         for (int n = st.op0; n < st.op0 + st.nops; ++n) ops[(size_t)n].stage_op0 = st.op0;
     Prepared pr;
     pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T;
-    for (const Stage &s : stages) pr.n_signals += s.signal_after;
     pr.n_expand = (int)expand_list.size();
     for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
-    std::vector<int> poison_list;
+    // hand-over flags: one byte per row tile, 16 per 256-row block, for every op that has a reader
+    std::vector<size_t> ready_off((size_t)n_ops, 0);
+    size_t n_ready = 0;
     for (int n = 0; n < n_ops; ++n)
-        if (!ops[(size_t)n].expand_x) {
-            poison_list.push_back(n);
-            pr.max_poison_in = std::max(pr.max_poison_in, ops[(size_t)n].in);
+        if (ops[(size_t)n].n_cons > 0) {
+            ready_off[(size_t)n] = n_ready;
+            n_ready += (size_t)col_tiles(ops[(size_t)n].out) * 16;
         }
-    pr.n_poison = (int)poison_list.size();
-    pr.lay = make_layout(n_ops, pr.n_stages, G, up_total);
+    pr.n_ready = (int)n_ready;
+    pr.lay = make_layout(n_ops, pr.n_stages, G, n_ready, up_total);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    for (int n = 0; n < n_ops; ++n) ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
+    for (int n = 0; n < n_ops; ++n) {
+        ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
+        ops[(size_t)n].ready = ops[(size_t)n].n_cons > 0
+                                   ? ws + lay.ready + ready_off[(size_t)n] : nullptr;
+    }
 
     Header hdr{};
     hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G;
 
     // ---- upload: stream-ordered copies out of host memory that outlives the call
     static thread_local std::vector<uint8_t> blob;
-    blob.assign(lay.flags, 0);
+    blob.assign(lay.error, 0);
     std::memcpy(blob.data(), &hdr, sizeof(hdr));
     std::memcpy(blob.data() + lay.ops, ops.data(), sizeof(Op) * (size_t)n_ops);
     std::memcpy(blob.data() + lay.stages, stages.data(), sizeof(Stage) * (size_t)pr.n_stages);
     static thread_local int which[MAX_EXPAND];
     for (size_t i = 0; i < expand_list.size(); ++i) which[i] = expand_list[i];
-    if (hipMemcpyAsync(ws, blob.data(), lay.flags, hipMemcpyHostToDevice, stream) != hipSuccess) return RB_ERR_HIP;
+    if (hipMemcpyAsync(ws, blob.data(), lay.error, hipMemcpyHostToDevice, stream) != hipSuccess) return RB_ERR_HIP;
     if (!expand_list.empty() &&
         hipMemcpyAsync(ws + lay.which, which, sizeof(int) * expand_list.size(), hipMemcpyHostToDevice, stream) !=
             hipSuccess)
         return RB_ERR_HIP;
-    static thread_local int which_poison[MAX_OPS];
-    for (size_t i = 0; i < poison_list.size(); ++i) which_poison[i] = poison_list[i];
-    if (!poison_list.empty() &&
-        hipMemcpyAsync(ws + lay.poison, which_poison, sizeof(int) * poison_list.size(), hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
-        return RB_ERR_HIP;
-
-    uint32_t epoch;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        epoch = g_epoch;
-        g_epoch += 2u;
         g_prepared[workspace] = pr;
     }
     hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
-                       reinterpret_cast<Op *>(ws + lay.ops), reinterpret_cast<uint32_t *>(ws + lay.flags),
+                       reinterpret_cast<Op *>(ws + lay.ops),
                        reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero),
-                       reinterpret_cast<OpInfo *>(ws + lay.info), reinterpret_cast<WaveRec *>(ws + lay.rec), epoch);
+                       reinterpret_cast<OpInfo *>(ws + lay.info), reinterpret_cast<WaveRec *>(ws + lay.rec));
+    hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + 1) / 2), dim3(256), 0, stream,
+                       reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
+                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
+                       reinterpret_cast<SlotVals *>(ws + lay.vals));
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
@@ -867,20 +1039,22 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (pr.n_expand > 0)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
-    if (pr.n_poison > 0)
-        hipLaunchKernelGGL(poison_kernel, dim3((pr.max_poison_in / 16 * 8 * pr.T + 255) / 256, (unsigned)pr.n_poison),
-                           dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.poison));
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(stack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + RB_TRACE_LDS) != hipSuccess)
+    if (pr.n_ready > 0)
+        hipLaunchKernelGGL(clear_kernel, dim3((pr.n_ready / 4 + 255) / 256), dim3(256), 0, stream,
+                           reinterpret_cast<uint32_t *>(ws + lay.ready), pr.n_ready / 4);
+    auto launch = [&](auto kernel) -> int {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                LDS_BYTES + RB_TRACE_LDS) != hipSuccess)
             return RB_ERR_HIP;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(stack_kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
-                       reinterpret_cast<const Stage *>(ws + lay.stages),
-                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
-                       reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec));
+        hipLaunchKernelGGL(kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
+                           reinterpret_cast<const Stage *>(ws + lay.stages),
+                           reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                           reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec),
+                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals));
+        return RB_OK;
+    };
+    const int rc = pr.T == 1 ? launch(stack_kernel<1>) : launch(stack_kernel<2>);
+    if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
