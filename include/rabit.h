@@ -165,11 +165,13 @@ int rb_stream_read_groups(void);
 
 /* Which kernel family the most recent compute call of this thread enqueued:
  * RB_PATH_NONE, RB_PATH_SIGNADD (generic sign-XOR + add kernel, one launch per
- * op) or RB_PATH_MX (matrix-core kernel, all ops of the call in one persistent
+ * op), RB_PATH_GEMM (many-token matrix-core GEMM, one launch per op) or
+ * RB_PATH_MX (matrix-core kernel, all ops of the call in one persistent
  * launch).  For tests and benchmarks that must know what they measured. */
 #define RB_PATH_NONE    0
 #define RB_PATH_SIGNADD 1
 #define RB_PATH_MX      2
+#define RB_PATH_GEMM    3
 int rb_last_path(void);
 
 /* Library version: major*10000 + minor*100 + patch. */

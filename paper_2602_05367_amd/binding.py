@@ -269,7 +269,7 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
     return sink
 
 
-RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX = 0, 1, 2
+RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM = 0, 1, 2, 3
 
 
 def rb_last_path() -> int:

@@ -11,7 +11,13 @@ void set_last_path(int path) { g_last_path = path; }
 
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
-    if (T > 2) return 0;
+    if (T > 2) {
+        // ops run one after the other on the caller's stream and share the scratch of the GEMM path
+        size_t need = 0;
+        for (int l = 0; l < n_layers; ++l)
+            if (gemm::supported(&layers[l], T)) need = need > gemm::workspace_bytes(&layers[l], T) ? need : gemm::workspace_bytes(&layers[l], T);
+        return need;
+    }
     return mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
 }
 
@@ -24,6 +30,10 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
         uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};
         const int rc = mx::run_plan(L, &op, 1, bufs, T, workspace, workspace_bytes, stream);
         if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_MX; return rc; }
+    }
+    if (T > 2 && gemm::supported(L, T) && workspace && workspace_bytes >= gemm::workspace_bytes(L, T)) {
+        g_last_path = RB_PATH_GEMM;
+        return gemm::launch(L, X, Y, T, act_dtype, out_dtype, workspace, stream);
     }
     g_last_path = RB_PATH_SIGNADD;
     return launch_signadd(L, X, Y, T, act_dtype, out_dtype, stream);

@@ -23,6 +23,14 @@ int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes,
                    hipStream_t stream);
 
+namespace gemm {
+// many-token matrix-core GEMM (K = 2): workspace holds the scaled input of both paths
+bool supported(const rb_layer *L, int T);
+size_t workspace_bytes(const rb_layer *L, int T);
+int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype, void *workspace,
+           hipStream_t stream);
+}  // namespace gemm
+
 namespace mx {
 // matrix-core path (K = 2, T <= 2): whole op lists run as one persistent kernel
 bool layer_supported(const rb_layer *L, int T);
