@@ -8,16 +8,25 @@
 //     bit of the weight), the right operand is U_k.  Both paths land in the same fp32 sum, so
 //     the path sum of Eq. (stacked binary weight) costs nothing;
 //   * the left operand never exists in memory: each wavefront turns the packed sign words of its
-//     rows into v_mfma_f32_16x16x32_f16 operand registers with two vector instructions per
+//     rows into v_mfma_f32_32x32x16_f16 operand registers with two vector instructions per
 //     register (shift so that two sign bits land on bits 15 and 31, then and-or with the packed
 //     pair of |g|).  Inside a group of 32 columns the order of the contraction index is free as
 //     long as both operands agree; the pre-pass stores U in the order this shift produces:
 //     position 2n + hi holds the column whose sign is native bit n + 16 * hi of the word;
-//   * the right operand goes through LDS (double buffered, one barrier per 32 columns), shared by
-//     the four wavefronts of a 256-row x 256-token workgroup tile; a wavefront owns 128 x 128 of
-//     it in 64 accumulator tiles.
+//   * the right operand goes through LDS, shared by the four wavefronts of a workgroup tile.  It
+//     is copied global -> LDS without passing through registers, three 32-column steps ahead,
+//     into a ring of four buffers with one barrier per step; rows are 64 bytes and the four
+//     16-byte chunks of a row are XOR-swizzled with the token index so that neither the copy nor
+//     the operand reads collide on LDS banks;
+//   * two tile shapes: 256 rows x 256 tokens (a wavefront owns 128 x 128 in sixteen 32 x 32
+//     accumulator tiles) for prefill, and 256 rows x 32 tokens for small batches, where the
+//     contraction is also split over workgroups (fp32 partial outputs in scratch, one more
+//     small kernel sums and rounds them) so that a 4096-row matrix still fills
+//     the chip.  Either way the packed weights are read once per block of tokens.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+
+#include <algorithm>
 
 #include "rabit.h"
 #include "rb_device.h"
@@ -29,10 +38,18 @@ namespace gemm {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
-constexpr int BLK = 256;            // rows and tokens of a workgroup tile
-constexpr int LDS_STRIDE = 40;      // halves per token row in LDS: 32 of data + 8 of padding (bank spread)
+// steps between the request of a right-operand tile and its use (the ring has one buffer more): a
+// step of the large tile takes about a microsecond, one of the small tile a tenth of that
+constexpr int AHEAD_LARGE = 3, AHEAD_SMALL = 15;
+constexpr int BLK_ROWS = 256;       // rows of a workgroup tile, both shapes
+constexpr int SMALL_TOKENS = 32, LARGE_TOKENS = 256;
+#define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+
+// which 16-byte position of its 64-byte LDS row chunk c of a token sits at: c ^ swizzle(token)
+__device__ __forceinline__ int swizzle(int token) { return ((token >> 1) ^ (token >> 3)) & 3; }
 
 __host__ __device__ inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
@@ -62,144 +79,314 @@ __global__ __launch_bounds__(256) void scale_kernel(const ActT *__restrict__ X, 
     }
 }
 
-// ----------------------------------------------------------------- GEMM ---
-__device__ __forceinline__ void lds_barrier()
+// split-contraction variant: sums the partial outputs of the `split` workgroups of a row block and
+// rounds to the output type
+__global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ part, void *__restrict__ Y, int out_dtype,
+                                                     size_t n, int split)
 {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < split; ++k) s += part[(size_t)k * n + i];
+    store_out(Y, out_dtype, i, s);
 }
 
-template <int OUT_DT>
+// ----------------------------------------------------------------- GEMM ---
+// "at most N vector-memory loads outstanding", then the workgroup barrier.  The immediate of
+// s_waitcnt on gfx9: vmcnt in bits 3:0 and 15:14, expcnt (no wait: 7) in 6:4, lgkmcnt (no wait: 15) in 11:8.
+template <int N>
+__device__ __forceinline__ void wait_copies_and_sync()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// WM x WN wavefronts (four in all); a wavefront owns MP row pairs (32 rows each) x NT token tiles
+// (32 tokens each).  The workgroup covers the column tiles gridDim.y deals it; with Acc given it
+// writes its partial sums to slice blockIdx.y of that fp32 scratch [gridDim.y][T][out] instead of
+// storing the output.
+template <int OUT_DT, int WM, int WN, int MP, int NT, int AHEAD>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bits, const __half *__restrict__ g,
                                                       const _Float16 *__restrict__ U, void *__restrict__ Y,
-                                                      int out, int RT, int CT, int T, int T_pad)
+                                                      float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad)
 {
-    __shared__ __attribute__((aligned(16))) _Float16 Bs[2][BLK * LDS_STRIDE];
+    static_assert(WM * WN == 4 && WM * MP * 32 == BLK_ROWS, "tile shape");
+    constexpr int BLK_TOK = WN * NT * 32;
+    constexpr int NBUF = AHEAD + 1;
+    constexpr int BUF_BYTES = BLK_TOK * 64;
+    constexpr int GROUPS = BLK_TOK / 16;                  // copies of 16 tokens (1 KB) that fill one buffer
+    constexpr int COPIES = GROUPS >= 4 ? GROUPS / 4 : 1;  // per wavefront and step (the same for all: the waits count them)
+    extern __shared__ __attribute__((aligned(16))) uint8_t Bs[];       // NBUF * BUF_BYTES, given at launch
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
-    const int r = lane & 15, kg = lane >> 4;
+    const int wm = wave % WM, wn = wave / WM;
+    const int r = lane & 15, half_sel = (lane >> 4) & 1, kg = lane >> 5;    // row in its tile, which of two row tiles, k group
     const int in_pad = CT * TILE_COLS;
     // workgroups that share a token block sit on the same XCD (ids are dealt round-robin over
     // eight of them), so the slice of U they all walk stays in that XCD's L2
-    const int TB = T_pad / BLK;
+    const int TB = T_pad / BLK_TOK;
     const int tb = blockIdx.x % TB, rb = blockIdx.x / TB;
+    const int rt_base = rb * (BLK_ROWS / TILE_ROWS) + wm * MP * 2;           // first row tile of this wavefront
+    // column tiles of this workgroup
+    const int ct_begin = (int)((long)CT * blockIdx.y / gridDim.y);
+    const int ct_end = (int)((long)CT * (blockIdx.y + 1) / gridDim.y);
 
     // ---- per-row constants: |g| as a packed pair, and whether the sign bits must be flipped
-    uint32_t G2[8][2], flip[8][2];
+    // flip[i]: for the row this lane holds sign words of (row tile i, row r); G2[m]: for the row this
+    // lane feeds to the matrix instruction (row pair m, row l % 32)
+    uint32_t G2[MP][2], flip[2 * MP][2];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = (rb * 16 + wm * 8 + i) * TILE_ROWS + r;
+    for (int i = 0; i < 2 * MP; ++i) {
+        const int row = (rt_base + i) * TILE_ROWS + r;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t gb = row < out ? (uint32_t)__half_as_ushort(g[(size_t)k * out + row]) : 0u;
+            flip[i][k] = (gb & 0x8000u) ? 0xffffffffu : 0u;
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+        const int row = (rt_base + 2 * m + half_sel) * TILE_ROWS + r;
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint32_t gb = row < out ? (uint32_t)__half_as_ushort(g[(size_t)k * out + row]) : 0u;
             const uint32_t mag = gb & 0x7fffu;
-            G2[i][k] = mag | (mag << 16);
-            flip[i][k] = (gb & 0x8000u) ? 0xffffffffu : 0u;
+            G2[m][k] = mag | (mag << 16);
         }
     }
-    // lane (r, kg) takes columns 8kg..8kg+7 of the step: register i gets native bits n and n + 16,
-    // n = 4kg + i, on bits 15 and 31
-    uint32_t sh[4];
+    // A 32 x 32 x 16 instruction covers half a step: lane (row l % 32, k group kg = l / 32) of half
+    // kk holds positions 16kk + 8kg .. +7: register e gets native bits n and n + 16, n = 8kk + 4kg + e,
+    // on bits 15 and 31
+    uint32_t sh[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sh[i] = (uint32_t)(15 - 4 * kg - i);
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sh[kk][e] = (uint32_t)(15 - 8 * kk - 4 * kg - e);
 
-    // sign words of this wavefront's eight row tiles for one column tile: lane (r, q) holds, for row
-    // r, the four words [column half c][path k] of columns 128c + 32q .. +31
-    auto load_words = [&](int ct, v4u (&w)[8]) {
+    // sign words of this wavefront's row tiles for one column tile: lane (r, q) holds, for row r,
+    // the four words [column half c][path k] of columns 128c + 32q .. +31
+    auto load_words = [&](int ct, v4u (&w)[2 * MP]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int rt = rb * 16 + wm * 8 + i;
+        for (int i = 0; i < 2 * MP; ++i) {
+            const int rt = rt_base + i;
             v4u v = {0u, 0u, 0u, 0u};
             if (rt < RT) v = bits[((size_t)rt * CT + ct) * 64 + lane];
             v[0] ^= flip[i][0]; v[1] ^= flip[i][1]; v[2] ^= flip[i][0]; v[3] ^= flip[i][1];
             w[i] = v;
         }
     };
-
-    // right-operand staging: thread -> (token tid / 4 + 64 j, 16-byte chunk tid % 4), j = 0..3
-    const int st_tok = tid >> 2, st_chunk = tid & 3;
-    const _Float16 *Ubase = U + ((size_t)tb * BLK + st_tok) * in_pad + st_chunk * 8;
-    auto stage_load = [&](int k, int col0, v4u (&regs)[4]) {
+    // one of the four words again, for the next column tile, once its last use is behind
+    auto reload_word = [&](int ct, int comp, v4u (&w)[2 * MP]) {
+        const uint32_t *words = reinterpret_cast<const uint32_t *>(bits);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            regs[j] = *reinterpret_cast<const v4u *>(Ubase + ((size_t)k * T_pad + 64 * j) * in_pad + col0);
-    };
-    auto stage_store = [&](int buf, const v4u (&regs)[4]) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            *reinterpret_cast<v4u *>(&Bs[buf][(st_tok + 64 * j) * LDS_STRIDE + st_chunk * 8]) = regs[j];
-    };
-
-    v4f acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int n = 0; n < 8; ++n) acc[i][n] = (v4f){0.f, 0.f, 0.f, 0.f};
-
-    v4u cur[8], nxt[8];
-    load_words(0, cur);
-    v4u staged[4];
-    stage_load(0, 0, staged);
-
-    int buf = 0;
-    for (int ct = 0; ct < CT; ++ct) {
-        if (ct + 1 < CT) load_words(ct + 1, nxt);
-#pragma unroll
-        for (int step = 0; step < 16; ++step) {
-            const int k = step >> 3, c = (step >> 2) & 1, q = step & 3;     // path, column half, 32-column group
-            stage_store(buf, staged);
-            {
-                // request the right operand of the next step while this one is computed
-                const int ns = step + 1;
-                const int nct = ns < 16 ? ct : ct + 1;
-                const int nk = (ns & 15) >> 3, ncq = ns & 7;
-                if (nct < CT) stage_load(nk, nct * TILE_COLS + ncq * 32, staged);
-            }
-            lds_barrier();
-            // left operand: every lane fetches the word of its row from lane (r, q), then expands
-            // its quarter of the 32 columns
-            v8h a[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t w = (uint32_t)__shfl((int)cur[i][c * 2 + k], r + 16 * q);
-                union { uint32_t u[4]; v8h h; } f;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) f.u[e] = ((w << sh[e]) & 0x80008000u) | G2[i][k];
-                a[i] = f.h;
-            }
-#pragma unroll
-            for (int n = 0; n < 8; ++n) {
-                const v8h b = *reinterpret_cast<const v8h *>(&Bs[buf][(wn * 128 + n * 16 + r) * LDS_STRIDE + kg * 8]);
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b, acc[i][n], 0, 0, 0);
-            }
-            buf ^= 1;
+        for (int i = 0; i < 2 * MP; ++i) {
+            const int rt = rt_base + i;
+            uint32_t v = 0u;
+            if (rt < RT) v = words[(((size_t)rt * CT + ct) * 64 + lane) * 4 + comp];
+            w[i][comp] = v ^ flip[i][comp & 1];
         }
+    };
+
+    // right-operand staging: one copy instruction moves 16 tokens x 64 bytes; lane L lands at LDS
+    // position (token L / 4, chunk position L % 4) and therefore fetches chunk
+    // (L % 4) ^ swizzle(token) from memory.  With fewer than four groups some wavefronts repeat a
+    // copy another one makes (same bytes to the same place).
+    const uint8_t *stage_src[COPIES];
+    int stage_group[COPIES];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    for (int j = 0; j < COPIES; ++j) {
+        stage_group[j] = (wave * COPIES + j) % GROUPS;
+        const int token = 16 * stage_group[j] + (lane >> 2);
+        const int chunk = (lane & 3) ^ swizzle(token);
+        stage_src[j] = reinterpret_cast<const uint8_t *>(U + ((size_t)tb * BLK_TOK + token) * in_pad + chunk * 8);
+    }
+    const size_t path_stride = (size_t)T_pad * in_pad * sizeof(_Float16);
+    // step s = 16 (ct - ct_begin) + (8 path + 4 column half + 32-column group); its right operand
+    // lives in buffer s % NBUF
+    const int n_steps = (ct_end - ct_begin) * 16;
+    auto stage_step = [&](int s) {
+        // past the end: repeat the first copy, so that the number of copies per step stays constant
+        const int sc = s < n_steps ? s : 0;
+        const size_t off = ((sc >> 3) & 1) * path_stride +
+                           (size_t)((ct_begin + (sc >> 4)) * TILE_COLS + (sc & 7) * 32) * sizeof(_Float16);
+#pragma unroll
+        for (int j = 0; j < COPIES; ++j)
+            __builtin_amdgcn_global_load_lds(static_cast<const void *>(stage_src[j] + off),
+                                             RB_LDS(&Bs[(s % NBUF) * BUF_BYTES + stage_group[j] * 1024]), 16, 0, 0);
+    };
+    // operand reads are written as instructions: a read the compiler can see would make it wait for
+    // every copy still in flight
+    uint32_t b_addr[NT][2];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int token = (wn * NT + n) * 32 + (lane & 31);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+            b_addr[n][kk] = (uint32_t)(size_t)RB_LDS(&Bs[token * 64 + (((2 * kk + kg) ^ swizzle(token)) * 16)]);
     }
 
-    // ---- epilogue: lane (r, kg) of tile (i, n) holds token 16n + r, rows 4kg .. 4kg + 3
+    v16f acc[MP][NT];
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-        const int t = tb * BLK + wn * 128 + n * 16 + r;
+    for (int m = 0; m < MP; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[m][n][e] = 0.f;
+
+    v4u cur[2 * MP];
+    v8h a[2][MP][2], b[2][NT][2];
+    uint32_t wq[MP], wsel0[MP], wsel1[MP];
+    const uint32_t sel_mask = half_sel ? 0xffffffffu : 0u;      // which of the two fetched words is this lane's
+    // the pieces of work one step does for the next one, so that they can be spread between the
+    // matrix instructions: B reads (NT * 2), word fetches (MP), register expansions (MP * 4 pairs)
+    auto read_b = [&](int s, int i, v8h (&bb)[NT][2]) {
+        asm volatile("ds_read_b128 %0, %1" : "=v"(bb[i >> 1][i & 1])
+                     : "v"(b_addr[i >> 1][i & 1] + (uint32_t)((s % NBUF) * BUF_BYTES)) : "memory");
+    };
+    auto fetch_a = [&](const v4u (&w)[2 * MP], int k, int c, int q, int m) {
+        // every lane gets the word of its row (row tile 2m + half_sel, row r) from lane (r, q) of
+        // that tile's register
+        wsel0[m] = (uint32_t)__shfl((int)w[2 * m][c * 2 + k], r + 16 * q);
+        wsel1[m] = (uint32_t)__shfl((int)w[2 * m + 1][c * 2 + k], r + 16 * q);
+    };
+    auto expand_a = [&](int i, int k, v8h (&aa)[MP][2]) {
+        // two of the four registers of (row pair m, half kk)
+        const int m = i >> 2, kk = (i >> 1) & 1, e0 = (i & 1) * 2;
+        if ((i & 3) == 0) wq[m] = (wsel0[m] & ~sel_mask) | (wsel1[m] & sel_mask);     // one bit-field insert
+        union { v8h h; uint32_t u[4]; } f;
+        f.h = aa[m][kk];
+#pragma unroll
+        for (int e = e0; e < e0 + 2; ++e) f.u[e] = ((wq[m] << sh[kk][e]) & 0x80008000u) | G2[m][k];
+        aa[m][kk] = f.h;
+    };
+    auto wait_b = [&](v8h (&bb)[NT][2]) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int n = 0; n < NT; ++n) asm volatile("" : "+v"(bb[n][0]), "+v"(bb[n][1]));
+    };
+
+    if (n_steps > 0) {
+        // ---- prologue: NBUF steps of copies in flight, operands of step 0 in registers
+        load_words(ct_begin, cur);
+#pragma unroll
+        for (int s = 0; s < NBUF; ++s) stage_step(s);
+#pragma unroll
+        for (int m = 0; m < MP; ++m) fetch_a(cur, 0, 0, 0, m);
+#pragma unroll
+        for (int i = 0; i < MP * 4; ++i) expand_a(i, 0, a[0]);
+        wait_copies_and_sync<COPIES * AHEAD>();
+#pragma unroll
+        for (int i = 0; i < NT * 2; ++i) read_b(0, i, b[0]);
+        wait_b(b[0]);
+    }
+
+    // ---- main loop.  One wavefront runs per SIMD, so nothing but its own instruction order keeps
+    // the matrix pipe busy: the matrix instructions of step s are interleaved with everything step
+    // s + 1 needs (barrier, copy request, operand reads, sign expansion).
+    constexpr int SLOTS = MP * NT * 2;                          // matrix instructions per step
+    constexpr int JOBS = 2 + NT * 2 + MP + MP * 4;              // sync, copies, B reads, fetches, expansions
+    for (int ct = ct_begin; ct < ct_end; ++ct) {
+#pragma unroll
+        for (int step = 0; step < 16; ++step) {
+            const int s = (ct - ct_begin) * 16 + step;
+            const int p = step & 1, pn = p ^ 1;                       // register sets of this step and the next
+            const int ns = (step + 1) & 15;                           // next step inside its column tile
+            const int k_ = ns >> 3, c_ = (ns >> 2) & 1, q_ = ns & 3;
+#pragma unroll
+            for (int j = 0; j < SLOTS; ++j) {
+                const int kk = j / (MP * NT), n = (j / MP) % NT, m = j % MP;
+                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[p][m][kk], b[p][n][kk], acc[m][n], 0, 0, 0);
+#pragma unroll
+                for (int job = j * JOBS / SLOTS; job < (j + 1) * JOBS / SLOTS; ++job) {
+                    if (job == 0) {
+                        // The copies of step s + 1 were requested AHEAD steps before that step and
+                        // COPIES * (AHEAD - 1) copies came after them (the sign-word loads at the top of
+                        // a column tile only make this wait longer than needed).  Every wavefront has
+                        // read its operands of step s before it gets here, so after the barrier the
+                        // buffer of step s may be overwritten.
+                        wait_copies_and_sync<COPIES * (AHEAD - 1)>();
+                    } else if (job == 1) {
+                        stage_step(s + NBUF);
+                    } else if (job < 2 + NT * 2) {
+                        read_b(s + 1, job - 2, b[pn]);
+                    } else if (job < 2 + NT * 2 + MP) {
+                        fetch_a(cur, k_, c_, q_, job - (2 + NT * 2));
+                    } else {
+                        expand_a(job - (2 + NT * 2 + MP), k_, a[pn]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_b(b[pn]);
+            // The four steps that use word [c][k] end with step 8k + 4c + 3, and the fetch for that
+            // step happened one step earlier: the register is free for the next column tile, which
+            // needs it 13 steps from now at the earliest.
+            if ((step & 3) == 3 && ct + 1 < ct_end) reload_word(ct + 1, ((step >> 2) & 1) * 2 + (step >> 3), cur);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no copy may land in LDS after the end
+
+    // ---- epilogue: lane l of tile (m, n) holds token 32n + l % 32 and, in register 4a + e, row
+    // 8a + 4 (l / 32) + e of the 32.  (The width is passed through an opaque statement so that
+    // none of the address arithmetic below is computed ahead of the main loop, where registers
+    // are scarce.)
+    asm volatile("" : "+s"(out));
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int t = tb * BLK_TOK + (wn * NT + n) * 32 + (lane & 31);
         if (t >= T) continue;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row0 = (rb * 16 + wm * 8 + i) * TILE_ROWS + 4 * kg;
+        for (int m = 0; m < MP; ++m) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (row0 + e < out) store_out(Y, OUT_DT, (size_t)t * out + row0 + e, acc[i][n][e]);
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const int row0 = (rt_base + 2 * m) * TILE_ROWS + 8 * a4 + 4 * kg;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (row0 + e >= out) continue;
+                    const size_t idx = (size_t)t * out + row0 + e;
+                    if (Acc)
+                        Acc[(size_t)blockIdx.y * T * out + idx] = acc[m][n][4 * a4 + e];
+                    else
+                        store_out(Y, OUT_DT, idx, acc[m][n][4 * a4 + e]);
+                }
+            }
         }
     }
 }
 
+// ------------------------------------------------------------------ host ---
+struct Plan {
+    bool small;          // 32-token tiles with the contraction split over workgroups
+    int T_pad, CT, in_pad, RT, RB, TB, split;
+    size_t u_bytes, acc_bytes;
+};
+
+static Plan make_plan(const rb_layer *L, int T)
+{
+    Plan p;
+    p.small = T <= SMALL_TOKENS;
+    const int blk_tok = p.small ? SMALL_TOKENS : LARGE_TOKENS;
+    p.T_pad = round_up(T, blk_tok);
+    p.CT = col_tiles(L->in);
+    p.in_pad = p.CT * TILE_COLS;
+    p.RT = row_tiles(L->out);
+    p.RB = (p.RT + BLK_ROWS / TILE_ROWS - 1) / (BLK_ROWS / TILE_ROWS);
+    p.TB = p.T_pad / blk_tok;
+    // enough workgroups for every compute unit of an MI355X (256), never less than one column tile each
+    p.split = p.small ? std::max(1, std::min(p.CT, (256 + p.RB * p.TB - 1) / (p.RB * p.TB))) : 1;
+    p.u_bytes = (2 * (size_t)p.T_pad * p.in_pad * sizeof(_Float16) + 255) / 256 * 256;
+    p.acc_bytes = p.split > 1 ? (size_t)p.split * T * L->out * sizeof(float) : 0;
+    return p;
+}
+
 size_t workspace_bytes(const rb_layer *L, int T)
 {
-    const size_t T_pad = (size_t)round_up(T, BLK), in_pad = (size_t)col_tiles(L->in) * TILE_COLS;
-    return 2 * T_pad * in_pad * sizeof(_Float16);
+    const Plan p = make_plan(L, T);
+    return p.u_bytes + p.acc_bytes;
 }
 
 bool supported(const rb_layer *L, int T)
@@ -210,25 +397,38 @@ bool supported(const rb_layer *L, int T)
 int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype, void *workspace,
            hipStream_t stream)
 {
-    const int T_pad = round_up(T, BLK), CT = col_tiles(L->in), in_pad = CT * TILE_COLS, RT = row_tiles(L->out);
+    const Plan p = make_plan(L, T);
     _Float16 *U = static_cast<_Float16 *>(workspace);
+    float *Acc = p.split > 1 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.u_bytes) : nullptr;
     const __half *h = reinterpret_cast<const __half *>(L->h);
-    const dim3 sgrid(in_pad / 256, T_pad);
+    const dim3 sgrid(p.in_pad / 256, p.T_pad);
     if (act_dtype == RB_F16)
         hipLaunchKernelGGL(scale_kernel<__half>, sgrid, dim3(256), 0, stream, static_cast<const __half *>(X), h, U,
-                           T, T_pad, L->in, in_pad);
+                           T, p.T_pad, L->in, p.in_pad);
     else
         hipLaunchKernelGGL(scale_kernel<bf16_t>, sgrid, dim3(256), 0, stream, static_cast<const bf16_t *>(X), h, U,
-                           T, T_pad, L->in, in_pad);
-    const int RB = (RT + 15) / 16, TB = T_pad / BLK;
-    const dim3 grid((unsigned)(RB * TB));
+                           T, p.T_pad, L->in, p.in_pad);
     const v4u *bits = static_cast<const v4u *>(L->bits);
     const __half *g = reinterpret_cast<const __half *>(L->g);
-#define RB_GEMM(DT) \
-    hipLaunchKernelGGL(gemm_kernel<DT>, grid, dim3(256), 0, stream, bits, g, U, Y, L->out, RT, CT, T, T_pad)
-    if (out_dtype == RB_F16) RB_GEMM(RB_F16);
-    else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16);
-    else RB_GEMM(RB_F32);
+    const dim3 grid((unsigned)(p.RB * p.TB), (unsigned)p.split);
+    const size_t lds = p.small ? (size_t)(AHEAD_SMALL + 1) * SMALL_TOKENS * 64 : (size_t)(AHEAD_LARGE + 1) * LARGE_TOKENS * 64;
+#define RB_GEMM(DT, WM, WN, MP, NT)                                                                              \
+    hipLaunchKernelGGL((gemm_kernel<DT, WM, WN, MP, NT, (NT == 1 ? AHEAD_SMALL : AHEAD_LARGE)>), grid, dim3(256), lds, \
+                       stream, bits, g, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad)
+    if (p.small && p.split > 1) {
+        RB_GEMM(RB_F32, 4, 1, 2, 1);
+        const size_t n = (size_t)T * L->out;
+        hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype, n,
+                           p.split);
+    } else if (p.small) {
+        if (out_dtype == RB_F16) RB_GEMM(RB_F16, 4, 1, 2, 1);
+        else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 4, 1, 2, 1);
+        else RB_GEMM(RB_F32, 4, 1, 2, 1);
+    } else {
+        if (out_dtype == RB_F16) RB_GEMM(RB_F16, 2, 2, 4, 4);
+        else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 2, 2, 4, 4);
+        else RB_GEMM(RB_F32, 2, 2, 4, 4);
+    }
 #undef RB_GEMM
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
