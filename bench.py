@@ -98,6 +98,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extras", action="store_true", help="skip comparators and the CPU baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -138,11 +140,14 @@ def main() -> int:
         "ms_per_step_min": ms_min,
         "wall_ms_per_step": wall * 1e3 / args.steps,
     }
+    # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, scaled
+    # by what the same counters read for a plain copy of known size)
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", "stack_kernel_7b_T1_pmc.json")
+    pmc = os.path.join(ROOT, "profiles", "stack_kernel_7b_T1_pmc.txt")
     if os.path.exists(pmc):
-        with open(pmc) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+        import re
+        m = re.search(r"hbm_bytes_per_launch\s*:\s*(\d+)", open(pmc).read())
+        traffic = int(m.group(1)) if m else None
     result["roofline"] = {
         "bound": "hbm", "kernel": "rb::mx::stack_kernel",
         "achieved": packed_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -151,6 +156,14 @@ def main() -> int:
         "note": "one launch per step; duration = HIP events around rb_stack_run on its stream "
                 "(includes the ~3 us input-expansion kernel)",
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_extras:
         # the same 224 matrices without data dependencies: every op reads the stack input or a
@@ -194,6 +207,35 @@ def main() -> int:
                                      "GBps": 2 * 8 * packed_bytes / 2 / (per_tok_us * 1e-6) / 1e9}
         result["speedup_vs_dense_fp16"] = result["tokens_per_s"] / result["dense_fp16_gemv"]["tokens_per_s"]
         result["paper_context"] = "RTX 4090: 291.88 tok/s = 4.49x FP16, whole Llama2-7B model (inference table)"
+        # prefill GEMM (configs[4]): T = 2048 tokens, 70B-shaped MLP matrices, bf16 activations
+        prefill = {}
+        Tp = 2048
+        for (o, i) in ((28672, 8192), (8192, 28672)):
+            nb = rb.rb_native_bytes(2, o, i)
+            bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb // 4,), dtype=torch.int32, device="cuda")
+            gg = (torch.randn(2, o, device="cuda").abs() * 0.02).half()
+            hh = (torch.randn(2, i, device="cuda").abs() * 0.02).half()
+            Lp = rb.Layer(bits, gg, hh, 2, o, i)
+            Xp = torch.randn((Tp, i), device="cuda").to(torch.bfloat16)
+            Yp = torch.empty((Tp, o), dtype=torch.float16, device="cuda")
+            wsp = rb.binding._workspace([Lp], Tp, Xp.device)
+            _, per_p = time_steps(torch, lambda: rb.rb_linear_gemm(Lp, Xp, Y=Yp, workspace=wsp), 8, 2)
+            msp = sum(per_p) / len(per_p)
+            flops = 2.0 * 2 * o * i * Tp
+            prefill[f"{o}x{i}"] = {"ms": msp, "TFLOPs": flops / msp / 1e9, "frac_of_fp16_mfma_peak": flops / msp / 1e9 / 2500.0}
+            del bits, Lp, Xp, Yp, wsp
+        result["prefill_gemm_T2048"] = prefill
+        # small decode batches (configs[2]): the 7B-shaped stack, every op on its own input buffer
+        skinny = {}
+        for Ts in (4, 16):
+            fbs = [torch.randn(Ts, w, device="cuda").half() for w in (4096, 11008)]
+            outs_s = [torch.zeros((Ts, op.out), dtype=torch.float16, device="cuda") for op in ops]
+            st_s = rb.Stack(layers, [(n, 0 if op.inn == 4096 else 1, 2 + n) for n, op in enumerate(ops)], fbs + outs_s, Ts)
+            _, per_s = time_steps(torch, st_s.run, 4, 1)
+            ms_s = sum(per_s) / len(per_s)
+            skinny[f"T{Ts}"] = {"ms_per_pass": ms_s, "tokens_per_s": Ts / (ms_s * 1e-3), "GBps": packed_bytes / (ms_s * 1e-3) / 1e9}
+            del fbs, outs_s, st_s
+        result["small_batch_stack"] = skinny
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)
     else:
         result["cpu_baseline"] = None
