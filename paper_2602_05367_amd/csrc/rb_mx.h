@@ -43,7 +43,7 @@ constexpr int MAXSLOT = 8;         // (op, row tile) pairs one CU finishes per s
 constexpr int MAX_CONS = 3;        // ops that read one op's output inside a fused stack
 constexpr int MAX_DEPS = 3;        // distinct ops of earlier stages whose output one stage reads
 constexpr int MAX_T = 2;           // tokens per call on this path
-constexpr int MAX_OPS = 320;       // ops per launch (their per-wavefront records live in LDS)
+constexpr int MAX_OPS = 4096;      // ops per launch
 constexpr size_t MAX_EXPAND = 1024;
 static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1) <= 63 && wait_of(2) <= 63,
               "the in-order wait counts on this");
@@ -53,15 +53,11 @@ constexpr int LDS_RING_BYTES = CWAVES * RING_D * 1024;
 // partial sums: [parity][slot][compute wavefront][path][token][row] fp32
 constexpr int LDS_PART_SLOT_BYTES = CWAVES * 2 * 2 * 16 * 4;
 constexpr int LDS_PART_BYTES = 2 * MAXSLOT * LDS_PART_SLOT_BYTES;
-constexpr int LDS_REC_BYTES = CWAVES * MAX_OPS * 8;      // WaveRec per (wavefront, op)
-constexpr int LDS_INFO_BYTES = MAX_OPS * 32;             // OpInfo per op
 constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
 constexpr int LDS_MISC_BYTES = 256 + CWAVES * 256 + EWAVES * LDS_STAGE_BYTES;   // + per-wavefront dummy-load target
 constexpr int LDS_RING_OFF = 0;
 constexpr int LDS_PART_OFF = LDS_RING_OFF + LDS_RING_BYTES;
-constexpr int LDS_REC_OFF = LDS_PART_OFF + LDS_PART_BYTES;
-constexpr int LDS_INFO_OFF = LDS_REC_OFF + LDS_REC_BYTES;
-constexpr int LDS_MISC_OFF = LDS_INFO_OFF + LDS_INFO_BYTES;
+constexpr int LDS_MISC_OFF = LDS_PART_OFF + LDS_PART_BYTES;
 constexpr int LDS_BYTES = LDS_MISC_OFF + LDS_MISC_BYTES;
 static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 
@@ -107,22 +103,27 @@ struct Op {
     float inv_sc[2];
 };
 
-// what a compute wavefront needs to know about an op (copied to LDS)
-struct OpInfo {
-    uint64_t bits;            // address of the sign tiles
-    uint64_t up;              // address of the expanded input
-    uint32_t CT;
-    uint32_t in;
-    int32_t dep_slot;         // which entry of the stage's list writes the input during this launch (-1: none)
-    uint32_t pad_;
-};
-static_assert(sizeof(OpInfo) == 32, "LDS_INFO_BYTES");
-
-// tiles of one op that one compute wavefront of one workgroup streams (copied to LDS)
-struct WaveRec {
-    uint32_t tile0;           // first tile, counted from the start of the op's sign array
-    uint32_t packed;          // n (tiles, bits 0..15) | ct0 (column tile of the first, 16..23) | slot0 (24..31)
-};
+// What a compute wavefront does, step by step (one step = one 1 KB sign tile), written out once per
+// plan so that the kernel's loop is a walk over two lists and not a search through op tables:
+//   sign list:    the address of each tile, in the order the wavefront meets them (requested
+//                 RING_D steps ahead, across stages)
+//   operand list: per stage, one entry per tile (the address of the tile's expanded input and what
+//                 to do after the MFMAs) followed by nb_of(T) empty entries; the first empty entry
+//                 that reaches the front of the operand ring ends the stage
+// A list is stored in blocks of 64 entries, field by field (64 low words, 64 high words, ...), so
+// that a wavefront loads a block with one dword load per field, an entry per lane, and picks the
+// entry of a step out of its registers.
+constexpr int DESC_BLOCK = 64;               // entries per block (one per lane)
+constexpr int SIGN_FIELDS = 2;               // address low, high
+constexpr int OPND_FIELDS = 3;               // address low, high, STEP_* fields
+constexpr uint32_t STEP_VALID = 1u;          // a tile (empty entries are all zero)
+constexpr uint32_t STEP_FLUSH = 2u;          // last tile of its row tile for this wavefront: write the partial sums
+constexpr int STEP_SLOT_SHIFT = 8;           // 8 bits: partial-sum slot
+constexpr int STEP_DEP_SHIFT = 16;           // 3 bits: 1 + entry of the stage's dependency list (0: input was complete before the launch)
+constexpr int STEP_CT_SHIFT = 20;            // 12 bits: column tile (which hand-over bit to wait for)
+// blocks a wavefront may load for a list of n entries read front to back: it holds the block it
+// reads from and the one after it
+__host__ __device__ constexpr uint32_t desc_blocks(uint32_t n) { return n / DESC_BLOCK + 2; }
 
 // What a finishing wavefront needs for finishing slot `slot` of workgroup `grp` in stage `st`
 // (one row tile of one op), laid out flat so that its address follows from (st, grp, slot) alone:
@@ -158,13 +159,13 @@ struct Header {
     int n_ops, n_stages, T, n_groups;
 };
 
-// workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 128 B]
+// workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]
 //            [indices of the ops whose input is expanded by a kernel of its own]
 //            [hand-over flags: one byte per row tile (padded to 16 per 256-row block) of every op that has a reader]
-//            [OpInfo x n_ops][WaveRec x n_groups x CWAVES x n_ops]
+//            [sign lists, operand lists: blocks x n_groups x CWAVES each]
 //            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
 struct Layout {
-    size_t ops, stages, error, zero, which, ready, info, rec, slots, vals, up, total;
+    size_t ops, stages, error, zero, which, ready, sdesc, odesc, slots, vals, up, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

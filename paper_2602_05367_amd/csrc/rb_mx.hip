@@ -5,6 +5,9 @@
 //   * every op's row tiles are cut into contiguous shares, one per workgroup;
 //     a share is a contiguous run of 1 KB sign tiles in the native layout and
 //     is cut again into eight runs, one per compute wavefront;
+//   * what each compute wavefront does is written out once per plan as a list
+//     of steps (tile address, operand address, what to do afterwards), so the
+//     kernel's loop has no op tables to search;
 //   * a compute wavefront keeps RING_D sign tiles in flight from HBM into its
 //     LDS ring (the weights of later ops do not depend on activations, so the
 //     stream never stops at a stage boundary), reads the expanded input of the
@@ -122,47 +125,12 @@ __host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G
 }
 
 // ------------------------------------------------------------ prep kernel ---
-// One workgroup per op: power-of-two scale of each path's input scales, the zero fill of the
-// expanded-input array (padding columns and unused operand columns must read as zero), and the
-// tables the stack kernel keeps in LDS.
-__global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *error,
-                                                   uint32_t *zero_page, OpInfo *info, WaveRec *rec)
+// One workgroup per op: power-of-two scale of each path's input scales and the zero fill of the
+// expanded-input array (padding columns and unused operand columns must read as zero).
+__global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *error, uint32_t *zero_page)
 {
     const int o = blockIdx.x;
     Op &op = ops[o];
-    // Which tiles of this op every (workgroup, compute wavefront) pair streams: row tiles are dealt to
-    // the workgroups in contiguous, nearly equal shares, and a share (row tiles x column tiles,
-    // contiguous in the native layout) is cut into CWAVES contiguous runs.
-    {
-        const uint32_t G = (uint32_t)hdr->n_groups, RT = (uint32_t)op.RT, CT = (uint32_t)op.CT;
-        const uint32_t n_ops = (uint32_t)hdr->n_ops;
-        for (uint32_t idx = threadIdx.x; idx < G * CWAVES; idx += 256) {
-            const uint32_t grp = idx / CWAVES, wave = idx % CWAVES;
-            uint32_t rt0, nrt;
-            group_rows(RT, grp, G, rt0, nrt);
-            const uint32_t U = nrt * CT, u0 = wave * U / CWAVES, u1 = (wave + 1) * U / CWAVES;
-            uint32_t slot_base = 0;                       // row tiles of the earlier ops of the stage
-            for (int m = op.stage_op0; m < o; ++m) {
-                uint32_t a, b;
-                group_rows((uint32_t)ops[m].RT, grp, G, a, b);
-                slot_base += b;
-            }
-            WaveRec r;
-            r.tile0 = rt0 * CT + u0;
-            r.packed = (u1 - u0) | ((u0 % CT) << 16) | ((slot_base + u0 / CT) << 24);
-            rec[(size_t)idx * n_ops + o] = r;
-        }
-        if (threadIdx.x == 0) {
-            OpInfo inf;
-            inf.bits = (uint64_t)op.bits;
-            inf.up = (uint64_t)op.up;
-            inf.CT = CT;
-            inf.in = (uint32_t)op.in;
-            inf.dep_slot = op.dep_slot;
-            inf.pad_ = 0;
-            info[o] = inf;
-        }
-    }
     __shared__ float red[256];
     for (int p = 0; p < 2; ++p) {
         float m = 0.f;
@@ -191,8 +159,61 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
     if (o == 0) {
-        if (threadIdx.x < 32) zero_page[threadIdx.x] = 0;
+        zero_page[threadIdx.x] = 0;                       // 1 KB: what a padding step of the sign stream reads
         if (threadIdx.x == 0) *error = 0;
+    }
+}
+
+// The step lists of the compute wavefronts; one thread per (workgroup, wavefront).  Row tiles of an
+// op are dealt to the workgroups in contiguous, nearly equal shares, and a share (row tiles x column
+// tiles, contiguous in the native layout) is cut into CWAVES contiguous runs.
+__global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *ops, const Stage *stages,
+                                                  const uint32_t *zero_page, uint32_t *sdesc, uint32_t *odesc,
+                                                  uint32_t sblocks, uint32_t oblocks)
+{
+    const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x * 64 + threadIdx.x;
+    if (id >= G * CWAVES) return;
+    const uint32_t grp = id / CWAVES, wave = id % CWAVES;
+    const int T = hdr->T, n_stages = hdr->n_stages;
+    uint32_t *sd = sdesc + (size_t)id * sblocks * (SIGN_FIELDS * DESC_BLOCK);
+    uint32_t *od = odesc + (size_t)id * oblocks * (OPND_FIELDS * DESC_BLOCK);
+    const uint32_t s_cap = sblocks * DESC_BLOCK, o_cap = oblocks * DESC_BLOCK;
+    auto put_sign = [&](uint32_t e, uint64_t addr) {
+        if (e >= s_cap) return;
+        uint32_t *b = sd + (size_t)(e / DESC_BLOCK) * (SIGN_FIELDS * DESC_BLOCK) + e % DESC_BLOCK;
+        b[0] = (uint32_t)addr;
+        b[DESC_BLOCK] = (uint32_t)(addr >> 32);
+    };
+    auto put_opnd = [&](uint32_t e, uint64_t addr, uint32_t meta) {
+        if (e >= o_cap) return;
+        uint32_t *b = od + (size_t)(e / DESC_BLOCK) * (OPND_FIELDS * DESC_BLOCK) + e % DESC_BLOCK;
+        b[0] = (uint32_t)addr;
+        b[DESC_BLOCK] = (uint32_t)(addr >> 32);
+        b[2 * DESC_BLOCK] = meta;
+    };
+    // every entry empty first: a sign request past the last tile reads a page of zeros
+    for (uint32_t e = 0; e < s_cap; ++e) put_sign(e, (uint64_t)zero_page);
+    for (uint32_t e = 0; e < o_cap; ++e) put_opnd(e, 0, 0u);
+    uint32_t gs = 0, go = 0;
+    for (int st = 0; st < n_stages; ++st) {
+        const Stage stage = stages[st];
+        uint32_t slot_base = 0;
+        for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+            const Op &op = ops[o];
+            const uint32_t CT = (uint32_t)op.CT;
+            uint32_t rt0, nrt;
+            group_rows((uint32_t)op.RT, grp, G, rt0, nrt);
+            const uint32_t U = nrt * CT, u0 = wave * U / CWAVES, u1 = (wave + 1) * U / CWAVES;
+            for (uint32_t u = u0; u < u1; ++u) {
+                const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
+                put_sign(gs++, (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
+                put_opnd(go++, (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
+                         STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) | (slot << STEP_SLOT_SHIFT) |
+                             ((uint32_t)(op.dep_slot + 1) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
+            }
+            slot_base += nrt;
+        }
+        go += (uint32_t)nb_of(T);              // the empty entries that end the stage
     }
 }
 
@@ -319,8 +340,9 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                                                            const Stage *__restrict__ stages,
                                                            uint32_t *__restrict__ error,
                                                            const uint32_t *__restrict__ zero_page,
-                                                           const OpInfo *__restrict__ info_g,
-                                                           const WaveRec *__restrict__ rec_g,
+                                                           const uint32_t *__restrict__ sdesc_g,
+                                                           const uint32_t *__restrict__ odesc_g,
+                                                           uint32_t sblocks, uint32_t oblocks,
                                                            const SlotRec *__restrict__ slots_g,
                                                            const SlotVals *__restrict__ vals_g)
 {
@@ -333,19 +355,11 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x, G = gridDim.x;
-    const int n_ops = hdr_p->n_ops, n_stages = hdr_p->n_stages;
+    const int n_stages = hdr_p->n_stages;
     constexpr int T = TT, NB = nb_of(TT), KOP = kop_of(TT);
 
-    // ---- LDS set-up: clear the partial sums, copy this workgroup's records and the op table
+    // ---- LDS set-up: clear the partial sums
     for (int i = threadIdx.x; i < LDS_PART_BYTES / 4; i += THREADS) part[i] = 0.f;
-    {
-        const uint2 *src = reinterpret_cast<const uint2 *>(rec_g + (size_t)grp * CWAVES * n_ops);
-        uint2 *dst = reinterpret_cast<uint2 *>(lds + LDS_REC_OFF);
-        for (int i = threadIdx.x; i < CWAVES * n_ops; i += THREADS) dst[(i / n_ops) * MAX_OPS + (i % n_ops)] = src[i];
-        const uint4 *isrc = reinterpret_cast<const uint4 *>(info_g);
-        uint4 *idst = reinterpret_cast<uint4 *>(lds + LDS_INFO_OFF);
-        for (int i = threadIdx.x; i < 2 * n_ops; i += THREADS) idst[i] = isrc[i];
-    }
     __syncthreads();
 
     if (wave < CWAVES) {
@@ -365,48 +379,98 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         auto issue_dummies = [&](int n) {
             for (int i = 0; i < n; ++i) __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
         };
-        // LDS tables are read with explicit instructions: a compiler-visible LDS read would make the
-        // compiler wait for every sign tile still in flight into the ring
-        const uint32_t rec_base = lds_addr(lds + LDS_REC_OFF) + (uint32_t)wave * MAX_OPS * 8;
-        const uint32_t info_base = lds_addr(lds + LDS_INFO_OFF);
-        auto read_rec = [&](int op, uint32_t &tile0, uint32_t &packed) {
-            uint2 v;
-            asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(rec_base + (uint32_t)op * 8) : "memory");
-            tile0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.x);
-            packed = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.y);
+        // ---- the step lists of this wavefront.  Each list is read front to back, a block of 64
+        // entries (one per lane) at a time: the wavefront holds the block it reads from and the one
+        // after it, and replaces the latter, 64 steps before it is needed, each time it moves on.
+        // The replacing loads are written as instructions and never waited for by name: loads
+        // complete in order and every step waits for all but its youngest few, so a block has
+        // arrived a few steps after its request (steps_done tells when that cannot be relied on).
+        const size_t my_list = (size_t)grp * CWAVES + wave;
+        const uint32_t *sd_next = sdesc_g + my_list * sblocks * (SIGN_FIELDS * DESC_BLOCK) + lane;
+        const uint32_t *od_next = odesc_g + my_list * oblocks * (OPND_FIELDS * DESC_BLOCK) + lane;
+        int s_lo, s_hi, sn_lo, sn_hi;                 // sign list: current block, next block
+        int o_lo, o_hi, o_m, on_lo, on_hi, on_m;      // operand list
+        asm volatile("global_load_dword %0, %10, off\n\t"
+                     "global_load_dword %1, %10, off offset:256\n\t"
+                     "global_load_dword %2, %10, off offset:512\n\t"
+                     "global_load_dword %3, %10, off offset:768\n\t"
+                     "global_load_dword %4, %11, off\n\t"
+                     "global_load_dword %5, %11, off offset:256\n\t"
+                     "global_load_dword %6, %11, off offset:512\n\t"
+                     "global_load_dword %7, %11, off offset:768\n\t"
+                     "global_load_dword %8, %11, off offset:1024\n\t"
+                     "global_load_dword %9, %11, off offset:1280\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(s_lo), "=&v"(s_hi), "=&v"(sn_lo), "=&v"(sn_hi), "=&v"(o_lo), "=&v"(o_hi), "=&v"(o_m),
+                       "=&v"(on_lo), "=&v"(on_hi), "=&v"(on_m)
+                     : "v"(sd_next), "v"(od_next)
+                     : "memory");
+        sd_next += 2 * SIGN_FIELDS * DESC_BLOCK;
+        od_next += 2 * OPND_FIELDS * DESC_BLOCK;
+        uint32_t p_sign = 0, p_opnd = 0;              // entries read so far
+        uint32_t steps_done = 0, s_mark = 0, o_mark = 0;   // steps consumed; the same at the last block requests
+        auto next_sign = [&]() -> uint64_t {
+            const int l = (int)(p_sign & (DESC_BLOCK - 1));
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(s_lo, l), hi = (uint32_t)__builtin_amdgcn_readlane(s_hi, l);
+            ++p_sign;
+            if ((p_sign & (DESC_BLOCK - 1)) == 0) {
+                if (steps_done - s_mark < (uint32_t)NB + 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("v_mov_b32 %0, %2\n\t"
+                             "v_mov_b32 %1, %3\n\t"
+                             "global_load_dword %2, %4, off\n\t"
+                             "global_load_dword %3, %4, off offset:256"
+                             : "=&v"(s_lo), "=&v"(s_hi), "+v"(sn_lo), "+v"(sn_hi)
+                             : "v"(sd_next)
+                             : "memory");
+                sd_next += SIGN_FIELDS * DESC_BLOCK;
+                s_mark = steps_done;
+            }
+            return ((uint64_t)hi << 32) | lo;
+        };
+        struct OpndDesc { uint32_t lo, hi, meta; };
+        auto next_opnd = [&]() -> OpndDesc {
+            const int l = (int)(p_opnd & (DESC_BLOCK - 1));
+            OpndDesc d;
+            d.lo = (uint32_t)__builtin_amdgcn_readlane(o_lo, l);
+            d.hi = (uint32_t)__builtin_amdgcn_readlane(o_hi, l);
+            d.meta = (uint32_t)__builtin_amdgcn_readlane(o_m, l);
+            ++p_opnd;
+            if ((p_opnd & (DESC_BLOCK - 1)) == 0) {
+                if (steps_done - o_mark < (uint32_t)NB + 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("v_mov_b32 %0, %3\n\t"
+                             "v_mov_b32 %1, %4\n\t"
+                             "v_mov_b32 %2, %5\n\t"
+                             "global_load_dword %3, %6, off\n\t"
+                             "global_load_dword %4, %6, off offset:256\n\t"
+                             "global_load_dword %5, %6, off offset:512"
+                             : "=&v"(o_lo), "=&v"(o_hi), "=&v"(o_m), "+v"(on_lo), "+v"(on_hi), "+v"(on_m)
+                             : "v"(od_next)
+                             : "memory");
+                od_next += OPND_FIELDS * DESC_BLOCK;
+                o_mark = steps_done;
+            }
+            return d;
+        };
+        // the registers of the blocks on their way stay allocated (see keep_operands below)
+        auto keep_blocks = [&]() {
+            asm volatile("" : "+v"(sn_lo), "+v"(sn_hi), "+v"(on_lo), "+v"(on_hi), "+v"(on_m));
         };
 
         // ---- sign-tile stream (runs RING_D tiles ahead of the MFMAs, across ops and stages)
-        int a_op = -1;
-        uint32_t a_n = 0;
-        const uint8_t *a_ptr = nullptr;
         uint8_t *a_slot = ring;
         auto issue_a = [&]() {
-            while (a_n == 0 && a_op + 1 < n_ops) {
-                ++a_op;
-                uint32_t tile0, packed;
-                read_rec(a_op, tile0, packed);
-                a_n = packed & 0xffffu;
-                if (a_n != 0) {
-                    uint2 v;
-                    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(info_base + (uint32_t)a_op * 32) : "memory");
-                    a_ptr = reinterpret_cast<const uint8_t *>(uniform64(v.x, v.y)) + (size_t)tile0 * 1024;
-                }
-            }
-            if (a_n != 0) {
-                // non-temporal: every sign tile is read once (measured: the stream is ~13% faster)
-                __builtin_amdgcn_global_load_lds(a_ptr + lane * 16, RB_LDS(a_slot), 16, 0, 2);
-                a_ptr += 1024;
-                --a_n;
-            } else {
-                __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
-            }
+            // non-temporal: every sign tile is read once (measured: the stream is ~13% faster)
+            const uint64_t addr = next_sign();
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint8_t *>(addr) + lane * 16, RB_LDS(a_slot), 16, 0, 2);
             a_slot += 1024;
             if (a_slot == ring_end) a_slot = ring;
         };
 
 #pragma unroll 1
-        for (int d = 0; d < RING_D; ++d) { issue_a(); issue_dummies(KOP); }
+        for (int d = 0; d < RING_D; ++d) {
+            issue_a();
+            issue_dummies(KOP);
+        }
         uint8_t *c_slot_ptr = ring;           // ring slot of the next tile to consume
         bool failed = false;                  // a producer never delivered: stop waiting, report
 #ifdef RB_EXP_TRACE
@@ -428,47 +492,46 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         };
 
         for (int st = 0; st < n_stages; ++st) {
-            const Stage stage = stages[st];
-            const int stage_end = stage.op0 + stage.nops;
             RB_TRACE(0);
             keep_operands();
+            keep_blocks();
 
             // ---- expanded-input stream of this stage (NB tiles ahead of the MFMAs).  What the
-            // consuming step needs to know about a tile travels with it in meta[]:
-            // bit 0: a tile (not the end of the stage), bit 1: last tile of its row tile for this
-            // wavefront (write the partial sums), bits 8..: partial-sum slot.
-            int b_op = stage.op0 - 1;
-            uint32_t b_n = 0, b_ct = 0, b_CT = 1, b_slot = 0;
-            v4i b_rsrc = {0, 0, 0, 0x00020000};               // empty buffer: every load returns zero
+            // consuming step needs to know about a tile travels with it in meta[] (STEP_* fields).
             uint32_t meta[NB];
-            auto load_operand = [&](BTile<TT> &dst, uint32_t off0, v4i rsrc) {
+            auto load_operand = [&](BTile<TT> &dst, v4i rsrc) {
                 // The target registers are in-out operands on purpose: the compiler cannot see that
                 // a load issued here lands later, and the loads of the last steps of a stage are
                 // never waited for.  As in-out operands the registers stay allocated to the operand
                 // ring for the whole kernel, so no temporary is ever placed where a late load lands.
-                // Plain loads: the counters have shown that these bytes are final, and nobody in
+                // Plain loads: the flags have shown that these bytes are final, and nobody in
                 // this XCD has read them before that, so its L2 holds no older copy.  Each load
                 // reads 1 KB of consecutive bytes (the layout of the expanded input sees to that).
+                // An empty buffer (no tile) returns zeros without touching memory.  The descriptor's
+                // words come out of vector registers (v_readlane) just before; the compiler does not
+                // look inside this block, so the wait states a vector-memory instruction needs after
+                // such a write are spelled out.
                 if constexpr (TT == 1)
-                    asm volatile("buffer_load_dwordx4 %0, %2, %3, 0 offen\n\t"
+                    asm volatile("s_nop 4\n\t"
+                                 "buffer_load_dwordx4 %0, %2, %3, 0 offen\n\t"
                                  "buffer_load_dwordx4 %1, %2, %3, 0 offen offset:1024"
                                  : "+v"(dst.r[0]), "+v"(dst.r[1])
-                                 : "v"(off0), "s"(rsrc)
+                                 : "v"(lane_off), "s"(rsrc)
                                  : "memory");
                 else
-                    asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
+                    asm volatile("s_nop 4\n\t"
+                                 "buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
                                  "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:1024\n\t"
                                  "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048\n\t"
                                  "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:3072"
                                  : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
-                                 : "v"(off0), "s"(rsrc)
+                                 : "v"(lane_off), "s"(rsrc)
                                  : "memory");
             };
-            // Hand-over: a finishing wavefront of this workgroup watches the counters of the ops
+            // Hand-over: a finishing wavefront of this workgroup watches the flags of the ops
             // this stage reads from and keeps one bit per 256-column block in LDS; nothing but that
             // wavefront polls memory.  A compute wavefront requests an operand tile only after its
             // bit is set, so no line of an expanded input is read before it is final.
-            int b_dep = -1;                                   // entry of the stage's list (-1: input complete before the launch)
             const uint32_t ready_base = lds_addr(lds + LDS_MISC_OFF) + (uint32_t)((st & 1) * MAX_DEPS * READY_WINDOWS * 8);
             auto block_ready = [&](int dep, uint32_t ct) -> bool {
                 uint2 v;
@@ -477,55 +540,31 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 const uint64_t bits = uniform64(v.x, v.y);
                 return (bits >> (ct & 63u)) & 1ull;
             };
+            // requests the operand of the next entry of the operand list (nothing for an empty entry)
             auto issue_b = [&](BTile<TT> &dst, uint32_t &m) {
-                while (b_n == 0 && b_op + 1 < stage_end) {
-                    ++b_op;
-                    uint32_t tile0, packed;
-                    read_rec(b_op, tile0, packed);
-                    b_n = packed & 0xffffu;
-                    if (b_n != 0) {
-                        b_ct = (packed >> 16) & 0xffu;
-                        b_slot = packed >> 24;
-                        uint4 v;
-                        asm volatile("ds_read_b128 %0, %1 offset:8\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(info_base + (uint32_t)b_op * 32) : "memory");
-                        // raw buffer descriptor: base, stride 0, size of token pair 0, 32-bit untyped
-                        b_CT = (uint32_t)__builtin_amdgcn_readfirstlane((int)v.z);
-                        b_rsrc[0] = __builtin_amdgcn_readfirstlane((int)v.x);
-                        b_rsrc[1] = __builtin_amdgcn_readfirstlane((int)v.y) & 0xffff;
-                        b_rsrc[2] = (int)(2 * b_CT * up_block_bytes(TT));
-                        b_rsrc[3] = 0x00020000;
-                        uint32_t r;
-                        asm volatile("ds_read_b32 %0, %1 offset:24\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(r) : "v"(info_base + (uint32_t)b_op * 32) : "memory");
-                        b_dep = __builtin_amdgcn_readfirstlane((int)r);
-                    }
-                }
-                if (b_n != 0 && b_dep >= 0 && !failed) {
+                const OpndDesc d = next_opnd();
+                m = d.meta;
+#ifdef RB_EXP_SKIP_OPERANDS
+                const bool valid = false;
+#else
+                const bool valid = (m & STEP_VALID) != 0;
+#endif
+                const uint32_t dep = (m >> STEP_DEP_SHIFT) & 7u;
+                if (dep != 0 && !failed) {
+                    const uint32_t ct = m >> STEP_CT_SHIFT;
                     int spins = 0;
-                    while (!block_ready(b_dep, b_ct)) {
+                    while (!block_ready((int)dep - 1, ct)) {
                         __builtin_amdgcn_s_sleep(2);
                         if (++spins > (1 << 24)) { failed = true; break; }    // the watcher reports; just go on
                     }
                 }
-                // Always the same number of loads, written as instructions so that their order and their number
-                // per step are exactly what the wait before the MFMAs counts on.  Without a tile
-                // left the offset lies past the end of the buffer: a bounds-checked zero, no access.
-#ifdef RB_EXP_SKIP_OPERANDS
-                const bool valid = false;
-#else
-                const bool valid = b_n != 0;
-#endif
-                const uint32_t off0 = valid ? b_ct * (2 * up_block_bytes(TT)) + lane_off : 0x80000000u;
-                load_operand(dst, off0, b_rsrc);
-                m = 0;
-                if (b_n != 0) {
-                    --b_n;
-                    ++b_ct;
-                    const bool wrap = b_ct == b_CT;
-                    m = 1u | ((wrap || b_n == 0) ? 2u : 0u) | (b_slot << 8);
-                    if (wrap) { b_ct = 0; ++b_slot; }
-                }
+                // raw buffer descriptor: base, stride 0, size (nothing without a tile), 32-bit untyped
+                v4i rsrc;
+                rsrc[0] = (int)d.lo;
+                rsrc[1] = (int)(d.hi & 0xffffu);
+                rsrc[2] = valid ? 2 * up_block_bytes(TT) : 0;
+                rsrc[3] = 0x00020000;
+                load_operand(dst, rsrc);
             };
 
             v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
@@ -559,7 +598,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #pragma unroll
                 for (int s = 0; s < NB; ++s) {
                     const uint32_t m = meta[s];
-                    if (!(m & 1u)) { more = false; break; }
+                    if (!(m & STEP_VALID)) { more = false; break; }
                     // Every step issues exactly KOP + 1 vector-memory loads (the operand loads, one
                     // sign tile or its stand-in) and loads complete in order.  The operand of this
                     // tile was requested NB steps ago, followed by wait_of(T) younger loads; the
@@ -607,8 +646,9 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #else
                     acc0[0] += __uint_as_float((w.x ^ w.y ^ w.z ^ w.w) & 0x007fffffu) + (float)b0[0] + (float)b1[0];
 #endif
-                    if (m & 2u) flush(m >> 8);
+                    if (m & STEP_FLUSH) flush((m >> STEP_SLOT_SHIFT) & 0xffu);
                     RB_STEP(2);
+                    ++steps_done;
                     issue_b(B[s], meta[s]);
                     issue_a();
                     RB_STEP(3);
@@ -619,8 +659,9 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             lds_barrier();                                    // partial sums of the stage are in LDS
             RB_TRACE(3);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land in LDS after the end
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land in LDS or registers after the end
         keep_operands();
+        keep_blocks();
         RB_TRACE_DUMP();
     } else {
         // ========================= finishing wavefront ======================
@@ -762,7 +803,10 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         for (int win = 0; win < READY_WINDOWS; ++win) publish(d, win, ~0ull);
                 };
                 bool narrow = true;                               // every op in the list has at most 64 blocks
-                for (int d = 0; d < nx.n_deps; ++d) narrow = narrow && col_tiles(ops[nx.dep[d]].out) <= 64;
+                // (the list is indexed with constants only: a run-time index would put it in scratch memory)
+#pragma unroll
+                for (int d = 0; d < MAX_DEPS; ++d)
+                    if (d < nx.n_deps) narrow = narrow && col_tiles(ops[nx.dep[d]].out) <= 64;
                 if (!all && narrow) {
                     // A load of this compute unit queues behind the weight prefetch of its compute
                     // wavefronts, so one round trip takes microseconds.  Keep several polls in flight:
@@ -772,7 +816,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     __amdgpu_buffer_rsrc_t flags[MAX_DEPS];
 #pragma unroll
                     for (int d = 0; d < MAX_DEPS; ++d) {
-                        const Op &pr = ops[nx.dep[d < nx.n_deps ? d : 0]];
+                        const Op &pr = ops[d < nx.n_deps ? nx.dep[d] : nx.dep[0]];
                         expect[d] = d < nx.n_deps ? min(16, (pr.out - 256 * lane + 15) >> 4) : 0;
                         flags[d] = __builtin_amdgcn_make_buffer_rsrc(pr.ready, 0, col_tiles(pr.out) * 16, 0x00020000);
                     }
@@ -805,7 +849,9 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 }
                 while (!all) {
                     all = true;
-                    for (int d = 0; d < nx.n_deps; ++d) {
+#pragma unroll
+                    for (int d = 0; d < MAX_DEPS; ++d) {
+                        if (d >= nx.n_deps) continue;
                         const Op &pr = ops[nx.dep[d]];
                         const int nwin = (col_tiles(pr.out) + 63) >> 6;
                         for (int win = 0; win < nwin; ++win) {
@@ -835,18 +881,19 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 }
 
 // ------------------------------------------------------------------ host ---
-static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t n_ready, size_t up_total)
+static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t n_ready, size_t up_total, size_t sblocks,
+                          size_t oblocks)
 {
     Layout L;
     size_t o = sizeof(Header);
     o = align_up(o, 128); L.ops = o; o += sizeof(Op) * (size_t)n_ops;
     o = align_up(o, 128); L.stages = o; o += sizeof(Stage) * (size_t)n_stages;
     o = align_up(o, 128); L.error = o; o += 128;
-    L.zero = o; o += 128;
+    L.zero = o; o += 1024;
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
     L.ready = o; o += align_up(n_ready, 128);
-    L.info = o; o += sizeof(OpInfo) * (size_t)n_ops;
-    o = align_up(o, 128); L.rec = o; o += sizeof(WaveRec) * (size_t)n_ops * (size_t)n_groups * CWAVES;
+    o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * CWAVES;
+    o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * CWAVES;
     o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 256); L.up = o; o += up_total;
@@ -882,13 +929,23 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
     }
     int G = device_groups();
     if (G <= 0) G = 1024;  // no device to ask: a bound on compute units
-    return make_layout(n_ops, n_ops, G, ready_max * (size_t)n_ops, align_up(up_max, 256) * (size_t)n_ops).total;
+    // steps of one compute wavefront: at most this many per op for the layer with the largest share
+    size_t per_op = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const size_t share = (size_t)((row_tiles(layers[l].out) + G - 1) / G) * col_tiles(layers[l].in);
+        per_op = std::max(per_op, (share + CWAVES - 1) / CWAVES + 1);
+    }
+    const size_t steps = per_op * (size_t)n_ops;
+    return make_layout(n_ops, n_ops, G, ready_max * (size_t)n_ops, align_up(up_max, 256) * (size_t)n_ops,
+                       desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)))
+        .total;
 }
 
 // Host record of a prepared plan, keyed by the workspace that holds its device part.
 struct Prepared {
     Layout lay;
     int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0, n_ready = 0;
+    uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
@@ -981,7 +1038,24 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             n_ready += (size_t)col_tiles(ops[(size_t)n].out) * 16;
         }
     pr.n_ready = (int)n_ready;
-    pr.lay = make_layout(n_ops, pr.n_stages, G, n_ready, up_total);
+    // longest step list of a compute wavefront (same arithmetic as desc_kernel)
+    {
+        size_t longest = 0;
+        for (uint32_t grp = 0; grp < (uint32_t)G; ++grp) {
+            size_t per_wave[CWAVES] = {0};
+            for (int n = 0; n < n_ops; ++n) {
+                uint32_t rt0, nrt;
+                group_rows((uint32_t)ops[(size_t)n].RT, grp, (uint32_t)G, rt0, nrt);
+                const uint32_t U = nrt * (uint32_t)ops[(size_t)n].CT;
+                for (uint32_t w = 0; w < (uint32_t)CWAVES; ++w) per_wave[w] += (w + 1) * U / CWAVES - w * U / CWAVES;
+            }
+            for (int w = 0; w < CWAVES; ++w) longest = std::max(longest, per_wave[w]);
+        }
+        // entries a wavefront reads: every tile's, plus the look-ahead past the end
+        pr.sblocks = desc_blocks((uint32_t)(longest + RING_D));
+        pr.oblocks = desc_blocks((uint32_t)(longest + (size_t)nb_of(T) * (size_t)pr.n_stages));
+    }
+    pr.lay = make_layout(n_ops, pr.n_stages, G, n_ready, up_total, pr.sblocks, pr.oblocks);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -1013,8 +1087,12 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     }
     hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
                        reinterpret_cast<Op *>(ws + lay.ops),
-                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero),
-                       reinterpret_cast<OpInfo *>(ws + lay.info), reinterpret_cast<WaveRec *>(ws + lay.rec));
+                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero));
+    hipLaunchKernelGGL(desc_kernel, dim3((G * CWAVES + 63) / 64), dim3(64), 0, stream,
+                       reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
+                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                       reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc),
+                       pr.sblocks, pr.oblocks);
     hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + 1) / 2), dim3(256), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
@@ -1049,7 +1127,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
         hipLaunchKernelGGL(kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
                            reinterpret_cast<const Stage *>(ws + lay.stages),
                            reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
-                           reinterpret_cast<const OpInfo *>(ws + lay.info), reinterpret_cast<const WaveRec *>(ws + lay.rec),
+                           reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
+                           pr.sblocks, pr.oblocks,
                            reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals));
         return RB_OK;
     };
