@@ -53,34 +53,68 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 // which also count as LDS traffic: every LDS wait would then wait for global stores to be acknowledged.
 #define RB_GLOBAL(T, p) ((__attribute__((address_space(1))) T *)(p))
 
+// Hand-over polling of the watching wavefront (see the stack kernel): polls in flight, pause
+// between polls, and the pause before the first poll of a stage for a wavefront that had nothing /
+// something to store (s_sleep units of 64 clocks).
+#ifndef RB_POLLS
+#define RB_POLLS 1
+#endif
+#ifndef RB_POLL_SLEEP
+#define RB_POLL_SLEEP 0
+#endif
+#ifndef RB_POLL_DELAY
+#define RB_POLL_DELAY 80
+#endif
+#ifndef RB_POLL_DELAY2
+#define RB_POLL_DELAY2 48
+#endif
+
 #ifdef RB_EXP_TRACE
 #ifndef RB_TRACE_GRP
 #define RB_TRACE_GRP 0
 #endif
-// experiment builds: per-stage timestamps of workgroup 0 (wavefronts 0 and CWAVES), printed at the end
+// experiment builds: per-stage timestamps of one workgroup (RB_TRACE_GRP < 0: of all of them, on the
+// clock all compute units share), wavefronts 0 and CWAVES, printed at the end
+#define RB_TRACE_ON (RB_TRACE_GRP < 0 ? grp % 8 == 3 : grp == RB_TRACE_GRP)
+#define RB_TRACE_NOW() (RB_TRACE_GRP < 0 ? __builtin_amdgcn_s_memrealtime() : __builtin_amdgcn_s_memtime())
+#define RB_TRACE_STAGES (RB_TRACE_GRP < 0 ? 10 : 64)
 #define RB_TRACE(k)                                                                                        \
     do {                                                                                                   \
-        if (grp == RB_TRACE_GRP && (wave == 0 || wave == CWAVES) && lane == 0 && st < 64)                             \
-            trace[((wave ? 64 : 0) + st) * 8 + (k)] = __builtin_amdgcn_s_memtime();                        \
+        if (RB_TRACE_ON && (wave == 0 || wave == CWAVES) && lane == 0 && st < 64)                             \
+            trace[((wave ? 64 : 0) + st) * 8 + (k)] = RB_TRACE_NOW();                        \
     } while (0)
 #define RB_TRACE_DUMP()                                                                                    \
     do {                                                                                                   \
-        if (grp == RB_TRACE_GRP && wave == 0 && lane == 0)                                                 \
+        if (RB_TRACE_GRP >= 0 && RB_TRACE_ON && wave == 0 && lane == 0)                                                 \
             for (int q = 0; q < 48; ++q)                                                                  \
                 printf("S %d %llu %llu %llu %llu\n", q, trace[128 * 8 + q * 4], trace[128 * 8 + q * 4 + 1], \
                        trace[128 * 8 + q * 4 + 2], trace[128 * 8 + q * 4 + 3]);                            \
-        if (grp == RB_TRACE_GRP && (wave == 0 || wave == CWAVES) && lane == 0)                             \
-            for (int q = 0; q < n_stages && q < 64; ++q) {                                                 \
+        if (RB_TRACE_ON && (wave == 0 || wave == CWAVES) && lane == 0)                             \
+            for (int q = 0; q < n_stages && q < RB_TRACE_STAGES; ++q) {                                                 \
                 const unsigned long long *tq = trace + ((wave ? 64 : 0) + q) * 8;                          \
-                printf("T w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu %llu\n", wave, q, stages[q].nops,  \
+                printf("T g%d w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu %llu\n", grp, wave, q, stages[q].nops,  \
                        tq[0], tq[1], tq[2], tq[3], tq[4], tq[5], tq[6], tq[7]);                            \
             }                                                                                              \
     } while (0)
-#define RB_TRACE_LDS (128 * 8 * 8 + 48 * 4 * 8)
+#define RB_TRACE_LDS (128 * 8 * 8 + 48 * 4 * 8 + EWAVES * 64 * 4 * 8)
+// every finishing wavefront: (k = 0) after the barrier, (1) stores issued, (2) stores acknowledged
+#define RB_FTRACE(k)                                                                                       \
+    do {                                                                                                   \
+        if (RB_TRACE_ON && lane == 0 && st < 64)                                                           \
+            trace[128 * 8 + 48 * 4 + (ew * 64 + st) * 4 + (k)] = RB_TRACE_NOW();                           \
+    } while (0)
+#define RB_FTRACE_DUMP()                                                                                   \
+    do {                                                                                                   \
+        if (RB_TRACE_ON && lane == 0)                                                                      \
+            for (int q = 0; q < n_stages && q < RB_TRACE_STAGES; ++q) {                                    \
+                const unsigned long long *tq = trace + 128 * 8 + 48 * 4 + (ew * 64 + q) * 4;               \
+                printf("F g%d e%d st%d %llu %llu %llu\n", grp, ew, q, tq[0], tq[1], tq[2]);                \
+            }                                                                                              \
+    } while (0)
 #define RB_STEP(k)                                                                                         \
     do {                                                                                                   \
-        if (grp == RB_TRACE_GRP && wave == 0 && lane == 0 && step_no < 48)                                           \
-            trace[128 * 8 + step_no * 4 + (k)] = __builtin_amdgcn_s_memtime();                             \
+        if (RB_TRACE_ON && wave == 0 && lane == 0 && step_no < 48)                                           \
+            trace[128 * 8 + step_no * 4 + (k)] = RB_TRACE_NOW();                             \
     } while (0)
 #define RB_STEP_NEXT() (++step_no)
 #else
@@ -89,6 +123,8 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 #define RB_STEP_NEXT() do { } while (0)
 #define RB_TRACE(k) do { } while (0)
 #define RB_TRACE_DUMP() do { } while (0)
+#define RB_FTRACE(k) do { } while (0)
+#define RB_FTRACE_DUMP() do { } while (0)
 #endif
 
 // ---------------------------------------------------------------- helpers ---
@@ -117,11 +153,14 @@ __device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
     return up_group_offset(T, j & ~15, 8 * tok + 4 * p + t) + (size_t)(j & 15);
 }
 
-// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt)
-__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, uint32_t &rt0, uint32_t &nrt)
+// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt).  Shares differ by one row
+// tile when G does not divide RT; every other op of a stage (pos = its position in the stage) deals
+// its shares out in the opposite order, so that the totals of a stage of like-shaped ops even out.
+__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
 {
-    rt0 = grp * RT / G;
-    nrt = (grp + 1) * RT / G - rt0;
+    const uint32_t g = (pos & 1) ? G - 1 - grp : grp;
+    rt0 = g * RT / G;
+    nrt = (g + 1) * RT / G - rt0;
 }
 
 // ------------------------------------------------------------ prep kernel ---
@@ -202,7 +241,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             const Op &op = ops[o];
             const uint32_t CT = (uint32_t)op.CT;
             uint32_t rt0, nrt;
-            group_rows((uint32_t)op.RT, grp, G, rt0, nrt);
+            group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
             const uint32_t U = nrt * CT, u0 = wave * U / CWAVES, u1 = (wave + 1) * U / CWAVES;
             for (uint32_t u = u0; u < u1; ++u) {
                 const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
@@ -231,7 +270,7 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     int my_op = -1, row0 = 0, slot_base = 0;
     for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
         uint32_t rt0, nrt;
-        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, rt0, nrt);
+        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, o - stage.op0, rt0, nrt);
         if (slot >= slot_base && slot < slot_base + (int)nrt) {
             my_op = o;
             row0 = (int)(rt0 + (uint32_t)(slot - slot_base)) * 16;
@@ -704,6 +743,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             RB_TRACE(4);
             lds_barrier();                                    // partial sums complete
             RB_TRACE(5);
+            RB_FTRACE(0);
             const bool have_slot = cur.r.op >= 0;
             const int grow = cur.r.row0 + row;
             const bool active = have_slot && tok < T && grow < cur.r.out;
@@ -774,6 +814,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
+                RB_FTRACE(1);
                 // publish: once the stores are acknowledged, raise the flag byte of this row tile (a plain
                 // device-scope store: read-modify-write counters shared by 16 producers took ~1 us per update)
 #ifdef RB_EXP_WBL2
@@ -781,6 +822,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 #else
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
+                RB_FTRACE(2);
                 if ((lane & 31) == 0 && have_slot && n_cons > 0)
                     asm volatile("global_store_byte %0, %1, off sc1" : : "v"(cur.r.ready), "v"(1u) : "memory");
             }
@@ -808,10 +850,13 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 for (int d = 0; d < MAX_DEPS; ++d)
                     if (d < nx.n_deps) narrow = narrow && col_tiles(ops[nx.dep[d]].out) <= 64;
                 if (!all && narrow) {
-                    // A load of this compute unit queues behind the weight prefetch of its compute
-                    // wavefronts, so one round trip takes microseconds.  Keep several polls in flight:
-                    // after the first has come back, a fresh sample arrives every fraction of that time.
-                    constexpr int POLLS = 4;
+                    // Measured on the 7B-shaped stack: a flag is seen by a load from another compute
+                    // unit about 1.4 us after its store at the earliest, and loads that reach the flag
+                    // lines while the 256 producers are still storing to them slow those stores down
+                    // (hand-overs of 7-13 us instead of 3-4 us).  So the first poll waits for the time a
+                    // flag needs anyway (longer if this wavefront had nothing to store and got here
+                    // early: s_sleep counts in units of 64 clocks), and only one poll is in flight.
+                    constexpr int POLLS = RB_POLLS;
                     int expect[MAX_DEPS];
                     __amdgpu_buffer_rsrc_t flags[MAX_DEPS];
 #pragma unroll
@@ -826,6 +871,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     auto raised = [&](v4u f) -> int {
                         return __builtin_popcount(f[0]) + __builtin_popcount(f[1]) + __builtin_popcount(f[2]) + __builtin_popcount(f[3]);
                     };
+                    if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(RB_POLL_DELAY2);
+                    else __builtin_amdgcn_s_sleep(RB_POLL_DELAY);
                     v4u q[POLLS][MAX_DEPS];
 #pragma unroll
                     for (int p = 0; p < POLLS; ++p)
@@ -836,6 +883,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                         for (int p = 0; p < POLLS; ++p) {
                             if (all) break;
                             all = true;
+                            if (RB_POLL_SLEEP > 0) __builtin_amdgcn_s_sleep(RB_POLL_SLEEP);
 #pragma unroll
                             for (int d = 0; d < MAX_DEPS; ++d) {
                                 const unsigned long long bal = __ballot(raised(q[p][d]) >= expect[d]);
@@ -868,8 +916,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     if (!all && ++spins > (1 << 16)) { give_up(); all = true; }
                 }
 #ifdef RB_EXP_TRACE
-                if (grp == RB_TRACE_GRP && lane == 0 && st < 64) {
-                    trace[(64 + st) * 8 + 7] = __builtin_amdgcn_s_memtime();
+                if (RB_TRACE_ON && lane == 0 && st < 64) {
+                    trace[(64 + st) * 8 + 7] = RB_TRACE_NOW();
                     trace[st * 8 + 7] = (unsigned long long)spins;
                 }
 #endif
@@ -877,6 +925,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             cur = nxt;
         }
         RB_TRACE_DUMP();
+        RB_FTRACE_DUMP();
     }
 }
 
@@ -1045,7 +1094,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             size_t per_wave[CWAVES] = {0};
             for (int n = 0; n < n_ops; ++n) {
                 uint32_t rt0, nrt;
-                group_rows((uint32_t)ops[(size_t)n].RT, grp, (uint32_t)G, rt0, nrt);
+                group_rows((uint32_t)ops[(size_t)n].RT, grp, (uint32_t)G, n - ops[(size_t)n].stage_op0, rt0, nrt);
                 const uint32_t U = nrt * (uint32_t)ops[(size_t)n].CT;
                 for (uint32_t w = 0; w < (uint32_t)CWAVES; ++w) per_wave[w] += (w + 1) * U / CWAVES - w * U / CWAVES;
             }
