@@ -20,9 +20,17 @@
 namespace rb {
 namespace mx {
 
-constexpr int CWAVES = 8;          // wavefronts that stream weights and issue MFMAs
+// Wavefronts that stream weights and issue MFMAs.  One compute unit holds one workgroup of at
+// most 16 wavefronts; what a step costs is instruction issue, so more wavefronts per SIMD help as
+// long as the registers suffice: twelve for one token (128 registers each), eight for two.
+#ifndef RB_CWAVES1
+#define RB_CWAVES1 12
+#endif
+constexpr int cwaves_of(int T) { return T == 1 ? RB_CWAVES1 : 8; }
+constexpr int MAX_CWAVES = 12;
+static_assert(cwaves_of(1) <= MAX_CWAVES && cwaves_of(2) <= MAX_CWAVES, "sizes of per-wavefront tables");
 constexpr int EWAVES = 4;          // wavefronts that finish rows and talk to other CUs
-constexpr int THREADS = (CWAVES + EWAVES) * 64;
+constexpr int threads_of(int T) { return (cwaves_of(T) + EWAVES) * 64; }
 #ifndef RB_RING_D
 #define RB_RING_D 6
 #endif
@@ -48,18 +56,21 @@ constexpr size_t MAX_EXPAND = 1024;
 static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1) <= 63 && wait_of(2) <= 63,
               "the in-order wait counts on this");
 
-// LDS map of the stack kernel
-constexpr int LDS_RING_BYTES = CWAVES * RING_D * 1024;
-// partial sums: [parity][slot][compute wavefront][path][token][row] fp32
-constexpr int LDS_PART_SLOT_BYTES = CWAVES * 2 * 2 * 16 * 4;
-constexpr int LDS_PART_BYTES = 2 * MAXSLOT * LDS_PART_SLOT_BYTES;
+// LDS map of the stack kernel with CW compute wavefronts
 constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
-constexpr int LDS_MISC_BYTES = 256 + CWAVES * 256 + EWAVES * LDS_STAGE_BYTES;   // + per-wavefront dummy-load target
-constexpr int LDS_RING_OFF = 0;
-constexpr int LDS_PART_OFF = LDS_RING_OFF + LDS_RING_BYTES;
-constexpr int LDS_MISC_OFF = LDS_PART_OFF + LDS_PART_BYTES;
-constexpr int LDS_BYTES = LDS_MISC_OFF + LDS_MISC_BYTES;
-static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+template <int CW> struct LdsMap {
+    static constexpr int RING_BYTES = CW * RING_D * 1024;
+    // partial sums: [parity][slot][compute wavefront][path][token][row] fp32
+    static constexpr int PART_SLOT_BYTES = CW * 2 * 2 * 16 * 4;
+    static constexpr int PART_BYTES = 2 * MAXSLOT * PART_SLOT_BYTES;
+    // hand-over bits, per-wavefront target of the stand-in loads, staging of the finishing wavefronts
+    static constexpr int MISC_BYTES = 256 + CW * 256 + EWAVES * LDS_STAGE_BYTES;
+    static constexpr int RING_OFF = 0;
+    static constexpr int PART_OFF = RING_OFF + RING_BYTES;
+    static constexpr int MISC_OFF = PART_OFF + PART_BYTES;
+    static constexpr int BYTES = MISC_OFF + MISC_BYTES;
+    static_assert(BYTES <= 160 * 1024, "LDS of one compute unit");
+};
 
 // Expanded input ("right operand") of one op, stored as the register image the MFMA wants, so
 // that one load instruction of a wavefront reads 1 KB of consecutive bytes (16 per lane).
@@ -162,7 +173,7 @@ struct Header {
 // workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]
 //            [indices of the ops whose input is expanded by a kernel of its own]
 //            [hand-over flags: one byte per row tile (padded to 16 per 256-row block) of every op that has a reader]
-//            [sign lists, operand lists: blocks x n_groups x CWAVES each]
+//            [sign lists, operand lists: blocks x n_groups x cwaves_of(T) each]
 //            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
 struct Layout {
     size_t ops, stages, error, zero, which, ready, sdesc, odesc, slots, vals, up, total;

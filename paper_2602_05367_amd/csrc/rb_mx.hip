@@ -66,7 +66,7 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 #define RB_POLL_DELAY 80
 #endif
 #ifndef RB_POLL_DELAY2
-#define RB_POLL_DELAY2 48
+#define RB_POLL_DELAY2 64
 #endif
 
 #ifdef RB_EXP_TRACE
@@ -74,13 +74,13 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 #define RB_TRACE_GRP 0
 #endif
 // experiment builds: per-stage timestamps of one workgroup (RB_TRACE_GRP < 0: of all of them, on the
-// clock all compute units share), wavefronts 0 and CWAVES, printed at the end
+// clock all compute units share), the first compute and the first finishing wavefront, printed at the end
 #define RB_TRACE_ON (RB_TRACE_GRP < 0 ? grp % 8 == 3 : grp == RB_TRACE_GRP)
 #define RB_TRACE_NOW() (RB_TRACE_GRP < 0 ? __builtin_amdgcn_s_memrealtime() : __builtin_amdgcn_s_memtime())
 #define RB_TRACE_STAGES (RB_TRACE_GRP < 0 ? 10 : 64)
 #define RB_TRACE(k)                                                                                        \
     do {                                                                                                   \
-        if (RB_TRACE_ON && (wave == 0 || wave == CWAVES) && lane == 0 && st < 64)                             \
+        if (RB_TRACE_ON && (wave == 0 || wave == CW) && lane == 0 && st < 64)                             \
             trace[((wave ? 64 : 0) + st) * 8 + (k)] = RB_TRACE_NOW();                        \
     } while (0)
 #define RB_TRACE_DUMP()                                                                                    \
@@ -89,7 +89,7 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
             for (int q = 0; q < 48; ++q)                                                                  \
                 printf("S %d %llu %llu %llu %llu\n", q, trace[128 * 8 + q * 4], trace[128 * 8 + q * 4 + 1], \
                        trace[128 * 8 + q * 4 + 2], trace[128 * 8 + q * 4 + 3]);                            \
-        if (RB_TRACE_ON && (wave == 0 || wave == CWAVES) && lane == 0)                             \
+        if (RB_TRACE_ON && (wave == 0 || wave == CW) && lane == 0)                             \
             for (int q = 0; q < n_stages && q < RB_TRACE_STAGES; ++q) {                                                 \
                 const unsigned long long *tq = trace + ((wave ? 64 : 0) + q) * 8;                          \
                 printf("T g%d w%d st%d nops%d %llu %llu %llu %llu %llu %llu %llu %llu\n", grp, wave, q, stages[q].nops,  \
@@ -205,15 +205,16 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
 
 // The step lists of the compute wavefronts; one thread per (workgroup, wavefront).  Row tiles of an
 // op are dealt to the workgroups in contiguous, nearly equal shares, and a share (row tiles x column
-// tiles, contiguous in the native layout) is cut into CWAVES contiguous runs.
+// tiles, contiguous in the native layout) is cut into one contiguous run per compute wavefront.
 __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *ops, const Stage *stages,
                                                   const uint32_t *zero_page, uint32_t *sdesc, uint32_t *odesc,
                                                   uint32_t sblocks, uint32_t oblocks)
 {
     const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x * 64 + threadIdx.x;
-    if (id >= G * CWAVES) return;
-    const uint32_t grp = id / CWAVES, wave = id % CWAVES;
     const int T = hdr->T, n_stages = hdr->n_stages;
+    const uint32_t CW = (uint32_t)cwaves_of(T);
+    if (id >= G * CW) return;
+    const uint32_t grp = id / CW, wave = id % CW;
     uint32_t *sd = sdesc + (size_t)id * sblocks * (SIGN_FIELDS * DESC_BLOCK);
     uint32_t *od = odesc + (size_t)id * oblocks * (OPND_FIELDS * DESC_BLOCK);
     const uint32_t s_cap = sblocks * DESC_BLOCK, o_cap = oblocks * DESC_BLOCK;
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             const uint32_t CT = (uint32_t)op.CT;
             uint32_t rt0, nrt;
             group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
-            const uint32_t U = nrt * CT, u0 = wave * U / CWAVES, u1 = (wave + 1) * U / CWAVES;
+            const uint32_t U = nrt * CT, u0 = wave * U / CW, u1 = (wave + 1) * U / CW;
             for (uint32_t u = u0; u < u1; ++u) {
                 const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
                 put_sign(gs++, (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
@@ -374,7 +375,7 @@ __device__ __forceinline__ float quad_sum(float v)
 template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile: two 128-column blocks
 
 template <int TT>
-__global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restrict__ hdr_p,
+__global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
                                                            uint32_t *__restrict__ error,
@@ -385,10 +386,12 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                                                            const SlotRec *__restrict__ slots_g,
                                                            const SlotVals *__restrict__ vals_g)
 {
+    constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
+    using Lds = LdsMap<CW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    float *part = reinterpret_cast<float *>(lds + LDS_PART_OFF);
+    float *part = reinterpret_cast<float *>(lds + Lds::PART_OFF);
 #ifdef RB_EXP_TRACE
-    unsigned long long *trace = reinterpret_cast<unsigned long long *>(lds + LDS_BYTES);
+    unsigned long long *trace = reinterpret_cast<unsigned long long *>(lds + Lds::BYTES);
 #endif
 
     const int lane = threadIdx.x & 63;
@@ -398,12 +401,12 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
     constexpr int T = TT, NB = nb_of(TT), KOP = kop_of(TT);
 
     // ---- LDS set-up: clear the partial sums
-    for (int i = threadIdx.x; i < LDS_PART_BYTES / 4; i += THREADS) part[i] = 0.f;
+    for (int i = threadIdx.x; i < Lds::PART_BYTES / 4; i += THREADS) part[i] = 0.f;
     __syncthreads();
 
-    if (wave < CWAVES) {
+    if (wave < CW) {
         // ======================= compute wavefront ==========================
-        uint8_t *const ring = lds + LDS_RING_OFF + wave * (RING_D * 1024);
+        uint8_t *const ring = lds + Lds::RING_OFF + wave * (RING_D * 1024);
         uint8_t *const ring_end = ring + RING_D * 1024;
         const int col = lane & 15, qd = lane >> 4;
         const int scale_b = (127 - 3 * (col & 3)) * 0x01010101;
@@ -413,7 +416,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         // A load that carries no data but keeps the number of vector-memory operations per
         // step constant (the in-order completion counter is what the ring relies on): four
         // bytes per lane from the zero page into a scratch corner of LDS.
-        uint8_t *dummy_dst = lds + LDS_MISC_OFF + 256 + wave * 256;
+        uint8_t *dummy_dst = lds + Lds::MISC_OFF + 256 + wave * 256;
         const uint32_t *dummy_src = zero_page;
         auto issue_dummies = [&](int n) {
             for (int i = 0; i < n; ++i) __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         // The replacing loads are written as instructions and never waited for by name: loads
         // complete in order and every step waits for all but its youngest few, so a block has
         // arrived a few steps after its request (steps_done tells when that cannot be relied on).
-        const size_t my_list = (size_t)grp * CWAVES + wave;
+        const size_t my_list = (size_t)grp * CW + wave;
         const uint32_t *sd_next = sdesc_g + my_list * sblocks * (SIGN_FIELDS * DESC_BLOCK) + lane;
         const uint32_t *od_next = odesc_g + my_list * oblocks * (OPND_FIELDS * DESC_BLOCK) + lane;
         int s_lo, s_hi, sn_lo, sn_hi;                 // sign list: current block, next block
@@ -571,7 +574,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             // this stage reads from and keeps one bit per 256-column block in LDS; nothing but that
             // wavefront polls memory.  A compute wavefront requests an operand tile only after its
             // bit is set, so no line of an expanded input is read before it is final.
-            const uint32_t ready_base = lds_addr(lds + LDS_MISC_OFF) + (uint32_t)((st & 1) * MAX_DEPS * READY_WINDOWS * 8);
+            const uint32_t ready_base = lds_addr(lds + Lds::MISC_OFF) + (uint32_t)((st & 1) * MAX_DEPS * READY_WINDOWS * 8);
             auto block_ready = [&](int dep, uint32_t ct) -> bool {
                 uint2 v;
                 asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)"
@@ -611,7 +614,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             // a quad of lanes holds the four terms of (path = quad & 1, token = quad >> 1); its
             // first lane writes rows 4*qd .. 4*qd+3 of that path and token
             const int quad = col >> 2;
-            const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * LDS_PART_SLOT_BYTES +
+            const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * Lds::PART_SLOT_BYTES +
                                        (uint32_t)wave * 256 + (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
             auto flush = [&](uint32_t slot) {
                 v4f v;
@@ -623,7 +626,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                 if ((col & 3) == 0)
                     asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                  :
-                                 : "v"(part_lane + slot * LDS_PART_SLOT_BYTES), "v"(v)
+                                 : "v"(part_lane + slot * Lds::PART_SLOT_BYTES), "v"(v)
                                  : "memory");
                 acc0 = (v4f){0, 0, 0, 0};
                 acc1 = (v4f){0, 0, 0, 0};
@@ -644,16 +647,13 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
                     // sign tile is older still (RING_D > NB).  So "at most wait_of(T) outstanding"
                     // means both have arrived.
                     RB_STEP(0);
-                    uint4 w;
-                    {
-                        const uint32_t addr = lds_addr(c_slot_ptr) + lane * 16;
-                        asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(w)
-                                     : "v"(addr), "n"(wait_of(TT))
-                                     : "memory");
+                    v4u w;
+                    asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(w)
+                                 : "v"(lds_addr(c_slot_ptr) + lane * 16), "n"(wait_of(TT))
+                                 : "memory");
 #pragma unroll
-                        for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
-                    }
+                    for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
                     RB_STEP(1);
                     c_slot_ptr += 1024;
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
@@ -704,13 +704,13 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         RB_TRACE_DUMP();
     } else {
         // ========================= finishing wavefront ======================
-        const int ew = wave - CWAVES;
+        const int ew = wave - CW;
         // lane -> (slot, row, token): a wavefront finishes two slots per stage, one per half
         const int half = lane >> 5;
         const int my_slot = ew + EWAVES * half;
         const int row = lane & 15, tok = (lane >> 4) & 1;
         // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
-        uint8_t *stage_bytes = lds + LDS_MISC_OFF + 256 + CWAVES * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
+        uint8_t *stage_bytes = lds + Lds::MISC_OFF + 256 + CW * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
 
         // Everything a stage's epilogue needs from memory sits in two flat tables indexed by
         // (stage, workgroup, slot) and is requested one stage ahead, while the compute wavefronts
@@ -732,7 +732,7 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
         };
         Fin cur = fetch(0);
 
-        const uint32_t ready_lds = lds_addr(lds + LDS_MISC_OFF);
+        const uint32_t ready_lds = lds_addr(lds + Lds::MISC_OFF);
         for (int st = 0; st < n_stages; ++st) {
             const Fin nxt = fetch(st + 1);
             // the bits of the next stage: nobody reads them before this stage's barrier
@@ -752,16 +752,16 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
             float yf = 0.f;
             if (active) {
                 // sum the partial sums of the compute wavefronts, clear them for the next use
-                float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CWAVES) * 64 + tok * 16 + row;
+                float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * 64 + tok * 16 + row;
                 float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-                for (int w = 0; w < CWAVES; ++w) {
+                for (int w = 0; w < CW; ++w) {
                     s0 += P[w * 64];
                     s1 += P[w * 64 + 32];
                 }
                 RB_TRACE(2);
 #pragma unroll
-                for (int w = 0; w < CWAVES; ++w) {
+                for (int w = 0; w < CW; ++w) {
                     P[w * 64] = 0.f;
                     P[w * 64 + 32] = 0.f;
                 }
@@ -930,8 +930,8 @@ __global__ __launch_bounds__(THREADS, 1) void stack_kernel(const Header *__restr
 }
 
 // ------------------------------------------------------------------ host ---
-static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t n_ready, size_t up_total, size_t sblocks,
-                          size_t oblocks)
+static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, size_t n_ready, size_t up_total,
+                          size_t sblocks, size_t oblocks)
 {
     Layout L;
     size_t o = sizeof(Header);
@@ -941,8 +941,8 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, size_t n_ready,
     L.zero = o; o += 1024;
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
     L.ready = o; o += align_up(n_ready, 128);
-    o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * CWAVES;
-    o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * CWAVES;
+    o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * (size_t)cwaves;
+    o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * (size_t)cwaves;
     o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 256); L.up = o; o += up_total;
@@ -979,13 +979,14 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
     int G = device_groups();
     if (G <= 0) G = 1024;  // no device to ask: a bound on compute units
     // steps of one compute wavefront: at most this many per op for the layer with the largest share
+    const size_t CW = (size_t)cwaves_of(T);
     size_t per_op = 0;
     for (int l = 0; l < n_layers; ++l) {
         const size_t share = (size_t)((row_tiles(layers[l].out) + G - 1) / G) * col_tiles(layers[l].in);
-        per_op = std::max(per_op, (share + CWAVES - 1) / CWAVES + 1);
+        per_op = std::max(per_op, (share + CW - 1) / CW + 1);
     }
     const size_t steps = per_op * (size_t)n_ops;
-    return make_layout(n_ops, n_ops, G, ready_max * (size_t)n_ops, align_up(up_max, 256) * (size_t)n_ops,
+    return make_layout(n_ops, n_ops, G, (int)CW, ready_max * (size_t)n_ops, align_up(up_max, 256) * (size_t)n_ops,
                        desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)))
         .total;
 }
@@ -1089,22 +1090,23 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     pr.n_ready = (int)n_ready;
     // longest step list of a compute wavefront (same arithmetic as desc_kernel)
     {
+        const uint32_t CW = (uint32_t)cwaves_of(T);
         size_t longest = 0;
         for (uint32_t grp = 0; grp < (uint32_t)G; ++grp) {
-            size_t per_wave[CWAVES] = {0};
+            size_t per_wave[MAX_CWAVES] = {0};
             for (int n = 0; n < n_ops; ++n) {
                 uint32_t rt0, nrt;
                 group_rows((uint32_t)ops[(size_t)n].RT, grp, (uint32_t)G, n - ops[(size_t)n].stage_op0, rt0, nrt);
                 const uint32_t U = nrt * (uint32_t)ops[(size_t)n].CT;
-                for (uint32_t w = 0; w < (uint32_t)CWAVES; ++w) per_wave[w] += (w + 1) * U / CWAVES - w * U / CWAVES;
+                for (uint32_t w = 0; w < CW; ++w) per_wave[w] += (w + 1) * U / CW - w * U / CW;
             }
-            for (int w = 0; w < CWAVES; ++w) longest = std::max(longest, per_wave[w]);
+            for (uint32_t w = 0; w < CW; ++w) longest = std::max(longest, per_wave[w]);
         }
         // entries a wavefront reads: every tile's, plus the look-ahead past the end
         pr.sblocks = desc_blocks((uint32_t)(longest + RING_D));
         pr.oblocks = desc_blocks((uint32_t)(longest + (size_t)nb_of(T) * (size_t)pr.n_stages));
     }
-    pr.lay = make_layout(n_ops, pr.n_stages, G, n_ready, up_total, pr.sblocks, pr.oblocks);
+    pr.lay = make_layout(n_ops, pr.n_stages, G, cwaves_of(T), n_ready, up_total, pr.sblocks, pr.oblocks);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -1137,7 +1139,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
                        reinterpret_cast<Op *>(ws + lay.ops),
                        reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero));
-    hipLaunchKernelGGL(desc_kernel, dim3((G * CWAVES + 63) / 64), dim3(64), 0, stream,
+    hipLaunchKernelGGL(desc_kernel, dim3((G * cwaves_of(T) + 63) / 64), dim3(64), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<const uint32_t *>(ws + lay.zero),
                        reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc),
@@ -1169,11 +1171,11 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (pr.n_ready > 0)
         hipLaunchKernelGGL(clear_kernel, dim3((pr.n_ready / 4 + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint32_t *>(ws + lay.ready), pr.n_ready / 4);
-    auto launch = [&](auto kernel) -> int {
+    auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                LDS_BYTES + RB_TRACE_LDS) != hipSuccess)
+                                lds_bytes + RB_TRACE_LDS) != hipSuccess)
             return RB_ERR_HIP;
-        hipLaunchKernelGGL(kernel, dim3(pr.G), dim3(THREADS), LDS_BYTES + RB_TRACE_LDS, stream, d_hdr, d_ops,
+        hipLaunchKernelGGL(kernel, dim3(pr.G), dim3(threads), lds_bytes + RB_TRACE_LDS, stream, d_hdr, d_ops,
                            reinterpret_cast<const Stage *>(ws + lay.stages),
                            reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
                            reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
@@ -1181,7 +1183,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals));
         return RB_OK;
     };
-    const int rc = pr.T == 1 ? launch(stack_kernel<1>) : launch(stack_kernel<2>);
+    const int rc = pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+                             : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
     if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
