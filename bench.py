@@ -225,15 +225,23 @@ def main() -> int:
             prefill[f"{o}x{i}"] = {"ms": msp, "TFLOPs": flops / msp / 1e9, "frac_of_fp16_mfma_peak": flops / msp / 1e9 / 2500.0}
             del bits, Lp, Xp, Yp, wsp
         result["prefill_gemm_T2048"] = prefill
-        # small decode batches (configs[2]): the 7B-shaped stack, every op on its own input buffer
+        # small decode batches (configs[2]): the 7B-shaped stack, every op on its own input buffer.
+        # Up to 8 tokens the prepared stack runs the fused decode kernel (one launch per pair of tokens);
+        # beyond that every op is a launch sequence of the many-token kernel.
         skinny = {}
-        for Ts in (4, 16):
+        for Ts in (2, 4, 8, 16):
             fbs = [torch.randn(Ts, w, device="cuda").half() for w in (4096, 11008)]
             outs_s = [torch.zeros((Ts, op.out), dtype=torch.float16, device="cuda") for op in ops]
             st_s = rb.Stack(layers, [(n, 0 if op.inn == 4096 else 1, 2 + n) for n, op in enumerate(ops)], fbs + outs_s, Ts)
-            _, per_s = time_steps(torch, st_s.run, 4, 1)
+            if Ts <= 8:
+                st_s.prepare()
+                _, per_s = time_steps(torch, st_s.run_prepared, 8, 2)
+                st_s.forget()
+            else:
+                _, per_s = time_steps(torch, st_s.run, 4, 1)
             ms_s = sum(per_s) / len(per_s)
-            skinny[f"T{Ts}"] = {"ms_per_pass": ms_s, "tokens_per_s": Ts / (ms_s * 1e-3), "GBps": packed_bytes / (ms_s * 1e-3) / 1e9}
+            skinny[f"T{Ts}"] = {"ms_per_pass": ms_s, "tokens_per_s": Ts / (ms_s * 1e-3), "GBps": packed_bytes / (ms_s * 1e-3) / 1e9,
+                                "entry_point": "rb_stack_run" if Ts <= 8 else "rb_layer_stack"}
             del fbs, outs_s, st_s
         result["small_batch_stack"] = skinny
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)

@@ -58,6 +58,10 @@ extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_s
     const int rc = check_stack(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes);
     if (rc != RB_OK) return rc;
     if (!workspace) return RB_ERR_WORKSPACE;
+    rb::forget_pairs(workspace);
+    if (T > 2)
+        return rb::prepare_pairs(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
+                                 static_cast<hipStream_t>(stream));
     for (int n = 0; n < n_ops; ++n)
         if (!rb::mx::layer_supported(&layers[ops[n].layer], T)) return RB_ERR_UNSUPPORTED;
     return rb::mx::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes,
@@ -67,7 +71,9 @@ extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_s
 extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace) return RB_ERR_NULL;
-    const int rc = rb::mx::launch_plan(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    int rc = rb::run_pairs(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    if (rc == RB_ERR_UNSUPPORTED)
+        rc = rb::mx::launch_plan(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     if (rc == RB_OK) rb::set_last_path(RB_PATH_MX);
     return rc;
 }
@@ -75,6 +81,7 @@ extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *strea
 extern "C" int rb_stack_forget(const void *workspace)
 {
     if (!workspace) return RB_ERR_NULL;
+    rb::forget_pairs(workspace);
     rb::mx::forget_plan(workspace);
     return RB_OK;
 }

@@ -23,6 +23,13 @@ int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes,
                    hipStream_t stream);
 
+// stacks of 3..8 tokens as passes of the fused two-token kernel over token pairs: one plan per pair
+// in consecutive parts of the workspace (RB_ERR_UNSUPPORTED where that does not apply)
+int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs,
+                  int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
+int run_pairs(void *workspace, size_t workspace_bytes, hipStream_t stream);
+void forget_pairs(const void *workspace);
+
 namespace gemm {
 // many-token matrix-core GEMM (K = 2): workspace holds the scaled input of both paths
 bool supported(const rb_layer *L, int T);

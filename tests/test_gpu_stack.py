@@ -16,14 +16,24 @@ from helpers import TOL, build_stack, to_device_layer, random_layer
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_check(ops, widths, layers, bufs0, T, label):
+def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
     dev_layers = [to_device_layer(*l) for l in layers]
     dev_bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
     dev_bufs[0].copy_(torch.from_numpy(bufs0[0]))
     op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
-    print(f"{label}: {len(ops)} ops, T={T}", flush=True)
-    rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
+    print(f"{label}: {len(ops)} ops, T={T}, prepared={prepared}", flush=True)
+    if prepared:
+        stack = rb.Stack(dev_layers, op_list, dev_bufs, T)
+        stack.prepare()
+        stack.run_prepared()
+        torch.cuda.synchronize()
+        assert rb.rb_last_path() == rb.RB_PATH_MX
+        stack.forget()
+    else:
+        rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
     torch.cuda.synchronize()
+    # 3..8 tokens run as token pairs on the fused kernel, a single call on the many-token kernel
+    same_kernel = T <= 2 or T > 8
     got = [b.cpu().numpy() for b in dev_bufs]
     forced = [got[op.src] for op in ops]
     refs = oracle.stack_forward(layers, op_list, [None] * len(widths), forced_inputs=forced)
@@ -35,7 +45,10 @@ def _run_and_check(ops, widths, layers, bufs0, T, label):
         assert err <= TOL, (op.name, err)
         # the op must equal the single-layer call on the same input
         y1 = rb.rb_linear_gemm(dev_layers[n], dev_bufs[op.src])
-        assert torch.equal(y1, dev_bufs[op.dst]), op.name
+        if same_kernel:
+            assert torch.equal(y1, dev_bufs[op.dst]), op.name
+        else:
+            assert float(oracle.relative_l2(y1.cpu().numpy().astype(np.float64), refs[n]).max()) <= TOL, op.name
     # free-running drift against the oracle's own chain: information only
     drift = float(oracle.relative_l2(got[ops[-1].dst].astype(np.float64),
                                      bufs0[ops[-1].dst].astype(np.float64)).max())
@@ -54,13 +67,23 @@ def test_one_full_width_7b_block_derived():
     _run_and_check(ops, widths, layers, bufs, 1, "one 7B-shaped block, derived")
 
 
-@pytest.mark.parametrize("T", [2, 16])
+@pytest.mark.parametrize("T", [2, 4, 16])
 def test_small_stack_batched_with_outliers(T):
     shrink = {4096: 512, 11008: 1376}
     # uniform-sign layers with 0.02-scale g and h: a gain on g keeps activations near RMS 1
     ops, widths, layers, bufs = build_stack("7b", 2, 3, T, derived=False, shrink=shrink, outliers=True,
                                             gain=100.0)
     _run_and_check(ops, widths, layers, bufs, T, "batched small stack")
+
+
+@pytest.mark.parametrize("T", [3, 8])
+def test_prepared_small_batches_run_as_token_pairs(T):
+    """rb_stack_prepare / rb_stack_run at 3..8 tokens: one launch of the fused kernel per pair of
+    tokens (one token in the last launch when T is odd), every op checked against the oracle."""
+    shrink = {4096: 512, 11008: 1376}
+    ops, widths, layers, bufs = build_stack("7b", 2, 5, T, derived=False, shrink=shrink, outliers=True,
+                                            gain=100.0)
+    _run_and_check(ops, widths, layers, bufs, T, "prepared small batch", prepared=True)
 
 
 def test_one_13b_block_derived():
