@@ -26,7 +26,10 @@ namespace mx {
 #ifndef RB_CWAVES1
 #define RB_CWAVES1 12
 #endif
-constexpr int cwaves_of(int T) { return T == 1 ? RB_CWAVES1 : 8; }
+#ifndef RB_CWAVES2
+#define RB_CWAVES2 8
+#endif
+constexpr int cwaves_of(int T) { return T == 1 ? RB_CWAVES1 : RB_CWAVES2; }
 constexpr int MAX_CWAVES = 12;
 static_assert(cwaves_of(1) <= MAX_CWAVES && cwaves_of(2) <= MAX_CWAVES, "sizes of per-wavefront tables");
 constexpr int EWAVES = 4;          // wavefronts that finish rows and talk to other CUs
