@@ -138,6 +138,7 @@ def main() -> int:
         "pct_of_hbm_peak": 100.0 * packed_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "us_per_layer": ms * 1e3 / len(ops),
         "ms_per_step_min": ms_min,
+        "ms_per_step_median": sorted(per)[len(per) // 2],
         "wall_ms_per_step": wall * 1e3 / args.steps,
     }
     # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, scaled
@@ -179,6 +180,44 @@ def main() -> int:
         result["independent_ops"] = {"ms_per_step": ms_f, "GBps": packed_bytes / (ms_f * 1e-3) / 1e9,
                                      "pct_of_hbm_peak": 100.0 * packed_bytes / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         free.forget()
+        # single calls (rb_linear_gemv) on the three 7B shapes: cold = rotating over distinct weight
+        # copies (more than the 256 MB cache holds), warm = the same matrix again and again
+        single = {}
+        for (o, i) in ((4096, 4096), (11008, 4096), (4096, 11008)):
+            nb = rb.rb_native_bytes(2, o, i)
+            copies = max(80, (1 << 30) // nb)
+            pool = torch.randint(-2 ** 31, 2 ** 31 - 1, (copies, nb // 4), dtype=torch.int32, device="cuda")
+            gg = (torch.randn(2, o, device="cuda").abs() * 0.02).half()
+            hh = (torch.randn(2, i, device="cuda").abs() * 0.02).half()
+            Ls = [rb.Layer(pool[c], gg, hh, 2, o, i) for c in range(copies)]
+            xs = torch.randn(1, i, device="cuda").half()
+            ys = torch.empty((1, o), dtype=torch.float16, device="cuda")
+            wss = rb.binding._workspace([Ls[0]], 1, xs.device)
+            k = [0]
+
+            def cold(Ls=Ls, xs=xs, ys=ys, wss=wss, k=k, copies=copies):
+                rb.rb_linear_gemm(Ls[k[0] % copies], xs, Y=ys, workspace=wss)
+                k[0] += 1
+            _, per_c = time_steps(torch, cold, 160, 16)
+            _, per_w = time_steps(torch, lambda: rb.rb_linear_gemm(Ls[0], xs, Y=ys, workspace=wss), 50, 10)
+            pb = 2 * o * i // 8
+            med_c, med_w = sorted(per_c)[len(per_c) // 2], sorted(per_w)[len(per_w) // 2]
+            single[f"{o}x{i}"] = {"cold_us_median": med_c * 1e3, "cold_us_min": min(per_c) * 1e3,
+                                  "cold_GBps": pb / (med_c * 1e-3) / 1e9,
+                                  "warm_us_median": med_w * 1e3, "warm_GBps_cache_resident": pb / (med_w * 1e-3) / 1e9}
+            del pool, Ls, wss
+        result["single_call_gemv"] = single
+        # the 13B-shaped stack (configs[3]): 40 blocks x (4 x 5120^2, 2 x 13824x5120, 5120x13824)
+        ops13, layers13, bufs13, op_list13, packed13 = build_stack(rb, synth, torch, "13b", T)
+        stack13 = rb.Stack(layers13, op_list13, bufs13, T)
+        stack13.prepare()
+        _, per13 = time_steps(torch, stack13.run_prepared, 30, 5)
+        ms13 = sum(per13) / len(per13)
+        result["stack_13b"] = {"ms_per_token": ms13, "tokens_per_s": 1.0 / (ms13 * 1e-3), "packed_bytes": packed13,
+                               "GBps": packed13 / (ms13 * 1e-3) / 1e9,
+                               "pct_of_hbm_peak": 100.0 * packed13 / (ms13 * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        stack13.forget()
+        del ops13, layers13, bufs13, stack13
         # one-call form (set-up inside the call)
         _, per_o = time_steps(torch, stack.run, 20, 3)
         result["rb_layer_stack_ms"] = sum(per_o) / len(per_o)
