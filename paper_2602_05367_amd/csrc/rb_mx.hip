@@ -619,10 +619,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             auto flush = [&](uint32_t slot) {
                 v4f v;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float s0 = quad_sum(acc0[r]), s1 = quad_sum(acc1[r]);
-                    v[r] = (quad & 1) ? s1 : s0;
-                }
+                for (int r = 0; r < 4; ++r)       // the four lanes of a quad hold terms of the same path
+                    v[r] = quad_sum((quad & 1) ? acc1[r] : acc0[r]);
                 if ((col & 3) == 0)
                     asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                  :
