@@ -171,8 +171,8 @@ int rb_stream_read_groups(void);
 /* Which kernel family the most recent compute call of this thread enqueued:
  * RB_PATH_NONE, RB_PATH_SIGNADD (generic sign-XOR + add kernel, one launch per
  * op), RB_PATH_GEMM (many-token matrix-core GEMM, one launch per op) or
- * RB_PATH_MX (matrix-core kernel, all ops of the call in one persistent
- * launch).  For tests and benchmarks that must know what they measured. */
+ * RB_PATH_MX (matrix-core decode kernels: one layer and token in one launch,
+ * or all ops of a stack in one persistent launch).  For tests and benchmarks that must know what they measured. */
 #define RB_PATH_NONE    0
 #define RB_PATH_SIGNADD 1
 #define RB_PATH_MX      2

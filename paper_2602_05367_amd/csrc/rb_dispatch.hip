@@ -117,6 +117,10 @@ void forget_pairs(const void *workspace)
 int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
                     void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    if (act_dtype == RB_F16 && out_dtype == RB_F16 && gemv1::supported(L, T)) {
+        g_last_path = RB_PATH_MX;
+        return gemv1::launch(L, X, Y, stream);
+    }
     if (act_dtype == RB_F16 && out_dtype == RB_F16 && mx::layer_supported(L, T) && workspace &&
         workspace_bytes >= mx::plan_workspace_bytes(L, 1, 1, T)) {
         const rb_stack_op op{0, 0, 1};

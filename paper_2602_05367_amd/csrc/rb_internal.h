@@ -38,7 +38,16 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
            hipStream_t stream);
 }  // namespace gemm
 
+namespace gemv1 {
+// one layer, one token, one launch, nothing prepared (K = 2; the expanded input must fit in LDS);
+// same bits as the op would give inside a stack
+bool supported(const rb_layer *L, int T);
+int launch(const rb_layer *L, const void *x, void *y, hipStream_t stream);
+}  // namespace gemv1
+
 namespace mx {
+// workgroups of the decode kernels: one per compute unit of the current device (0: no device)
+int device_groups();
 // matrix-core path (K = 2, T <= 2): whole op lists run as one persistent kernel
 bool layer_supported(const rb_layer *L, int T);
 size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);

@@ -4,7 +4,7 @@
 // Work split of the persistent kernel (one workgroup per compute unit):
 //   * every op's row tiles are cut into contiguous shares, one per workgroup;
 //     a share is a contiguous run of 1 KB sign tiles in the native layout and
-//     is cut again into eight runs, one per compute wavefront;
+//     is cut again into one run per compute wavefront;
 //   * what each compute wavefront does is written out once per plan as a list
 //     of steps (tile address, operand address, what to do afterwards), so the
 //     kernel's loop has no op tables to search;
@@ -18,14 +18,14 @@
 //     next, written with device-scope 16-byte stores.  Keeping this traffic on
 //     wavefronts of their own means no wait on it ever drains a weight prefetch;
 //   * hand-over between compute units: a finishing wavefront, once its stores
-//     are acknowledged, adds one to a device-scope counter of the 256-row block
-//     of y its row tile belongs to; a compute wavefront reads the counters of
-//     the op that writes its input (one load covers 64 blocks) before it
-//     requests the first expanded-input tile of a block, and only then touches
-//     those bytes.  Nothing reads a line before it is final, so the reads may be
-//     plain ones that the 32 compute units of an XCD share in its L2; device-
-//     coherent reads of every operand would put twice the weight traffic on the
-//     fabric that also carries the HBM stream.
+//     are acknowledged, raises the flag byte of its row tile; one finishing
+//     wavefront per workgroup watches the flags of the ops the next stage reads
+//     and keeps one bit per 256-row block in LDS; a compute wavefront requests
+//     an expanded-input tile only after its bit is set.  Nothing reads a line
+//     before it is final, so the reads may be plain ones that the 32 compute
+//     units of an XCD share in its L2; device-coherent reads of every operand
+//     would put twice the weight traffic on the fabric that also carries the
+//     HBM stream.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -39,14 +39,11 @@
 #include "rb_internal.h"
 #include "rb_layout.h"
 #include "rb_mx.h"
+#include "rb_mx_device.h"
 
 namespace rb {
 namespace mx {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 #define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 // Pointers read from the op table are generic; dereferencing them as such makes FLAT instructions,
@@ -133,36 +130,6 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
     return (uint32_t)(size_t)RB_LDS(p);
 }
 
-// four bf8 terms of u: u ~= t0 + t1/8 + t2/64 + t3/512 (each term rounds the rest)
-__device__ __forceinline__ uint32_t expand4(float u)
-{
-    uint32_t out = 0;
-    float r = u;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int pk = __builtin_amdgcn_cvt_pk_bf8_f32(r, 0.f, 0, false);
-        out |= (uint32_t)(pk & 0xff) << (8 * t);
-        r = (r - __builtin_amdgcn_cvt_f32_bf8(pk, 0)) * 8.f;
-    }
-    return out;
-}
-
-// byte address of (token, path, term, input column j) in an op's expanded input
-__device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
-{
-    return up_group_offset(T, j & ~15, 8 * tok + 4 * p + t) + (size_t)(j & 15);
-}
-
-// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt).  Shares differ by one row
-// tile when G does not divide RT; every other op of a stage (pos = its position in the stage) deals
-// its shares out in the opposite order, so that the totals of a stage of like-shaped ops even out.
-__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
-{
-    const uint32_t g = (pos & 1) ? G - 1 - grp : grp;
-    rt0 = g * RT / G;
-    nrt = (g + 1) * RT / G - rt0;
-}
-
 // ------------------------------------------------------------ prep kernel ---
 // One workgroup per op: power-of-two scale of each path's input scales and the zero fill of the
 // expanded-input array (padding columns and unused operand columns must read as zero).
@@ -182,13 +149,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
             __syncthreads();
         }
         if (threadIdx.x == 0) {
-            const float mx_ = red[0];
-            float sc = 1.f;
-            if (mx_ > 0.f && mx_ < INFINITY) {
-                int e;
-                frexpf(mx_, &e);                 // mx_ = f * 2^e, f in [0.5, 1)
-                sc = ldexpf(1.f, -e - 1);        // mx_ * sc in [0.25, 0.5)
-            }
+            const float sc = input_scale(red[0]);
             op.sc[p] = sc;
             op.inv_sc[p] = 1.f / sc;
         }
@@ -352,26 +313,6 @@ __device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
            (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
 }
 
-__device__ __forceinline__ v4f mfma_signs(uint32_t w, v8i b, v4f acc, uint32_t c22, int scale_b)
-{
-    v8i a;
-    a[0] = (int)(((w << 3) & 0x88888888u) | c22);
-    a[1] = (int)(((w << 2) & 0x88888888u) | c22);
-    a[2] = (int)(((w << 1) & 0x88888888u) | c22);
-    a[3] = (int)((w & 0x88888888u) | c22);
-    a[4] = 0; a[5] = 0; a[6] = 0; a[7] = 0;
-    // A: fp4 (cbsz = 4), B: bf8 (blgp = 1); scale bytes are E8M0 exponents
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 1, 0, 0x7f7f7f7f, 0, scale_b);
-}
-
-// sum over the four lanes of a quad (the four terms of one path and token)
-__device__ __forceinline__ float quad_sum(float v)
-{
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));   // 1,0,3,2
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));   // 2,3,0,1
-    return v;
-}
-
 template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile: two 128-column blocks
 
 template <int TT>
@@ -409,7 +350,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         uint8_t *const ring = lds + Lds::RING_OFF + wave * (RING_D * 1024);
         uint8_t *const ring_end = ring + RING_D * 1024;
         const int col = lane & 15, qd = lane >> 4;
-        const int scale_b = (127 - 3 * (col & 3)) * 0x01010101;
+        const int scale_b = term_scale(col);
         const uint32_t lane_off = (uint32_t)lane * 16u;
         uint32_t c22;
         asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c22));
@@ -764,7 +705,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     P[w * 64 + 32] = 0.f;
                 }
                 RB_TRACE(3);
-                const _Float16 y16 = (_Float16)(cur.a[0] * s0 + cur.a[1] * s1);      // round to nearest even
+                const _Float16 y16 = (_Float16)path_sum(cur.a[0], s0, cur.a[1], s1);   // round to nearest even
                 RB_GLOBAL(_Float16, cur.r.y)[(size_t)tok * cur.r.out + grow] = y16;
                 yf = (float)y16;
             }
@@ -948,7 +889,7 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, siz
     return L;
 }
 
-static int device_groups()
+int device_groups()
 {
     static int cus = 0;
     if (cus == 0) {

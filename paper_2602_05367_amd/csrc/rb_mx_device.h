@@ -1,0 +1,97 @@
+// Device arithmetic shared by the matrix-core decode kernels (the persistent stack kernel and the
+// single-op kernel): both must produce the same bits for the same op, so everything that rounds
+// lives here once.  See rb_mx.h for the formats.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "rb_mx.h"
+
+namespace rb {
+namespace mx {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// power-of-two scale of one path's input scales: max|h| * sc lies in [1/4, 1/2), so that
+// |h x sc| < 2^15 for any fp16 x (1 for an all-zero or non-finite h)
+__device__ __forceinline__ float input_scale(float max_abs_h)
+{
+    float sc = 1.f;
+    if (max_abs_h > 0.f && max_abs_h < INFINITY) {
+        int e;
+        frexpf(max_abs_h, &e);              // max_abs_h = f * 2^e, f in [0.5, 1)
+        sc = ldexpf(1.f, -e - 1);
+    }
+    return sc;
+}
+
+// four bf8 terms of u: u ~= t0 + t1/8 + t2/64 + t3/512 (each term rounds the rest)
+__device__ __forceinline__ uint32_t expand4(float u)
+{
+    uint32_t out = 0;
+    float r = u;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int pk = __builtin_amdgcn_cvt_pk_bf8_f32(r, 0.f, 0, false);
+        out |= (uint32_t)(pk & 0xff) << (8 * t);
+        r = (r - __builtin_amdgcn_cvt_f32_bf8(pk, 0)) * 8.f;
+    }
+    return out;
+}
+
+// byte address of (token, path, term, input column j) in an op's expanded input
+__device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
+{
+    return up_group_offset(T, j & ~15, 8 * tok + 4 * p + t) + (size_t)(j & 15);
+}
+
+// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt).  Shares differ by one row
+// tile when G does not divide RT; every other op of a stage (pos = its position in the stage) deals
+// its shares out in the opposite order, so that the totals of a stage of like-shaped ops even out.
+__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
+{
+    const uint32_t g = (pos & 1) ? G - 1 - grp : grp;
+    rt0 = g * RT / G;
+    nrt = (g + 1) * RT / G - rt0;
+}
+
+// 16 rows x 128 columns of one path's signs (one word per lane, see rb_layout.h) times the 16
+// operand columns of b, accumulated into acc
+__device__ __forceinline__ v4f mfma_signs(uint32_t w, v8i b, v4f acc, uint32_t c22, int scale_b)
+{
+    v8i a;
+    a[0] = (int)(((w << 3) & 0x88888888u) | c22);
+    a[1] = (int)(((w << 2) & 0x88888888u) | c22);
+    a[2] = (int)(((w << 1) & 0x88888888u) | c22);
+    a[3] = (int)((w & 0x88888888u) | c22);
+    a[4] = 0; a[5] = 0; a[6] = 0; a[7] = 0;
+    // A: fp4 (cbsz = 4), B: bf8 (blgp = 1); scale bytes are E8M0 exponents
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 1, 0, 0x7f7f7f7f, 0, scale_b);
+}
+
+// E8M0 scale bytes of the right operand for the lane that holds operand column col: term t = col % 4
+// carries the factor 8^-t
+__device__ __forceinline__ int term_scale(int col) { return (127 - 3 * (col & 3)) * 0x01010101; }
+
+// sum over the four lanes of a quad (the four terms of one path and token)
+__device__ __forceinline__ float quad_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));   // 1,0,3,2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));   // 2,3,0,1
+    return v;
+}
+
+// y = (g_1 / sc_1) * acc_1 + (g_2 / sc_2) * acc_2, one rounding of the product of path 2 and one of the sum
+__device__ __forceinline__ float path_sum(float a0, float s0, float a1, float s1)
+{
+    return __builtin_fmaf(a0, s0, a1 * s1);
+}
+
+}  // namespace mx
+}  // namespace rb
