@@ -136,3 +136,44 @@ def test_independent_ops_need_no_hand_over():
     for n in range(len(shapes)):
         ref = oracle.forward(*layers[n], xs[n])
         assert oracle.relative_l2(bufs[len(shapes) + n].cpu().numpy().astype(np.float64), ref).max() <= TOL
+
+
+def test_full_7b_stack_as_benchmarked_sampled_outputs():
+    """The 224-op 7B-shaped stack exactly as bench.py builds and times it (prepared, one launch per
+    token, signs drawn on the device in native order).  For the ops of the first, a middle and the
+    last block, 48 sampled rows are recomputed by the oracle from the unpacked rows and from the
+    input the GPU run actually used; a second run over the same input must repeat the first bit
+    for bit (flags and scratch are cleared correctly between launches)."""
+    import bench
+    ops, layers, bufs, op_list, packed_bytes = bench.build_stack(rb, synth, torch, "7b", 1)
+    assert len(ops) == 224 and packed_bytes == 1619001344
+    stack = rb.Stack(layers, op_list, bufs, 1)
+    stack.prepare()
+    print("full 7B-shaped stack, prepared, run 1", flush=True)
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX
+    first = [b.clone() for b in bufs]
+    print("full 7B-shaped stack, run 2", flush=True)
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    for a, b in zip(first, bufs):
+        assert torch.equal(a, b)
+    stack.forget()
+    pick = np.random.default_rng(11)
+    worst = 0.0
+    for blk in (0, 15, 31):
+        for n in range(7 * blk, 7 * blk + 7):
+            op, L = ops[n], layers[n]
+            y = bufs[op.dst].cpu().numpy().astype(np.float64)
+            assert np.all(np.isfinite(y)) and np.any(y != 0), op.name
+            native = L.bits.cpu().numpy().view(np.uint32)
+            packed = rb.rb_unpack_native(native, 2, L.out, L.inn)
+            rows = np.unique(pick.integers(0, L.out, size=48))
+            S = rb.rb_unpack(packed[:, rows, :])
+            g = L.g.cpu().numpy()[:, rows]
+            ref = oracle.forward(S, g, L.h.cpu().numpy(), bufs[op.src].cpu().numpy())
+            err = float(oracle.relative_l2(y[:, rows], ref).max())
+            worst = max(worst, err)
+            assert err <= TOL, (op.name, err)
+    print(f"  worst sampled rel_l2={worst:.3e}", flush=True)
