@@ -218,6 +218,26 @@ def main() -> int:
                                "pct_of_hbm_peak": 100.0 * packed13 / (ms13 * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         stack13.forget()
         del ops13, layers13, bufs13, stack13
+        # three paths (the paper's 3-bit variant): no fused kernel, one launch of the generic
+        # sign-XOR + add kernel per op; one block of the 7B shape, scaled to 32
+        ops1, _ = synth.llama_stack("7b", n_layers=1)
+        lay3, bytes3 = [], 0
+        for op in ops1:
+            nb3 = rb.rb_native_bytes(3, op.out, op.inn)
+            b3 = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb3 // 4,), dtype=torch.int32, device="cuda")
+            lay3.append(rb.Layer(b3, (torch.randn(3, op.out, device="cuda").abs() * 0.02).half(),
+                                 (torch.randn(3, op.inn, device="cuda").abs() * 0.02).half(), 3, op.out, op.inn))
+            bytes3 += 3 * op.out * op.inn // 8
+        ins3 = {4096: torch.randn(1, 4096, device="cuda").half(), 11008: torch.randn(1, 11008, device="cuda").half()}
+        outs3 = [torch.zeros((1, op.out), dtype=torch.float16, device="cuda") for op in ops1]
+        st3 = rb.Stack(lay3, [(n, 0 if op.inn == 4096 else 1, 2 + n) for n, op in enumerate(ops1)],
+                       [ins3[4096], ins3[11008]] + outs3, 1)
+        _, per3 = time_steps(torch, st3.run, 30, 5)
+        ms3 = sum(per3) / len(per3)
+        result["three_path_block_generic_kernel"] = {"ms_per_block": ms3, "GBps": bytes3 / (ms3 * 1e-3) / 1e9,
+                                                     "tokens_per_s_32_blocks": 1.0 / (32 * ms3 * 1e-3),
+                                                     "path": rb.rb_last_path()}
+        del lay3, outs3, st3
         # one-call form (set-up inside the call)
         _, per_o = time_steps(torch, stack.run, 20, 3)
         result["rb_layer_stack_ms"] = sum(per_o) / len(per_o)

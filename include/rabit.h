@@ -42,7 +42,9 @@ extern "C" {
 #define RB_ERR_WORKSPACE   -6   /* workspace missing or smaller than rb_workspace_bytes */
 #define RB_ERR_VALUE       -7   /* rb_pack: an entry is neither +1 nor -1             */
 
-#define RB_MAX_K 2
+/* K = 2 is the 2-bit layer every kernel here is built for; K = 1 and K = 3 (the 3-bit variant of
+ * the paper's packing appendix) run on the generic sign-XOR + add kernel. */
+#define RB_MAX_K 3
 
 /* element types for rb_linear_gemm */
 #define RB_F16  0

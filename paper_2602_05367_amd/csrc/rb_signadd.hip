@@ -3,7 +3,7 @@
 // Section 4.1: y = g (.) (B (h (.) x)) needs only additions and subtractions;
 // Eq. (stacked binary weight): the K paths accumulate into one output.
 // This kernel is the direct form of that statement and accepts every shape the
-// library supports (any out, in % 32 == 0, K = 1 or 2, any T via grid.y).  The
+// library supports (any out, in % 32 == 0, K = 1, 2 or 3, any T via grid.y).  The
 // matrix-core kernels are faster where they apply; this one is the fallback.
 //
 // One wavefront owns one 16-row tile and walks it along the columns.  The
@@ -78,6 +78,13 @@ __global__ __launch_bounds__(SIGNADD_WAVES * 64) void signadd_gemv_kernel(
                 if constexpr (K == 2) {
                     const uint4 v = *reinterpret_cast<const uint4 *>(tile);
                     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+                } else if constexpr (K == 3) {
+                    // 24 bytes per lane, 8-byte aligned: words [c][k] = c * 3 + k
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        const uint2 v = reinterpret_cast<const uint2 *>(tile)[i];
+                        w[2 * i] = v.x; w[2 * i + 1] = v.y;
+                    }
                 } else {
                     const uint2 v = *reinterpret_cast<const uint2 *>(tile);
                     w[0] = v.x; w[1] = v.y;
@@ -118,9 +125,9 @@ int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dty
     hipLaunchKernelGGL((signadd_gemv_kernel<KK, ACT>), grid, block, 0, stream, bits, g, h,  \
                        static_cast<const ACT *>(X), Y, out_dtype, L->out, L->in)
     if (act_dtype == RB_F16) {
-        if (L->K == 1) RB_LAUNCH(1, __half); else RB_LAUNCH(2, __half);
+        if (L->K == 1) RB_LAUNCH(1, __half); else if (L->K == 2) RB_LAUNCH(2, __half); else RB_LAUNCH(3, __half);
     } else {
-        if (L->K == 1) RB_LAUNCH(1, bf16_t); else RB_LAUNCH(2, bf16_t);
+        if (L->K == 1) RB_LAUNCH(1, bf16_t); else if (L->K == 2) RB_LAUNCH(2, bf16_t); else RB_LAUNCH(3, bf16_t);
     }
 #undef RB_LAUNCH
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;

@@ -38,6 +38,7 @@ def test_config1_single_layer_2048():
 @pytest.mark.parametrize("K,out,inn", [
     (1, 1, 32), (2, 1, 32), (2, 16, 256), (2, 17, 288), (1, 50, 544), (2, 100, 1056),
     (2, 257, 4096 + 32), (1, 64, 8192), (2, 48, 4096 * 2 + 256), (2, 333, 11008 // 4),
+    (3, 16, 256), (3, 100, 1056), (3, 257, 4096 + 32),
 ])
 def test_gemv_shapes_and_tails(K, out, inn):
     rng = synth.child_rng(0, 200, K, out, inn)
@@ -51,6 +52,28 @@ def test_gemv_shapes_and_tails(K, out, inn):
     err = max_rel_l2(y, oracle.forward(signs, g, h, x))
     _say(f"  rel_l2={err:.3e} path={rb.rb_last_path()}")
     assert err <= TOL
+
+
+def test_three_paths_derived_and_batched():
+    """K = 3 (the 3-bit variant of the paper's packing appendix): paths derived from a Gaussian
+    matrix, one token and a small batch, on the generic kernel."""
+    rng = synth.child_rng(0, 260)
+    W = rng.standard_normal((160, 544)) * 0.02
+    signs, g, h, norms = oracle.derive(W, 3)
+    assert norms[3] < norms[2] < norms[1] < norms[0]
+    L = to_device_layer(signs, g, h)
+    for T in (1, 4):
+        X = synth.outlier_activations(rng, T, 544)
+        _say(f"K=3 derived 160x544 T={T}")
+        Y = rb.rb_linear_gemm(L, torch.from_numpy(X).cuda())
+        torch.cuda.synchronize()
+        assert rb.rb_last_path() == rb.RB_PATH_SIGNADD
+        assert max_rel_l2(Y, oracle.forward(signs, g, h, X)) <= TOL
+        # the third path refines the second: closer to the dense W x than the two-path layer
+        dense = (X.astype(np.float64) @ W.T)
+        e3 = np.linalg.norm(Y.cpu().numpy().astype(np.float64) - dense)
+        e2 = np.linalg.norm(oracle.forward(signs[:2], g[:2], h[:2], X) - dense)
+        assert e3 < e2
 
 
 def test_probe_vectors_recover_every_stored_bit():

@@ -177,3 +177,27 @@ def test_full_7b_stack_as_benchmarked_sampled_outputs():
             worst = max(worst, err)
             assert err <= TOL, (op.name, err)
     print(f"  worst sampled rel_l2={worst:.3e}", flush=True)
+
+
+def test_three_path_layers_in_a_stack():
+    """K = 3 layers have no fused kernel: rb_layer_stack runs them op by op on the generic kernel,
+    same dataflow rules, every op checked against the oracle."""
+    rng = synth.child_rng(3, 88)
+    shapes = [(192, 256), (320, 192), (192, 320)]              # x -> a -> b -> c
+    layers = []
+    for (o, i) in shapes:
+        W = rng.standard_normal((o, i)) / np.sqrt(i)
+        signs, g, h, _ = oracle.derive(W, 3)
+        layers.append((signs, g, h))
+    T = 2
+    x = synth.gaussian_activations(rng, T, 256)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    bufs = [torch.from_numpy(x).cuda()] + [torch.zeros((T, o), dtype=torch.float16, device="cuda") for (o, _) in shapes]
+    op_list = [(0, 0, 1), (1, 1, 2), (2, 2, 3)]
+    print("K=3 stack of three ops, T=2", flush=True)
+    rb.rb_layer_stack(dev_layers, op_list, bufs, T)
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_SIGNADD
+    for n, (l, s, d) in enumerate(op_list):
+        ref = oracle.forward(*layers[l], bufs[s].cpu().numpy())
+        assert oracle.relative_l2(bufs[d].cpu().numpy().astype(np.float64), ref).max() <= TOL, n

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     assert sorted(rb.EXPORTS) == declared
 
 
-@pytest.mark.parametrize("shape", [(1, 1, 32), (2, 16, 256), (2, 37, 160), (1, 50, 544), (2, 64, 1024)])
+@pytest.mark.parametrize("shape", [(1, 1, 32), (2, 16, 256), (2, 37, 160), (1, 50, 544), (2, 64, 1024), (3, 21, 288)])
 def test_pack_is_bit_exact_against_oracle(shape):
     rng = synth.child_rng(0, 100, *shape)
     signs = synth.uniform_signs(rng, *shape)
@@ -40,7 +40,7 @@ def test_pack_is_bit_exact_against_oracle(shape):
     assert np.array_equal(rb.rb_unpack(oracle.pack(signs)), oracle.unpack(packed))
 
 
-@pytest.mark.parametrize("shape", [(1, 1, 32), (2, 16, 256), (2, 37, 160), (1, 50, 544), (2, 33, 1056)])
+@pytest.mark.parametrize("shape", [(1, 1, 32), (2, 16, 256), (2, 37, 160), (1, 50, 544), (2, 33, 1056), (3, 18, 544)])
 def test_native_layout_round_trip_and_size(shape):
     K, out, inn = shape
     rng = synth.child_rng(0, 101, *shape)
@@ -74,7 +74,7 @@ def test_pack_error_codes():
     assert rb.lib.rb_pack(p(i8), 1, 2, 32, None) == rb.RB_ERR_NULL
     assert rb.lib.rb_pack(p(i8), 1, 2, 48, p(out)) == rb.RB_ERR_SHAPE
     assert rb.lib.rb_pack(p(i8), 0, 2, 32, p(out)) == rb.RB_ERR_SHAPE
-    assert rb.lib.rb_pack(p(i8), 3, 2, 32, p(out)) == rb.RB_ERR_SHAPE
+    assert rb.lib.rb_pack(p(i8), 4, 2, 32, p(out)) == rb.RB_ERR_SHAPE
     bad = i8.copy(); bad[0, 1, 5] = 0
     assert rb.lib.rb_pack(p(bad), 1, 2, 32, p(out)) == rb.RB_ERR_VALUE
     assert rb.rb_native_bytes(2, 16, 48) == 0
@@ -91,7 +91,7 @@ def test_compute_entry_points_reject_bad_arguments_without_a_gpu():
     assert gemm(ref(L), 0x10, 0x24, 1, 0, 0, None, 0, None) == rb.RB_ERR_ALIGN
     assert gemm(ref(L), 0x10, 0x20, 1, 7, 0, None, 0, None) == rb.RB_ERR_UNSUPPORTED
     assert gemm(ref(L), 0x10, 0x20, 1, 0, 9, None, 0, None) == rb.RB_ERR_UNSUPPORTED
-    for field, value, code in [("inn", 250, rb.RB_ERR_SHAPE), ("K", 3, rb.RB_ERR_SHAPE),
+    for field, value, code in [("inn", 250, rb.RB_ERR_SHAPE), ("K", 4, rb.RB_ERR_SHAPE),
                                ("out", 0, rb.RB_ERR_SHAPE), ("bits", 0, rb.RB_ERR_NULL),
                                ("bits", 0x1004, rb.RB_ERR_ALIGN), ("g", 0, rb.RB_ERR_NULL)]:
         bad = rb.binding.rb_layer(64, 256, 2, 0x1000, 0x2000, 0x3000)
