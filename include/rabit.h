@@ -41,6 +41,7 @@ extern "C" {
 #define RB_ERR_HIP         -5   /* the HIP runtime reported an error on launch        */
 #define RB_ERR_WORKSPACE   -6   /* workspace missing or smaller than rb_workspace_bytes */
 #define RB_ERR_VALUE       -7   /* rb_pack: an entry is neither +1 nor -1             */
+#define RB_ERR_HANDOVER    -8   /* rb_stack_status: a run gave up waiting for another compute unit */
 
 /* K = 2 is the 2-bit layer every kernel here is built for; K = 1 and K = 3 (the 3-bit variant of
  * the paper's packing appendix) run on the generic sign-XOR + add kernel. */
@@ -147,6 +148,18 @@ int rb_stack_prepare(const rb_layer *layers, int n_layers,
                      void *workspace, size_t workspace_bytes, void *stream);
 int rb_stack_run(void *workspace, size_t workspace_bytes, void *stream);
 int rb_stack_forget(const void *workspace);
+/*
+ * The fused kernel hands activations from compute unit to compute unit while it
+ * runs and assumes that all of its workgroups are resident at once (one per
+ * compute unit of the device).  Every wait in it is bounded: if something
+ * keeps a workgroup from running (compute units reserved by someone else), the
+ * others stop waiting, finish with meaningless outputs and leave a mark in the
+ * workspace.  rb_stack_status waits for `stream` (the only call of this library
+ * that synchronises) and returns RB_ERR_HANDOVER if any run since
+ * rb_stack_prepare left that mark, RB_OK otherwise, RB_ERR_WORKSPACE for a
+ * workspace that holds no prepared stack.
+ */
+int rb_stack_status(const void *workspace, void *stream);
 
 /* Bytes of workspace that a compute call over n_ops ops on these layers needs
  * at T tokens (n_ops = 1 for rb_linear_gemv / rb_linear_gemm; 16-byte aligned

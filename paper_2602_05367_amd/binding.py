@@ -19,15 +19,15 @@ LIB_PATH = os.path.join(_HERE, "librabit.so")
 
 RB_OK = 0
 RB_ERR_NULL, RB_ERR_SHAPE, RB_ERR_ALIGN, RB_ERR_UNSUPPORTED = -1, -2, -3, -4
-RB_ERR_HIP, RB_ERR_WORKSPACE, RB_ERR_VALUE = -5, -6, -7
+RB_ERR_HIP, RB_ERR_WORKSPACE, RB_ERR_VALUE, RB_ERR_HANDOVER = -5, -6, -7, -8
 RB_F16, RB_BF16, RB_F32 = 0, 1, 2
 _ERR_NAMES = {-1: "RB_ERR_NULL", -2: "RB_ERR_SHAPE", -3: "RB_ERR_ALIGN", -4: "RB_ERR_UNSUPPORTED",
-              -5: "RB_ERR_HIP", -6: "RB_ERR_WORKSPACE", -7: "RB_ERR_VALUE"}
+              -5: "RB_ERR_HIP", -6: "RB_ERR_WORKSPACE", -7: "RB_ERR_VALUE", -8: "RB_ERR_HANDOVER"}
 
 EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
-    "rb_stack_prepare", "rb_stack_run", "rb_stack_forget",
+    "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -66,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_prepare.argtypes = lib.rb_layer_stack.argtypes
     lib.rb_stack_run.argtypes = [p, z, p]
     lib.rb_stack_forget.argtypes = [p]
+    lib.rb_stack_status.argtypes = [p, p]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
     lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
@@ -240,6 +241,10 @@ class Stack:
     def run_prepared(self) -> None:
         """rb_stack_run: one pass of the prepared ops over the current buffer contents."""
         _check("rb_stack_run", lib.rb_stack_run(self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+    def status(self) -> int:
+        """rb_stack_status: waits for the stream; RB_OK, or RB_ERR_HANDOVER if a run gave up a wait."""
+        return int(lib.rb_stack_status(self.ws.data_ptr(), _stream()))
 
     def forget(self) -> None:
         _check("rb_stack_forget", lib.rb_stack_forget(self.ws.data_ptr()))

@@ -78,6 +78,14 @@ extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *strea
     return rc;
 }
 
+extern "C" int rb_stack_status(const void *workspace, void *stream)
+{
+    if (!workspace) return RB_ERR_NULL;
+    const int rc = rb::pairs_status(workspace, static_cast<hipStream_t>(stream));
+    if (rc != RB_ERR_UNSUPPORTED) return rc;
+    return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int rb_stack_forget(const void *workspace)
 {
     if (!workspace) return RB_ERR_NULL;

@@ -101,6 +101,22 @@ int run_pairs(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return RB_OK;
 }
 
+int pairs_status(const void *workspace, hipStream_t stream)
+{
+    PairPlans pp;
+    {
+        std::lock_guard<std::mutex> lock(g_pairs_mutex);
+        const auto it = g_pairs.find(workspace);
+        if (it == g_pairs.end()) return RB_ERR_UNSUPPORTED;
+        pp = it->second;
+    }
+    for (int p = 0; p < pp.passes; ++p) {
+        const int rc = mx::plan_status(static_cast<const uint8_t *>(workspace) + (size_t)p * pp.stride, stream);
+        if (rc != RB_OK) return rc;
+    }
+    return RB_OK;
+}
+
 void forget_pairs(const void *workspace)
 {
     PairPlans pp{0, 0};

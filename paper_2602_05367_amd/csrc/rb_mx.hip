@@ -1128,6 +1128,23 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
+int plan_status(const void *workspace, hipStream_t stream)
+{
+    Prepared pr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        const auto it = g_prepared.find(workspace);
+        if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
+        pr = it->second;
+    }
+    uint32_t mark = 0;
+    if (hipMemcpyAsync(&mark, static_cast<const uint8_t *>(workspace) + pr.lay.error, sizeof(mark), hipMemcpyDeviceToHost,
+                       stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return RB_ERR_HIP;
+    return mark ? RB_ERR_HANDOVER : RB_OK;
+}
+
 void forget_plan(const void *workspace)
 {
     std::lock_guard<std::mutex> lock(g_mutex);

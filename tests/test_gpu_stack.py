@@ -28,6 +28,7 @@ def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
         stack.run_prepared()
         torch.cuda.synchronize()
         assert rb.rb_last_path() == rb.RB_PATH_MX
+        assert stack.status() == rb.RB_OK
         stack.forget()
     else:
         rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
@@ -113,7 +114,9 @@ def test_prepare_once_run_many_tokens():
             assert torch.equal(a, b)
         last = oracle.forward(*layers[-1], dev_bufs[ops[-1].src].cpu().numpy())
         assert oracle.relative_l2(dev_bufs[ops[-1].dst].cpu().numpy().astype(np.float64), last).max() <= TOL
+    assert stack.status() == rb.RB_OK                 # no run gave up a hand-over wait
     stack.forget()
+    assert stack.status() == rb.RB_ERR_WORKSPACE
     with pytest.raises(rb.RabitError):
         stack.run_prepared()
 
