@@ -204,3 +204,28 @@ def test_three_path_layers_in_a_stack():
     for n, (l, s, d) in enumerate(op_list):
         ref = oracle.forward(*layers[l], bufs[s].cpu().numpy())
         assert oracle.relative_l2(bufs[d].cpu().numpy().astype(np.float64), ref).max() <= TOL, n
+
+
+def test_hand_over_at_full_scale_many_tokens():
+    """Every op of the full 7B-shaped stack, over 40 tokens, against the single-op kernel on the
+    input that op actually read: the two share every rounding step, so any operand that a compute
+    unit picked up before its producer had finished shows up as a mismatch."""
+    import bench
+    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", 1)
+    stack = rb.Stack(layers, op_list, bufs, 1)
+    stack.prepare()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(77)
+    ys = [torch.empty_like(bufs[op.dst]) for op in ops]
+    ws = rb.binding._workspace(layers[:7], 1, bufs[0].device)       # all seven shapes
+    for token in range(40):
+        bufs[0].copy_(torch.randn(1, ops[0].inn, device="cuda", generator=gen).half())
+        if token % 10 == 0:
+            print(f"full stack, token {token}", flush=True)
+        stack.run_prepared()
+        for n, op in enumerate(ops):
+            rb.rb_linear_gemm(layers[n], bufs[op.src], Y=ys[n], workspace=ws)
+        torch.cuda.synchronize()
+        bad = [op.name for n, op in enumerate(ops) if not torch.equal(ys[n], bufs[op.dst])]
+        assert not bad, (token, bad[:5])
+    assert stack.status() == rb.RB_OK
+    stack.forget()
