@@ -171,7 +171,8 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
                                                   const uint32_t *zero_page, uint32_t *sdesc, uint32_t *odesc,
                                                   uint32_t sblocks, uint32_t oblocks)
 {
-    const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x * 64 + threadIdx.x;
+    // one wavefront per list; its lanes write the entries of an op's run side by side
+    const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x, lane = threadIdx.x;
     const int T = hdr->T, n_stages = hdr->n_stages;
     const uint32_t CW = (uint32_t)cwaves_of(T);
     if (id >= G * CW) return;
@@ -192,10 +193,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
         b[DESC_BLOCK] = (uint32_t)(addr >> 32);
         b[2 * DESC_BLOCK] = meta;
     };
-    // every entry empty first: a sign request past the last tile reads a page of zeros
-    for (uint32_t e = 0; e < s_cap; ++e) put_sign(e, (uint64_t)zero_page);
-    for (uint32_t e = 0; e < o_cap; ++e) put_opnd(e, 0, 0u);
-    uint32_t gs = 0, go = 0;
+    uint32_t gs = 0, go = 0;                  // entries written so far (the same in every lane)
     for (int st = 0; st < n_stages; ++st) {
         const Stage stage = stages[st];
         uint32_t slot_base = 0;
@@ -205,17 +203,23 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             uint32_t rt0, nrt;
             group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
             const uint32_t U = nrt * CT, u0 = wave * U / CW, u1 = (wave + 1) * U / CW;
-            for (uint32_t u = u0; u < u1; ++u) {
+            for (uint32_t u = u0 + lane; u < u1; u += 64) {
                 const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
-                put_sign(gs++, (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
-                put_opnd(go++, (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
+                put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
+                put_opnd(go + (u - u0), (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
                          STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) | (slot << STEP_SLOT_SHIFT) |
                              ((uint32_t)(op.dep_slot + 1) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
             }
+            gs += u1 - u0;
+            go += u1 - u0;
             slot_base += nrt;
         }
-        go += (uint32_t)nb_of(T);              // the empty entries that end the stage
+        if (lane < (uint32_t)nb_of(T)) put_opnd(go + lane, 0, 0u);      // the empty entries that end the stage
+        go += (uint32_t)nb_of(T);
     }
+    // past the last tile: a sign request reads a page of zeros, an operand entry is empty
+    for (uint32_t e = gs + lane; e < s_cap; e += 64) put_sign(e, (uint64_t)zero_page);
+    for (uint32_t e = go + lane; e < o_cap; e += 64) put_opnd(e, 0, 0u);
 }
 
 // Second set-up pass (needs the scales of every op): the tables of the finishing wavefronts.
@@ -1027,19 +1031,15 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             n_ready += (size_t)col_tiles(ops[(size_t)n].out) * 16;
         }
     pr.n_ready = (int)n_ready;
-    // longest step list of a compute wavefront (same arithmetic as desc_kernel)
+    // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
+    // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
+    // the few blocks it saves)
     {
-        const uint32_t CW = (uint32_t)cwaves_of(T);
+        const size_t CW = (size_t)cwaves_of(T);
         size_t longest = 0;
-        for (uint32_t grp = 0; grp < (uint32_t)G; ++grp) {
-            size_t per_wave[MAX_CWAVES] = {0};
-            for (int n = 0; n < n_ops; ++n) {
-                uint32_t rt0, nrt;
-                group_rows((uint32_t)ops[(size_t)n].RT, grp, (uint32_t)G, n - ops[(size_t)n].stage_op0, rt0, nrt);
-                const uint32_t U = nrt * (uint32_t)ops[(size_t)n].CT;
-                for (uint32_t w = 0; w < CW; ++w) per_wave[w] += (w + 1) * U / CW - w * U / CW;
-            }
-            for (uint32_t w = 0; w < CW; ++w) longest = std::max(longest, per_wave[w]);
+        for (int n = 0; n < n_ops; ++n) {
+            const size_t share = (size_t)((ops[(size_t)n].RT + G - 1) / G) * (size_t)ops[(size_t)n].CT;
+            longest += (share + CW - 1) / CW;
         }
         // entries a wavefront reads: every tile's, plus the look-ahead past the end
         pr.sblocks = desc_blocks((uint32_t)(longest + RING_D));
@@ -1078,7 +1078,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
                        reinterpret_cast<Op *>(ws + lay.ops),
                        reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero));
-    hipLaunchKernelGGL(desc_kernel, dim3((G * cwaves_of(T) + 63) / 64), dim3(64), 0, stream,
+    hipLaunchKernelGGL(desc_kernel, dim3(G * cwaves_of(T)), dim3(64), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<const uint32_t *>(ws + lay.zero),
                        reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc),
