@@ -92,12 +92,35 @@ def cpu_baseline(synth, packed_bytes_total: int):
             "tokens_per_s_extrapolated": 1.0 / (dt * packed_bytes_total / sample_bytes)}
 
 
+def prefill_figures(rb, torch):
+    """Prefill GEMM (configs[4]): T = 2048 tokens, 70B-shaped MLP matrices, bf16 activations."""
+    prefill = {}
+    Tp = 2048
+    for (o, i) in ((28672, 8192), (8192, 28672)):
+        nb = rb.rb_native_bytes(2, o, i)
+        bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb // 4,), dtype=torch.int32, device="cuda")
+        gg = (torch.randn(2, o, device="cuda").abs() * 0.02).half()
+        hh = (torch.randn(2, i, device="cuda").abs() * 0.02).half()
+        Lp = rb.Layer(bits, gg, hh, 2, o, i)
+        Xp = torch.randn((Tp, i), device="cuda").to(torch.bfloat16)
+        Yp = torch.empty((Tp, o), dtype=torch.float16, device="cuda")
+        wsp = rb.binding._workspace([Lp], Tp, Xp.device)
+        _, per_p = time_steps(torch, lambda: rb.rb_linear_gemm(Lp, Xp, Y=Yp, workspace=wsp), 8, 2)
+        msp = sum(per_p) / len(per_p)
+        flops = 2.0 * 2 * o * i * Tp
+        prefill[f"{o}x{i}"] = {"ms": msp, "TFLOPs": flops / msp / 1e9, "frac_of_fp16_mfma_peak": flops / msp / 1e9 / 2500.0}
+        del bits, Lp, Xp, Yp, wsp
+    return prefill
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extras", action="store_true", help="skip comparators and the CPU baseline")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="only the prefill GEMM figures (for profiling that kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -110,6 +133,10 @@ def main() -> int:
     import paper_2602_05367_amd as rb
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+
+    if args.prefill_only:
+        print(json.dumps({"prefill_gemm_T2048": prefill_figures(rb, torch)}))
+        return 0
 
     T = 1
     ops, layers, bufs, op_list, packed_bytes = build_stack(rb, synth, torch, "7b", T)
@@ -266,24 +293,7 @@ def main() -> int:
                                      "GBps": 2 * 8 * packed_bytes / 2 / (per_tok_us * 1e-6) / 1e9}
         result["speedup_vs_dense_fp16"] = result["tokens_per_s"] / result["dense_fp16_gemv"]["tokens_per_s"]
         result["paper_context"] = "RTX 4090: 291.88 tok/s = 4.49x FP16, whole Llama2-7B model (inference table)"
-        # prefill GEMM (configs[4]): T = 2048 tokens, 70B-shaped MLP matrices, bf16 activations
-        prefill = {}
-        Tp = 2048
-        for (o, i) in ((28672, 8192), (8192, 28672)):
-            nb = rb.rb_native_bytes(2, o, i)
-            bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb // 4,), dtype=torch.int32, device="cuda")
-            gg = (torch.randn(2, o, device="cuda").abs() * 0.02).half()
-            hh = (torch.randn(2, i, device="cuda").abs() * 0.02).half()
-            Lp = rb.Layer(bits, gg, hh, 2, o, i)
-            Xp = torch.randn((Tp, i), device="cuda").to(torch.bfloat16)
-            Yp = torch.empty((Tp, o), dtype=torch.float16, device="cuda")
-            wsp = rb.binding._workspace([Lp], Tp, Xp.device)
-            _, per_p = time_steps(torch, lambda: rb.rb_linear_gemm(Lp, Xp, Y=Yp, workspace=wsp), 8, 2)
-            msp = sum(per_p) / len(per_p)
-            flops = 2.0 * 2 * o * i * Tp
-            prefill[f"{o}x{i}"] = {"ms": msp, "TFLOPs": flops / msp / 1e9, "frac_of_fp16_mfma_peak": flops / msp / 1e9 / 2500.0}
-            del bits, Lp, Xp, Yp, wsp
-        result["prefill_gemm_T2048"] = prefill
+        result["prefill_gemm_T2048"] = prefill_figures(rb, torch)
         # small decode batches (configs[2]): the 7B-shaped stack, every op on its own input buffer.
         # Up to 8 tokens the prepared stack runs the fused decode kernel (one launch per pair of tokens);
         # beyond that every op is a launch sequence of the many-token kernel.
