@@ -30,6 +30,7 @@
 #include <hip/hip_fp16.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -64,6 +65,17 @@ namespace mx {
 #endif
 #ifndef RB_POLL_DELAY2
 #define RB_POLL_DELAY2 64
+#endif
+
+// validated hand-over: pause between a workgroup's own stores and its "go", pause between retries
+#ifndef RB_VAL_GO_PAUSE
+#define RB_VAL_GO_PAUSE 56
+#endif
+#ifndef RB_VAL_GO_PAUSE_IDLE
+#define RB_VAL_GO_PAUSE_IDLE 56
+#endif
+#ifndef RB_VAL_RETRY_SLEEP
+#define RB_VAL_RETRY_SLEEP 8
 #endif
 
 #ifdef RB_EXP_TRACE
@@ -303,6 +315,24 @@ __global__ __launch_bounds__(256) void clear_kernel(uint32_t *ready, int n)
     if (i < n) ready[i] = 0;
 }
 
+// Validated hand-over, before every launch: the expanded input of every op that a producer of this
+// launch will write is set to "not written yet" (0xff in every byte of the 16-byte groups of real
+// columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  One workgroup
+// per op; one-token layout.
+__global__ __launch_bounds__(256) void poison_kernel(const Op *ops)
+{
+    const Op &op = ops[blockIdx.x];
+    if (op.dep < 0) return;
+    const int groups = (int)(up_bytes(op.in, 1) / 16);
+    uint4 *up = reinterpret_cast<uint4 *>(op.up);
+    for (int i = threadIdx.x; i < groups; i += 256) {
+        // group i of block b = i / 64 is [q][half j][operand column]: input columns b*128 + j*64 + q*16 .. +15
+        const int b = i >> 6, within = i & 63, q = within >> 4, j = (within >> 3) & 1;
+        const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
+        up[i] = make_uint4(v, v, v, v);
+    }
+}
+
 // ---------------------------------------------------------- stack kernel ---
 // workgroup barrier that orders LDS only: the weight prefetch of a compute wavefront stays in
 // flight across it (a full fence would wait for every outstanding global load)
@@ -319,7 +349,14 @@ __device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
 
 template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile: two 128-column blocks
 
-template <int TT>
+// VAL (one token only): hand-over without flags.  What a producer stores carries its own validity (a
+// 16-byte group of an expanded input is all 0xff until it is written), so a producer neither waits for
+// its stores to be acknowledged nor raises a flag, and nobody polls: the finishing wavefront that
+// would watch the flags tells the compute wavefronts of its workgroup, a fixed pause after its own
+// stores, that the next stage's inputs are probably there.  A compute wavefront looks at the first
+// byte of each group of a tile before it uses it and, if a producer was late, loads that tile again
+// past the L2 (which now holds the unwritten line) until it is complete.
+template <int TT, bool VAL>
 __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
@@ -331,6 +368,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const SlotRec *__restrict__ slots_g,
                                                            const SlotVals *__restrict__ vals_g)
 {
+    static_assert(!VAL || TT == 1, "the validated hand-over is built for the one-token layout");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     using Lds = LdsMap<CW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -485,7 +523,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 
             // ---- expanded-input stream of this stage (NB tiles ahead of the MFMAs).  What the
             // consuming step needs to know about a tile travels with it in meta[] (STEP_* fields).
-            uint32_t meta[NB];
+            uint32_t meta[NB], opnd_lo[NB], opnd_hi[NB];      // per ring slot: STEP_* fields and where the tile's operand lives
             auto load_operand = [&](BTile<TT> &dst, v4i rsrc) {
                 // The target registers are in-out operands on purpose: the compiler cannot see that
                 // a load issued here lands later, and the loads of the last steps of a stage are
@@ -528,16 +566,29 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 return (bits >> (ct & 63u)) & 1ull;
             };
             // requests the operand of the next entry of the operand list (nothing for an empty entry)
-            auto issue_b = [&](BTile<TT> &dst, uint32_t &m) {
+            bool go_seen = false;                             // (VAL) this stage's inputs have been announced
+            auto issue_b = [&](BTile<TT> &dst, uint32_t &m, uint32_t &addr_lo, uint32_t &addr_hi) {
                 const OpndDesc d = next_opnd();
                 m = d.meta;
+                addr_lo = d.lo;
+                addr_hi = d.hi & 0xffffu;
 #ifdef RB_EXP_SKIP_OPERANDS
                 const bool valid = false;
 #else
                 const bool valid = (m & STEP_VALID) != 0;
 #endif
                 const uint32_t dep = (m >> STEP_DEP_SHIFT) & 7u;
-                if (dep != 0 && !failed) {
+                if constexpr (VAL) {
+                    // one announcement per stage (the first word of the stage's bits)
+                    if (dep != 0 && !go_seen && !failed) {
+                        int spins = 0;
+                        while (!block_ready(0, 0u)) {
+                            __builtin_amdgcn_s_sleep(2);
+                            if (++spins > (1 << 24)) { failed = true; break; }
+                        }
+                        go_seen = true;
+                    }
+                } else if (dep != 0 && !failed) {
                     const uint32_t ct = m >> STEP_CT_SHIFT;
                     int spins = 0;
                     while (!block_ready((int)dep - 1, ct)) {
@@ -576,7 +627,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             };
 
 #pragma unroll
-            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i]); issue_dummies(1); }
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], opnd_lo[i], opnd_hi[i]); issue_dummies(1); }
 
             bool more = true;
             while (more) {
@@ -597,6 +648,55 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                  : "memory");
 #pragma unroll
                     for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
+                    if constexpr (VAL) {
+                        // Each lane holds one 16-byte group per load; a group that was written does not
+                        // start with 0xff.  A tile that is not complete (its producer was late, or the
+                        // L2 of this XCD got hold of the line before it was written) is waited for by
+                        // looking at the first word of every group past the L2, and then loaded again
+                        // whole.  One statement, so that the operand registers keep their place (a loop
+                        // the compiler can see around a reload makes it move them while loads are in flight).
+                        if (((m >> STEP_DEP_SHIFT) & 7u) != 0 && !failed &&
+                            __ballot((B[s].r[0][0] & 0xff) == 0xff || (B[s].r[1][0] & 0xff) == 0xff) != 0ull) {
+                            v4i rsrc;
+                            rsrc[0] = (int)opnd_lo[s];
+                            rsrc[1] = (int)opnd_hi[s];
+                            rsrc[2] = 2 * up_block_bytes(TT);
+                            rsrc[3] = 0x00020000;
+                            int c0, c1;
+                            uint32_t left;
+                            unsigned long long unwritten;
+                            asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                         "1:\n\t"
+                                         "s_nop 4\n\t"
+                                         "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                         "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                         "s_waitcnt vmcnt(0)\n\t"
+                                         "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                         "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                         "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                         "s_mov_b64 %[un], vcc\n\t"
+                                         "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
+                                         "s_or_b64 %[un], %[un], vcc\n\t"
+                                         "s_cmp_eq_u64 %[un], 0\n\t"
+                                         "s_cbranch_scc1 2f\n\t"
+                                         "s_sleep 8\n\t"
+                                         "s_sub_u32 %[left], %[left], 1\n\t"
+                                         "s_cmp_lg_u32 %[left], 0\n\t"
+                                         "s_cbranch_scc1 1b\n"
+                                         "2:\n\t"
+                                         "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                         "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                         "s_waitcnt vmcnt(0)"
+                                         : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [c0] "=&v"(c0), [c1] "=&v"(c1),
+                                           [un] "=&s"(unwritten), [left] "=&s"(left)
+                                         : [off] "v"(lane_off), [rs] "s"(rsrc)
+                                         : "vcc", "scc", "memory");
+                            if (left == 0) {                  // a producer never delivered: report, stop checking
+                                failed = true;
+                                if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+                        }
+                    }
                     RB_STEP(1);
                     c_slot_ptr += 1024;
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
@@ -631,7 +731,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     if (m & STEP_FLUSH) flush((m >> STEP_SLOT_SHIFT) & 0xffu);
                     RB_STEP(2);
                     ++steps_done;
-                    issue_b(B[s], meta[s]);
+                    issue_b(B[s], meta[s], opnd_lo[s], opnd_hi[s]);
                     issue_a();
                     RB_STEP(3);
                     RB_STEP_NEXT();
@@ -760,14 +860,19 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 RB_FTRACE(1);
                 // publish: once the stores are acknowledged, raise the flag byte of this row tile (a plain
                 // device-scope store: read-modify-write counters shared by 16 producers took ~1 us per update)
-#ifdef RB_EXP_WBL2
-                asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
-#else
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifdef RB_EXP_VAL_KEEPWAIT
+                if constexpr (VAL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
-                RB_FTRACE(2);
-                if ((lane & 31) == 0 && have_slot && n_cons > 0)
-                    asm volatile("global_store_byte %0, %1, off sc1" : : "v"(cur.r.ready), "v"(1u) : "memory");
+                if constexpr (!VAL) {
+#ifdef RB_EXP_WBL2
+                    asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+#else
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+                    RB_FTRACE(2);
+                    if ((lane & 31) == 0 && have_slot && n_cons > 0)
+                        asm volatile("global_store_byte %0, %1, off sc1" : : "v"(cur.r.ready), "v"(1u) : "memory");
+                }
             }
             RB_TRACE(6);
             // ---- watch the counters the next stage depends on (one wavefront per workgroup) and
@@ -787,6 +892,16 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     for (int d = 0; d < MAX_DEPS; ++d)
                         for (int win = 0; win < READY_WINDOWS; ++win) publish(d, win, ~0ull);
                 };
+                if constexpr (VAL) {
+                    // no flags to watch: after the time the slowest producer's stores need to land, tell
+                    // the compute wavefronts to go (they check what they get)
+                    if (!all) {
+                        if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(RB_VAL_GO_PAUSE);
+                        else __builtin_amdgcn_s_sleep(RB_VAL_GO_PAUSE_IDLE);      // nothing to store: it got here earlier
+                        publish(0, 0, ~0ull);
+                        all = true;
+                    }
+                }
                 bool narrow = true;                               // every op in the list has at most 64 blocks
                 // (the list is indexed with constants only: a run-time index would put it in scratch memory)
 #pragma unroll
@@ -939,6 +1054,7 @@ struct Prepared {
     Layout lay;
     int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0, n_ready = 0;
     uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
+    bool validated = false;                 // hand-over without flags (one token, ops that depend on each other)
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
@@ -1031,6 +1147,12 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             n_ready += (size_t)col_tiles(ops[(size_t)n].out) * 16;
         }
     pr.n_ready = (int)n_ready;
+    // hand-over without flags: one token, ops that depend on each other; RB_VALIDATED=0 in the
+    // environment keeps the flags (for comparisons)
+    {
+        const char *env = std::getenv("RB_VALIDATED");
+        pr.validated = T == 1 && n_ready > 0 && !(env && env[0] == '0');
+    }
     // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
     // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
     // the few blocks it saves)
@@ -1107,7 +1229,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (pr.n_expand > 0)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
-    if (pr.n_ready > 0)
+    if (pr.validated)
+        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops), dim3(256), 0, stream, d_ops);
+    else if (pr.n_ready > 0)
         hipLaunchKernelGGL(clear_kernel, dim3((pr.n_ready / 4 + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint32_t *>(ws + lay.ready), pr.n_ready / 4);
     auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
@@ -1122,8 +1246,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals));
         return RB_OK;
     };
-    const int rc = pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
-                             : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
+    const int rc = pr.T == 1 ? (pr.validated ? launch(stack_kernel<1, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+                                             : launch(stack_kernel<1, false>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES))
+                             : launch(stack_kernel<2, false>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
     if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
