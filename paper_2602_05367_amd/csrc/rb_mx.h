@@ -132,7 +132,7 @@ constexpr int SIGN_FIELDS = 2;               // address low, high
 constexpr int OPND_FIELDS = 3;               // address low, high, STEP_* fields
 constexpr uint32_t STEP_VALID = 1u;          // a tile (empty entries are all zero)
 constexpr uint32_t STEP_FLUSH = 2u;          // last tile of its row tile for this wavefront: write the partial sums
-constexpr int STEP_SLOT_SHIFT = 8;           // 8 bits: partial-sum slot
+constexpr int STEP_PART_SHIFT = 8;           // 8 bits: where the partial sums go: slot * cwaves_of(T) + run of the share
 constexpr int STEP_DEP_SHIFT = 16;           // 3 bits: 1 + entry of the stage's dependency list (0: input was complete before the launch)
 constexpr int STEP_CT_SHIFT = 20;            // 12 bits: column tile (which hand-over bit to wait for)
 // blocks a wavefront may load for a list of n entries read front to back: it holds the block it

@@ -67,15 +67,12 @@ namespace mx {
 #define RB_POLL_DELAY2 64
 #endif
 
-// validated hand-over: pause between a workgroup's own stores and its "go", pause between retries
+// validated hand-over: pause between a workgroup's own stores and its "go" (s_sleep units)
 #ifndef RB_VAL_GO_PAUSE
 #define RB_VAL_GO_PAUSE 56
 #endif
 #ifndef RB_VAL_GO_PAUSE_IDLE
 #define RB_VAL_GO_PAUSE_IDLE 56
-#endif
-#ifndef RB_VAL_RETRY_SLEEP
-#define RB_VAL_RETRY_SLEEP 8
 #endif
 
 #ifdef RB_EXP_TRACE
@@ -214,12 +211,19 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             const uint32_t CT = (uint32_t)op.CT;
             uint32_t rt0, nrt;
             group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
-            const uint32_t U = nrt * CT, u0 = wave * U / CW, u1 = (wave + 1) * U / CW;
+            // Run `run` of the share goes to this wavefront.  Runs differ by one tile when CW does not
+            // divide the share, and the longer ones sit at the same positions for every op of equal
+            // shape; dealing op number n of the stage from wavefront n on spreads them.  The partial
+            // sums are filed under the run, not the wavefront, so the order of the final sum is the
+            // single-op kernel's whichever wavefront worked on a run.
+            const uint32_t run = (wave + (uint32_t)(o - stage.op0)) % CW;
+            const uint32_t U = nrt * CT, u0 = run * U / CW, u1 = (run + 1) * U / CW;
             for (uint32_t u = u0 + lane; u < u1; u += 64) {
                 const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
                 put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
                 put_opnd(go + (u - u0), (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
-                         STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) | (slot << STEP_SLOT_SHIFT) |
+                         STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) |
+                             ((slot * CW + run) << STEP_PART_SHIFT) |
                              ((uint32_t)(op.dep_slot + 1) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
             }
             gs += u1 - u0;
@@ -317,15 +321,16 @@ __global__ __launch_bounds__(256) void clear_kernel(uint32_t *ready, int n)
 
 // Validated hand-over, before every launch: the expanded input of every op that a producer of this
 // launch will write is set to "not written yet" (0xff in every byte of the 16-byte groups of real
-// columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  One workgroup
-// per op; one-token layout.
+// columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  POISON_SPLIT
+// workgroups per op; one-token layout.
+constexpr int POISON_SPLIT = 4;
 __global__ __launch_bounds__(256) void poison_kernel(const Op *ops)
 {
     const Op &op = ops[blockIdx.x];
     if (op.dep < 0) return;
     const int groups = (int)(up_bytes(op.in, 1) / 16);
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
-    for (int i = threadIdx.x; i < groups; i += 256) {
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
         // group i of block b = i / 64 is [q][half j][operand column]: input columns b*128 + j*64 + q*16 .. +15
         const int b = i >> 6, within = i & 63, q = within >> 4, j = (within >> 3) & 1;
         const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
@@ -572,11 +577,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 m = d.meta;
                 addr_lo = d.lo;
                 addr_hi = d.hi & 0xffffu;
-#ifdef RB_EXP_SKIP_OPERANDS
-                const bool valid = false;
-#else
                 const bool valid = (m & STEP_VALID) != 0;
-#endif
                 const uint32_t dep = (m >> STEP_DEP_SHIFT) & 7u;
                 if constexpr (VAL) {
                     // one announcement per stage (the first word of the stage's bits)
@@ -611,8 +612,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             // first lane writes rows 4*qd .. 4*qd+3 of that path and token
             const int quad = col >> 2;
             const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * Lds::PART_SLOT_BYTES +
-                                       (uint32_t)wave * 256 + (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
-            auto flush = [&](uint32_t slot) {
+                                       (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
+            auto flush = [&](uint32_t part_index) {       // slot * CW + run: 256 bytes each
                 v4f v;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)       // the four lanes of a quad hold terms of the same path
@@ -620,7 +621,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 if ((col & 3) == 0)
                     asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                  :
-                                 : "v"(part_lane + slot * Lds::PART_SLOT_BYTES), "v"(v)
+                                 : "v"(part_lane + part_index * 256u), "v"(v)
                                  : "memory");
                 acc0 = (v4f){0, 0, 0, 0};
                 acc1 = (v4f){0, 0, 0, 0};
@@ -720,15 +721,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                             b1[i] = bt.r[2 % KOP][i]; b1[4 + i] = bt.r[3 % KOP][i];
                         }
                     }
-#ifndef RB_EXP_NO_MFMA
                     acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
                     acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
                     acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
                     acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
-#else
-                    acc0[0] += __uint_as_float((w.x ^ w.y ^ w.z ^ w.w) & 0x007fffffu) + (float)b0[0] + (float)b1[0];
-#endif
-                    if (m & STEP_FLUSH) flush((m >> STEP_SLOT_SHIFT) & 0xffu);
+                    if (m & STEP_FLUSH) flush((m >> STEP_PART_SHIFT) & 0xffu);
                     RB_STEP(2);
                     ++steps_done;
                     issue_b(B[s], meta[s], opnd_lo[s], opnd_hi[s]);
@@ -789,44 +786,63 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             RB_FTRACE(0);
             const bool have_slot = cur.r.op >= 0;
             const int grow = cur.r.row0 + row;
-            const bool active = have_slot && tok < T && grow < cur.r.out;
+            // One token: the lanes of a row's second-token position are free, so the two lanes of a
+            // row split the paths between them (sub = which path) for the sums and the expansion.
+            constexpr bool SPLIT = TT == 1;
+            const int sub = tok;
+            const bool active = have_slot && (SPLIT || tok < T) && grow < cur.r.out;
             const int n_cons = have_slot ? cur.r.n_cons : 0;
             const float hs[MAX_CONS][2] = {{cur.a[2], cur.a[3]}, {cur.b[0], cur.b[1]}, {cur.b[2], cur.b[3]}};
+            // this lane's path of each reader's scales (selected value by value: an indexed array
+            // would live in scratch memory)
+            const float hsub[MAX_CONS] = {sub ? cur.a[3] : cur.a[2], sub ? cur.b[1] : cur.b[0], sub ? cur.b[3] : cur.b[2]};
             float yf = 0.f;
+            // partial sums of this lane's row: [run][path][token][row]
+            float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * 64 + (SPLIT ? 0 : tok * 16) + row;
             if (active) {
-                // sum the partial sums of the compute wavefronts, clear them for the next use
-                float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * 64 + tok * 16 + row;
+                // sum the partial sums of the runs in run order
                 float s0 = 0.f, s1 = 0.f;
+                if constexpr (SPLIT) {
+                    float mine = 0.f;
 #pragma unroll
-                for (int w = 0; w < CW; ++w) {
-                    s0 += P[w * 64];
-                    s1 += P[w * 64 + 32];
+                    for (int w = 0; w < CW; ++w) mine += P[w * 64 + sub * 32];
+                    const float other = __shfl_xor(mine, 16);      // the lane with the same row and the other path
+                    s0 = sub ? other : mine;
+                    s1 = sub ? mine : other;
+                } else {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) {
+                        s0 += P[w * 64];
+                        s1 += P[w * 64 + 32];
+                    }
                 }
                 RB_TRACE(2);
-#pragma unroll
-                for (int w = 0; w < CW; ++w) {
-                    P[w * 64] = 0.f;
-                    P[w * 64 + 32] = 0.f;
-                }
                 RB_TRACE(3);
                 const _Float16 y16 = (_Float16)path_sum(cur.a[0], s0, cur.a[1], s1);   // round to nearest even
-                RB_GLOBAL(_Float16, cur.r.y)[(size_t)tok * cur.r.out + grow] = y16;
+                if (!SPLIT || sub == 0) RB_GLOBAL(_Float16, cur.r.y)[(size_t)(SPLIT ? 0 : tok) * cur.r.out + grow] = y16;
                 yf = (float)y16;
             }
             RB_TRACE(0);
             // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
             // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
             if (__any(n_cons > 0)) {
-                if (have_slot && tok < T) {
+                if (have_slot && (SPLIT || tok < T)) {
 #pragma unroll
                     for (int c = 0; c < MAX_CONS; ++c) {
                         if (c < n_cons) {
-#pragma unroll
-                            for (int p = 0; p < 2; ++p) {
-                                const uint32_t terms = active ? expand4(hs[c][p] * yf) : 0u;
-                                uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
+                            if constexpr (SPLIT) {
+                                const uint32_t terms = active ? expand4(hsub[c] * yf) : 0u;
+                                uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2) * 2 + sub) * 4) * 16 + row;
 #pragma unroll
                                 for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
+                            } else {
+#pragma unroll
+                                for (int p = 0; p < 2; ++p) {
+                                    const uint32_t terms = active ? expand4(hs[c][p] * yf) : 0u;
+                                    uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
+#pragma unroll
+                                    for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
+                                }
                             }
                         }
                     }
@@ -860,18 +876,25 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 RB_FTRACE(1);
                 // publish: once the stores are acknowledged, raise the flag byte of this row tile (a plain
                 // device-scope store: read-modify-write counters shared by 16 producers took ~1 us per update)
-#ifdef RB_EXP_VAL_KEEPWAIT
-                if constexpr (VAL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
                 if constexpr (!VAL) {
-#ifdef RB_EXP_WBL2
-                    asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
-#else
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
                     RB_FTRACE(2);
                     if ((lane & 31) == 0 && have_slot && n_cons > 0)
                         asm volatile("global_store_byte %0, %1, off sc1" : : "v"(cur.r.ready), "v"(1u) : "memory");
+                }
+            }
+            // clear the partial sums for the stage after next (a run without tiles writes nothing);
+            // off the path from the barrier to the stores
+            if (active) {
+                if constexpr (SPLIT) {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) P[w * 64 + sub * 32] = 0.f;
+                } else {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) {
+                        P[w * 64] = 0.f;
+                        P[w * 64 + 32] = 0.f;
+                    }
                 }
             }
             RB_TRACE(6);
@@ -1230,7 +1253,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
     if (pr.validated)
-        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops), dim3(256), 0, stream, d_ops);
+        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops);
     else if (pr.n_ready > 0)
         hipLaunchKernelGGL(clear_kernel, dim3((pr.n_ready / 4 + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint32_t *>(ws + lay.ready), pr.n_ready / 4);
