@@ -74,6 +74,9 @@ namespace mx {
 #ifndef RB_VAL_GO_PAUSE_IDLE
 #define RB_VAL_GO_PAUSE_IDLE 56
 #endif
+#ifndef RB_VAL_GO_PAUSE2
+#define RB_VAL_GO_PAUSE2 72                 // two tokens
+#endif
 
 #ifdef RB_EXP_TRACE
 #ifndef RB_TRACE_GRP
@@ -322,17 +325,20 @@ __global__ __launch_bounds__(256) void clear_kernel(uint32_t *ready, int n)
 // Validated hand-over, before every launch: the expanded input of every op that a producer of this
 // launch will write is set to "not written yet" (0xff in every byte of the 16-byte groups of real
 // columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  POISON_SPLIT
-// workgroups per op; one-token layout.
+// workgroups per op.
 constexpr int POISON_SPLIT = 4;
-__global__ __launch_bounds__(256) void poison_kernel(const Op *ops)
+__global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T)
 {
     const Op &op = ops[blockIdx.x];
     if (op.dep < 0) return;
-    const int groups = (int)(up_bytes(op.in, 1) / 16);
+    const int groups = (int)(up_bytes(op.in, T) / 16);
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (int i = blockIdx.y * 256 + threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
-        // group i of block b = i / 64 is [q][half j][operand column]: input columns b*128 + j*64 + q*16 .. +15
-        const int b = i >> 6, within = i & 63, q = within >> 4, j = (within >> 3) & 1;
+        // which 16 input columns group i holds (see up_group_offset): a block of 128 columns is
+        // [q][half j][operand column 0..7] for one token and [half j][q][operand column 0..15] for two
+        const int b = T == 1 ? i >> 6 : i >> 7;
+        const int q = T == 1 ? (i >> 4) & 3 : (i >> 4) & 3;
+        const int j = T == 1 ? (i >> 3) & 1 : (i >> 6) & 1;
         const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
         up[i] = make_uint4(v, v, v, v);
     }
@@ -373,7 +379,6 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const SlotRec *__restrict__ slots_g,
                                                            const SlotVals *__restrict__ vals_g)
 {
-    static_assert(!VAL || TT == 1, "the validated hand-over is built for the one-token layout");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     using Lds = LdsMap<CW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -656,42 +661,85 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         // looking at the first word of every group past the L2, and then loaded again
                         // whole.  One statement, so that the operand registers keep their place (a loop
                         // the compiler can see around a reload makes it move them while loads are in flight).
-                        if (((m >> STEP_DEP_SHIFT) & 7u) != 0 && !failed &&
-                            __ballot((B[s].r[0][0] & 0xff) == 0xff || (B[s].r[1][0] & 0xff) == 0xff) != 0ull) {
+                        bool poisoned = false;
+#pragma unroll
+                        for (int r = 0; r < KOP; ++r) poisoned |= (B[s].r[r][0] & 0xff) == 0xff;
+                        if (((m >> STEP_DEP_SHIFT) & 7u) != 0 && !failed && __ballot(poisoned) != 0ull) {
                             v4i rsrc;
                             rsrc[0] = (int)opnd_lo[s];
                             rsrc[1] = (int)opnd_hi[s];
                             rsrc[2] = 2 * up_block_bytes(TT);
                             rsrc[3] = 0x00020000;
-                            int c0, c1;
                             uint32_t left;
                             unsigned long long unwritten;
-                            asm volatile("s_mov_b32 %[left], 0x40000\n"
-                                         "1:\n\t"
-                                         "s_nop 4\n\t"
-                                         "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
-                                         "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
-                                         "s_waitcnt vmcnt(0)\n\t"
-                                         "v_and_b32 %[c0], 0xff, %[c0]\n\t"
-                                         "v_and_b32 %[c1], 0xff, %[c1]\n\t"
-                                         "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
-                                         "s_mov_b64 %[un], vcc\n\t"
-                                         "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
-                                         "s_or_b64 %[un], %[un], vcc\n\t"
-                                         "s_cmp_eq_u64 %[un], 0\n\t"
-                                         "s_cbranch_scc1 2f\n\t"
-                                         "s_sleep 8\n\t"
-                                         "s_sub_u32 %[left], %[left], 1\n\t"
-                                         "s_cmp_lg_u32 %[left], 0\n\t"
-                                         "s_cbranch_scc1 1b\n"
-                                         "2:\n\t"
-                                         "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
-                                         "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
-                                         "s_waitcnt vmcnt(0)"
-                                         : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [c0] "=&v"(c0), [c1] "=&v"(c1),
-                                           [un] "=&s"(unwritten), [left] "=&s"(left)
-                                         : [off] "v"(lane_off), [rs] "s"(rsrc)
-                                         : "vcc", "scc", "memory");
+                            if constexpr (TT == 1) {
+                                int c0, c1;
+                                asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                             "1:\n\t"
+                                             "s_nop 4\n\t"
+                                             "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
+                                             "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                             "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                             "s_mov_b64 %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "s_cmp_eq_u64 %[un], 0\n\t"
+                                             "s_cbranch_scc1 2f\n\t"
+                                             "s_sleep 8\n\t"
+                                             "s_sub_u32 %[left], %[left], 1\n\t"
+                                             "s_cmp_lg_u32 %[left], 0\n\t"
+                                             "s_cbranch_scc1 1b\n"
+                                             "2:\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)"
+                                             : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [c0] "=&v"(c0), [c1] "=&v"(c1),
+                                               [un] "=&s"(unwritten), [left] "=&s"(left)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc)
+                                             : "vcc", "scc", "memory");
+                            } else {
+                                int c0, c1, c2, c3;
+                                asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                             "1:\n\t"
+                                             "s_nop 4\n\t"
+                                             "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dword %[c2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dword %[c3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
+                                             "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                             "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                             "v_and_b32 %[c2], 0xff, %[c2]\n\t"
+                                             "v_and_b32 %[c3], 0xff, %[c3]\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                             "s_mov_b64 %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c2]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c3]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "s_cmp_eq_u64 %[un], 0\n\t"
+                                             "s_cbranch_scc1 2f\n\t"
+                                             "s_sleep 8\n\t"
+                                             "s_sub_u32 %[left], %[left], 1\n\t"
+                                             "s_cmp_lg_u32 %[left], 0\n\t"
+                                             "s_cbranch_scc1 1b\n"
+                                             "2:\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)"
+                                             : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [b2] "+v"(B[s].r[2 % KOP]),
+                                               [b3] "+v"(B[s].r[3 % KOP]), [c0] "=&v"(c0), [c1] "=&v"(c1), [c2] "=&v"(c2),
+                                               [c3] "=&v"(c3), [un] "=&s"(unwritten), [left] "=&s"(left)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc)
+                                             : "vcc", "scc", "memory");
+                            }
                             if (left == 0) {                  // a producer never delivered: report, stop checking
                                 failed = true;
                                 if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -919,8 +967,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     // no flags to watch: after the time the slowest producer's stores need to land, tell
                     // the compute wavefronts to go (they check what they get)
                     if (!all) {
-                        if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(RB_VAL_GO_PAUSE);
-                        else __builtin_amdgcn_s_sleep(RB_VAL_GO_PAUSE_IDLE);      // nothing to store: it got here earlier
+                        if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE : RB_VAL_GO_PAUSE2);
+                        else __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE_IDLE : RB_VAL_GO_PAUSE2);      // nothing to store: it got here earlier
                         publish(0, 0, ~0ull);
                         all = true;
                     }
@@ -1077,7 +1125,7 @@ struct Prepared {
     Layout lay;
     int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0, n_ready = 0;
     uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
-    bool validated = false;                 // hand-over without flags (one token, ops that depend on each other)
+    bool validated = false;                 // hand-over without flags (ops that depend on each other)
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
@@ -1174,7 +1222,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     // environment keeps the flags (for comparisons)
     {
         const char *env = std::getenv("RB_VALIDATED");
-        pr.validated = T == 1 && n_ready > 0 && !(env && env[0] == '0');
+        pr.validated = n_ready > 0 && !(env && env[0] == '0');
     }
     // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
     // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
@@ -1253,7 +1301,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
     if (pr.validated)
-        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops);
+        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops, pr.T);
     else if (pr.n_ready > 0)
         hipLaunchKernelGGL(clear_kernel, dim3((pr.n_ready / 4 + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint32_t *>(ws + lay.ready), pr.n_ready / 4);
@@ -1271,7 +1319,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     };
     const int rc = pr.T == 1 ? (pr.validated ? launch(stack_kernel<1, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
                                              : launch(stack_kernel<1, false>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES))
-                             : launch(stack_kernel<2, false>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
+                             : (pr.validated ? launch(stack_kernel<2, true>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES)
+                                             : launch(stack_kernel<2, false>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES));
     if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
