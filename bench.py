@@ -182,7 +182,7 @@ def main() -> int:
         "frac": packed_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "traffic": traffic,
         "note": "one launch per step; duration = HIP events around rb_stack_run on its stream "
-                "(includes the ~3 us input-expansion kernel)",
+                "(includes the ~4 us input-expansion kernel and the ~6 us kernel that marks inputs not yet written)",
     }
 
     if args.calibrate_copy:

@@ -121,6 +121,34 @@ def test_prepare_once_run_many_tokens():
         stack.run_prepared()
 
 
+@pytest.mark.parametrize("T", [1, 2])
+def test_flag_hand_over_gives_the_same_bits(T, monkeypatch):
+    """RB_VALIDATED=0 at prepare time selects the hand-over with one flag per row tile in place of
+    the flag-free one; both must give the same outputs bit for bit, and both pass the oracle check."""
+    shrink = {4096: 512, 11008: 1376}
+    ops, widths, layers, bufs = build_stack("7b", 2, 6, T, derived=False, shrink=shrink, gain=100.0)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
+    results = []
+    for switch in ("1", "0"):
+        monkeypatch.setenv("RB_VALIDATED", switch)
+        dev_bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
+        dev_bufs[0].copy_(torch.from_numpy(bufs[0]))
+        print(f"hand-over switch {switch}, T={T}", flush=True)
+        stack = rb.Stack(dev_layers, op_list, dev_bufs, T)
+        stack.prepare()
+        for _ in range(3):
+            stack.run_prepared()
+        torch.cuda.synchronize()
+        assert stack.status() == rb.RB_OK
+        stack.forget()
+        results.append(dev_bufs)
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    last = oracle.forward(*layers[-1], results[0][ops[-1].src].cpu().numpy())
+    assert oracle.relative_l2(results[0][ops[-1].dst].cpu().numpy().astype(np.float64), last).max() <= TOL
+
+
 def test_independent_ops_need_no_hand_over():
     """Ops that all read buffers nobody writes (the small-batch recipe: every op has its own
     input) run in one launch without waiting on each other."""
