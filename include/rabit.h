@@ -118,7 +118,9 @@ int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
  * both are held to).  An op may read any buffer written by an
  * earlier op (or never written: stack inputs); dst buffers must be distinct
  * from the op's src.  layers, ops and bufs are host arrays; bufs holds n_bufs
- * device pointers.
+ * device pointers.  Activations are expected to be finite: an infinity or NaN
+ * in an op's input (an fp16 overflow upstream) makes that op's outputs NaN on
+ * the fused kernels, where plain arithmetic could still give an infinity.
  */
 typedef struct rb_stack_op { int layer; int src; int dst; } rb_stack_op;
 

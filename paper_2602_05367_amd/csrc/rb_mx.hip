@@ -17,15 +17,20 @@
 //     the store, and the four-term expansion of h (.) y for the ops that read y
 //     next, written with device-scope 16-byte stores.  Keeping this traffic on
 //     wavefronts of their own means no wait on it ever drains a weight prefetch;
-//   * hand-over between compute units: a finishing wavefront, once its stores
-//     are acknowledged, raises the flag byte of its row tile; one finishing
-//     wavefront per workgroup watches the flags of the ops the next stage reads
-//     and keeps one bit per 256-row block in LDS; a compute wavefront requests
-//     an expanded-input tile only after its bit is set.  Nothing reads a line
-//     before it is final, so the reads may be plain ones that the 32 compute
-//     units of an XCD share in its L2; device-coherent reads of every operand
-//     would put twice the weight traffic on the fabric that also carries the
-//     HBM stream.
+//   * hand-over between compute units (VAL = true, the default): before a launch every 16-byte
+//     group of an expanded input that a producer of the launch will write is filled with 0xff
+//     bytes, which no bf8 term of a finite value has.  Producers just store.  One finishing
+//     wavefront per workgroup announces the next stage to its compute wavefronts a fixed pause
+//     after its own stores; a compute wavefront requests operand tiles with plain loads (shared
+//     by the 32 compute units of an XCD in its L2) and, when it consumes a tile, checks the first
+//     byte of every group; only a tile with a group that still reads 0xff is waited for and read
+//     again past the L2.  The pause is a matter of speed, not of correctness;
+//   * the older hand-over (VAL = false; RB_VALIDATED=0 in the environment when a plan is made): a
+//     finishing wavefront, once its stores are acknowledged, raises the flag byte of its row tile;
+//     the watching wavefront polls the flags of the ops the next stage reads and keeps one bit per
+//     256-row block in LDS; a compute wavefront requests an operand tile only after its bit is
+//     set.  Device-coherent reads of every operand would put twice the weight traffic on the
+//     fabric that also carries the HBM stream, which is why neither scheme uses them by default.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 

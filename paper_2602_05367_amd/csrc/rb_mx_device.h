@@ -42,7 +42,10 @@ __device__ __forceinline__ uint32_t expand4(float u)
         out |= (uint32_t)(pk & 0xff) << (8 * t);
         r = (r - __builtin_amdgcn_cvt_f32_bf8(pk, 0)) * 8.f;
     }
-    return out;
+    // A value that is not finite (an fp16 overflow upstream) becomes four NaN terms of one fixed
+    // pattern, so that the product is NaN whatever the conversion would have made of it and no
+    // term byte is ever 0xff, which the stack kernel reads as "not written yet".
+    return fabsf(u) < __builtin_inff() ? out : 0x7e7e7e7eu;
 }
 
 // byte address of (token, path, term, input column j) in an op's expanded input

@@ -149,6 +149,29 @@ def test_flag_hand_over_gives_the_same_bits(T, monkeypatch):
     assert oracle.relative_l2(results[0][ops[-1].dst].cpu().numpy().astype(np.float64), last).max() <= TOL
 
 
+def test_non_finite_activation_propagates_and_ends(monkeypatch):
+    """An infinity in the input must come out as non-finite outputs of every dependent op, at once:
+    the flag-free hand-over tells "not written yet" from data by a byte pattern that a NaN term
+    could otherwise take, and a wait on it would only end at its (long) bound with RB_ERR_HANDOVER."""
+    shrink = {4096: 512, 11008: 1376}
+    ops, widths, layers, bufs = build_stack("7b", 1, 7, 1, derived=False, shrink=shrink, gain=100.0)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
+    dev_bufs = [torch.zeros((1, w), dtype=torch.float16, device="cuda") for w in widths]
+    x = torch.from_numpy(bufs[0]).clone()
+    x[0, 5] = float("inf")
+    x[0, 77] = float("nan")
+    dev_bufs[0].copy_(x)
+    stack = rb.Stack(dev_layers, op_list, dev_bufs, 1)
+    stack.prepare()
+    print("non-finite input through a dependent stack", flush=True)
+    stack.run_prepared()
+    assert stack.status() == rb.RB_OK
+    stack.forget()
+    for op in ops:
+        assert not torch.isfinite(dev_bufs[op.dst]).any(), op.name
+
+
 def test_independent_ops_need_no_hand_over():
     """Ops that all read buffers nobody writes (the small-batch recipe: every op has its own
     input) run in one launch without waiting on each other."""
