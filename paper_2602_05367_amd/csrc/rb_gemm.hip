@@ -79,16 +79,18 @@ __global__ __launch_bounds__(256) void scale_kernel(const ActT *__restrict__ X, 
     }
 }
 
-// split-contraction variant: sums the partial outputs of the `split` workgroups of a row block and
-// rounds to the output type
+// split-contraction: sums the partial outputs of the `split` workgroups that share an output tile
+// and rounds to the output type.  part is [split][T][rows] for rows row0 .. row0 + rows - 1 of Y.
 __global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ part, void *__restrict__ Y, int out_dtype,
-                                                     size_t n, int split)
+                                                     int T, int out, int row0, int rows, int split)
 {
+    const size_t n = (size_t)T * rows;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     float s = 0.f;
     for (int k = 0; k < split; ++k) s += part[(size_t)k * n + i];
-    store_out(Y, out_dtype, i, s);
+    const size_t t = i / rows, r = i % rows;
+    store_out(Y, out_dtype, t * out + row0 + r, s);
 }
 
 // ----------------------------------------------------------------- GEMM ---
@@ -105,13 +107,17 @@ __device__ __forceinline__ void wait_copies_and_sync()
 }
 
 // WM x WN wavefronts (four in all); a wavefront owns MP row pairs (32 rows each) x NT token tiles
-// (32 tokens each).  The workgroup covers the column tiles gridDim.y deals it; with Acc given it
-// writes its partial sums to slice blockIdx.y of that fp32 scratch [gridDim.y][T][out] instead of
-// storing the output.
+// (32 tokens each).  Output tiles are numbered row block by row block.  Workgroups 0 .. full_tiles - 1
+// take one tile each and all of its column tiles (those gridDim.y deals them, when the whole grid
+// is split that way); the tiles after that - the last, partly filled round of the device - are
+// shared by tail_split workgroups each, which take a slice of the column tiles.  Whoever covers
+// only a slice writes fp32 partial sums to Acc [slice][T][tail_rows] (rows tail_row0 ..) instead
+// of storing the output; finish_kernel adds the slices.
 template <int OUT_DT, int WM, int WN, int MP, int NT, int AHEAD>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bits, const __half *__restrict__ g,
                                                       const _Float16 *__restrict__ U, void *__restrict__ Y,
-                                                      float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad)
+                                                      float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad,
+                                                      int full_tiles, int tail_split, int tail_row0, int tail_rows)
 {
     static_assert(WM * WN == 4 && WM * MP * 32 == BLK_ROWS, "tile shape");
     constexpr int BLK_TOK = WN * NT * 32;
@@ -129,11 +135,19 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
     // workgroups that share a token block sit on the same XCD (ids are dealt round-robin over
     // eight of them), so the slice of U they all walk stays in that XCD's L2
     const int TB = T_pad / BLK_TOK;
-    const int tb = blockIdx.x % TB, rb = blockIdx.x / TB;
+    int tile = (int)blockIdx.x, slice = (int)blockIdx.y, n_slices = (int)gridDim.y;
+    if (tile >= full_tiles) {
+        const int u = tile - full_tiles;
+        tile = full_tiles + u / tail_split;
+        slice = u % tail_split;
+        n_slices = tail_split;
+    }
+    const bool partial = n_slices > 1;
+    const int tb = tile % TB, rb = tile / TB;
     const int rt_base = rb * (BLK_ROWS / TILE_ROWS) + wm * MP * 2;           // first row tile of this wavefront
     // column tiles of this workgroup
-    const int ct_begin = (int)((long)CT * blockIdx.y / gridDim.y);
-    const int ct_end = (int)((long)CT * (blockIdx.y + 1) / gridDim.y);
+    const int ct_begin = (int)((long)CT * slice / n_slices);
+    const int ct_end = (int)((long)CT * (slice + 1) / n_slices);
 
     // ---- per-row constants: |g| as a packed pair, and whether the sign bits must be flipped
     // flip[i]: for the row this lane holds sign words of (row tile i, row r); G2[m]: for the row this
@@ -347,11 +361,10 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (row0 + e >= out) continue;
-                    const size_t idx = (size_t)t * out + row0 + e;
-                    if (Acc)
-                        Acc[(size_t)blockIdx.y * T * out + idx] = acc[m][n][4 * a4 + e];
+                    if (partial)
+                        Acc[((size_t)slice * T + t) * tail_rows + (row0 + e - tail_row0)] = acc[m][n][4 * a4 + e];
                     else
-                        store_out(Y, OUT_DT, idx, acc[m][n][4 * a4 + e]);
+                        store_out(Y, OUT_DT, (size_t)t * out + row0 + e, acc[m][n][4 * a4 + e]);
                 }
             }
         }
@@ -362,6 +375,8 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
 struct Plan {
     bool small;          // 32-token tiles with the contraction split over workgroups
     int T_pad, CT, in_pad, RT, RB, TB, split;
+    // 256-token tiles: the tiles of the last, partly filled round are shared by tail_split workgroups each
+    int full_tiles, tail_split, tail_row0, tail_rows;
     size_t u_bytes, acc_bytes;
 };
 
@@ -380,6 +395,28 @@ static Plan make_plan(const rb_layer *L, int T)
     p.split = p.small ? std::max(1, std::min(p.CT, (256 + p.RB * p.TB - 1) / (p.RB * p.TB))) : 1;
     p.u_bytes = (2 * (size_t)p.T_pad * p.in_pad * sizeof(_Float16) + 255) / 256 * 256;
     p.acc_bytes = p.split > 1 ? (size_t)p.split * T * L->out * sizeof(float) : 0;
+    const int tiles = p.RB * p.TB;
+    p.full_tiles = tiles;
+    p.tail_split = 1;
+    p.tail_row0 = 0;
+    p.tail_rows = L->out;
+    if (!p.small) {
+        // A tile takes the same time wherever it runs, so a last round that fills half of the
+        // compute units or less costs a whole round.  Its tiles (whole row blocks) are cut along
+        // the contraction instead, into as many slices as fill the round.
+        const int cus = mx::device_groups();
+        const int G = cus > 0 ? cus : 256;               // no device (size queries on a host): an MI355X
+        const int full = tiles / G * G / p.TB * p.TB;
+        const int tail = tiles - full;
+        const int cut = tail > 0 ? std::min(std::min(G / tail, 4), p.CT) : 1;
+        if (cut > 1) {
+            p.full_tiles = full;
+            p.tail_split = cut;
+            p.tail_row0 = full / p.TB * BLK_ROWS;
+            p.tail_rows = L->out - p.tail_row0;
+            p.acc_bytes = (size_t)cut * T * p.tail_rows * sizeof(float);
+        }
+    }
     return p;
 }
 
@@ -399,7 +436,7 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
 {
     const Plan p = make_plan(L, T);
     _Float16 *U = static_cast<_Float16 *>(workspace);
-    float *Acc = p.split > 1 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.u_bytes) : nullptr;
+    float *Acc = p.acc_bytes > 0 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.u_bytes) : nullptr;
     const __half *h = reinterpret_cast<const __half *>(L->h);
     const dim3 sgrid(p.in_pad / 256, p.T_pad);
     if (act_dtype == RB_F16)
@@ -410,16 +447,18 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
                            T, p.T_pad, L->in, p.in_pad);
     const v4u *bits = static_cast<const v4u *>(L->bits);
     const __half *g = reinterpret_cast<const __half *>(L->g);
-    const dim3 grid((unsigned)(p.RB * p.TB), (unsigned)p.split);
+    const int tail_tiles = p.RB * p.TB - p.full_tiles;
+    const dim3 grid((unsigned)(p.full_tiles + tail_tiles * p.tail_split), (unsigned)p.split);
     const size_t lds = p.small ? (size_t)(AHEAD_SMALL + 1) * SMALL_TOKENS * 64 : (size_t)(AHEAD_LARGE + 1) * LARGE_TOKENS * 64;
 #define RB_GEMM(DT, WM, WN, MP, NT)                                                                              \
     hipLaunchKernelGGL((gemm_kernel<DT, WM, WN, MP, NT, (NT == 1 ? AHEAD_SMALL : AHEAD_LARGE)>), grid, dim3(256), lds, \
-                       stream, bits, g, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad)
+                       stream, bits, g, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad, p.full_tiles, p.tail_split, p.tail_row0, \
+                       p.tail_rows)
     if (p.small && p.split > 1) {
         RB_GEMM(RB_F32, 4, 1, 2, 1);
         const size_t n = (size_t)T * L->out;
-        hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype, n,
-                           p.split);
+        hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype, T,
+                           L->out, 0, L->out, p.split);
     } else if (p.small) {
         if (out_dtype == RB_F16) RB_GEMM(RB_F16, 4, 1, 2, 1);
         else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 4, 1, 2, 1);
@@ -428,6 +467,11 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
         if (out_dtype == RB_F16) RB_GEMM(RB_F16, 2, 2, 4, 4);
         else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 2, 2, 4, 4);
         else RB_GEMM(RB_F32, 2, 2, 4, 4);
+        if (p.tail_split > 1) {
+            const size_t n = (size_t)T * p.tail_rows;
+            hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype,
+                               T, L->out, p.tail_row0, p.tail_rows, p.tail_split);
+        }
     }
 #undef RB_GEMM
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;

@@ -923,7 +923,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         const v4i bytes = *reinterpret_cast<const v4i *>(
                             stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
                         uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 16;
-                        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
+                                                asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
                 RB_FTRACE(1);

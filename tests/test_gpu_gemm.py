@@ -27,6 +27,9 @@ def _say(msg):
     (272, 320, 33),         # ragged rows (17 row tiles), ragged columns (in % 256 != 0)
     (1000, 2080, 517),      # everything ragged, three token blocks
     (48, 32, 3),            # tiny: one row tile group, the smallest input width
+    (4096, 1024, 256),      # 16 output tiles on 256 compute units: every tile's contraction cut in four
+    (8400, 1024, 2048),     # 264 tiles: one full round, then 8 tiles (ragged last row block) cut in four
+    (2816, 512, 2048),      # 88 tiles: cut in two, as many slices as column tiles
 ])
 def test_gemm_matches_oracle(out, inn, T):
     rng = synth.child_rng(5, 100, out, inn, T)
@@ -104,12 +107,14 @@ def test_prefill_70b_shapes_sampled(out, inn):
     scale = np.sqrt(np.mean(ref ** 2))
     assert np.max(np.abs(got - ref)) <= 4 * TOL * scale, (np.max(np.abs(got - ref)), scale)
     # two whole token rows over a 512-row slice: per-vector relative L2 as everywhere else
-    r0 = 3 * 512 if out >= 2048 else 0
-    rows2 = np.arange(r0, r0 + 512)
-    S2 = signs_rows(rows2)
-    for t in (0, T - 1):
-        x64 = oracle.bf16_bits_to_f64(bf16_bits(Xt[t:t + 1].cpu())).reshape(1, inn)
-        ref2 = oracle.forward(S2, g[:, rows2], h, x64)
-        err = max_rel_l2(Y[t:t + 1, r0:r0 + 512], ref2)
-        _say(f"  t={t} rel_l2={err:.3e}")
-        assert err <= TOL
+    # (for 28672 rows also the last 512: the row blocks of the partly filled last round, whose
+    # contraction is shared by two workgroups)
+    for r0 in ([3 * 512, out - 512] if out >= 2048 * 2 else [0]):
+        rows2 = np.arange(r0, r0 + 512)
+        S2 = signs_rows(rows2)
+        for t in (0, T - 1):
+            x64 = oracle.bf16_bits_to_f64(bf16_bits(Xt[t:t + 1].cpu())).reshape(1, inn)
+            ref2 = oracle.forward(S2, g[:, rows2], h, x64)
+            err = max_rel_l2(Y[t:t + 1, r0:r0 + 512], ref2)
+            _say(f"  rows {r0}.. t={t} rel_l2={err:.3e}")
+            assert err <= TOL
