@@ -125,3 +125,22 @@ def test_storage_accounting_reproduces_effective_bits():
     assert sum(2 * op.out * op.inn // 8 for op in ops13) == 3_171_942_400
     # the native layout adds no bytes when out % 16 == 0 and in % 256 == 0
     assert rb.rb_native_bytes(2, 4096, 11008) == 2 * 4096 * 11008 // 8
+
+
+def test_many_token_workspace_counts_the_shared_last_round():
+    """The many-token GEMM needs the scaled input (2 paths x T x in fp16) and, when the output
+    tiles (256 rows x 256 tokens) do not fill whole rounds of the device's 256 compute units, fp32
+    partial sums for the row blocks of the last round, one copy per workgroup that shares a tile."""
+    def need(out, inn, T):
+        L = rb.binding.rb_layer(out, inn, 2, 0x1000, 0x2000, 0x3000)
+        return rb.lib.rb_workspace_bytes(ctypes.byref(L), 1, 1, T)
+    T = 2048
+    u = lambda inn: 2 * T * inn * 2
+    # 112 x 8 = 896 tiles = 3.5 rounds: the last 16 row blocks (4096 rows), two workgroups per tile
+    assert need(28672, 8192, T) == u(8192) + 2 * T * 4096 * 4
+    # 32 x 8 = 256 tiles: one full round, nothing shared
+    assert need(8192, 28672, T) == u(28672)
+    # 16 x 8 = 128 tiles: half a round, every tile shared by two
+    assert need(4096, 4096, T) == u(4096) + 2 * T * 4096 * 4
+    # 43 x 8 = 344 tiles: one round, then 88 tiles (rows 8192..11007) shared by two
+    assert need(11008, 4096, T) == u(4096) + 2 * T * (11008 - 8192) * 4
