@@ -112,8 +112,8 @@ int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
  * inference table, reduced to its linear layers).  Op n applies
  * layers[ops[n].layer] to bufs[ops[n].src] and writes bufs[ops[n].dst]; every
  * buffer is device fp16 [T][width].  The result of each op equals
- * rb_linear_gemm on the same input (bit for bit for T <= 2 and T > 8; for
- * 3 <= T <= 8 the stack runs token pairs on the fused decode kernel while a
+ * rb_linear_gemm on the same input (bit for bit for T <= 2 and T > 16; for
+ * 3 <= T <= 16 a stack may run token pairs on the fused decode kernel while a
  * single call takes the many-token kernel, and the two agree to the accuracy
  * both are held to).  An op may read any buffer written by an
  * earlier op (or never written: stack inputs); dst buffers must be distinct
@@ -138,10 +138,10 @@ int rb_layer_stack(const rb_layer *layers, int n_layers,
  * between runs the caller must not write to the workspace nor change layers,
  * buffers addresses or T; rb_stack_forget drops the library's host-side record
  * of a workspace (call it before the memory is reused for something else).
- * T <= 2 runs as one launch; 3 <= T <= 8 as one launch per pair of consecutive
+ * T <= 2 runs as one launch; 3 <= T <= 16 as one launch per pair of consecutive
  * tokens (every layer's out a multiple of 8, at least two ops).
  * rb_stack_prepare returns RB_ERR_UNSUPPORTED for stacks that only
- * rb_layer_stack's general path can run (K != 2, T > 8, an output read by more
+ * rb_layer_stack's general path can run (K != 2, T > 16, an output read by more
  * than three ops, more than 1024 ops fed from outside the stack).
  */
 int rb_stack_prepare(const rb_layer *layers, int n_layers,

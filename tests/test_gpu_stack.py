@@ -33,8 +33,8 @@ def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
     else:
         rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
     torch.cuda.synchronize()
-    # 3..8 tokens run as token pairs on the fused kernel, a single call on the many-token kernel
-    same_kernel = T <= 2 or T > 8
+    # 3..16 tokens may run as token pairs on the fused kernel, a single call on the many-token kernel
+    same_kernel = T <= 2 or T > 16
     got = [b.cpu().numpy() for b in dev_bufs]
     forced = [got[op.src] for op in ops]
     refs = oracle.stack_forward(layers, op_list, [None] * len(widths), forced_inputs=forced)
@@ -77,9 +77,9 @@ def test_small_stack_batched_with_outliers(T):
     _run_and_check(ops, widths, layers, bufs, T, "batched small stack")
 
 
-@pytest.mark.parametrize("T", [3, 8])
+@pytest.mark.parametrize("T", [3, 8, 16])
 def test_prepared_small_batches_run_as_token_pairs(T):
-    """rb_stack_prepare / rb_stack_run at 3..8 tokens: one launch of the fused kernel per pair of
+    """rb_stack_prepare / rb_stack_run at 3..16 tokens: one launch of the fused kernel per pair of
     tokens (one token in the last launch when T is odd), every op checked against the oracle."""
     shrink = {4096: 512, 11008: 1376}
     ops, widths, layers, bufs = build_stack("7b", 2, 5, T, derived=False, shrink=shrink, outliers=True,
