@@ -148,7 +148,8 @@ struct SlotRec {
     uint64_t up[MAX_CONS];    // per reading op: the 16-byte group of operand column 0 these rows fill
     int out, n_cons;          // rows of the op; ops that read its output
     int row0, op;             // first row of the row tile; op index (< 0: slot unused)
-    uint64_t pad_;
+    uint32_t behind;          // sign tiles the busiest workgroup of this stage has more than this one
+    uint32_t pad_;
 };
 static_assert(sizeof(SlotRec) == 64, "four 16-byte loads");
 // per row of the slot: g_1 / sc_1, g_2 / sc_2 of the op (its output scales over the input scaling

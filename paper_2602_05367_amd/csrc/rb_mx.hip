@@ -74,13 +74,19 @@ namespace mx {
 
 // validated hand-over: pause between a workgroup's own stores and its "go" (s_sleep units)
 #ifndef RB_VAL_GO_PAUSE
-#define RB_VAL_GO_PAUSE 56
+#define RB_VAL_GO_PAUSE 32
 #endif
 #ifndef RB_VAL_GO_PAUSE_IDLE
-#define RB_VAL_GO_PAUSE_IDLE 56
+#define RB_VAL_GO_PAUSE_IDLE 32
+#endif
+#ifndef RB_VAL_TILE_PAUSE
+#define RB_VAL_TILE_PAUSE 32                // s_sleep units per 16 sign tiles that a workgroup is ahead of the busiest one
+#endif
+#ifndef RB_VAL_TILE_PAUSE2
+#define RB_VAL_TILE_PAUSE2 44               // the same for two tokens
 #endif
 #ifndef RB_VAL_GO_PAUSE2
-#define RB_VAL_GO_PAUSE2 72                 // two tokens
+#define RB_VAL_GO_PAUSE2 40                 // two tokens
 #endif
 
 #ifdef RB_EXP_TRACE
@@ -269,7 +275,22 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     }
     const size_t idx = ((size_t)st * G + grp) * MAXSLOT + slot;
     SlotRec sr;
-    sr.y = 0; sr.ready = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
+    sr.y = 0; sr.ready = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.behind = 0; sr.pad_ = 0;
+    if (row == 0) {
+        // how much less this workgroup has to do in this stage than the busiest one
+        uint32_t mine = 0, most = 0;
+        for (int gg = 0; gg < G; ++gg) {
+            uint32_t tiles = 0;
+            for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+                uint32_t rt0, nrt;
+                group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, o - stage.op0, rt0, nrt);
+                tiles += nrt * (uint32_t)ops[o].CT;
+            }
+            most = tiles > most ? tiles : most;
+            if (gg == grp) mine = tiles;
+        }
+        sr.behind = most - mine;
+    }
     for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
     float v[2 + 2 * MAX_CONS];
     for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) v[i] = 0.f;
@@ -974,6 +995,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     if (!all) {
                         if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE : RB_VAL_GO_PAUSE2);
                         else __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE_IDLE : RB_VAL_GO_PAUSE2);      // nothing to store: it got here earlier
+                        // a workgroup with a smaller share got here that much before the busiest one,
+                        // whose outputs its compute wavefronts would then request too early
+                        const uint32_t ahead = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur.r.behind) * (TT == 1 ? RB_VAL_TILE_PAUSE : RB_VAL_TILE_PAUSE2) / 16u;
+                        for (uint32_t i = 0; i < ahead; ++i) __builtin_amdgcn_s_sleep(1);
                         publish(0, 0, ~0ull);
                         all = true;
                     }
