@@ -260,9 +260,30 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     const int G = hdr->n_groups, T = hdr->T;
     const int st = blockIdx.x;
     const int grp = blockIdx.y * 2 + (threadIdx.x >> 7);
-    if (grp >= G) return;
-    const int slot = (threadIdx.x >> 4) & 7, row = threadIdx.x & 15;
     const Stage stage = stages[st];
+    // sign tiles of workgroup gg in this stage; the most any workgroup has (all threads take part)
+    auto stage_tiles = [&](int gg) {
+        uint32_t tiles = 0;
+        for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+            uint32_t rt0, nrt;
+            group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, o - stage.op0, rt0, nrt);
+            tiles += nrt * (uint32_t)ops[o].CT;
+        }
+        return tiles;
+    };
+    __shared__ uint32_t most_of[256];
+    uint32_t most = 0;
+    for (int gg = threadIdx.x; gg < G; gg += 256) most = max(most, stage_tiles(gg));
+    most_of[threadIdx.x] = most;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) most_of[threadIdx.x] = max(most_of[threadIdx.x], most_of[threadIdx.x + s]);
+        __syncthreads();
+    }
+    most = most_of[0];
+    if (grp >= G) return;
+    const uint32_t mine = stage_tiles(grp);
+    const int slot = (threadIdx.x >> 4) & 7, row = threadIdx.x & 15;
     int my_op = -1, row0 = 0, slot_base = 0;
     for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
         uint32_t rt0, nrt;
@@ -275,22 +296,8 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     }
     const size_t idx = ((size_t)st * G + grp) * MAXSLOT + slot;
     SlotRec sr;
-    sr.y = 0; sr.ready = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.behind = 0; sr.pad_ = 0;
-    if (row == 0) {
-        // how much less this workgroup has to do in this stage than the busiest one
-        uint32_t mine = 0, most = 0;
-        for (int gg = 0; gg < G; ++gg) {
-            uint32_t tiles = 0;
-            for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
-                uint32_t rt0, nrt;
-                group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, o - stage.op0, rt0, nrt);
-                tiles += nrt * (uint32_t)ops[o].CT;
-            }
-            most = tiles > most ? tiles : most;
-            if (gg == grp) mine = tiles;
-        }
-        sr.behind = most - mine;
-    }
+    sr.y = 0; sr.ready = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
+    sr.behind = most - mine;
     for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
     float v[2 + 2 * MAX_CONS];
     for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) v[i] = 0.f;
