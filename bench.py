@@ -167,6 +167,9 @@ def main() -> int:
         "ms_per_step_min": ms_min,
         "ms_per_step_median": sorted(per)[len(per) // 2],
         "wall_ms_per_step": wall * 1e3 / args.steps,
+        # input tiles (of 1,581,056 per token) that were requested before their producer had written
+        # them and had to be waited for: what the pacing of the hand-over costs
+        "tiles_waited_per_step": stack.waited() / float(args.steps + args.warmup),
     }
     # HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, scaled
     # by what the same counters read for a plain copy of known size)

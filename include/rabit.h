@@ -162,6 +162,14 @@ int rb_stack_forget(const void *workspace);
  * workspace that holds no prepared stack.
  */
 int rb_stack_status(const void *workspace, void *stream);
+/*
+ * Diagnostic of the hand-over pacing: like rb_stack_status (waits for `stream`,
+ * same return values), and stores in *tiles (host) how many input tiles, over
+ * all runs since rb_stack_prepare, a wavefront found not yet written when it
+ * came to use them and therefore waited for and read again.  Results do not
+ * depend on it; a large count per run means time lost to such waits.
+ */
+int rb_stack_waited(const void *workspace, void *stream, unsigned long long *tiles);
 
 /* Bytes of workspace that a compute call over n_ops ops on these layers needs
  * at T tokens (n_ops = 1 for rb_linear_gemv / rb_linear_gemm; 16-byte aligned

@@ -27,7 +27,7 @@ _ERR_NAMES = {-1: "RB_ERR_NULL", -2: "RB_ERR_SHAPE", -3: "RB_ERR_ALIGN", -4: "RB
 EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
-    "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status",
+    "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status", "rb_stack_waited",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -67,6 +67,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_run.argtypes = [p, z, p]
     lib.rb_stack_forget.argtypes = [p]
     lib.rb_stack_status.argtypes = [p, p]
+    lib.rb_stack_waited.argtypes = [p, p, ctypes.POINTER(ctypes.c_ulonglong)]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
     lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
@@ -245,6 +246,13 @@ class Stack:
     def status(self) -> int:
         """rb_stack_status: waits for the stream; RB_OK, or RB_ERR_HANDOVER if a run gave up a wait."""
         return int(lib.rb_stack_status(self.ws.data_ptr(), _stream()))
+
+    def waited(self) -> int:
+        """rb_stack_waited: input tiles, over all runs since prepare, that were requested before they
+        were written and had to be waited for (waits for the stream)."""
+        n = ctypes.c_ulonglong(0)
+        _check("rb_stack_waited", lib.rb_stack_waited(self.ws.data_ptr(), _stream(), ctypes.byref(n)))
+        return int(n.value)
 
     def forget(self) -> None:
         _check("rb_stack_forget", lib.rb_stack_forget(self.ws.data_ptr()))

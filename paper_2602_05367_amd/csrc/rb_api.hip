@@ -86,6 +86,15 @@ extern "C" int rb_stack_status(const void *workspace, void *stream)
     return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int rb_stack_waited(const void *workspace, void *stream, unsigned long long *tiles)
+{
+    if (!workspace || !tiles) return RB_ERR_NULL;
+    *tiles = 0;
+    const int rc = rb::pairs_status(workspace, static_cast<hipStream_t>(stream), tiles);
+    if (rc != RB_ERR_UNSUPPORTED) return rc;
+    return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream), tiles);
+}
+
 extern "C" int rb_stack_forget(const void *workspace)
 {
     if (!workspace) return RB_ERR_NULL;

@@ -102,7 +102,7 @@ int run_pairs(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return RB_OK;
 }
 
-int pairs_status(const void *workspace, hipStream_t stream)
+int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited)
 {
     PairPlans pp;
     {
@@ -112,7 +112,7 @@ int pairs_status(const void *workspace, hipStream_t stream)
         pp = it->second;
     }
     for (int p = 0; p < pp.passes; ++p) {
-        const int rc = mx::plan_status(static_cast<const uint8_t *>(workspace) + (size_t)p * pp.stride, stream);
+        const int rc = mx::plan_status(static_cast<const uint8_t *>(workspace) + (size_t)p * pp.stride, stream, waited);
         if (rc != RB_OK) return rc;
     }
     return RB_OK;

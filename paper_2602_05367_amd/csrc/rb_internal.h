@@ -29,7 +29,7 @@ int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, 
                   int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
 int run_pairs(void *workspace, size_t workspace_bytes, hipStream_t stream);
 void forget_pairs(const void *workspace);
-int pairs_status(const void *workspace, hipStream_t stream);     // RB_ERR_UNSUPPORTED: no plans of this kind
+int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);     // RB_ERR_UNSUPPORTED: no plans of this kind
 
 namespace gemm {
 // many-token matrix-core GEMM (K = 2): workspace holds the scaled input of both paths
@@ -61,7 +61,8 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint
 int launch_plan(void *workspace, size_t workspace_bytes, hipStream_t stream);
 void forget_plan(const void *workspace);
 // waits for the stream; RB_ERR_HANDOVER if a run of this plan gave up a wait, RB_ERR_WORKSPACE: no plan
-int plan_status(const void *workspace, hipStream_t stream);
+// waited (optional): += input tiles that compute wavefronts found not yet written and waited for, since the plan was made
+int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);
 }  // namespace mx
 
 }  // namespace rb

@@ -168,7 +168,8 @@ struct Stage {
 // set = 256-row block 64 * window + b of that op's output is final.
 constexpr int READY_WINDOWS = 4;   // inputs of up to 65536 columns
 constexpr int LDS_READY_BYTES = 2 * MAX_DEPS * READY_WINDOWS * 8;
-static_assert(LDS_READY_BYTES <= 256, "the first 256 bytes of the miscellaneous LDS area");
+constexpr int WAITED_LDS_OFF = 240;   // a counter behind the bits: lanes that waited for a tile not yet written
+static_assert(LDS_READY_BYTES <= WAITED_LDS_OFF && WAITED_LDS_OFF + 4 <= 256, "the first 256 bytes of the miscellaneous LDS area");
 
 struct Header {
     int n_ops, n_stages, T, n_groups;

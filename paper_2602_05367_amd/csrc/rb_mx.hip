@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
     if (o == 0) {
         zero_page[threadIdx.x] = 0;                       // 1 KB: what a padding step of the sign stream reads
-        if (threadIdx.x == 0) *error = 0;
+        if (threadIdx.x < 2) error[threadIdx.x] = 0;      // the give-up mark and the count of tiles waited for
     }
 }
 
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const uint32_t *__restrict__ odesc_g,
                                                            uint32_t sblocks, uint32_t oblocks,
                                                            const SlotRec *__restrict__ slots_g,
-                                                           const SlotVals *__restrict__ vals_g)
+                                                           const SlotVals *__restrict__ vals_g, int go_pause)
 {
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     using Lds = LdsMap<CW>;
@@ -428,6 +428,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 
     // ---- LDS set-up: clear the partial sums
     for (int i = threadIdx.x; i < Lds::PART_BYTES / 4; i += THREADS) part[i] = 0.f;
+    if (threadIdx.x == 0) *reinterpret_cast<uint32_t *>(lds + Lds::MISC_OFF + WAITED_LDS_OFF) = 0u;
     __syncthreads();
 
     if (wave < CW) {
@@ -437,6 +438,9 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         const int col = lane & 15, qd = lane >> 4;
         const int scale_b = term_scale(col);
         const uint32_t lane_off = (uint32_t)lane * 16u;
+        // diagnostic: every lane of a wavefront that had to wait for a tile adds one here (so 64 per
+        // tile); the watching wavefront hands the sum to the workspace at the end
+        const uint32_t waited_lds = lds_addr(lds + Lds::MISC_OFF + WAITED_LDS_OFF);
         uint32_t c22;
         asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c22));
         // A load that carries no data but keeps the number of vector-memory operations per
@@ -712,6 +716,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_nop 4\n\t"
                                              "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
                                              "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
                                              "s_waitcnt vmcnt(0)\n\t"
                                              "v_and_b32 %[c0], 0xff, %[c0]\n\t"
                                              "v_and_b32 %[c1], 0xff, %[c1]\n\t"
@@ -726,12 +732,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
                                              "2:\n\t"
-                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
-                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
-                                             "s_waitcnt vmcnt(0)"
+                                             "v_mov_b32 %[c0], 1\n\t"
+                                             "ds_add_u32 %[cnt], %[c0]"
                                              : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [c0] "=&v"(c0), [c1] "=&v"(c1),
                                                [un] "=&s"(unwritten), [left] "=&s"(left)
-                                             : [off] "v"(lane_off), [rs] "s"(rsrc)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
                                              : "vcc", "scc", "memory");
                             } else {
                                 int c0, c1, c2, c3;
@@ -742,6 +747,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
                                              "buffer_load_dword %[c2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
                                              "buffer_load_dword %[c3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
                                              "s_waitcnt vmcnt(0)\n\t"
                                              "v_and_b32 %[c0], 0xff, %[c0]\n\t"
                                              "v_and_b32 %[c1], 0xff, %[c1]\n\t"
@@ -762,17 +771,22 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
                                              "2:\n\t"
-                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
-                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
-                                             "s_waitcnt vmcnt(0)"
+                                             "v_mov_b32 %[c0], 1\n\t"
+                                             "ds_add_u32 %[cnt], %[c0]"
                                              : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [b2] "+v"(B[s].r[2 % KOP]),
                                                [b3] "+v"(B[s].r[3 % KOP]), [c0] "=&v"(c0), [c1] "=&v"(c1), [c2] "=&v"(c2),
                                                [c3] "=&v"(c3), [un] "=&s"(unwritten), [left] "=&s"(left)
-                                             : [off] "v"(lane_off), [rs] "s"(rsrc)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
                                              : "vcc", "scc", "memory");
                             }
+                            // Each look reads the first word of every group and then, with later loads
+                            // of the same wavefront from the same addresses, the groups themselves: when
+                            // the first words show data, so do the groups.  Should a group still start
+                            // with the pattern all the same, the run is reported, not trusted.
+                            bool still = false;
+#pragma unroll
+                            for (int r = 0; r < KOP; ++r) still |= (B[s].r[r][0] & 0xff) == 0xff;
+                            if (left != 0 && __ballot(still) != 0ull) left = 0;
                             if (left == 0) {                  // a producer never delivered: report, stop checking
                                 failed = true;
                                 if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -999,6 +1013,13 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 if constexpr (VAL) {
                     // no flags to watch: after the time the slowest producer's stores need to land, tell
                     // the compute wavefronts to go (they check what they get)
+                    if (!all && go_pause >= 0) {
+                        // a pause given by the caller of the launch (tests: none at all, so that
+                        // nearly every tile is requested before it is written)
+                        for (int i = 0; i < go_pause; ++i) __builtin_amdgcn_s_sleep(1);
+                        publish(0, 0, ~0ull);
+                        all = true;
+                    }
                     if (!all) {
                         if (__any(n_cons > 0)) __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE : RB_VAL_GO_PAUSE2);
                         else __builtin_amdgcn_s_sleep(TT == 1 ? RB_VAL_GO_PAUSE_IDLE : RB_VAL_GO_PAUSE2);      // nothing to store: it got here earlier
@@ -1091,6 +1112,13 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             cur = nxt;
         }
         RB_TRACE_DUMP();
+        // after the last barrier no compute wavefront waits for a tile any more
+        if (VAL && ew == 0 && lane == 0) {
+            const uint32_t lanes_waited = *reinterpret_cast<const uint32_t *>(lds + Lds::MISC_OFF + WAITED_LDS_OFF);
+            if (lanes_waited != 0)
+                __hip_atomic_fetch_add(RB_GLOBAL(uint32_t, error) + 1, lanes_waited / 64u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        }
         RB_FTRACE_DUMP();
     }
 }
@@ -1163,6 +1191,7 @@ struct Prepared {
     int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0, n_ready = 0;
     uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
     bool validated = false;                 // hand-over without flags (ops that depend on each other)
+    int go_pause = -1;                      // >= 0: pause before a stage is announced, in s_sleep units (RB_GO_PAUSE)
 };
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
@@ -1260,6 +1289,8 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     {
         const char *env = std::getenv("RB_VALIDATED");
         pr.validated = n_ready > 0 && !(env && env[0] == '0');
+        const char *pause = std::getenv("RB_GO_PAUSE");
+        pr.go_pause = pause && pause[0] >= '0' && pause[0] <= '9' ? std::min(std::atoi(pause), 4096) : -1;
     }
     // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
     // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
@@ -1351,7 +1382,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
                            reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
                            pr.sblocks, pr.oblocks,
-                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals));
+                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals),
+                           pr.go_pause);
         return RB_OK;
     };
     const int rc = pr.T == 1 ? (pr.validated ? launch(stack_kernel<1, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
@@ -1362,7 +1394,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
-int plan_status(const void *workspace, hipStream_t stream)
+int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited)
 {
     Prepared pr;
     {
@@ -1371,12 +1403,13 @@ int plan_status(const void *workspace, hipStream_t stream)
         if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
         pr = it->second;
     }
-    uint32_t mark = 0;
-    if (hipMemcpyAsync(&mark, static_cast<const uint8_t *>(workspace) + pr.lay.error, sizeof(mark), hipMemcpyDeviceToHost,
+    uint32_t mark[2] = {0, 0};               // gave up a wait; tiles waited for
+    if (hipMemcpyAsync(mark, static_cast<const uint8_t *>(workspace) + pr.lay.error, sizeof(mark), hipMemcpyDeviceToHost,
                        stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess)
         return RB_ERR_HIP;
-    return mark ? RB_ERR_HANDOVER : RB_OK;
+    if (waited) *waited += mark[1];
+    return mark[0] ? RB_ERR_HANDOVER : RB_OK;
 }
 
 void forget_plan(const void *workspace)

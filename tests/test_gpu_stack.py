@@ -172,6 +172,48 @@ def test_non_finite_activation_propagates_and_ends(monkeypatch):
         assert not torch.isfinite(dev_bufs[op.dst]).any(), op.name
 
 
+@pytest.mark.parametrize("T", [1, 2])
+def test_requests_ahead_of_the_writes_are_caught(T, monkeypatch):
+    """RB_GO_PAUSE=0 at prepare time lets every workgroup announce a stage the moment its own
+    stores are issued, so most input tiles are requested before the other workgroups have written
+    them.  The consumer must notice every such tile (the 'not written yet' byte pattern), wait
+    for it and read it again: same bits as the normally paced run, clean status, every kernel
+    ends by itself."""
+    shrink = {4096: 1024, 11008: 2752}
+    ops, widths, layers, bufs = build_stack("7b", 2, 8, T, derived=False, shrink=shrink, gain=100.0)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
+    results, waited = [], []
+    for pause in (None, "0", "3"):
+        if pause is None:
+            monkeypatch.delenv("RB_GO_PAUSE", raising=False)
+        else:
+            monkeypatch.setenv("RB_GO_PAUSE", pause)
+        dev_bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
+        print(f"go pause {pause}, T={T}", flush=True)
+        stack = rb.Stack(dev_layers, op_list, dev_bufs, T)
+        stack.prepare()
+        runs = []
+        for token in range(6):
+            x = synth.gaussian_activations(synth.child_rng(2, 61, token), T, widths[0])
+            dev_bufs[0].copy_(torch.from_numpy(x))
+            stack.run_prepared()
+            torch.cuda.synchronize()
+            runs.append([b.clone() for b in dev_bufs])
+        assert stack.status() == rb.RB_OK
+        waited.append(stack.waited())
+        print(f"  tiles waited for: {waited[-1]}", flush=True)
+        stack.forget()
+        results.append(runs)
+    assert waited[1] > 0                                     # the unpaced run did exercise the waits
+    for other in results[1:]:
+        for run_a, run_b in zip(results[0], other):
+            for a, b in zip(run_a, run_b):
+                assert torch.equal(a, b)
+    last = oracle.forward(*layers[-1], results[0][-1][ops[-1].src].cpu().numpy())
+    assert oracle.relative_l2(results[0][-1][ops[-1].dst].cpu().numpy().astype(np.float64), last).max() <= TOL
+
+
 def test_independent_ops_need_no_hand_over():
     """Ops that all read buffers nobody writes (the small-batch recipe: every op has its own
     input) run in one launch without waiting on each other."""
