@@ -74,11 +74,16 @@ namespace mx {
 
 // validated hand-over: pause between a workgroup's own stores and its "go" (s_sleep units)
 #ifndef RB_VAL_GO_PAUSE
-#define RB_VAL_GO_PAUSE 32
+#define RB_VAL_GO_PAUSE 20
 #endif
 #ifndef RB_VAL_GO_PAUSE_IDLE
-#define RB_VAL_GO_PAUSE_IDLE 32
+#define RB_VAL_GO_PAUSE_IDLE 20
 #endif
+#ifndef RB_VAL_POLL_SLEEP
+#define RB_VAL_POLL_SLEEP 8                 // between two looks at a tile that was not yet written
+#endif
+#define RB_STR_(x) #x
+#define RB_STR(x) RB_STR_(x)
 #ifndef RB_VAL_TILE_PAUSE
 #define RB_VAL_TILE_PAUSE 32                // s_sleep units per 16 sign tiles that a workgroup is ahead of the busiest one
 #endif
@@ -86,7 +91,7 @@ namespace mx {
 #define RB_VAL_TILE_PAUSE2 44               // the same for two tokens
 #endif
 #ifndef RB_VAL_GO_PAUSE2
-#define RB_VAL_GO_PAUSE2 40                 // two tokens
+#define RB_VAL_GO_PAUSE2 28                 // two tokens
 #endif
 
 #ifdef RB_EXP_TRACE
@@ -727,7 +732,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_or_b64 %[un], %[un], vcc\n\t"
                                              "s_cmp_eq_u64 %[un], 0\n\t"
                                              "s_cbranch_scc1 2f\n\t"
-                                             "s_sleep 8\n\t"
+                                             "s_sleep " RB_STR(RB_VAL_POLL_SLEEP) "\n\t"
                                              "s_sub_u32 %[left], %[left], 1\n\t"
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
@@ -766,7 +771,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_or_b64 %[un], %[un], vcc\n\t"
                                              "s_cmp_eq_u64 %[un], 0\n\t"
                                              "s_cbranch_scc1 2f\n\t"
-                                             "s_sleep 8\n\t"
+                                             "s_sleep " RB_STR(RB_VAL_POLL_SLEEP) "\n\t"
                                              "s_sub_u32 %[left], %[left], 1\n\t"
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
