@@ -55,11 +55,13 @@ __device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
 }
 
 // row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt).  Shares differ by one row
-// tile when G does not divide RT; every other op of a stage (pos = its position in the stage) deals
-// its shares out in the opposite order, so that the totals of a stage of like-shaped ops even out.
+// tile when G does not divide RT, and the larger ones sit at the same places for every op of that
+// height (every fourth share for 5120 rows on 256 workgroups); the op at position pos of its stage
+// deals its shares starting pos workgroups further on, so that the larger shares of like-shaped ops
+// of a stage fall on different workgroups where they can.
 __host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
 {
-    const uint32_t g = (pos & 1) ? G - 1 - grp : grp;
+    const uint32_t g = (grp + (uint32_t)pos) % G;
     rt0 = g * RT / G;
     nrt = (g + 1) * RT / G - rt0;
 }
