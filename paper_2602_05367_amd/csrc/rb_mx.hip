@@ -74,10 +74,10 @@ namespace mx {
 
 // validated hand-over: pause between a workgroup's own stores and its "go" (s_sleep units)
 #ifndef RB_VAL_GO_PAUSE
-#define RB_VAL_GO_PAUSE 20
+#define RB_VAL_GO_PAUSE 24
 #endif
 #ifndef RB_VAL_GO_PAUSE_IDLE
-#define RB_VAL_GO_PAUSE_IDLE 20
+#define RB_VAL_GO_PAUSE_IDLE 24
 #endif
 #ifndef RB_VAL_POLL_SLEEP
 #define RB_VAL_POLL_SLEEP 8                 // between two looks at a tile that was not yet written
