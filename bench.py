@@ -248,6 +248,17 @@ def main() -> int:
                                "pct_of_hbm_peak": 100.0 * packed13 / (ms13 * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         stack13.forget()
         del ops13, layers13, bufs13, stack13
+        # two tokens per pass through the same 7B-shaped chain (both tokens share every MFMA)
+        ops2, layers2, bufs2, op_list2, packed2 = build_stack(rb, synth, torch, "7b", 2)
+        stack2 = rb.Stack(layers2, op_list2, bufs2, 2)
+        stack2.prepare()
+        _, per2 = time_steps(torch, stack2.run_prepared, 30, 5)
+        ms2 = sum(per2) / len(per2)
+        result["stack_7b_two_tokens"] = {"ms_per_pass": ms2, "tokens_per_s": 2.0 / (ms2 * 1e-3),
+                                         "GBps": packed2 / (ms2 * 1e-3) / 1e9,
+                                         "tiles_waited_per_pass": stack2.waited() / 35.0}
+        stack2.forget()
+        del ops2, layers2, bufs2, stack2
         # three paths (the paper's 3-bit variant): no fused kernel, one launch of the generic
         # sign-XOR + add kernel per op; one block of the 7B shape, scaled to 32
         ops1, _ = synth.llama_stack("7b", n_layers=1)
