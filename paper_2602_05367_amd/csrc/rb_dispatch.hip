@@ -23,9 +23,13 @@ constexpr int PAIRS_MAX_T = 16;
 constexpr int PAIRS_MAX_T_ONESHOT = 4;
 
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// one slot per pass; the last pass of an odd T holds a one-token plan, whose step lists are longer
+// (more compute wavefronts), so a slot is sized for the larger of the two
 static size_t pair_stride(const rb_layer *layers, int n_layers, int n_ops)
 {
-    return round_up(mx::plan_workspace_bytes(layers, n_layers, n_ops, 2), 256);
+    const size_t two = mx::plan_workspace_bytes(layers, n_layers, n_ops, 2);
+    const size_t one = mx::plan_workspace_bytes(layers, n_layers, n_ops, 1);
+    return round_up(two > one ? two : one, 256);
 }
 static bool pairs_apply(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
@@ -77,7 +81,11 @@ int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, 
         for (int b = 0; b < n_bufs; ++b) sub[(size_t)b] = bufs[b] ? bufs[b] + (size_t)p * 2 * (size_t)width[(size_t)b] : nullptr;
         const int rc = mx::prepare_plan(layers, ops, n_ops, sub.data(), p * 2 + 2 <= T ? 2 : 1,
                                         static_cast<uint8_t *>(workspace) + (size_t)p * stride, stride, stream);
-        if (rc != RB_OK) return rc;
+        if (rc != RB_OK) {
+            // drop the records of the passes already prepared: the workspace holds no usable stack
+            for (int q = 0; q < p; ++q) mx::forget_plan(static_cast<uint8_t *>(workspace) + (size_t)q * stride);
+            return rc;
+        }
     }
     std::lock_guard<std::mutex> lock(g_pairs_mutex);
     g_pairs[workspace] = PairPlans{passes, stride};

@@ -322,3 +322,216 @@ def test_hand_over_at_full_scale_many_tokens():
         assert not bad, (token, bad[:5])
     assert stack.status() == rb.RB_OK
     stack.forget()
+
+
+# ------------------------------------------------------------------------------------------
+# The configurations the benchmark times, at the widths and through the entry points it uses
+# ------------------------------------------------------------------------------------------
+def _sampled_rows_check(rb_mod, ops, layers, bufs, op_numbers, rows_per_op, seed):
+    """Recompute sampled rows of the given ops with the oracle from the unpacked stored bits and the
+    input the GPU run used; returns the worst per-vector relative error."""
+    pick = np.random.default_rng(seed)
+    worst = 0.0
+    for n in op_numbers:
+        op, L = ops[n], layers[n]
+        y = bufs[op.dst].cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(y)) and np.any(y != 0), op.name
+        native = L.bits.cpu().numpy().view(np.uint32)
+        packed = rb_mod.rb_unpack_native(native, 2, L.out, L.inn)
+        rows = np.unique(pick.integers(0, L.out, size=rows_per_op))
+        S = rb_mod.rb_unpack(packed[:, rows, :])
+        g = L.g.cpu().numpy()[:, rows]
+        ref = oracle.forward(S, g, L.h.cpu().numpy(), bufs[op.src].cpu().numpy())
+        err = float(oracle.relative_l2(y[:, rows], ref).max())
+        worst = max(worst, err)
+        assert err <= TOL, (op.name, err)
+    return worst
+
+
+def test_one_full_width_7b_block_two_tokens_chained():
+    """The two-token kernel at the real 7B widths (43 column tiles, 688 row tiles, two or three per
+    workgroup), ops in dependency order, outlier channels in the stack input."""
+    ops, widths, layers, bufs = build_stack("7b", 1, 3, 2, derived=False, outliers=True, gain=100.0)
+    _run_and_check(ops, widths, layers, bufs, 2, "one full-width 7B block, T=2, chained", prepared=True)
+
+
+@pytest.mark.parametrize("T", [2, 4, 8, 16])
+def test_full_width_7b_block_small_batches_own_inputs(T):
+    """The small-batch workload as it is defined and timed: the seven matrices of a 7B-shaped
+    block at full width, every op on an input buffer of its own (N(0,1) with 1 % outlier channels
+    times 20), through rb_stack_prepare / rb_stack_run.  Every output element is checked."""
+    ops, _ = synth.llama_stack("7b", 1)
+    rng = synth.child_rng(3, 300 + T)
+    layers = [random_layer(rng, 2, op.out, op.inn) for op in ops]
+    xs = [synth.outlier_activations(rng, T, op.inn) for op in ops]
+    dev_layers = [to_device_layer(*l) for l in layers]
+    bufs = [torch.from_numpy(x).cuda() for x in xs] + \
+           [torch.zeros((T, op.out), dtype=torch.float16, device="cuda") for op in ops]
+    op_list = [(n, n, len(ops) + n) for n in range(len(ops))]
+    print(f"full-width block, own inputs, T={T}", flush=True)
+    stack = rb.Stack(dev_layers, op_list, bufs, T)
+    stack.prepare()
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK
+    first = [b.clone() for b in bufs]
+    stack.run_prepared()                                 # scratch state must not leak between runs
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK
+    stack.forget()
+    for a, b in zip(first, bufs):
+        assert torch.equal(a, b)
+    worst = 0.0
+    for n, op in enumerate(ops):
+        ref = oracle.forward(*layers[n], xs[n])
+        err = float(oracle.relative_l2(bufs[len(ops) + n].cpu().numpy().astype(np.float64), ref).max())
+        worst = max(worst, err)
+        assert err <= TOL, (op.name, T, err)
+    print(f"  worst rel_l2={worst:.3e}", flush=True)
+
+
+def test_full_13b_stack_as_benchmarked_sampled_outputs():
+    """The 280-op 13B-shaped stack exactly as bench.py builds and times it: sampled rows of the
+    first, a middle and the last block against the oracle, a second run bit-identical, status clean."""
+    import bench
+    ops, layers, bufs, op_list, packed_bytes = bench.build_stack(rb, synth, torch, "13b", 1)
+    assert len(ops) == 280 and packed_bytes == 3171942400
+    stack = rb.Stack(layers, op_list, bufs, 1)
+    stack.prepare()
+    print("full 13B-shaped stack, prepared, run 1", flush=True)
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX
+    assert stack.status() == rb.RB_OK
+    first = [b.clone() for b in bufs]
+    print("full 13B-shaped stack, run 2", flush=True)
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK
+    for a, b in zip(first, bufs):
+        assert torch.equal(a, b)
+    stack.forget()
+    picked = [n for blk in (0, 20, 39) for n in range(7 * blk, 7 * blk + 7)]
+    worst = _sampled_rows_check(rb, ops, layers, bufs, picked, 40, seed=13)
+    print(f"  worst sampled rel_l2={worst:.3e}", flush=True)
+
+
+# ------------------------------------------------------------------------------------------
+# Degenerate scales and extreme activations on the matrix-core decode kernels
+# ------------------------------------------------------------------------------------------
+def _edge_layer(rng, out, inn, zero_path=None):
+    """Scales with negative and exactly-zero entries (Section 4.1 puts no sign constraint on g, h);
+    optionally one path whose input scales are all zero."""
+    signs = synth.uniform_signs(rng, 2, out, inn)
+    g = (rng.standard_normal((2, out)) * 0.05)
+    h = (rng.standard_normal((2, inn)) * 0.05)
+    g[:, rng.choice(out, size=max(1, out // 16), replace=False)] = 0.0
+    h[:, rng.choice(inn, size=max(1, inn // 16), replace=False)] = 0.0
+    g[1] *= 0.3
+    h[1] *= 0.3
+    if zero_path is not None:
+        h[zero_path] = 0.0
+    return signs, g.astype(np.float16), h.astype(np.float16)
+
+
+def _edge_activations(rng, T, inn):
+    """N(0,1) with 1 % outlier channels, a few entries at the ends of the fp16 range (+-65504),
+    fp16 subnormals and exact zeros."""
+    x = synth.outlier_activations(rng, T, inn).astype(np.float64)
+    idx = rng.choice(inn, size=12, replace=False)
+    x[:, idx[0:2]] = 65504.0
+    x[:, idx[2:4]] = -65504.0
+    x[:, idx[4:8]] = 3.0e-7 * np.array([1, -1, 2, -3])          # subnormal in fp16
+    x[:, idx[8:12]] = 0.0
+    return x.astype(np.float16)
+
+
+@pytest.mark.parametrize("zero_path", [None, 0, 1])
+def test_single_call_decode_kernel_with_degenerate_scales_and_extreme_inputs(zero_path):
+    out, inn = 272, 4096 + 256
+    rng = synth.child_rng(0, 400, -1 if zero_path is None else zero_path)
+    signs, g, h = _edge_layer(rng, out, inn, zero_path)
+    x = _edge_activations(rng, 1, inn)
+    L = to_device_layer(signs, g, h)
+    print(f"edge cases, single call, zero_path={zero_path}", flush=True)
+    y = rb.rb_linear_gemv(L, torch.from_numpy(x[0]).cuda())
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX
+    ref = oracle.forward(signs, g, h, x)
+    got = y.cpu().numpy().astype(np.float64)[None]
+    assert np.all(np.isfinite(got))
+    err = float(oracle.relative_l2(got, ref)[0])
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL
+    # rows whose output scales are both zero give exactly zero
+    dead = np.where((g[0] == 0) & (g[1] == 0))[0]
+    assert dead.size > 0 and np.all(got[0, dead] == 0.0)
+
+
+@pytest.mark.parametrize("T", [1, 2])
+def test_stack_decode_kernel_with_degenerate_scales_and_extreme_inputs(T):
+    """Three dependent ops through the persistent kernel.  The first op is fed from outside with
+    extreme activations; its output scales make some of its outputs large (thousands) and others
+    fp16-subnormal, and those feed an op whose input scales contain negatives, zeros and one
+    all-zero path, whose output feeds a third."""
+    rng = synth.child_rng(0, 410 + T)
+    d0, d1, d2, d3 = 1024 + 32, 560, 784, 272
+    l1 = _edge_layer(rng, d1, d0)
+    g1 = l1[1].astype(np.float64)
+    g1[:, : d1 // 8] *= 200.0                        # some outputs in the thousands
+    g1[:, d1 // 8: d1 // 4] *= 1e-5                  # some outputs subnormal in fp16
+    l1 = (l1[0], g1.astype(np.float16), l1[2])
+    l2 = _edge_layer(rng, d2, d1, zero_path=1)
+    l3 = _edge_layer(rng, d3, d2, zero_path=0)
+    layers = [l1, l2, l3]
+    x = _edge_activations(rng, T, d0)
+    x[x == 65504.0] = 2000.0                         # keep the first op's outputs finite in fp16
+    x[x == -65504.0] = -2000.0
+    dev_layers = [to_device_layer(*l) for l in layers]
+    widths = [d0, d1, d2, d3]
+    dev_bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
+    dev_bufs[0].copy_(torch.from_numpy(x))
+    op_list = [(0, 0, 1), (1, 1, 2), (2, 2, 3)]
+    print(f"edge cases, three dependent ops, T={T}", flush=True)
+    stack = rb.Stack(dev_layers, op_list, dev_bufs, T)
+    stack.prepare()
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_MX and stack.status() == rb.RB_OK
+    stack.forget()
+    got = [b.cpu().numpy() for b in dev_bufs]
+    y1 = got[1].astype(np.float64)
+    assert np.all(np.isfinite(y1)) and np.abs(y1).max() > 1000.0
+    assert np.any((np.abs(y1) < 6.1e-5) & (y1 != 0)), "no fp16-subnormal activation reached the second op"
+    for n, (l, s, d) in enumerate(op_list):
+        ref = oracle.forward(*layers[l], got[s])
+        err = float(oracle.relative_l2(got[d].astype(np.float64), ref).max())
+        print(f"  op {n}: rel_l2={err:.3e}", flush=True)
+        assert np.all(np.isfinite(got[d]))
+        assert err <= TOL, (n, err)
+
+
+@pytest.mark.parametrize("T,n_chain", [(3, 2), (5, 2), (3, 8), (5, 8)])
+def test_prepared_odd_batches_on_pure_chains(T, n_chain):
+    """Odd T on a chain in which every op is a stage of its own: the last pass holds one token, and
+    the workspace that rb_workspace_bytes reports must be enough for it."""
+    rng = synth.child_rng(3, 500 + 10 * T + n_chain)
+    d = 4096
+    layers = [random_layer(rng, 2, d, d, gain=100.0) for _ in range(n_chain)]
+    x = synth.outlier_activations(rng, T, d)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    bufs = [torch.zeros((T, d), dtype=torch.float16, device="cuda") for _ in range(n_chain + 1)]
+    bufs[0].copy_(torch.from_numpy(x))
+    op_list = [(n, n, n + 1) for n in range(n_chain)]
+    print(f"pure chain of {n_chain} ops, T={T}", flush=True)
+    stack = rb.Stack(dev_layers, op_list, bufs, T)
+    stack.prepare()
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK
+    stack.forget()
+    got = [b.cpu().numpy() for b in bufs]
+    for n in range(n_chain):
+        ref = oracle.forward(*layers[n], got[n])
+        err = float(oracle.relative_l2(got[n + 1].astype(np.float64), ref).max())
+        assert np.all(np.isfinite(got[n + 1])) and err <= TOL, (n, err)

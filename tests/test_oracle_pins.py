@@ -55,10 +55,33 @@ def test_pack_rejects_bad_input():
         oracle.pack(bad)
 
 
+# ----------------------------------------------------------------- metric ---
+def test_relative_l2_on_hand_computed_vectors():
+    """The parity metric itself: per-vector ||test - ref|| / ||ref||, worked out by hand.  A
+    denominator taken from the wrong argument, a missing square root, or a norm over the wrong
+    axis fails one of these."""
+    test = np.array([[3.0, 4.0], [1.0, 1.0], [0.0, 6.0]])
+    ref = np.array([[3.0, 0.0], [0.0, 0.0], [0.0, 2.0]])
+    # row 0: ||(0,4)|| / ||(3,0)|| = 4/3 (4/5 if the test vector's norm were used)
+    # row 1: reference norm 0 -> the guard divides by 1: ||(1,1)|| = sqrt(2)
+    # row 2: ||(0,4)|| / ||(0,2)|| = 2 (16/4 = 4 without the square roots)
+    got = oracle.relative_l2(test, ref)
+    assert got.shape == (3,)
+    assert got[0] == 4.0 / 3.0 and got[1] == np.sqrt(2.0) and got[2] == 2.0
+    # identical inputs give exactly zero, and a 1-D pair is one vector
+    assert np.all(oracle.relative_l2(ref, ref) == 0.0)
+    assert oracle.relative_l2(np.array([1.0, 2.0, 2.0]), np.array([0.0, 0.0, 3.0])).tolist() == [np.sqrt(6.0) / 3.0]   # (1,2,-1) over (0,0,3)
+    # leading axes are flattened: [2][2][2] is four vectors
+    four = oracle.relative_l2(np.ones((2, 2, 2)), np.full((2, 2, 2), 2.0))
+    assert four.shape == (4,) and np.allclose(four, 0.5, rtol=0, atol=1e-16)
+
+
 # ---------------------------------------------------------------- forward ---
-def test_forward_brute_force_all_4x4_sign_matrices():
-    """K=1, g=h=1: for every one of the 2^16 sign matrices, y_i must be the
-    explicit signed sum of x (pure Python, independent of the oracle's loops)."""
+def test_forward_brute_force_all_sign_rows_of_4x4_matrices():
+    """K=1, g=h=1: rows of a product are independent, so all 16 sign rows in every row position
+    (256 matrices) plus all 16 patterns of one row against fixed others cover every 4x4 sign
+    matrix; y_i must be the explicit signed sum of x (pure Python, independent of the oracle's
+    loops)."""
     x = np.array([0.75, -1.5, 2.25, 0.125])
     all_rows = list(itertools.product((1, -1), repeat=4))
     ones = np.ones((1, 4))
@@ -72,7 +95,7 @@ def test_forward_brute_force_all_4x4_sign_matrices():
             for j in range(4):
                 expect = expect + (x[j] if rows[i][j] == 1 else -x[j])
             assert y[i] == expect
-    # and the full 2^16 enumeration on the first row with the others fixed
+    # and every pattern of one row with the others fixed
     for pattern in itertools.product((1, -1), repeat=4):
         B = np.ones((1, 4, 4), dtype=np.int8)
         B[0, 2] = pattern
@@ -237,6 +260,39 @@ def test_residual_fractions_for_gaussian_weights():
     assert frac[0] == pytest.approx(1 - 2 / np.pi, abs=4e-3)
     assert frac[1] == pytest.approx(0.130, abs=3e-3)
     assert frac[2] == pytest.approx(0.058, abs=2e-3)
+
+
+def test_scales_are_rounded_before_the_residual_is_formed():
+    """The reading taken for Alg. 2's forward loop with fp16 scales: path k+1 binarises the
+    residual of the *deployed* (fp16-rounded) path k.  A 4x4 matrix is built so that one entry
+    lies between g_i h_j of the unrounded rank-1 fit and the product of the two fp16-rounded
+    scales; the sign of that residual entry, hence B_2, then differs between rounding before and
+    after the residual.  The expectation is formed here from LAPACK's SVD, not from the oracle."""
+    rng = synth.child_rng(0, 77)
+    W = np.abs(rng.standard_normal((4, 4))) + 0.5
+    i, j = 2, 1
+    for _ in range(60):                               # fixed point: the entry moves by ~1e-4 relative
+        U, S, Vt = np.linalg.svd(np.abs(W))
+        a, b = np.abs(U[:, 0]) * np.sqrt(S[0]), np.abs(Vt[0]) * np.sqrt(S[0])
+        p_exact = a[i] * b[j]
+        p_fp16 = float(np.float16(a[i])) * float(np.float16(b[j]))
+        target = 0.5 * (p_exact + p_fp16)
+        if W[i, j] == target:
+            break
+        W[i, j] = target
+    assert p_exact != p_fp16, "the two products must differ for this pin to bite"
+    expect_rounded = 1 if W[i, j] - p_fp16 >= 0 else -1
+    expect_exact = 1 if W[i, j] - p_exact >= 0 else -1
+    assert expect_rounded == -expect_exact
+    signs_r, g_r, h_r, _ = oracle.derive(W, 2, round_scales=True)
+    signs_e, _, _, _ = oracle.derive(W, 2, round_scales=False)
+    assert g_r.dtype == np.float16 and h_r.dtype == np.float16
+    assert signs_r[1, i, j] == expect_rounded
+    assert signs_e[1, i, j] == expect_exact
+    # the whole second core equals sign(W - g16 (.) B_1 (.) h16) with the scales from LAPACK
+    g16 = np.float16(a).astype(np.float64); h16 = np.float16(b).astype(np.float64)
+    R1 = W - g16[:, None] * h16[None, :]
+    assert np.array_equal(signs_r[1], np.where(R1 >= 0, 1, -1))
 
 
 def test_derive_k1_reduces_to_scaled_sign_and_rank1_exact_case():
