@@ -108,6 +108,23 @@ int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * rb_linear_gemm for callers that cannot allocate or hold a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * status codes as rb_linear_gemm without the workspace pair; the scratch memory of the many-token
+ * kernel is a device array inside the library (RB_NOALLOC_SCRATCH_BYTES per GPU that uses the
+ * library, held until the process ends).  The call allocates nothing on host or device.  It returns
+ * RB_ERR_WORKSPACE when rb_workspace_bytes(L, 1, 1, T) of the many-token kernel exceeds
+ * RB_NOALLOC_SCRATCH_BYTES (roughly T_padded * in above 4 M elements).  Every call on one GPU
+ * shares that GPU's array: calls that may overlap in time on one GPU (different streams or
+ * threads) race and must be ordered by the caller; calls on one stream are ordered already.
+ * rb_noalloc_scratch_bytes returns RB_NOALLOC_SCRATCH_BYTES.
+ */
+#define RB_NOALLOC_SCRATCH_BYTES (32u << 20)
+int rb_linear_gemm_noalloc(const rb_layer *L, const void *X, void *Y, int T,
+                           int act_dtype, int out_dtype, void *stream);
+size_t rb_noalloc_scratch_bytes(void);
+
+/*
  * A stack of layers run in order (the end-to-end decode setting of the paper's
  * inference table, reduced to its linear layers).  Op n applies
  * layers[ops[n].layer] to bufs[ops[n].src] and writes bufs[ops[n].dst]; every

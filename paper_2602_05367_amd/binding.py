@@ -28,6 +28,7 @@ EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
     "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status", "rb_stack_waited",
+    "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -61,6 +62,9 @@ def _load() -> ctypes.CDLL:
     lib.rb_unpack_native.argtypes = [p, i, i, i, p]
     lib.rb_linear_gemv.argtypes = [ctypes.POINTER(rb_layer), p, p, p, z, p]
     lib.rb_linear_gemm.argtypes = [ctypes.POINTER(rb_layer), p, p, i, i, i, p, z, p]
+    lib.rb_linear_gemm_noalloc.argtypes = [ctypes.POINTER(rb_layer), p, p, i, i, i, p]
+    lib.rb_noalloc_scratch_bytes.argtypes = []
+    lib.rb_noalloc_scratch_bytes.restype = z
     lib.rb_layer_stack.argtypes = [ctypes.POINTER(rb_layer), i, ctypes.POINTER(rb_stack_op), i,
                                    ctypes.POINTER(ctypes.c_void_p), i, i, p, z, p]
     lib.rb_stack_prepare.argtypes = lib.rb_layer_stack.argtypes
@@ -76,7 +80,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_version.argtypes = []
     lib.rb_last_path.argtypes = []
     for name in EXPORTS:
-        if name not in ("rb_native_bytes", "rb_workspace_bytes"):
+        if name not in ("rb_native_bytes", "rb_workspace_bytes", "rb_noalloc_scratch_bytes"):
             getattr(lib, name).restype = i
     return lib
 
@@ -211,6 +215,22 @@ def rb_linear_gemm(layer: Layer, X: torch.Tensor, out_dtype=torch.float16, Y: to
                                                 _DTYPE_CODE[X.dtype], _DTYPE_CODE[Y.dtype],
                                                 ws.data_ptr(), n, _stream()))
     return Y
+
+
+def rb_linear_gemm_noalloc(layer: Layer, X: torch.Tensor, Y: torch.Tensor) -> torch.Tensor:
+    """rb_linear_gemm_noalloc: like rb_linear_gemm, scratch memory inside the library; the caller
+    passes the output tensor, so that nothing is allocated on the way."""
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.inn
+    assert Y.is_cuda and Y.is_contiguous() and tuple(Y.shape) == (X.shape[0], layer.out)
+    s = layer.struct()
+    _check("rb_linear_gemm_noalloc", lib.rb_linear_gemm_noalloc(
+        ctypes.byref(s), X.data_ptr(), Y.data_ptr(), X.shape[0], _DTYPE_CODE[X.dtype], _DTYPE_CODE[Y.dtype],
+        _stream()))
+    return Y
+
+
+def rb_noalloc_scratch_bytes() -> int:
+    return int(lib.rb_noalloc_scratch_bytes())
 
 
 class Stack:
