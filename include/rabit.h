@@ -188,6 +188,17 @@ int rb_stack_status(const void *workspace, void *stream);
  */
 int rb_stack_waited(const void *workspace, void *stream, unsigned long long *tiles);
 
+/*
+ * Tuning and test knob of the fused kernel; affects stacks prepared afterwards (process-wide).
+ * RB_OPT_HANDOVER_PAUSE: clocks a compute unit lets pass, after it has stored its own part of an
+ * op's output, before it asks for the parts the other compute units store.  Results never depend
+ * on it (what is read too early is detected and read again); 0 makes nearly every input tile an
+ * early read, which is what the tests use it for.  Returns RB_ERR_UNSUPPORTED for an unknown
+ * option, RB_ERR_SHAPE for a negative value.
+ */
+#define RB_OPT_HANDOVER_PAUSE 1
+int rb_stack_set_option(int option, int value);
+
 /* Bytes of workspace that a compute call over n_ops ops on these layers needs
  * at T tokens (n_ops = 1 for rb_linear_gemv / rb_linear_gemm; 16-byte aligned
  * device memory, contents owned by the library between calls). */

@@ -28,6 +28,7 @@ EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
     "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status", "rb_stack_waited",
+    "rb_stack_set_option",
     "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
@@ -70,6 +71,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_prepare.argtypes = lib.rb_layer_stack.argtypes
     lib.rb_stack_run.argtypes = [p, z, p]
     lib.rb_stack_forget.argtypes = [p]
+    lib.rb_stack_set_option.argtypes = [i, i]
     lib.rb_stack_status.argtypes = [p, p]
     lib.rb_stack_waited.argtypes = [p, p, ctypes.POINTER(ctypes.c_ulonglong)]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
@@ -303,6 +305,11 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
 
 
 RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM = 0, 1, 2, 3
+RB_OPT_HANDOVER_PAUSE = 1
+
+
+def rb_stack_set_option(option: int, value: int) -> None:
+    _check("rb_stack_set_option", lib.rb_stack_set_option(option, value))
 
 
 def rb_last_path() -> int:

@@ -95,6 +95,16 @@ extern "C" int rb_stack_waited(const void *workspace, void *stream, unsigned lon
     return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream), tiles);
 }
 
+extern "C" int rb_stack_set_option(int option, int value)
+{
+    if (option == RB_OPT_HANDOVER_PAUSE) {
+        if (value < 0) return RB_ERR_SHAPE;
+        rb::mx::set_pause(value);
+        return RB_OK;
+    }
+    return RB_ERR_UNSUPPORTED;
+}
+
 extern "C" int rb_stack_forget(const void *workspace)
 {
     if (!workspace) return RB_ERR_NULL;
