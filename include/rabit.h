@@ -189,12 +189,12 @@ int rb_stack_status(const void *workspace, void *stream);
 int rb_stack_waited(const void *workspace, void *stream, unsigned long long *tiles);
 
 /*
- * Tuning and test knob of the fused kernel; affects stacks prepared afterwards (process-wide).
- * RB_OPT_HANDOVER_PAUSE: clocks a compute unit lets pass, after it has stored its own part of an
- * op's output, before it asks for the parts the other compute units store.  Results never depend
- * on it (what is read too early is detected and read again); 0 makes nearly every input tile an
- * early read, which is what the tests use it for.  Returns RB_ERR_UNSUPPORTED for an unknown
- * option, RB_ERR_SHAPE for a negative value.
+ * Tuning and test knob of the fused kernel; affects launches made afterwards (process-wide).
+ * RB_OPT_HANDOVER_PAUSE: clocks (rounded down to multiples of 64) a compute unit lets pass, after
+ * it has stored its own part of a group of independent ops, before it asks for the parts the other
+ * compute units store.  Results never depend on it (what is read too early is detected and read
+ * again); 0 makes nearly every input tile an early read, which is what the tests use it for.  A
+ * negative value restores the built-in timing.  Returns RB_ERR_UNSUPPORTED for an unknown option.
  */
 #define RB_OPT_HANDOVER_PAUSE 1
 int rb_stack_set_option(int option, int value);

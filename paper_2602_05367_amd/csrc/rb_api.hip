@@ -98,7 +98,6 @@ extern "C" int rb_stack_waited(const void *workspace, void *stream, unsigned lon
 extern "C" int rb_stack_set_option(int option, int value)
 {
     if (option == RB_OPT_HANDOVER_PAUSE) {
-        if (value < 0) return RB_ERR_SHAPE;
         rb::mx::set_pause(value);
         return RB_OK;
     }

@@ -49,7 +49,7 @@ int launch(const rb_layer *L, const void *x, void *y, hipStream_t stream);
 namespace mx {
 // workgroups of the decode kernels: one per compute unit of the current device (0: no device)
 int device_groups();
-// matrix-core path (K = 2, T <= 2, at most 32768 input columns): whole op lists run as one persistent kernel
+// matrix-core path (K = 2, T <= 2): whole op lists run as one persistent kernel
 bool layer_supported(const rb_layer *L, int T);
 size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 int run_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,
@@ -63,8 +63,8 @@ void forget_plan(const void *workspace);
 // waits for the stream; RB_ERR_HANDOVER if a run of this plan gave up a wait, RB_ERR_WORKSPACE: no plan
 // waited (optional): += input tiles that compute wavefronts found not yet written and waited for, since the plan was made
 int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);
-// pause between a workgroup finishing a phase and its consumers asking for that phase's outputs
-// (clocks of s_memtime); plans prepared afterwards use it
+// pause between a workgroup's last stores of a stage and the moment its compute wavefronts ask for
+// that stage's outputs, in clocks (< 0: the built-in timing); launches made afterwards use it
 void set_pause(int clks);
 }  // namespace mx
 

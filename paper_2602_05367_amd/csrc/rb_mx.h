@@ -20,61 +20,49 @@
 namespace rb {
 namespace mx {
 
-// ---- roles of the sixteen wavefronts of a workgroup of the persistent kernel (one per compute unit)
-constexpr int NL = 2;              // stream sign tiles from HBM into the LDS ring
-constexpr int NC = 12;             // consume tiles: sign expansion and matrix instructions
-constexpr int NF = 2;              // finish rows: sums, scales, rounding, stores, expansion for the readers
-constexpr int WAVES = NL + NC + NF;
-constexpr int THREADS = WAVES * 64;
-static_assert(WAVES == 16, "one workgroup of 1024 threads per compute unit");
-
-constexpr int RING_TILES = 128;    // sign tiles (1 KB each) the LDS ring of a compute unit holds
-constexpr int MAX_SLOTS = 2 * NF;  // row tiles one compute unit finishes per phase (a finishing wavefront takes two)
-constexpr int NPAR = 2;            // phases whose partial sums LDS holds at once
+// Wavefronts that stream weights and issue MFMAs.  One compute unit holds one workgroup of at
+// most 16 wavefronts; what a step costs is instruction issue, so more wavefronts per SIMD help as
+// long as the registers suffice: twelve for one token (128 registers each), eight for two.
+constexpr int cwaves_of(int T) { return T == 1 ? 12 : 8; }
+constexpr int MAX_CWAVES = 12;
+static_assert(cwaves_of(1) <= MAX_CWAVES && cwaves_of(2) <= MAX_CWAVES, "sizes of per-wavefront tables");
+constexpr int EWAVES = 4;          // wavefronts that finish rows and talk to other CUs
+constexpr int threads_of(int T) { return (cwaves_of(T) + EWAVES) * 64; }
+constexpr int RING_D = 6;           // sign tiles requested ahead per compute wavefront (1 KB each)
+// expanded-input operands requested ahead per compute wavefront (tiles); each holds 8 registers per
+// lane for one token and 16 for two.  Measured on the 7B-shaped stack: depths 2 to 8 stream equally
+// fast without dependencies between the ops; with them, a request made later is less often made
+// before its producer has written (2 against 4: -1.5 % per token, -2.7 % for two tokens), and one
+// tile ahead no longer hides the latency (+9 %).
+constexpr int nb_of(int T) { return T == 1 ? 2 : 2; }
+// vector-memory loads per step: operand loads (16 bytes per lane each) and one sign tile
+constexpr int kop_of(int T) { return T == 1 ? 2 : 4; }
+// Loads complete in order.  The operand of a tile is requested nb steps before its use, the sign
+// tile RING_D > nb steps before; when at most this many loads are outstanding both have arrived.
+constexpr int wait_of(int T) { return (nb_of(T) - 1) * (kop_of(T) + 1) + 1; }
+constexpr int MAXSLOT = 8;         // (op, row tile) pairs one CU finishes per stage
 constexpr int MAX_CONS = 3;        // ops that read one op's output inside a fused stack
-constexpr int MAX_T = 2;           // tokens per launch on this path
+constexpr int MAX_T = 2;           // tokens per call on this path
 constexpr int MAX_OPS = 4096;      // ops per launch
 constexpr size_t MAX_EXPAND = 1024;
-constexpr int LOADER_WINDOW = 12;  // sign tiles a loading wavefront keeps in flight (at most 48: see its wait for a free slot)
+static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1) <= 63 && wait_of(2) <= 63,
+              "the in-order wait counts on this");
 
-// ---- how a row tile's contraction is cut into partial sums.  The cut depends on the width of the
-// matrix only - not on the number of compute units, of wavefronts, or on how a plan splits an op
-// into phases - so that a layer gives the same bits wherever and however it is scheduled: a chunk
-// is chunk_tiles(CT) consecutive column tiles accumulated in order from zero, and the chunks of a
-// row are added in order.
-constexpr int MAX_CHUNKS = 12;
-__host__ __device__ constexpr int chunk_tiles(int CT) { return (CT + MAX_CHUNKS - 1) / MAX_CHUNKS; }
-__host__ __device__ constexpr int chunks_of(int CT) { return (CT + chunk_tiles(CT) - 1) / chunk_tiles(CT); }
-
-// operand tiles (expanded input of one sign tile) a consuming wavefront requests ahead
-constexpr int nb_of(int T) { return T == 1 ? 3 : 2; }
-// 16-byte loads per lane that bring in the operand of one tile
-constexpr int kop_of(int T) { return T == 1 ? 2 : 4; }
-
-// LDS map of the persistent kernel for T tokens
-template <int T> struct LdsMap {
-    static constexpr int RING_BYTES = RING_TILES * 1024;
-    static constexpr int PART_ENTRY = T * 2 * 16 * 4;                     // [path][token][row] fp32
-    static constexpr int PART_BYTES = NPAR * MAX_SLOTS * MAX_CHUNKS * PART_ENTRY;
-    static constexpr int STAGE_WAVE = 2 * MAX_CONS * T * 2 * 4 * 16;      // [half][reader][token][path][term][row] bytes
-    static constexpr int STAGE_BYTES = NF * STAGE_WAVE;
-    static constexpr int CTRL_BYTES = 256;
+// LDS map of the stack kernel with CW compute wavefronts
+constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
+template <int CW> struct LdsMap {
+    static constexpr int RING_BYTES = CW * RING_D * 1024;
+    // partial sums: [parity][slot][compute wavefront][path][token][row] fp32
+    static constexpr int PART_SLOT_BYTES = CW * 2 * 2 * 16 * 4;
+    static constexpr int PART_BYTES = 2 * MAXSLOT * PART_SLOT_BYTES;
+    // go words and a counter, per-wavefront target of the stand-in loads, staging of the finishing wavefronts
+    static constexpr int MISC_BYTES = 256 + CW * 256 + EWAVES * LDS_STAGE_BYTES;
     static constexpr int RING_OFF = 0;
     static constexpr int PART_OFF = RING_OFF + RING_BYTES;
-    static constexpr int STAGE_OFF = PART_OFF + PART_BYTES;
-    static constexpr int CTRL_OFF = STAGE_OFF + STAGE_BYTES;
-    static constexpr int BYTES = CTRL_OFF + CTRL_BYTES;
+    static constexpr int MISC_OFF = PART_OFF + PART_BYTES;
+    static constexpr int BYTES = MISC_OFF + MISC_BYTES;
     static_assert(BYTES <= 160 * 1024, "LDS of one compute unit");
 };
-// control words (uint32) at CTRL_OFF
-constexpr int CTRL_LANDED = 0;       // [NL] sign tiles each loading wavefront has brought in (8-byte aligned pair)
-constexpr int CTRL_CONSUMED = 2;     // sign tiles of completed phases (ring space that may be reused)
-constexpr int CTRL_FAILED = 3;       // a bounded wait ran out somewhere in this workgroup
-constexpr int CTRL_WAITED = 4;       // operand tiles found unwritten and read again
-constexpr int CTRL_FIN = 6;          // [NF] phases each finishing wavefront has completed (8-byte aligned pair)
-constexpr int CTRL_DONE = 8;         // [NPAR] consuming wavefronts that are through with a phase of this parity (running total)
-constexpr int CTRL_FIN_TIME = 16;    // [8] clock at which the outputs of phase (index mod 8) were stored
-static_assert(NL == 2 && NF == 2, "the pairs above are read with one 8-byte load");
 
 // Expanded input ("right operand") of one op, stored as the register image the MFMA wants, so
 // that one load instruction of a wavefront reads 1 KB of consecutive bytes (16 per lane).
@@ -98,14 +86,6 @@ __host__ __device__ inline size_t up_group_offset(int T, int j0, int c)
                   : (size_t)b * 2048 + (size_t)j * 1024 + (size_t)(q * 16 + c) * 16;
 }
 
-__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-__host__ __device__ inline size_t up_bytes(int in, int T)
-{
-    const int CB = (in + 255) / 256 * 2;           // whole column tiles: two blocks each
-    return (size_t)CB * up_block_bytes(T);
-}
-
 struct Op {
     const uint32_t *bits;     // native sign tiles
     const uint16_t *g;        // fp16 [K][out]
@@ -119,73 +99,81 @@ struct Op {
     int cons[MAX_CONS];
     int expand_x;             // 1: x comes from outside the fused ops and must be expanded first
     int dep;                  // op of this launch that writes x (-1: none)
-    int last_phase;           // the phase that completes this op's output
-    float sc[2];              // power-of-two input scale per path (max |h| * sc in [1/4, 1/2))
+    int stage_op0;            // first op of the stage this op belongs to
+    float sc[2];              // power-of-two input scale per path (max |h| * sc <= 1/2)
     float inv_sc[2];
 };
 
-// A phase is a range of row tiles of one op, dealt to the workgroups in contiguous shares; the
-// phases of a plan run in order on every compute unit, without a barrier between them.  What the
-// planner writes (host):
-struct PhaseSeed {
-    int op, rt_first, n_rt, rot;       // rot: the workgroup that gets the first share
-};
-// ... and what the kernel reads, complete with everything the finishing wavefronts need about the
-// op and the ops that read its output (uniform loads, no table look-ups on the way to the stores):
-struct Reader {
-    uint64_t up;              // expanded input of the reading op
-    uint64_t h;               // its input scales, fp16 [2][in]
-    float sc[2];              // its power-of-two input scale per path
-    int in, pad_;
-};
-struct Phase {
-    uint64_t bits, up, y, g;
-    int out, CT, rt_first, n_rt;
-    int dep_phase;            // phase that completes this op's input (-1: complete before the launch)
-    int n_cons;
-    float inv_sc[2];
-    int chunk, n_chunks;      // column tiles per partial sum; partial sums per row tile
-    int up_bytes, op;
-    Reader cons[MAX_CONS];
-    int pad_[8];
-};
-static_assert(sizeof(Reader) == 32 && sizeof(Phase) == 208, "read with scalar loads");
+// What a compute wavefront does, step by step (one step = one 1 KB sign tile), written out once per
+// plan so that the kernel's loop is a walk over two lists and not a search through op tables:
+//   sign list:    the address of each tile, in the order the wavefront meets them (requested
+//                 RING_D steps ahead, across stages)
+//   operand list: per stage, one entry per tile (the address of the tile's expanded input and what
+//                 to do after the MFMAs) followed by nb_of(T) empty entries; the first empty entry
+//                 that reaches the front of the operand ring ends the stage
+// A list is stored in blocks of 64 entries, field by field (64 low words, 64 high words, ...), so
+// that a wavefront loads a block with one dword load per field, an entry per lane, and picks the
+// entry of a step out of its registers.
+constexpr int DESC_BLOCK = 64;               // entries per block (one per lane)
+constexpr int SIGN_FIELDS = 2;               // address low, high
+constexpr int OPND_FIELDS = 3;               // address low, high, STEP_* fields
+constexpr uint32_t STEP_VALID = 1u;          // a tile (empty entries are all zero)
+constexpr uint32_t STEP_FLUSH = 2u;          // last tile of its row tile for this wavefront: write the partial sums
+constexpr int STEP_PART_SHIFT = 8;           // 8 bits: where the partial sums go: slot * cwaves_of(T) + run of the share
+constexpr int STEP_DEP_SHIFT = 16;           // 1 bit: the input is written by an op of this launch (0: it was complete before)
+constexpr int STEP_CT_SHIFT = 20;            // 12 bits: column tile
+// blocks a wavefront may load for a list of n entries read front to back: it holds the block it
+// reads from and the one after it
+__host__ __device__ constexpr uint32_t desc_blocks(uint32_t n) { return n / DESC_BLOCK + 2; }
 
-// the share of phase p that workgroup grp owns: row tiles [rt0, rt0 + nrt)
-struct Share {
-    int rt0, nrt;
+// What a finishing wavefront needs for finishing slot `slot` of workgroup `grp` in stage `st`
+// (one row tile of one op), laid out flat so that its address follows from (st, grp, slot) alone:
+// nothing on the path from the partial sums to the stores waits for a chain of dependent loads.
+struct SlotRec {
+    uint64_t y;               // fp16 output: row 0 of token 0
+    uint64_t pad64_;
+    uint64_t up[MAX_CONS];    // per reading op: the 16-byte group of operand column 0 these rows fill
+    int out, n_cons;          // rows of the op; ops that read its output
+    int row0, op;             // first row of the row tile; op index (< 0: slot unused)
+    uint32_t behind;          // sign tiles the busiest workgroup of this stage has more than this one
+    uint32_t pad_;
 };
+static_assert(sizeof(SlotRec) == 64, "four 16-byte loads");
+// per row of the slot: g_1 / sc_1, g_2 / sc_2 of the op (its output scales over the input scaling
+// it was fed with), then h_k * sc_k of each reading op (its input scales times its input scaling)
+struct SlotVals {
+    float v[16][2 + 2 * MAX_CONS];
+};
+static_assert(sizeof(SlotVals) == 512, "32 bytes per row");
 
-// What a consuming wavefront does is written out once per plan as the list of its units, in plan
-// order, so that its loop decodes one small record per unit instead of working out shares, chunks
-// and sequence numbers per phase, and so that it can request the expanded input of the units to
-// come while it still works on the present one.  A unit is a chunk of one row tile: `tiles`
-// consecutive sign tiles starting at number `seq0` of the workgroup's tile sequence (the ring slot
-// follows from it), against the expanded input that starts `up_off` bytes into the plan's array of
-// expanded inputs; its partial sums go to entry `part` of the partial-sum area.
-struct Unit {
-    uint32_t seq0;
-    uint32_t up_off;
-    uint32_t w2;              // tiles | part << UNIT_PART_SHIFT | UNIT_LAST: the wavefront's last unit of its phase
-    uint32_t w3;              // phase | (1 + phase that completes the input, 0: complete before the launch) << 16
+struct Stage {
+    int op0, nops;            // ops [op0, op0 + nops) are independent of each other
+    int n_deps;               // ops of this stage whose input an earlier stage of the launch writes
+    int pad_;
 };
-constexpr int UNIT_PART_SHIFT = 8;
-constexpr uint32_t UNIT_LAST = 1u << 20;
-static_assert(NPAR * MAX_SLOTS * MAX_CHUNKS < 4096, "twelve bits for the partial-sum entry");
-constexpr int MAX_PHASES = 65535;   // sixteen bits in a unit record
+// First 256 bytes of the miscellaneous LDS area: one "go" word per stage parity at bytes 0 and 8
+// (set = the inputs of that stage have probably been written), and a counter.
+constexpr int WAITED_LDS_OFF = 240;   // lanes that waited for a tile not yet written
 
 struct Header {
-    int n_ops, n_phases, T, n_groups;
-    int unit_stride;          // unit records per consuming wavefront (the last one used is an end mark: no tiles)
-    int pad_[3];
+    int n_ops, n_stages, T, n_groups;
 };
 
-// workspace: [Header][Op x n_ops][PhaseSeed x n_phases][error u32 x 2 ...][indices of the ops
-//            whose input a kernel of its own expands][Phase x n_phases][Share x n_phases x n_groups]
-//            [Unit x unit_stride x NC x n_groups][expanded inputs]
+// workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]
+//            [indices of the ops whose input is expanded by a kernel of its own]
+//            [sign lists, operand lists: blocks x n_groups x cwaves_of(T) each]
+//            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
 struct Layout {
-    size_t ops, seeds, error, which, phases, shares, units, up, total;
+    size_t ops, stages, error, zero, which, sdesc, odesc, slots, vals, up, total;
 };
+
+__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+__host__ __device__ inline size_t up_bytes(int in, int T)
+{
+    const int CB = (in + 255) / 256 * 2;           // whole column tiles: two blocks each
+    return (size_t)CB * up_block_bytes(T);
+}
 
 }  // namespace mx
 }  // namespace rb

@@ -1,0 +1,1165 @@
+// Matrix-core path: set-up kernels, the persistent stack kernel, and its host
+// planner.  See rb_mx.h for the arithmetic and the operand layout.
+//
+// Work split of the persistent kernel (one workgroup per compute unit):
+//   * every op's row tiles are cut into contiguous shares, one per workgroup;
+//     a share is a contiguous run of 1 KB sign tiles in the native layout and
+//     is cut again into one run per compute wavefront;
+//   * what each compute wavefront does is written out once per plan as a list
+//     of steps (tile address, operand address, what to do afterwards), so the
+//     kernel's loop has no op tables to search;
+//   * a compute wavefront keeps RING_D sign tiles in flight from HBM into its
+//     LDS ring (the weights of later ops do not depend on activations, so the
+//     stream never stops at a stage boundary), reads the expanded input of the
+//     current stage NB tiles ahead, and issues four MFMAs per tile;
+//   * partial sums of the wavefronts that share a row tile meet in LDS;
+//   * four more wavefronts finish rows: y = sum_k g_k * acc_k, fp16 rounding,
+//     the store, and the four-term expansion of h (.) y for the ops that read y
+//     next, written with device-scope 16-byte stores.  Keeping this traffic on
+//     wavefronts of their own means no wait on it ever drains a weight prefetch;
+//   * hand-over between compute units: before a launch every 16-byte group of an expanded input
+//     that a producer of the launch will write is filled with 0xff bytes, which no bf8 term of a
+//     finite value has.  Producers just store.  One finishing wavefront per workgroup announces the
+//     next stage to its compute wavefronts a fixed pause after its own stores; a compute wavefront
+//     requests operand tiles with plain loads (shared by the 32 compute units of an XCD in its L2)
+//     and, when it consumes a tile, checks every 32-bit word of every group; only a tile with a
+//     word that still reads 0xffffffff is waited for and read again past the L2.  The pause is a
+//     matter of speed, not of correctness.  Device-coherent reads of every operand would put twice
+//     the weight traffic on the fabric that also carries the HBM stream.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "rabit.h"
+#include "rb_internal.h"
+#include "rb_layout.h"
+#include "rb_mx.h"
+#include "rb_mx_device.h"
+
+namespace rb {
+namespace mx {
+
+
+#define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+// Pointers read from the op table are generic; dereferencing them as such makes FLAT instructions,
+// which also count as LDS traffic: every LDS wait would then wait for global stores to be acknowledged.
+#define RB_GLOBAL(T, p) ((__attribute__((address_space(1))) T *)(p))
+
+// Hand-over timing (a matter of speed only: a consuming wavefront checks what it gets).  Pauses are
+// in s_sleep units of 64 clocks.
+constexpr int GO_PAUSE_1 = 24;      // between a workgroup's own stores and its "go", one token
+constexpr int GO_PAUSE_2 = 28;      // ... two tokens
+constexpr int TILE_PAUSE_1 = 32;    // per 16 sign tiles that a workgroup is ahead of the busiest one, one token
+constexpr int TILE_PAUSE_2 = 44;    // ... two tokens
+#define RB_REPOLL_SLEEP "8"         // between two looks at a tile that was not yet written
+
+// ---------------------------------------------------------------- helpers ---
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(size_t)RB_LDS(p);
+}
+
+// ------------------------------------------------------------ prep kernel ---
+// One workgroup per op: power-of-two scale of each path's input scales and the zero fill of the
+// expanded-input array (padding columns and unused operand columns must read as zero).
+__global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_t *error, uint32_t *zero_page)
+{
+    const int o = blockIdx.x;
+    Op &op = ops[o];
+    __shared__ float red[256];
+    for (int p = 0; p < 2; ++p) {
+        float m = 0.f;
+        for (int j = threadIdx.x; j < op.in; j += 256)
+            m = fmaxf(m, fabsf(__half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j])));
+        red[threadIdx.x] = m;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            const float sc = input_scale(red[0]);
+            op.sc[p] = sc;
+            op.inv_sc[p] = 1.f / sc;
+        }
+        __syncthreads();
+    }
+    const size_t n16 = up_bytes(op.in, hdr->T) / 16;
+    uint4 *up = reinterpret_cast<uint4 *>(op.up);
+    for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
+    if (o == 0) {
+        zero_page[threadIdx.x] = 0;                       // 1 KB: what a padding step of the sign stream reads
+        if (threadIdx.x < 2) error[threadIdx.x] = 0;      // the give-up mark and the count of tiles waited for
+    }
+}
+
+// The step lists of the compute wavefronts; one thread per (workgroup, wavefront).  Row tiles of an
+// op are dealt to the workgroups in contiguous, nearly equal shares, and a share (row tiles x column
+// tiles, contiguous in the native layout) is cut into one contiguous run per compute wavefront.
+__global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *ops, const Stage *stages,
+                                                  const uint32_t *zero_page, uint32_t *sdesc, uint32_t *odesc,
+                                                  uint32_t sblocks, uint32_t oblocks)
+{
+    // one wavefront per list; its lanes write the entries of an op's run side by side
+    const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x, lane = threadIdx.x;
+    const int T = hdr->T, n_stages = hdr->n_stages;
+    const uint32_t CW = (uint32_t)cwaves_of(T);
+    if (id >= G * CW) return;
+    const uint32_t grp = id / CW, wave = id % CW;
+    uint32_t *sd = sdesc + (size_t)id * sblocks * (SIGN_FIELDS * DESC_BLOCK);
+    uint32_t *od = odesc + (size_t)id * oblocks * (OPND_FIELDS * DESC_BLOCK);
+    const uint32_t s_cap = sblocks * DESC_BLOCK, o_cap = oblocks * DESC_BLOCK;
+    auto put_sign = [&](uint32_t e, uint64_t addr) {
+        if (e >= s_cap) return;
+        uint32_t *b = sd + (size_t)(e / DESC_BLOCK) * (SIGN_FIELDS * DESC_BLOCK) + e % DESC_BLOCK;
+        b[0] = (uint32_t)addr;
+        b[DESC_BLOCK] = (uint32_t)(addr >> 32);
+    };
+    auto put_opnd = [&](uint32_t e, uint64_t addr, uint32_t meta) {
+        if (e >= o_cap) return;
+        uint32_t *b = od + (size_t)(e / DESC_BLOCK) * (OPND_FIELDS * DESC_BLOCK) + e % DESC_BLOCK;
+        b[0] = (uint32_t)addr;
+        b[DESC_BLOCK] = (uint32_t)(addr >> 32);
+        b[2 * DESC_BLOCK] = meta;
+    };
+    uint32_t gs = 0, go = 0;                  // entries written so far (the same in every lane)
+    for (int st = 0; st < n_stages; ++st) {
+        const Stage stage = stages[st];
+        uint32_t slot_base = 0;
+        for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+            const Op &op = ops[o];
+            const uint32_t CT = (uint32_t)op.CT;
+            uint32_t rt0, nrt;
+            group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
+            // Run `run` of the share goes to this wavefront.  Runs differ by one tile when CW does not
+            // divide the share, and the longer ones sit at the same positions for every op of equal
+            // shape; dealing op number n of the stage from wavefront n on spreads them.  The partial
+            // sums are filed under the run, not the wavefront, so the order of the final sum is the
+            // single-op kernel's whichever wavefront worked on a run.
+            const uint32_t run = (wave + (uint32_t)(o - stage.op0)) % CW;
+            const uint32_t U = nrt * CT, u0 = run * U / CW, u1 = (run + 1) * U / CW;
+            for (uint32_t u = u0 + lane; u < u1; u += 64) {
+                const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
+                put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
+                put_opnd(go + (u - u0), (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
+                         STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) |
+                             ((slot * CW + run) << STEP_PART_SHIFT) |
+                             ((op.dep >= 0 ? 1u : 0u) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
+            }
+            gs += u1 - u0;
+            go += u1 - u0;
+            slot_base += nrt;
+        }
+        if (lane < (uint32_t)nb_of(T)) put_opnd(go + lane, 0, 0u);      // the empty entries that end the stage
+        go += (uint32_t)nb_of(T);
+    }
+    // past the last tile: a sign request reads a page of zeros, an operand entry is empty
+    for (uint32_t e = gs + lane; e < s_cap; e += 64) put_sign(e, (uint64_t)zero_page);
+    for (uint32_t e = go + lane; e < o_cap; e += 64) put_opnd(e, 0, 0u);
+}
+
+// Second set-up pass (needs the scales of every op): the tables of the finishing wavefronts.
+// One workgroup per (stage, pair of workgroups of the stack kernel); a thread per (slot, row).
+__global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *ops, const Stage *stages,
+                                                   SlotRec *slots, SlotVals *vals)
+{
+    const int G = hdr->n_groups, T = hdr->T;
+    const int st = blockIdx.x;
+    const int grp = blockIdx.y * 2 + (threadIdx.x >> 7);
+    const Stage stage = stages[st];
+    // sign tiles of workgroup gg in this stage; the most any workgroup has (all threads take part)
+    auto stage_tiles = [&](int gg) {
+        uint32_t tiles = 0;
+        for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+            uint32_t rt0, nrt;
+            group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, o - stage.op0, rt0, nrt);
+            tiles += nrt * (uint32_t)ops[o].CT;
+        }
+        return tiles;
+    };
+    __shared__ uint32_t most_of[256];
+    uint32_t most = 0;
+    for (int gg = threadIdx.x; gg < G; gg += 256) most = max(most, stage_tiles(gg));
+    most_of[threadIdx.x] = most;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) most_of[threadIdx.x] = max(most_of[threadIdx.x], most_of[threadIdx.x + s]);
+        __syncthreads();
+    }
+    most = most_of[0];
+    if (grp >= G) return;
+    const uint32_t mine = stage_tiles(grp);
+    const int slot = (threadIdx.x >> 4) & 7, row = threadIdx.x & 15;
+    int my_op = -1, row0 = 0, slot_base = 0;
+    for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
+        uint32_t rt0, nrt;
+        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, o - stage.op0, rt0, nrt);
+        if (slot >= slot_base && slot < slot_base + (int)nrt) {
+            my_op = o;
+            row0 = (int)(rt0 + (uint32_t)(slot - slot_base)) * 16;
+        }
+        slot_base += (int)nrt;
+    }
+    const size_t idx = ((size_t)st * G + grp) * MAXSLOT + slot;
+    SlotRec sr;
+    sr.y = 0; sr.pad64_ = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
+    sr.behind = most - mine;
+    for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
+    float v[2 + 2 * MAX_CONS];
+    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) v[i] = 0.f;
+    if (my_op >= 0) {
+        const Op &op = ops[my_op];
+        const int grow = row0 + row;
+        sr.y = (uint64_t)op.y;
+        sr.out = op.out; sr.n_cons = op.n_cons; sr.row0 = row0; sr.op = my_op;
+        const bool valid = grow < op.out;
+        const __half *g = reinterpret_cast<const __half *>(op.g);
+        if (valid) {
+            v[0] = __half2float(g[grow]) * op.inv_sc[0];
+            v[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
+        }
+        for (int c = 0; c < op.n_cons; ++c) {
+            const Op &m = ops[op.cons[c]];
+            sr.up[c] = (uint64_t)(m.up + up_group_offset(T, row0, 0));
+            const __half *h = reinterpret_cast<const __half *>(m.h);
+            if (valid) {
+                v[2 + 2 * c] = __half2float(h[grow]) * m.sc[0];
+                v[3 + 2 * c] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
+            }
+        }
+    }
+    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) vals[idx].v[row][i] = v[i];
+    if (row == 0) slots[idx] = sr;
+}
+
+// --------------------------------------------------------- expand kernel ---
+// Input scaling u_k = h_k (.) x (Section 4.1) for ops whose input comes from
+// outside the fused ops, written as four bf8 terms in operand order.
+__global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op *ops, const int *which)
+{
+    const Op &op = ops[which[blockIdx.z]];
+    const int tok = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= op.in) return;
+    const int T = hdr->T;
+    const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
+        const uint32_t terms = expand4(h * x * op.sc[p]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) op.up[up_offset(T, tok, p, t, j)] = (uint8_t)(terms >> (8 * t));
+    }
+}
+
+// Before every launch: the expanded input of every op that a producer of this
+// launch will write is set to "not written yet" (0xff in every byte of the 16-byte groups of real
+// columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  POISON_SPLIT
+// workgroups per op.
+constexpr int POISON_SPLIT = 4;
+__global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T)
+{
+    const Op &op = ops[blockIdx.x];
+    if (op.dep < 0) return;
+    const int groups = (int)(up_bytes(op.in, T) / 16);
+    uint4 *up = reinterpret_cast<uint4 *>(op.up);
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
+        // which 16 input columns group i holds (see up_group_offset): a block of 128 columns is
+        // [q][half j][operand column 0..7] for one token and [half j][q][operand column 0..15] for two
+        const int b = T == 1 ? i >> 6 : i >> 7;
+        const int q = T == 1 ? (i >> 4) & 3 : (i >> 4) & 3;
+        const int j = T == 1 ? (i >> 3) & 1 : (i >> 6) & 1;
+        const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
+        up[i] = make_uint4(v, v, v, v);
+    }
+}
+
+// ---------------------------------------------------------- stack kernel ---
+// workgroup barrier that orders LDS only: the weight prefetch of a compute wavefront stays in
+// flight across it (a full fence would wait for every outstanding global load)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
+{
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
+}
+
+template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile: two 128-column blocks
+
+// What a producer stores carries its own validity (a 16-byte group of an expanded input is all 0xff
+// until it is written), so a producer neither waits for its stores to be acknowledged nor raises a
+// flag, and nobody polls memory for flags.
+template <int TT>
+__global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *__restrict__ hdr_p,
+                                                           const Op *__restrict__ ops,
+                                                           const Stage *__restrict__ stages,
+                                                           uint32_t *__restrict__ error,
+                                                           const uint32_t *__restrict__ zero_page,
+                                                           const uint32_t *__restrict__ sdesc_g,
+                                                           const uint32_t *__restrict__ odesc_g,
+                                                           uint32_t sblocks, uint32_t oblocks,
+                                                           const SlotRec *__restrict__ slots_g,
+                                                           const SlotVals *__restrict__ vals_g, int go_pause)
+{
+    constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
+    using Lds = LdsMap<CW>;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    float *part = reinterpret_cast<float *>(lds + Lds::PART_OFF);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = blockIdx.x, G = gridDim.x;
+    const int n_stages = hdr_p->n_stages;
+    constexpr int T = TT, NB = nb_of(TT), KOP = kop_of(TT);
+
+    // ---- LDS set-up: clear the partial sums
+    for (int i = threadIdx.x; i < Lds::PART_BYTES / 4; i += THREADS) part[i] = 0.f;
+    if (threadIdx.x == 0) *reinterpret_cast<uint32_t *>(lds + Lds::MISC_OFF + WAITED_LDS_OFF) = 0u;
+    __syncthreads();
+
+    if (wave < CW) {
+        // ======================= compute wavefront ==========================
+        uint8_t *const ring = lds + Lds::RING_OFF + wave * (RING_D * 1024);
+        uint8_t *const ring_end = ring + RING_D * 1024;
+        const int col = lane & 15, qd = lane >> 4;
+        const int scale_b = term_scale(col);
+        const uint32_t lane_off = (uint32_t)lane * 16u;
+        // diagnostic: every lane of a wavefront that had to wait for a tile adds one here (so 64 per
+        // tile); the watching wavefront hands the sum to the workspace at the end
+        const uint32_t waited_lds = lds_addr(lds + Lds::MISC_OFF + WAITED_LDS_OFF);
+        uint32_t c22;
+        asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(c22));
+        // A load that carries no data but keeps the number of vector-memory operations per
+        // step constant (the in-order completion counter is what the ring relies on): four
+        // bytes per lane from the zero page into a scratch corner of LDS.
+        uint8_t *dummy_dst = lds + Lds::MISC_OFF + 256 + wave * 256;
+        const uint32_t *dummy_src = zero_page;
+        auto issue_dummies = [&](int n) {
+            for (int i = 0; i < n; ++i) __builtin_amdgcn_global_load_lds(dummy_src, RB_LDS(dummy_dst), 4, 0, 0);
+        };
+        // ---- the step lists of this wavefront.  Each list is read front to back, a block of 64
+        // entries (one per lane) at a time: the wavefront holds the block it reads from and the one
+        // after it, and replaces the latter, 64 steps before it is needed, each time it moves on.
+        // The replacing loads are written as instructions and never waited for by name: loads
+        // complete in order and every step waits for all but its youngest few, so a block has
+        // arrived a few steps after its request (steps_done tells when that cannot be relied on).
+        const size_t my_list = (size_t)grp * CW + wave;
+        const uint32_t *sd_next = sdesc_g + my_list * sblocks * (SIGN_FIELDS * DESC_BLOCK) + lane;
+        const uint32_t *od_next = odesc_g + my_list * oblocks * (OPND_FIELDS * DESC_BLOCK) + lane;
+        int s_lo, s_hi, sn_lo, sn_hi;                 // sign list: current block, next block
+        int o_lo, o_hi, o_m, on_lo, on_hi, on_m;      // operand list
+        asm volatile("global_load_dword %0, %10, off\n\t"
+                     "global_load_dword %1, %10, off offset:256\n\t"
+                     "global_load_dword %2, %10, off offset:512\n\t"
+                     "global_load_dword %3, %10, off offset:768\n\t"
+                     "global_load_dword %4, %11, off\n\t"
+                     "global_load_dword %5, %11, off offset:256\n\t"
+                     "global_load_dword %6, %11, off offset:512\n\t"
+                     "global_load_dword %7, %11, off offset:768\n\t"
+                     "global_load_dword %8, %11, off offset:1024\n\t"
+                     "global_load_dword %9, %11, off offset:1280\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(s_lo), "=&v"(s_hi), "=&v"(sn_lo), "=&v"(sn_hi), "=&v"(o_lo), "=&v"(o_hi), "=&v"(o_m),
+                       "=&v"(on_lo), "=&v"(on_hi), "=&v"(on_m)
+                     : "v"(sd_next), "v"(od_next)
+                     : "memory");
+        sd_next += 2 * SIGN_FIELDS * DESC_BLOCK;
+        od_next += 2 * OPND_FIELDS * DESC_BLOCK;
+        uint32_t p_sign = 0, p_opnd = 0;              // entries read so far
+        uint32_t steps_done = 0, s_mark = 0, o_mark = 0;   // steps consumed; the same at the last block requests
+        auto next_sign = [&]() -> uint64_t {
+            const int l = (int)(p_sign & (DESC_BLOCK - 1));
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(s_lo, l), hi = (uint32_t)__builtin_amdgcn_readlane(s_hi, l);
+            ++p_sign;
+            if ((p_sign & (DESC_BLOCK - 1)) == 0) {
+                if (steps_done - s_mark < (uint32_t)NB + 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("v_mov_b32 %0, %2\n\t"
+                             "v_mov_b32 %1, %3\n\t"
+                             "global_load_dword %2, %4, off\n\t"
+                             "global_load_dword %3, %4, off offset:256"
+                             : "=&v"(s_lo), "=&v"(s_hi), "+v"(sn_lo), "+v"(sn_hi)
+                             : "v"(sd_next)
+                             : "memory");
+                sd_next += SIGN_FIELDS * DESC_BLOCK;
+                s_mark = steps_done;
+            }
+            return ((uint64_t)hi << 32) | lo;
+        };
+        struct OpndDesc { uint32_t lo, hi, meta; };
+        auto next_opnd = [&]() -> OpndDesc {
+            const int l = (int)(p_opnd & (DESC_BLOCK - 1));
+            OpndDesc d;
+            d.lo = (uint32_t)__builtin_amdgcn_readlane(o_lo, l);
+            d.hi = (uint32_t)__builtin_amdgcn_readlane(o_hi, l);
+            d.meta = (uint32_t)__builtin_amdgcn_readlane(o_m, l);
+            ++p_opnd;
+            if ((p_opnd & (DESC_BLOCK - 1)) == 0) {
+                if (steps_done - o_mark < (uint32_t)NB + 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("v_mov_b32 %0, %3\n\t"
+                             "v_mov_b32 %1, %4\n\t"
+                             "v_mov_b32 %2, %5\n\t"
+                             "global_load_dword %3, %6, off\n\t"
+                             "global_load_dword %4, %6, off offset:256\n\t"
+                             "global_load_dword %5, %6, off offset:512"
+                             : "=&v"(o_lo), "=&v"(o_hi), "=&v"(o_m), "+v"(on_lo), "+v"(on_hi), "+v"(on_m)
+                             : "v"(od_next)
+                             : "memory");
+                od_next += OPND_FIELDS * DESC_BLOCK;
+                o_mark = steps_done;
+            }
+            return d;
+        };
+        // the registers of the blocks on their way stay allocated (see keep_operands below)
+        auto keep_blocks = [&]() {
+            asm volatile("" : "+v"(sn_lo), "+v"(sn_hi), "+v"(on_lo), "+v"(on_hi), "+v"(on_m));
+        };
+
+        // ---- sign-tile stream (runs RING_D tiles ahead of the MFMAs, across ops and stages)
+        uint8_t *a_slot = ring;
+        auto issue_a = [&]() {
+            // non-temporal: every sign tile is read once (measured: the stream is ~13% faster)
+            const uint64_t addr = next_sign();
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint8_t *>(addr) + lane * 16, RB_LDS(a_slot), 16, 0, 2);
+            a_slot += 1024;
+            if (a_slot == ring_end) a_slot = ring;
+        };
+
+#pragma unroll 1
+        for (int d = 0; d < RING_D; ++d) {
+            issue_a();
+            issue_dummies(KOP);
+        }
+        uint8_t *c_slot_ptr = ring;           // ring slot of the next tile to consume
+        bool failed = false;                  // a producer never delivered: stop waiting, report
+        BTile<TT> B[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int r = 0; r < KOP; ++r) B[i].r[r] = (v4i){0, 0, 0, 0};
+        // Operand loads are written as instructions, so the compiler does not know that their
+        // target registers stay busy until the data arrives.  Naming the registers here keeps
+        // them allocated (never reused as temporaries) across the code between two stages.
+        auto keep_operands = [&]() {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[i].r[r]));
+        };
+
+        for (int st = 0; st < n_stages; ++st) {
+            keep_operands();
+            keep_blocks();
+
+            // ---- expanded-input stream of this stage (NB tiles ahead of the MFMAs).  What the
+            // consuming step needs to know about a tile travels with it in meta[] (STEP_* fields).
+            uint32_t meta[NB], opnd_lo[NB], opnd_hi[NB];      // per ring slot: STEP_* fields and where the tile's operand lives
+            auto load_operand = [&](BTile<TT> &dst, v4i rsrc) {
+                // The target registers are in-out operands on purpose: the compiler cannot see that
+                // a load issued here lands later, and the loads of the last steps of a stage are
+                // never waited for.  As in-out operands the registers stay allocated to the operand
+                // ring for the whole kernel, so no temporary is ever placed where a late load lands.
+                // Plain loads: the flags have shown that these bytes are final, and nobody in
+                // this XCD has read them before that, so its L2 holds no older copy.  Each load
+                // reads 1 KB of consecutive bytes (the layout of the expanded input sees to that).
+                // An empty buffer (no tile) returns zeros without touching memory.  The descriptor's
+                // words come out of vector registers (v_readlane) just before; the compiler does not
+                // look inside this block, so the wait states a vector-memory instruction needs after
+                // such a write are spelled out.
+                if constexpr (TT == 1)
+                    asm volatile("s_nop 4\n\t"
+                                 "buffer_load_dwordx4 %0, %2, %3, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %1, %2, %3, 0 offen offset:1024"
+                                 : "+v"(dst.r[0]), "+v"(dst.r[1])
+                                 : "v"(lane_off), "s"(rsrc)
+                                 : "memory");
+                else
+                    asm volatile("s_nop 4\n\t"
+                                 "buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:1024\n\t"
+                                 "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:2048\n\t"
+                                 "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:3072"
+                                 : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
+                                 : "v"(lane_off), "s"(rsrc)
+                                 : "memory");
+            };
+            // Hand-over: a finishing wavefront of this workgroup announces, with one word in LDS per
+            // stage parity, that the inputs of this stage have probably been written.
+            const uint32_t go_word = lds_addr(lds + Lds::MISC_OFF) + (uint32_t)((st & 1) * 8);
+            auto go_given = [&]() -> bool {
+                uint32_t v;
+                asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(go_word) : "memory");
+                return __builtin_amdgcn_readfirstlane((int)v) != 0;
+            };
+            // requests the operand of the next entry of the operand list (nothing for an empty entry)
+            bool go_seen = false;                             // this stage's inputs have been announced
+            auto issue_b = [&](BTile<TT> &dst, uint32_t &m, uint32_t &addr_lo, uint32_t &addr_hi) {
+                const OpndDesc d = next_opnd();
+                m = d.meta;
+                addr_lo = d.lo;
+                addr_hi = d.hi & 0xffffu;
+                const bool valid = (m & STEP_VALID) != 0;
+                const uint32_t dep = (m >> STEP_DEP_SHIFT) & 1u;
+                // one announcement per stage
+                if (dep != 0 && !go_seen && !failed) {
+                    int spins = 0;
+                    while (!go_given()) {
+                        __builtin_amdgcn_s_sleep(2);
+                        if (++spins > (1 << 24)) { failed = true; break; }
+                    }
+                    go_seen = true;
+                }
+                // raw buffer descriptor: base, stride 0, size (nothing without a tile), 32-bit untyped
+                v4i rsrc;
+                rsrc[0] = (int)d.lo;
+                rsrc[1] = (int)(d.hi & 0xffffu);
+                rsrc[2] = valid ? 2 * up_block_bytes(TT) : 0;
+                rsrc[3] = 0x00020000;
+                load_operand(dst, rsrc);
+            };
+
+            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+            const int parity = st & 1;
+            // a quad of lanes holds the four terms of (path = quad & 1, token = quad >> 1); its
+            // first lane writes rows 4*qd .. 4*qd+3 of that path and token
+            const int quad = col >> 2;
+            const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * Lds::PART_SLOT_BYTES +
+                                       (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
+            auto flush = [&](uint32_t part_index) {       // slot * CW + run: 256 bytes each
+                v4f v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)       // the four lanes of a quad hold terms of the same path
+                    v[r] = quad_sum((quad & 1) ? acc1[r] : acc0[r]);
+                if ((col & 3) == 0)
+                    asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                 :
+                                 : "v"(part_lane + part_index * 256u), "v"(v)
+                                 : "memory");
+                acc0 = (v4f){0, 0, 0, 0};
+                acc1 = (v4f){0, 0, 0, 0};
+            };
+
+#pragma unroll
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], opnd_lo[i], opnd_hi[i]); issue_dummies(1); }
+
+            bool more = true;
+            while (more) {
+#pragma unroll
+                for (int s = 0; s < NB; ++s) {
+                    const uint32_t m = meta[s];
+                    if (!(m & STEP_VALID)) { more = false; break; }
+                    // Every step issues exactly KOP + 1 vector-memory loads (the operand loads, one
+                    // sign tile or its stand-in) and loads complete in order.  The operand of this
+                    // tile was requested NB steps ago, followed by wait_of(T) younger loads; the
+                    // sign tile is older still (RING_D > NB).  So "at most wait_of(T) outstanding"
+                    // means both have arrived.
+                    v4u w;
+                    asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(w)
+                                 : "v"(lds_addr(c_slot_ptr) + lane * 16), "n"(wait_of(TT))
+                                 : "memory");
+#pragma unroll
+                    for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
+                    // Each lane holds one 16-byte group per load.  No byte of a written group is 0xff,
+                    // so a 32-bit word that reads 0xffffffff has not been written: a tile with such a
+                    // word (its producer was late, the L2 of this XCD got hold of the line before it
+                    // was written, or a 16-byte store has landed in part) is waited for by looking at
+                    // the first word of every group past the L2, and then loaded again whole.  The
+                    // look is one statement, so that the operand registers keep their place (a loop
+                    // the compiler can see around a reload makes it move them while loads are in flight).
+                    auto unwritten_word = [&]() -> bool {
+                        bool any = false;
+#pragma unroll
+                        for (int r = 0; r < KOP; ++r) {
+                            const v4i g = B[s].r[r];
+                            any |= max(max((uint32_t)g[0], (uint32_t)g[1]), max((uint32_t)g[2], (uint32_t)g[3])) == 0xffffffffu;
+                        }
+                        return __ballot(any) != 0ull;
+                    };
+                    if (((m >> STEP_DEP_SHIFT) & 1u) != 0 && !failed && unwritten_word()) {
+                        v4i rsrc;
+                        rsrc[0] = (int)opnd_lo[s];
+                        rsrc[1] = (int)opnd_hi[s];
+                        rsrc[2] = 2 * up_block_bytes(TT);
+                        rsrc[3] = 0x00020000;
+                        // polls until the first byte of every group is written, then holds the tile as
+                        // read after that; returns the polls it had left (0: gave up)
+                        auto look_again = [&]() -> uint32_t {
+                            uint32_t left;
+                            unsigned long long unwritten;
+                            if constexpr (TT == 1) {
+                                int c0, c1;
+                                asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                             "1:\n\t"
+                                             "s_nop 4\n\t"
+                                             "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
+                                             "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                             "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                             "s_mov_b64 %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "s_cmp_eq_u64 %[un], 0\n\t"
+                                             "s_cbranch_scc1 2f\n\t"
+                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             "s_sub_u32 %[left], %[left], 1\n\t"
+                                             "s_cmp_lg_u32 %[left], 0\n\t"
+                                             "s_cbranch_scc1 1b\n"
+                                             "2:\n\t"
+                                             "v_mov_b32 %[c0], 1\n\t"
+                                             "ds_add_u32 %[cnt], %[c0]"
+                                             : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [c0] "=&v"(c0), [c1] "=&v"(c1),
+                                               [un] "=&s"(unwritten), [left] "=&s"(left)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
+                                             : "vcc", "scc", "memory");
+                            } else {
+                                int c0, c1, c2, c3;
+                                asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                             "1:\n\t"
+                                             "s_nop 4\n\t"
+                                             "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dword %[c2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dword %[c3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
+                                             "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                             "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                             "v_and_b32 %[c2], 0xff, %[c2]\n\t"
+                                             "v_and_b32 %[c3], 0xff, %[c3]\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                             "s_mov_b64 %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c1]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c2]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c3]\n\t"
+                                             "s_or_b64 %[un], %[un], vcc\n\t"
+                                             "s_cmp_eq_u64 %[un], 0\n\t"
+                                             "s_cbranch_scc1 2f\n\t"
+                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             "s_sub_u32 %[left], %[left], 1\n\t"
+                                             "s_cmp_lg_u32 %[left], 0\n\t"
+                                             "s_cbranch_scc1 1b\n"
+                                             "2:\n\t"
+                                             "v_mov_b32 %[c0], 1\n\t"
+                                             "ds_add_u32 %[cnt], %[c0]"
+                                             : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [b2] "+v"(B[s].r[2 % KOP]),
+                                               [b3] "+v"(B[s].r[3 % KOP]), [c0] "=&v"(c0), [c1] "=&v"(c1), [c2] "=&v"(c2),
+                                               [c3] "=&v"(c3), [un] "=&s"(unwritten), [left] "=&s"(left)
+                                             : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
+                                             : "vcc", "scc", "memory");
+                            }
+                            return left;
+                        };
+                        // Each look reads the first word of every group and then, with later loads of
+                        // the same wavefront from the same addresses, the groups themselves.  A group
+                        // whose store had landed in part is complete one look later; should a word
+                        // still read as unwritten after that, the run is reported, not trusted.
+                        uint32_t left = look_again();
+                        if (left != 0 && unwritten_word()) left = look_again();
+                        if (left != 0 && unwritten_word()) left = 0;
+                        if (left == 0) {                      // a producer never delivered: report, stop checking
+                            failed = true;
+                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                    c_slot_ptr += 1024;
+                    if (c_slot_ptr == ring_end) c_slot_ptr = ring;
+                    const BTile<TT> bt = B[s];
+                    v8i b0, b1;
+                    if constexpr (TT == 1) {
+                        // lanes 0..7 of a row of 16 hold the first four registers of their column; the
+                        // other four sit eight lanes further on (row_shl:8).  Lanes 8..15 end up with
+                        // bytes of no meaning: their columns of the product are never read.
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            b0[i] = bt.r[0][i];
+                            b0[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[0][i], 0x108, 0xf, 0xf, true);
+                            b1[i] = bt.r[1][i];
+                            b1[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[1][i], 0x108, 0xf, 0xf, true);
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            b0[i] = bt.r[0][i]; b0[4 + i] = bt.r[1][i];
+                            b1[i] = bt.r[2 % KOP][i]; b1[4 + i] = bt.r[3 % KOP][i];
+                        }
+                    }
+                    acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
+                    acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
+                    acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
+                    acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
+                    if (m & STEP_FLUSH) flush((m >> STEP_PART_SHIFT) & 0xffu);
+                    ++steps_done;
+                    issue_b(B[s], meta[s], opnd_lo[s], opnd_hi[s]);
+                    issue_a();
+                }
+            }
+            lds_barrier();                                    // partial sums of the stage are in LDS
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land in LDS or registers after the end
+        keep_operands();
+        keep_blocks();
+    } else {
+        // ========================= finishing wavefront ======================
+        const int ew = wave - CW;
+        // lane -> (slot, row, token): a wavefront finishes two slots per stage, one per half
+        const int half = lane >> 5;
+        const int my_slot = ew + EWAVES * half;
+        const int row = lane & 15, tok = (lane >> 4) & 1;
+        // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
+        uint8_t *stage_bytes = lds + Lds::MISC_OFF + 256 + CW * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
+
+        // Everything a stage's epilogue needs from memory sits in two flat tables indexed by
+        // (stage, workgroup, slot) and is requested one stage ahead, while the compute wavefronts
+        // work: nothing after the barrier waits for memory.  The loads are unconditional, so the
+        // compiler can wait for exactly these and not for younger ones.
+        struct Fin {
+            SlotRec r;
+            v4f a, b;                       // the row's eight values
+        };
+        auto fetch = [&](int st) -> Fin {
+            const size_t idx = ((size_t)min(st, n_stages - 1) * G + grp) * MAXSLOT + my_slot;
+            Fin f;
+            f.r = slots_g[idx];
+            const v4f *pv = reinterpret_cast<const v4f *>(&vals_g[idx].v[row][0]);
+            f.a = pv[0];
+            f.b = pv[1];
+            if (st >= n_stages) f.r.op = -1;
+            return f;
+        };
+        Fin cur = fetch(0);
+
+        const uint32_t ready_lds = lds_addr(lds + Lds::MISC_OFF);
+        for (int st = 0; st < n_stages; ++st) {
+            const Fin nxt = fetch(st + 1);
+            // the go word of the next stage: nobody reads it before this stage's barrier
+            if (ew == 0 && lane == 0) {
+                const uint32_t a = ready_lds + (uint32_t)(((st + 1) & 1) * 8);
+                asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(0u) : "memory");
+            }
+            lds_barrier();                                    // partial sums complete
+            const bool have_slot = cur.r.op >= 0;
+            const int grow = cur.r.row0 + row;
+            // One token: the lanes of a row's second-token position are free, so the two lanes of a
+            // row split the paths between them (sub = which path) for the sums and the expansion.
+            constexpr bool SPLIT = TT == 1;
+            const int sub = tok;
+            const bool active = have_slot && (SPLIT || tok < T) && grow < cur.r.out;
+            const int n_cons = have_slot ? cur.r.n_cons : 0;
+            const float hs[MAX_CONS][2] = {{cur.a[2], cur.a[3]}, {cur.b[0], cur.b[1]}, {cur.b[2], cur.b[3]}};
+            // this lane's path of each reader's scales (selected value by value: an indexed array
+            // would live in scratch memory)
+            const float hsub[MAX_CONS] = {sub ? cur.a[3] : cur.a[2], sub ? cur.b[1] : cur.b[0], sub ? cur.b[3] : cur.b[2]};
+            float yf = 0.f;
+            // partial sums of this lane's row: [run][path][token][row]
+            float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * 64 + (SPLIT ? 0 : tok * 16) + row;
+            if (active) {
+                // sum the partial sums of the runs in run order
+                float s0 = 0.f, s1 = 0.f;
+                if constexpr (SPLIT) {
+                    float mine = 0.f;
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) mine += P[w * 64 + sub * 32];
+                    const float other = __shfl_xor(mine, 16);      // the lane with the same row and the other path
+                    s0 = sub ? other : mine;
+                    s1 = sub ? mine : other;
+                } else {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) {
+                        s0 += P[w * 64];
+                        s1 += P[w * 64 + 32];
+                    }
+                }
+                const _Float16 y16 = (_Float16)path_sum(cur.a[0], s0, cur.a[1], s1);   // round to nearest even
+                if (!SPLIT || sub == 0) RB_GLOBAL(_Float16, cur.r.y)[(size_t)(SPLIT ? 0 : tok) * cur.r.out + grow] = y16;
+                yf = (float)y16;
+            }
+            // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
+            // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
+            if (__any(n_cons > 0)) {
+                if (have_slot && (SPLIT || tok < T)) {
+#pragma unroll
+                    for (int c = 0; c < MAX_CONS; ++c) {
+                        if (c < n_cons) {
+                            if constexpr (SPLIT) {
+                                const uint32_t terms = active ? expand4(hsub[c] * yf) : 0u;
+                                uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2) * 2 + sub) * 4) * 16 + row;
+#pragma unroll
+                                for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
+                            } else {
+#pragma unroll
+                                for (int p = 0; p < 2; ++p) {
+                                    const uint32_t terms = active ? expand4(hs[c][p] * yf) : 0u;
+                                    uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
+#pragma unroll
+                                    for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
+                                }
+                            }
+                        }
+                    }
+                }
+                // lanes now act as (half, consumer, token, path, term): 96 vectors, two rounds
+#pragma unroll
+                for (int round = 0; round < 2; ++round) {
+                    const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
+                    const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vrest = v % 16;
+                    const int vtok = vrest >> 3, vpt = vrest & 7;
+                    // the slot's values live in the lanes of its half: take them from that half's lane 0
+                    const int src_lane = vh * 32;
+                    const int nc = __shfl(n_cons, src_lane);
+                    const bool has = __shfl((int)have_slot, src_lane) != 0;
+                    uint64_t base = 0;
+#pragma unroll
+                    for (int c = 0; c < MAX_CONS; ++c) {
+                        // the 16-byte group of operand column 0 that this slot's rows fill
+                        const uint64_t u = cur.r.up[c];
+                        const uint32_t lo = __shfl((uint32_t)u, src_lane), hi = __shfl((uint32_t)(u >> 32), src_lane);
+                        if (c == vc) base = ((uint64_t)hi << 32) | lo;
+                    }
+                    if (v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T) {
+                        const v4i bytes = *reinterpret_cast<const v4i *>(
+                            stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 16;
+                                                asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
+                    }
+                }
+            }
+            // clear the partial sums for the stage after next (a run without tiles writes nothing);
+            // off the path from the barrier to the stores
+            if (active) {
+                if constexpr (SPLIT) {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) P[w * 64 + sub * 32] = 0.f;
+                } else {
+#pragma unroll
+                    for (int w = 0; w < CW; ++w) {
+                        P[w * 64] = 0.f;
+                        P[w * 64 + 32] = 0.f;
+                    }
+                }
+            }
+            // ---- tell the compute wavefronts, which may already be in the next stage, when that
+            // stage's inputs have probably been written (one wavefront per workgroup)
+            if (ew == 0 && st + 1 < n_stages) {
+                const uint32_t go_lds = ready_lds + (uint32_t)(((st + 1) & 1) * 8);
+                if (stages[st + 1].n_deps != 0) {
+                    if (go_pause >= 0) {
+                        // a pause given by the caller (tests: none at all, so that nearly every tile is
+                        // requested before it is written)
+                        for (int i = 0; i < go_pause; ++i) __builtin_amdgcn_s_sleep(1);
+                    } else {
+                        // the time the slowest producer's stores need to land
+                        __builtin_amdgcn_s_sleep(TT == 1 ? GO_PAUSE_1 : GO_PAUSE_2);
+                        // a workgroup with a smaller share got here that much before the busiest one,
+                        // whose outputs its compute wavefronts would then request too early
+                        const uint32_t ahead = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur.r.behind) *
+                                               (TT == 1 ? TILE_PAUSE_1 : TILE_PAUSE_2) / 16u;
+                        for (uint32_t i = 0; i < ahead; ++i) __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                if (lane == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(go_lds), "v"(1u) : "memory");
+            }
+            cur = nxt;
+        }
+        // after the last barrier no compute wavefront waits for a tile any more
+        if (ew == 0 && lane == 0) {
+            const uint32_t lanes_waited = *reinterpret_cast<const uint32_t *>(lds + Lds::MISC_OFF + WAITED_LDS_OFF);
+            if (lanes_waited != 0)
+                __hip_atomic_fetch_add(RB_GLOBAL(uint32_t, error) + 1, lanes_waited / 64u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host ---
+static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, size_t up_total,
+                          size_t sblocks, size_t oblocks)
+{
+    Layout L;
+    size_t o = sizeof(Header);
+    o = align_up(o, 128); L.ops = o; o += sizeof(Op) * (size_t)n_ops;
+    o = align_up(o, 128); L.stages = o; o += sizeof(Stage) * (size_t)n_stages;
+    o = align_up(o, 128); L.error = o; o += 128;
+    L.zero = o; o += 1024;
+    L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
+    o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * (size_t)cwaves;
+    o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * (size_t)cwaves;
+    o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+    o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+    o = align_up(o, 256); L.up = o; o += up_total;
+    L.total = align_up(o, 256);
+    return L;
+}
+
+int device_groups()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        cus = prop.multiProcessorCount;
+    }
+    return cus;
+}
+
+bool layer_supported(const rb_layer *L, int T)
+{
+    return L->K == 2 && T >= 1 && T <= MAX_T && L->in % 32 == 0 && L->in <= 65536;
+}
+
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
+{
+    // upper bound: every op could use the widest layer
+    size_t up_max = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        up_max = std::max(up_max, up_bytes(layers[l].in, T));
+    }
+    int G = device_groups();
+    if (G <= 0) G = 1024;  // no device to ask: a bound on compute units
+    // steps of one compute wavefront: at most this many per op for the layer with the largest share
+    const size_t CW = (size_t)cwaves_of(T);
+    size_t per_op = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const size_t share = (size_t)((row_tiles(layers[l].out) + G - 1) / G) * col_tiles(layers[l].in);
+        per_op = std::max(per_op, (share + CW - 1) / CW + 1);
+    }
+    const size_t steps = per_op * (size_t)n_ops;
+    return make_layout(n_ops, n_ops, G, (int)CW, align_up(up_max, 256) * (size_t)n_ops,
+                       desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)))
+        .total;
+}
+
+// Host record of a prepared plan, keyed by the workspace that holds its device part.
+struct Prepared {
+    Layout lay;
+    int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0;
+    uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
+    bool chained = false;                   // some op reads what another op of the launch writes
+    // host memory the plan's tables are copied from: pageable, so it must outlive the queued copies
+    std::shared_ptr<std::vector<uint8_t>> blob;
+    std::shared_ptr<std::vector<int>> which;
+};
+// pause between a workgroup's stores and its announcement of the next stage, in clocks (< 0: the
+// built-in timing); see rb_stack_set_option
+static std::atomic<int> g_pause_clks{-1};
+void set_pause(int clks) { g_pause_clks.store(clks < 0 ? -1 : std::min(clks, 1 << 18)); }
+static std::mutex g_mutex;
+static std::map<const void *, Prepared> g_prepared;
+
+int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
+                 void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    const int G = device_groups();
+    if (G <= 0) return RB_ERR_HIP;
+
+    // ---- ops, consumers, stages
+    std::vector<Op> ops((size_t)n_ops);
+    std::vector<int> expand_list;
+    size_t up_total = 0;
+    std::vector<size_t> up_off((size_t)n_ops);
+    for (int n = 0; n < n_ops; ++n) {
+        const rb_layer &L = layers[sops[n].layer];
+        Op &o = ops[(size_t)n];
+        std::memset(&o, 0, sizeof(Op));
+        o.bits = static_cast<const uint32_t *>(L.bits);
+        o.g = L.g; o.h = L.h;
+        o.x = bufs[sops[n].src];
+        o.y = bufs[sops[n].dst];
+        o.out = L.out; o.in = L.in;
+        o.RT = row_tiles(L.out); o.CT = col_tiles(L.in);
+        up_off[(size_t)n] = up_total;
+        up_total += align_up(up_bytes(L.in, T), 256);
+        // producer of this op's input: the last earlier op that writes the same buffer
+        int producer = -1;
+        for (int m = n - 1; m >= 0; --m)
+            if (sops[m].dst == sops[n].src) { producer = m; break; }
+        o.dep = producer;
+        if (producer < 0) {
+            o.expand_x = 1;
+            expand_list.push_back(n);
+        } else {
+            Op &pr = ops[(size_t)producer];
+            if (pr.n_cons >= MAX_CONS) return RB_ERR_UNSUPPORTED;
+            if (pr.out != o.in) return RB_ERR_SHAPE;
+            pr.cons[pr.n_cons++] = n;
+        }
+    }
+    if (expand_list.size() > MAX_EXPAND || n_ops > MAX_OPS) return RB_ERR_UNSUPPORTED;
+    std::vector<Stage> stages;
+    {
+        int op0 = 0;
+        while (op0 < n_ops) {
+            Stage s{op0, 0, 0, 0};
+            int slots = 0;
+            for (int n = op0; n < n_ops; ++n) {
+                bool conflict = false;
+                for (int m = op0; m < n; ++m)
+                    if (sops[m].dst == sops[n].src || sops[m].dst == sops[n].dst || sops[m].src == sops[n].dst)
+                        conflict = true;
+                const int per_group = (ops[(size_t)n].RT + G - 1) / G;
+                if (per_group > MAXSLOT) return RB_ERR_UNSUPPORTED;
+                if (conflict || slots + per_group > MAXSLOT) break;
+                if (ops[(size_t)n].dep >= 0) ++s.n_deps;
+                slots += per_group;
+                ++s.nops;
+            }
+            stages.push_back(s);
+            op0 += s.nops;
+        }
+    }
+    for (const Stage &st : stages)
+        for (int n = st.op0; n < st.op0 + st.nops; ++n) ops[(size_t)n].stage_op0 = st.op0;
+    Prepared pr;
+    pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T;
+    pr.n_expand = (int)expand_list.size();
+    for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
+    for (int n = 0; n < n_ops; ++n) pr.chained = pr.chained || ops[(size_t)n].dep >= 0;
+    // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
+    // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
+    // the few blocks it saves)
+    {
+        const size_t CW = (size_t)cwaves_of(T);
+        size_t longest = 0;
+        for (int n = 0; n < n_ops; ++n) {
+            const size_t share = (size_t)((ops[(size_t)n].RT + G - 1) / G) * (size_t)ops[(size_t)n].CT;
+            longest += (share + CW - 1) / CW;
+        }
+        // entries a wavefront reads: every tile's, plus the look-ahead past the end
+        pr.sblocks = desc_blocks((uint32_t)(longest + RING_D));
+        pr.oblocks = desc_blocks((uint32_t)(longest + (size_t)nb_of(T) * (size_t)pr.n_stages));
+    }
+    pr.lay = make_layout(n_ops, pr.n_stages, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks);
+    const Layout &lay = pr.lay;
+    if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    for (int n = 0; n < n_ops; ++n) ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
+
+    Header hdr{};
+    hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G;
+
+    // ---- upload: stream-ordered copies out of host memory that the plan's record keeps alive
+    pr.blob = std::make_shared<std::vector<uint8_t>>(lay.error, (uint8_t)0);
+    std::vector<uint8_t> &blob = *pr.blob;
+    std::memcpy(blob.data(), &hdr, sizeof(hdr));
+    std::memcpy(blob.data() + lay.ops, ops.data(), sizeof(Op) * (size_t)n_ops);
+    std::memcpy(blob.data() + lay.stages, stages.data(), sizeof(Stage) * (size_t)pr.n_stages);
+    pr.which = std::make_shared<std::vector<int>>(expand_list);
+    const int *which = pr.which->data();
+    if (hipMemcpyAsync(ws, blob.data(), lay.error, hipMemcpyHostToDevice, stream) != hipSuccess) return RB_ERR_HIP;
+    if (!expand_list.empty() &&
+        hipMemcpyAsync(ws + lay.which, which, sizeof(int) * expand_list.size(), hipMemcpyHostToDevice, stream) !=
+            hipSuccess)
+        return RB_ERR_HIP;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_prepared[workspace] = pr;
+    }
+    hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
+                       reinterpret_cast<Op *>(ws + lay.ops),
+                       reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero));
+    hipLaunchKernelGGL(desc_kernel, dim3(G * cwaves_of(T)), dim3(64), 0, stream,
+                       reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
+                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                       reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc),
+                       pr.sblocks, pr.oblocks);
+    hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + 1) / 2), dim3(256), 0, stream,
+                       reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
+                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
+                       reinterpret_cast<SlotVals *>(ws + lay.vals));
+    return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+}
+
+int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    Prepared pr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        const auto it = g_prepared.find(workspace);
+        if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
+        pr = it->second;
+    }
+    if (workspace_bytes_ < pr.lay.total) return RB_ERR_WORKSPACE;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const Layout &lay = pr.lay;
+    Header *d_hdr = reinterpret_cast<Header *>(ws);
+    Op *d_ops = reinterpret_cast<Op *>(ws + lay.ops);
+    if (pr.n_expand > 0)
+        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
+                           dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
+    if (pr.chained)
+        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops, pr.T);
+    const int pause_clks = g_pause_clks.load();
+    const int go_pause = pause_clks < 0 ? -1 : pause_clks / 64;      // s_sleep units
+    auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds_bytes) != hipSuccess)
+            return RB_ERR_HIP;
+        hipLaunchKernelGGL(kernel, dim3(pr.G), dim3(threads), lds_bytes, stream, d_hdr, d_ops,
+                           reinterpret_cast<const Stage *>(ws + lay.stages),
+                           reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                           reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
+                           pr.sblocks, pr.oblocks,
+                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals),
+                           go_pause);
+        return RB_OK;
+    };
+    const int rc = pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+                             : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
+    if (rc != RB_OK) return rc;
+    return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+}
+
+int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited)
+{
+    Prepared pr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        const auto it = g_prepared.find(workspace);
+        if (it == g_prepared.end()) return RB_ERR_WORKSPACE;
+        pr = it->second;
+    }
+    uint32_t mark[2] = {0, 0};               // gave up a wait; tiles waited for
+    if (hipMemcpyAsync(mark, static_cast<const uint8_t *>(workspace) + pr.lay.error, sizeof(mark), hipMemcpyDeviceToHost,
+                       stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return RB_ERR_HIP;
+    if (waited) *waited += mark[1];
+    return mark[0] ? RB_ERR_HANDOVER : RB_OK;
+}
+
+void forget_plan(const void *workspace)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_prepared.erase(workspace);
+}
+
+int run_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
+             void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    const int rc = prepare_plan(layers, sops, n_ops, bufs, T, workspace, workspace_bytes_, stream);
+    if (rc != RB_OK) return rc;
+    return launch_plan(workspace, workspace_bytes_, stream);
+}
+
+}  // namespace mx
+}  // namespace rb

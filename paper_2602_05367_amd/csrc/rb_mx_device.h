@@ -54,11 +54,16 @@ __device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
     return up_group_offset(T, j & ~15, 8 * tok + 4 * p + t) + (size_t)(j & 15);
 }
 
-// contiguous, nearly equal shares of n row tiles for G workgroups: the share at position g
-__host__ __device__ inline void share_rows(uint32_t n, uint32_t g, uint32_t G, uint32_t &first, uint32_t &count)
+// row tiles of an op that workgroup grp (of G) owns: [rt0, rt0 + nrt).  Shares differ by one row
+// tile when G does not divide RT, and the larger ones sit at the same places for every op of that
+// height (every fourth share for 5120 rows on 256 workgroups); the op at position pos of its stage
+// deals its shares starting pos workgroups further on, so that the larger shares of like-shaped ops
+// of a stage fall on different workgroups where they can.
+__host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
 {
-    first = g * n / G;
-    count = (g + 1) * n / G - first;
+    const uint32_t g = (grp + (uint32_t)pos) % G;
+    rt0 = g * RT / G;
+    nrt = (g + 1) * RT / G - rt0;
 }
 
 // 16 rows x 128 columns of one path's signs (one word per lane, see rb_layout.h) times the 16

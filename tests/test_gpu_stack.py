@@ -15,7 +15,7 @@ from helpers import TOL, build_stack, to_device_layer, random_layer
 
 pytestmark = pytest.mark.gpu
 
-DEFAULT_PAUSE = 1400          # clocks; what the library starts with (rb_stack_set_option)
+DEFAULT_PAUSE = -1          # the kernel's built-in timing (rb_stack_set_option)
 
 
 def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
