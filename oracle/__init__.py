@@ -14,6 +14,11 @@ What each function follows:
 * ``svid`` / ``derive``      - Section 4.2 steps 1-3 and Alg. 2 forward loop for
                                the signs; Section 4.3 (SVID: rank-1 SVD of the
                                magnitudes) for the scales, one greedy pass.
+* ``precondition`` / ``derive_iterative``
+                             - Section 4.3 Eq. (init-iter), Eq. (init-calib) and
+                               Alg. 1: Gauss-Seidel sweeps of SVID over the
+                               residuals of a preconditioned target, scales
+                               mapped back to the original domain.
 * ``stack_forward``          - the layer applied op after op (fp16 between ops).
 
 All floating point is fp64.  Stored fp16 / bf16 values are widened exactly.
@@ -224,6 +229,61 @@ def derive(W: np.ndarray, K: int, round_scales: bool = True):
         R = R - g.astype(np.float64)[:, None] * B.astype(np.float64) * h.astype(np.float64)[None, :]
         norms.append(float(np.linalg.norm(R)))
     return signs, np.stack(gs), np.stack(hs), np.array(norms)
+
+
+def precondition(W: np.ndarray, s_in, s_out, alpha_in: float, alpha_out: float):
+    """Eq. (init-calib) with the normalisation of Alg. 1 step 1: both statistics
+    are divided by their maximum, then W' = s_out^a_out (.) W (.) s_in^a_in
+    (s_out scales rows, s_in columns).  Returns (W', row factors, column
+    factors); the factors are what step 3 divides the scales by."""
+    W = _f64(W)
+    s_in = _f64(s_in)
+    s_out = _f64(s_out)
+    if s_in.shape != (W.shape[1],) or s_out.shape != (W.shape[0],):
+        raise ValueError("s_in is per input column, s_out per output row")
+    if np.any(s_in <= 0.0) or np.any(s_out <= 0.0):
+        raise ValueError("channel statistics must be positive")
+    rows = (s_out / s_out.max()) ** alpha_out
+    cols = (s_in / s_in.max()) ** alpha_in
+    return rows[:, None] * W * cols[None, :], rows, cols
+
+
+def derive_iterative(W: np.ndarray, K: int, T_max: int = 20, s_in=None, s_out=None,
+                     alpha_in: float = 0.0, alpha_out: float = 0.0):
+    """Alg. 1 (calibrated Iterative Residual SVID), fp64 throughout.
+
+    Step 1: W' from ``precondition`` (no statistics given: W' = W).
+    Step 2: W_hat_i^(0) = 0; for t = 1..T_max, for i = 1..K:
+            R_i = W' - sum_{j<i} W_hat_j^(t) - sum_{j>i} W_hat_j^(t-1)   (Eq. init-iter)
+            (B_i, g_i', h_i') = SVID(R_i);  W_hat_i^(t) = g_i' (.) B_i (.) h_i'.
+    Step 3: g_i = g_i' / row factors, h_i = h_i' / column factors.
+
+    Returns (signs int8 [K][out][in], g [K][out], h [K][in], err) where
+    err[t][i] = || W' - sum_j W_hat_j ||_F right after path i was updated in
+    sweep t (err has shape [T_max][K]; the error lives in the preconditioned
+    domain, the one the iteration minimises).
+    """
+    if K < 1 or T_max < 1:
+        raise ValueError("K >= 1 and T_max >= 1")
+    W = _f64(W)
+    if s_in is None and s_out is None:
+        Wp, rows, cols = W.copy(), np.ones(W.shape[0]), np.ones(W.shape[1])
+    else:
+        Wp, rows, cols = precondition(W, s_in, s_out, alpha_in, alpha_out)
+    out, inn = Wp.shape
+    signs = np.ones((K, out, inn), dtype=np.int8)
+    g = np.zeros((K, out))
+    h = np.zeros((K, inn))
+    What = np.zeros((K, out, inn))
+    err = np.empty((T_max, K))
+    for t in range(T_max):
+        for i in range(K):
+            # paths j < i were already replaced in this sweep, paths j > i still hold sweep t - 1
+            R = Wp - (What.sum(axis=0) - What[i])
+            signs[i], g[i], h[i] = svid(R)
+            What[i] = g[i][:, None] * signs[i].astype(np.float64) * h[i][None, :]
+            err[t, i] = float(np.linalg.norm(Wp - What.sum(axis=0)))
+    return signs, g / rows[None, :], h / cols[None, :], err
 
 
 # --------------------------------------------------------------------------

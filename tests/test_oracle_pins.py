@@ -322,6 +322,112 @@ def test_derived_forward_approaches_dense_product():
     assert errs[0] > errs[1] > errs[2]
 
 
+# ---- Section 4.3, Eq. (init-iter), Eq. (init-calib), Alg. 1: iterative Residual SVID
+def _svid_by_lapack(R):
+    """SVID written out with LAPACK's SVD instead of the oracle's power iteration."""
+    U, S, Vt = np.linalg.svd(np.abs(R))
+    a, b = np.abs(U[:, 0]), np.abs(Vt[0])
+    return np.where(R >= 0, 1.0, -1.0), np.sqrt(S[0]) * a, np.sqrt(S[0]) * b
+
+
+def test_iterative_svid_one_sweep_is_the_greedy_pass():
+    """T_max = 1 (Appendix "SVID Iteration Convergence Analysis": one iteration is greedy SVID).
+    A Jacobi sweep (every path seeing sweep t - 1 only) would make path 2 a copy of path 1."""
+    W = synth.gaussian_weight(synth.child_rng(0, 41), 24, 40, std=1.0)
+    for K in (1, 2, 3):
+        signs, g, h, err = oracle.derive_iterative(W, K, T_max=1)
+        s0, g0, h0, norms = oracle.derive(W, K, round_scales=False)
+        assert np.array_equal(signs, s0)
+        np.testing.assert_allclose(g, g0, rtol=1e-12)
+        np.testing.assert_allclose(h, h0, rtol=1e-12)
+        np.testing.assert_allclose(err[0], norms[1:], rtol=1e-12)
+    assert not np.array_equal(signs[0], signs[1])
+
+
+def test_iterative_svid_every_update_lowers_the_error_and_beats_greedy():
+    """SVID(R) minimises ||R - g (.) B (.) h||_F over all sign matrices and non-negative scales
+    (| |r| - m | <= |r - s m| for m >= 0), so each Gauss-Seidel update is a descent step of
+    ||W - sum_i W_hat_i||_F; the paper's initialization table reports the same direction
+    (average MSE 0.150 greedy against 0.122 iterative on a real layer)."""
+    for key, (out, inn, K) in enumerate([(32, 48, 2), (40, 24, 3), (16, 16, 2)]):
+        W = synth.gaussian_weight(synth.child_rng(0, 42, key), out, inn, std=1.0)
+        signs, g, h, err = oracle.derive_iterative(W, K, T_max=20)
+        flat = err.reshape(-1)
+        assert np.all(np.diff(flat) <= 1e-9 * flat[0]), np.diff(flat).max()
+        greedy = oracle.derive(W, K, round_scales=False)[3][-1]
+        assert err[0, -1] == pytest.approx(greedy, rel=1e-12)
+        assert err[-1, -1] < 0.97 * greedy
+        # what is returned is what the error was measured on
+        What = oracle.effective_weight(signs, g, h)
+        assert np.linalg.norm(W - What) == pytest.approx(err[-1, -1], rel=1e-10)
+
+
+def test_iterative_svid_updates_follow_eq_init_iter_step_by_step():
+    """Two sweeps of K = 3 replayed with an SVID built on LAPACK: the residual of path i uses the
+    paths j < i of this sweep and the paths j > i of the previous one."""
+    W = synth.gaussian_weight(synth.child_rng(0, 43), 12, 20, std=1.0)
+    K, T = 3, 2
+    What = np.zeros((K,) + W.shape)
+    for t in range(T):
+        for i in range(K):
+            R = W - sum(What[j] for j in range(K) if j != i)
+            B, g, h = _svid_by_lapack(R)
+            What[i] = g[:, None] * B * h[None, :]
+    signs, g, h, err = oracle.derive_iterative(W, K, T_max=T)
+    got = g[:, :, None] * signs.astype(np.float64) * h[:, None, :]
+    np.testing.assert_allclose(got, What, rtol=0, atol=1e-9)
+    assert err[-1, -1] == pytest.approx(np.linalg.norm(W - What.sum(axis=0)), rel=1e-9)
+
+
+def test_iterative_svid_is_exact_on_a_weight_that_is_one_path():
+    rng = synth.child_rng(0, 44)
+    B = synth.uniform_signs(rng, 1, 9, 14)[0].astype(np.float64)
+    g = rng.uniform(0.5, 2.0, 9)
+    h = rng.uniform(0.5, 2.0, 14)
+    W = g[:, None] * B * h[None, :]
+    signs, gg, hh, err = oracle.derive_iterative(W, 2, T_max=3)
+    assert np.array_equal(signs[0], B.astype(np.int8))
+    np.testing.assert_allclose(np.outer(gg[0], hh[0]), np.outer(g, h), rtol=1e-9)
+    assert err.max() <= 1e-9 * np.linalg.norm(W)
+
+
+def test_preconditioning_formula_normalisation_and_mapping_back():
+    """Eq. (init-calib) and Alg. 1 steps 1 and 3 on a hand-made 2 x 3 case, then on random data:
+    the statistics are divided by their maximum, rows take s_out^a_out, columns s_in^a_in, and
+    the returned scales are those of the preconditioned problem divided by the same factors."""
+    W = np.array([[1.0, -2.0, 4.0], [8.0, 16.0, -32.0]])
+    s_in = np.array([4.0, 1.0, 16.0])        # / 16 -> 1/4, 1/16, 1;  ^0.5 -> 1/2, 1/4, 1
+    s_out = np.array([2.0, 8.0])             # / 8 -> 1/4, 1;  ^1 -> 1/4, 1
+    Wp, rows, cols = oracle.precondition(W, s_in, s_out, alpha_in=0.5, alpha_out=1.0)
+    np.testing.assert_allclose(rows, [0.25, 1.0])
+    np.testing.assert_allclose(cols, [0.5, 0.25, 1.0])
+    np.testing.assert_allclose(Wp, [[0.125, -0.125, 1.0], [4.0, 4.0, -32.0]])
+    # a common factor on a statistic changes nothing
+    Wp2, _, _ = oracle.precondition(W, 7.0 * s_in, 0.3 * s_out, 0.5, 1.0)
+    np.testing.assert_allclose(Wp2, Wp, rtol=1e-15)
+
+    rng = synth.child_rng(0, 45)
+    W = synth.gaussian_weight(rng, 20, 28, std=1.0)
+    s_in = rng.uniform(0.1, 3.0, 28)
+    s_out = rng.uniform(0.1, 3.0, 20)
+    a_in, a_out = 0.80, 0.65                 # the optimum the paper's grid search reports for Llama2-7B
+    signs, g, h, err = oracle.derive_iterative(W, 2, T_max=5, s_in=s_in, s_out=s_out, alpha_in=a_in, alpha_out=a_out)
+    Wp = (s_out / s_out.max())[:, None] ** a_out * W * (s_in / s_in.max())[None, :] ** a_in
+    sp, gp, hp, errp = oracle.derive_iterative(Wp, 2, T_max=5)
+    assert np.array_equal(signs, sp)
+    np.testing.assert_allclose(g * (s_out / s_out.max())[None, :] ** a_out, gp, rtol=1e-12)
+    np.testing.assert_allclose(h * (s_in / s_in.max())[None, :] ** a_in, hp, rtol=1e-12)
+    np.testing.assert_allclose(err, errp, rtol=1e-12)
+    # alpha = 0 switches the preconditioning off
+    s0, g0, h0, _ = oracle.derive_iterative(W, 2, T_max=5, s_in=s_in, s_out=s_out)
+    s1, g1, h1, _ = oracle.derive_iterative(W, 2, T_max=5)
+    assert np.array_equal(s0, s1) and np.allclose(g0, g1, rtol=1e-14) and np.allclose(h0, h1, rtol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.precondition(W, s_in[:-1], s_out, 0.5, 0.5)
+    with pytest.raises(ValueError):
+        oracle.precondition(W, np.zeros(28), s_out, 0.5, 0.5)
+
+
 # ------------------------------------------------------------------ stack ---
 def test_stack_forward_modes():
     rng = synth.child_rng(0, 14)
