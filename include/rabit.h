@@ -223,13 +223,17 @@ int rb_stream_read_groups(void);
 
 /* Which kernel family the most recent compute call of this thread enqueued:
  * RB_PATH_NONE, RB_PATH_SIGNADD (generic sign-XOR + add kernel, one launch per
- * op), RB_PATH_GEMM (many-token matrix-core GEMM, one launch per op) or
+ * op), RB_PATH_GEMM (many-token matrix-core GEMM, one launch per op),
  * RB_PATH_MX (matrix-core decode kernels: one layer and token in one launch,
- * or all ops of a stack in one persistent launch).  For tests and benchmarks that must know what they measured. */
+ * or all ops of a stack in one persistent launch) or RB_PATH_BATCH (small-batch
+ * kernel of a stack: one pass over the weights for up to 16 tokens, two or
+ * three paths, one launch per group of independent ops).  For tests and
+ * benchmarks that must know what they measured. */
 #define RB_PATH_NONE    0
 #define RB_PATH_SIGNADD 1
 #define RB_PATH_MX      2
 #define RB_PATH_GEMM    3
+#define RB_PATH_BATCH   4
 int rb_last_path(void);
 
 /* Library version: major*10000 + minor*100 + patch. */

@@ -304,7 +304,7 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
     return sink
 
 
-RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM = 0, 1, 2, 3
+RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM, RB_PATH_BATCH = 0, 1, 2, 3, 4
 RB_OPT_HANDOVER_PAUSE = 1
 
 

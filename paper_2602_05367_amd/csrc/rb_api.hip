@@ -59,6 +59,10 @@ extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_s
     if (rc != RB_OK) return rc;
     if (!workspace) return RB_ERR_WORKSPACE;
     rb::forget_pairs(workspace);
+    rb::batch::forget_plan(workspace);
+    if (n_ops > 1 && rb::batch_applies(layers, n_layers, T))
+        return rb::batch::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes,
+                                       static_cast<hipStream_t>(stream));
     if (T > 2)
         return rb::prepare_pairs(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
                                  static_cast<hipStream_t>(stream));
@@ -71,7 +75,12 @@ extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_s
 extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace) return RB_ERR_NULL;
-    int rc = rb::run_pairs(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    int rc = rb::batch::launch_plan(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    if (rc != RB_ERR_UNSUPPORTED) {
+        if (rc == RB_OK) rb::set_last_path(RB_PATH_BATCH);
+        return rc;
+    }
+    rc = rb::run_pairs(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     if (rc == RB_ERR_UNSUPPORTED)
         rc = rb::mx::launch_plan(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
     if (rc == RB_OK) rb::set_last_path(RB_PATH_MX);
@@ -81,6 +90,8 @@ extern "C" int rb_stack_run(void *workspace, size_t workspace_bytes, void *strea
 extern "C" int rb_stack_status(const void *workspace, void *stream)
 {
     if (!workspace) return RB_ERR_NULL;
+    if (rb::batch::has_plan(workspace))      // no hand-over inside a launch: nothing a run could give up
+        return hipStreamSynchronize(static_cast<hipStream_t>(stream)) == hipSuccess ? RB_OK : RB_ERR_HIP;
     const int rc = rb::pairs_status(workspace, static_cast<hipStream_t>(stream));
     if (rc != RB_ERR_UNSUPPORTED) return rc;
     return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream));
@@ -90,6 +101,7 @@ extern "C" int rb_stack_waited(const void *workspace, void *stream, unsigned lon
 {
     if (!workspace || !tiles) return RB_ERR_NULL;
     *tiles = 0;
+    if (rb::batch::has_plan(workspace)) return RB_OK;
     const int rc = rb::pairs_status(workspace, static_cast<hipStream_t>(stream), tiles);
     if (rc != RB_ERR_UNSUPPORTED) return rc;
     return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream), tiles);
@@ -109,6 +121,7 @@ extern "C" int rb_stack_forget(const void *workspace)
     if (!workspace) return RB_ERR_NULL;
     rb::forget_pairs(workspace);
     rb::mx::forget_plan(workspace);
+    rb::batch::forget_plan(workspace);
     return RB_OK;
 }
 

@@ -1,6 +1,7 @@
 // Kernel selection for one layer and for a stack of layers.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -13,11 +14,9 @@ namespace rb {
 thread_local int g_last_path = RB_PATH_NONE;
 void set_last_path(int path) { g_last_path = path; }
 
-// A stack of 3 to PAIRS_MAX_T tokens runs as passes of the fused two-token kernel over consecutive
-// token pairs (the last pass takes one token if T is odd): one pass is one launch for the whole op
-// list, while the many-token path pays three launches per op, which is what a short batch is bound
-// by (measured on the 7B-shaped stack: 0.6 ms per pair against 5.5 ms per batch of 16, so the pairs
-// win up to 16 tokens).  A call that also has to set the plans up does so for up to
+// A stack of 3 to BATCH_MIN_T - 1 tokens runs as passes of the fused two-token kernel over
+// consecutive token pairs (the last pass takes one token if T is odd): one pass is one launch for
+// the whole op list.  A call that also has to set the plans up does so for up to
 // PAIRS_MAX_T_ONESHOT tokens.
 constexpr int PAIRS_MAX_T = 16;
 constexpr int PAIRS_MAX_T_ONESHOT = 4;
@@ -39,8 +38,39 @@ static bool pairs_apply(const rb_layer *layers, int n_layers, int n_ops, int T)
     return true;
 }
 
+// Which stacks take the small-batch kernel (one pass over the weights for all tokens): every stack
+// with a three-path layer, and two-path stacks of BATCH_MIN_T tokens or more.  Below that the passes
+// over token pairs on the fused decode kernel are faster (measured on the 7B-shaped stack: 1.2 ms
+// for two passes at 4 tokens against 2.1 ms; 2.4 against 2.5 ms at 8; 4.8 against 3.1 ms at 16):
+// the small-batch kernel is one launch per group of independent ops, and a launch of a few hundred
+// KB per workgroup is bound by memory latency, not by the bytes it streams.
+constexpr int BATCH_MIN_T = 8;
+bool batch_applies(const rb_layer *layers, int n_layers, int T)
+{
+    bool three = false;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!batch::layer_supported(&layers[l], T)) return false;
+        three = three || layers[l].K == 3;
+    }
+    return three || T >= BATCH_MIN_T;
+}
+
+static bool batch_supported(const rb_layer *layers, int n_layers, int T)
+{
+    for (int l = 0; l < n_layers; ++l)
+        if (!batch::layer_supported(&layers[l], T)) return false;
+    return true;
+}
+
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
+    if (batch_applies(layers, n_layers, T) && n_ops > 1) {
+        size_t need = batch::plan_workspace_bytes(layers, n_layers, n_ops, T);
+        // the ops of a stack the kernel turns down run one after the other on the general paths
+        for (int l = 0; l < n_layers; ++l)
+            if (T > 2 && gemm::supported(&layers[l], T)) need = std::max(need, gemm::workspace_bytes(&layers[l], T));
+        return need;
+    }
     if (T > 2) {
         // ops run one after the other on the caller's stream and share the scratch of the GEMM path
         size_t need = 0;
@@ -50,6 +80,9 @@ size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
             const size_t pairs = (size_t)((T + 1) / 2) * pair_stride(layers, n_layers, n_ops);
             need = need > pairs ? need : pairs;
         }
+        // rb_layer_stack sets up pairs for up to PAIRS_MAX_T_ONESHOT tokens and takes the small-batch kernel above that
+        if (n_ops > 1 && T > PAIRS_MAX_T_ONESHOT && batch_supported(layers, n_layers, T))
+            need = std::max(need, batch::plan_workspace_bytes(layers, n_layers, n_ops, T));
         return need;
     }
     return mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
@@ -164,6 +197,13 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
 int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    if (n_ops > 1 && (batch_applies(layers, n_layers, T) ||
+                      (T > PAIRS_MAX_T_ONESHOT && batch_supported(layers, n_layers, T)))) {
+        int rc = batch::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes, stream);
+        if (rc == RB_OK) rc = batch::launch_plan(workspace, workspace_bytes, stream);
+        if (rc == RB_OK) g_last_path = RB_PATH_BATCH;
+        if (rc != RB_ERR_UNSUPPORTED && rc != RB_ERR_WORKSPACE) return rc;
+    }
     if (T > 2 && T <= PAIRS_MAX_T_ONESHOT) {
         int rc = prepare_pairs(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes, stream);
         if (rc == RB_OK) rc = run_pairs(workspace, workspace_bytes, stream);

@@ -15,6 +15,8 @@ int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dty
                    hipStream_t stream);
 
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
+// stacks that run on the small-batch kernel (see rb_dispatch.hip)
+bool batch_applies(const rb_layer *layers, int n_layers, int T);
 
 int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
                     void *workspace, size_t workspace_bytes, hipStream_t stream);
@@ -45,6 +47,18 @@ namespace gemv1 {
 bool supported(const rb_layer *L, int T);
 int launch(const rb_layer *L, const void *x, void *y, hipStream_t stream);
 }  // namespace gemv1
+
+namespace batch {
+// small-batch path (K = 2 or 3, up to 16 tokens): every op streams its weights once for all
+// tokens; independent ops share a launch, dependent ones are ordered by the stream
+bool layer_supported(const rb_layer *L, int T);
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
+int prepare_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,
+                 void *workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_plan(void *workspace, size_t workspace_bytes, hipStream_t stream);      // RB_ERR_UNSUPPORTED: no plan of this kind
+bool has_plan(const void *workspace);
+void forget_plan(const void *workspace);
+}  // namespace batch
 
 namespace mx {
 // workgroups of the decode kernels: one per compute unit of the current device (0: no device)

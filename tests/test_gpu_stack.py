@@ -29,13 +29,14 @@ def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
         stack.prepare()
         stack.run_prepared()
         torch.cuda.synchronize()
-        assert rb.rb_last_path() == rb.RB_PATH_MX
+        assert rb.rb_last_path() == (rb.RB_PATH_MX if T < 8 else rb.RB_PATH_BATCH)
         assert stack.status() == rb.RB_OK
         stack.forget()
     else:
         rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
     torch.cuda.synchronize()
-    # 3..16 tokens may run as token pairs on the fused kernel, a single call on the many-token kernel
+    # a stack of 3..16 tokens runs as token pairs on the fused kernel or on the small-batch kernel,
+    # a single call on the many-token kernel
     same_kernel = T <= 2 or T > 16
     got = [b.cpu().numpy() for b in dev_bufs]
     forced = [got[op.src] for op in ops]
@@ -80,9 +81,9 @@ def test_small_stack_batched_with_outliers(T):
 
 
 @pytest.mark.parametrize("T", [3, 8, 16])
-def test_prepared_small_batches_run_as_token_pairs(T):
-    """rb_stack_prepare / rb_stack_run at 3..16 tokens: one launch of the fused kernel per pair of
-    tokens (one token in the last launch when T is odd), every op checked against the oracle."""
+def test_prepared_small_batches(T):
+    """rb_stack_prepare / rb_stack_run at 3..16 tokens (token pairs on the fused kernel below 8
+    tokens, the small-batch kernel from 8 on), every op checked against the oracle."""
     shrink = {4096: 512, 11008: 1376}
     ops, widths, layers, bufs = build_stack("7b", 2, 5, T, derived=False, shrink=shrink, outliers=True,
                                             gain=100.0)
@@ -251,8 +252,8 @@ def test_full_7b_stack_as_benchmarked_sampled_outputs():
 
 
 def test_three_path_layers_in_a_stack():
-    """K = 3 layers have no fused kernel: rb_layer_stack runs them op by op on the generic kernel,
-    same dataflow rules, every op checked against the oracle."""
+    """K = 3 layers in a stack run on the small-batch matrix-core kernel (three right operands per
+    128 columns), every op checked against the oracle."""
     rng = synth.child_rng(3, 88)
     shapes = [(192, 256), (320, 192), (192, 320)]              # x -> a -> b -> c
     layers = []
@@ -268,7 +269,7 @@ def test_three_path_layers_in_a_stack():
     print("K=3 stack of three ops, T=2", flush=True)
     rb.rb_layer_stack(dev_layers, op_list, bufs, T)
     torch.cuda.synchronize()
-    assert rb.rb_last_path() == rb.RB_PATH_SIGNADD
+    assert rb.rb_last_path() == rb.RB_PATH_BATCH
     for n, (l, s, d) in enumerate(op_list):
         ref = oracle.forward(*layers[l], bufs[s].cpu().numpy())
         assert oracle.relative_l2(bufs[d].cpu().numpy().astype(np.float64), ref).max() <= TOL, n
