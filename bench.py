@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-def build_stack(rb, synth, torch, which: str, T: int, seed: int = 20260205):
+def build_stack(rb, synth, torch, which: str, T: int, seed: int = 20260205, K: int = 2):
     """Synthetic Llama-shaped stack resident on the GPU.
 
     Sign words are i.i.d. uniform bits drawn on the device directly in the
@@ -37,14 +37,15 @@ def build_stack(rb, synth, torch, which: str, T: int, seed: int = 20260205):
     gen.manual_seed(seed)
     layers, packed_bytes = [], 0
     for n, op in enumerate(ops):
-        nbytes = rb.rb_native_bytes(2, op.out, op.inn)
+        nbytes = rb.rb_native_bytes(K, op.out, op.inn)
         bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda", generator=gen)
-        a = torch.tensor([0.0160, 0.0097], device="cuda").sqrt()[:, None]
-        c = 1.0 / (op.inn * (0.0160 ** 2 + 0.0097 ** 2)) ** 0.5
-        g = (a * c * (1 + 0.01 * torch.randn(2, op.out, device="cuda", generator=gen))).half()
-        h = (a * (1 + 0.01 * torch.randn(2, op.inn, device="cuda", generator=gen))).half()
-        layers.append(rb.Layer(bits, g, h, 2, op.out, op.inn))
-        packed_bytes += 2 * op.out * op.inn // 8
+        gh = [0.0160, 0.0097, 0.0058][:K]            # third path: the residual shrinks by the same factor again
+        a = torch.tensor(gh, device="cuda").sqrt()[:, None]
+        c = 1.0 / (op.inn * sum(v ** 2 for v in gh)) ** 0.5
+        g = (a * c * (1 + 0.01 * torch.randn(K, op.out, device="cuda", generator=gen))).half()
+        h = (a * (1 + 0.01 * torch.randn(K, op.inn, device="cuda", generator=gen))).half()
+        layers.append(rb.Layer(bits, g, h, K, op.out, op.inn))
+        packed_bytes += K * op.out * op.inn // 8
     bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
     bufs[0].copy_(torch.randn(T, widths[0], device="cuda", generator=gen).half())
     op_list = [(n, op.src, op.dst) for n, op in enumerate(ops)]
@@ -144,6 +145,7 @@ def main() -> int:
     stack.prepare()
     wall, per = time_steps(torch, stack.run_prepared, args.steps, args.warmup)
     assert rb.rb_last_path() == rb.RB_PATH_MX
+    assert stack.status() == rb.RB_OK, "a run of the timed stack gave up a hand-over wait"
     ms = sum(per) / len(per)
     ms_min = min(per)
     y = bufs[ops[-1].dst].float()
@@ -157,9 +159,10 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "fp16 in/out, fp4 signs x 4-term bf8 inputs on MFMA, fp32 accumulate", "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-7B-shaped decode stack, batch 1, K=2, 32 blocks x "
-                               "(q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008)",
+                               "(q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008); i.i.d. sign bits, "
+                               "scales as the paper's derivation gives for Gaussian weights",
                    "tokens": T, "packed_bytes": packed_bytes, "entry_point": "rb_stack_run"},
         "tokens_per_s": T / (ms * 1e-3),
         "pct_of_hbm_peak": 100.0 * packed_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -184,6 +187,8 @@ def main() -> int:
         "achieved": packed_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": packed_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "traffic": traffic,
+        "traffic_source": "profiles/stack_kernel_7b_T1_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                          "scaled by a plain copy of known size; counters cannot be read from inside this process)",
         "note": "one launch per step; duration = HIP events around rb_stack_run on its stream "
                 "(includes the ~4 us input-expansion kernel and the ~6 us kernel that marks inputs not yet written)",
     }
@@ -206,6 +211,7 @@ def main() -> int:
         free = rb.Stack(layers, free_ops, fb, T)
         free.prepare()
         _, per_f = time_steps(torch, free.run_prepared, max(20, args.steps // 4), 5)
+        assert free.status() == rb.RB_OK
         ms_f = sum(per_f) / len(per_f)
         result["independent_ops"] = {"ms_per_step": ms_f, "GBps": packed_bytes / (ms_f * 1e-3) / 1e9,
                                      "pct_of_hbm_peak": 100.0 * packed_bytes / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBPS}
@@ -242,6 +248,7 @@ def main() -> int:
         stack13 = rb.Stack(layers13, op_list13, bufs13, T)
         stack13.prepare()
         _, per13 = time_steps(torch, stack13.run_prepared, 30, 5)
+        assert stack13.status() == rb.RB_OK
         ms13 = sum(per13) / len(per13)
         result["stack_13b"] = {"ms_per_token": ms13, "tokens_per_s": 1.0 / (ms13 * 1e-3), "packed_bytes": packed13,
                                "GBps": packed13 / (ms13 * 1e-3) / 1e9,
@@ -253,35 +260,36 @@ def main() -> int:
         stack2 = rb.Stack(layers2, op_list2, bufs2, 2)
         stack2.prepare()
         _, per2 = time_steps(torch, stack2.run_prepared, 30, 5)
+        assert stack2.status() == rb.RB_OK
         ms2 = sum(per2) / len(per2)
         result["stack_7b_two_tokens"] = {"ms_per_pass": ms2, "tokens_per_s": 2.0 / (ms2 * 1e-3),
                                          "GBps": packed2 / (ms2 * 1e-3) / 1e9,
                                          "tiles_waited_per_pass": stack2.waited() / 35.0}
         stack2.forget()
         del ops2, layers2, bufs2, stack2
-        # three paths (the paper's 3-bit variant): no fused kernel, one launch of the generic
-        # sign-XOR + add kernel per op; one block of the 7B shape, scaled to 32
-        ops1, _ = synth.llama_stack("7b", n_layers=1)
-        lay3, bytes3 = [], 0
-        for op in ops1:
-            nb3 = rb.rb_native_bytes(3, op.out, op.inn)
-            b3 = torch.randint(-2 ** 31, 2 ** 31 - 1, (nb3 // 4,), dtype=torch.int32, device="cuda")
-            lay3.append(rb.Layer(b3, (torch.randn(3, op.out, device="cuda").abs() * 0.02).half(),
-                                 (torch.randn(3, op.inn, device="cuda").abs() * 0.02).half(), 3, op.out, op.inn))
-            bytes3 += 3 * op.out * op.inn // 8
-        ins3 = {4096: torch.randn(1, 4096, device="cuda").half(), 11008: torch.randn(1, 11008, device="cuda").half()}
-        outs3 = [torch.zeros((1, op.out), dtype=torch.float16, device="cuda") for op in ops1]
-        st3 = rb.Stack(lay3, [(n, 0 if op.inn == 4096 else 1, 2 + n) for n, op in enumerate(ops1)],
-                       [ins3[4096], ins3[11008]] + outs3, 1)
-        _, per3 = time_steps(torch, st3.run, 30, 5)
-        ms3 = sum(per3) / len(per3)
-        result["three_path_block_generic_kernel"] = {"ms_per_block": ms3, "GBps": bytes3 / (ms3 * 1e-3) / 1e9,
-                                                     "tokens_per_s_32_blocks": 1.0 / (32 * ms3 * 1e-3),
-                                                     "path": rb.rb_last_path()}
-        del lay3, outs3, st3
+        # three paths (the paper's 3-bit variant), the whole 7B-shaped chain: the small-batch kernel
+        # (one launch per group of independent ops) at one token and at eight
+        three = {}
+        for T3 in (1, 8):
+            ops3, layers3, bufs3, op_list3, packed3 = build_stack(rb, synth, torch, "7b", T3, K=3)
+            stack3 = rb.Stack(layers3, op_list3, bufs3, T3)
+            stack3.prepare()
+            _, per3 = time_steps(torch, stack3.run_prepared, 20, 3)
+            assert rb.rb_last_path() == rb.RB_PATH_BATCH and stack3.status() == rb.RB_OK
+            ms3 = sum(per3) / len(per3)
+            three[f"T{T3}"] = {"ms_per_pass": ms3, "tokens_per_s": T3 / (ms3 * 1e-3), "packed_bytes": packed3,
+                               "GBps": packed3 / (ms3 * 1e-3) / 1e9,
+                               "pct_of_hbm_peak": 100.0 * packed3 / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            stack3.forget()
+            del ops3, layers3, bufs3, stack3
+        result["three_path_stack_7b"] = three
         # one-call form (set-up inside the call)
         _, per_o = time_steps(torch, stack.run, 20, 3)
-        result["rb_layer_stack_ms"] = sum(per_o) / len(per_o)
+        ms_o = sum(per_o) / len(per_o)
+        result["rb_layer_stack_ms"] = ms_o
+        result["roofline"]["rb_layer_stack"] = {"ms_per_step": ms_o, "achieved": packed_bytes / (ms_o * 1e-3) / 1e9,
+                                                "frac": packed_bytes / (ms_o * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                                "note": "the same step through the one-call entry point: plan set-up inside the timed call"}
         # read-bandwidth ceiling of this device
         big = layers[4].bits
         blob = torch.empty(packed_bytes // 4, dtype=torch.int32, device="cuda")
@@ -309,25 +317,38 @@ def main() -> int:
         result["paper_context"] = "RTX 4090: 291.88 tok/s = 4.49x FP16, whole Llama2-7B model (inference table)"
         result["prefill_gemm_T2048"] = prefill_figures(rb, torch)
         # small decode batches (configs[2]): the 7B-shaped stack, every op on its own input buffer.
-        # Up to 16 tokens the prepared stack runs the fused decode kernel (one launch per pair of
-        # tokens, i.e. T/2 passes over the weights); rb_layer_stack beyond 4 tokens makes every op a
-        # launch sequence of the many-token kernel (one pass over the weights, three launches per op).
+        # 2 tokens: the fused decode kernel, one launch.  4 tokens: the same kernel, one launch per
+        # pair of tokens (two passes over the weights).  8 and 16 tokens: the small-batch kernel,
+        # one pass over the weights, one launch per group of independent ops.
         skinny = {}
-        for Ts, prepared in ((2, True), (4, True), (8, True), (16, True), (16, False)):
+        for Ts in (2, 4, 8, 16):
             fbs = [torch.randn(Ts, w, device="cuda").half() for w in (4096, 11008)]
             outs_s = [torch.zeros((Ts, op.out), dtype=torch.float16, device="cuda") for op in ops]
             st_s = rb.Stack(layers, [(n, 0 if op.inn == 4096 else 1, 2 + n) for n, op in enumerate(ops)], fbs + outs_s, Ts)
-            if prepared:
-                st_s.prepare()
-                _, per_s = time_steps(torch, st_s.run_prepared, 8, 2)
-                st_s.forget()
-            else:
-                _, per_s = time_steps(torch, st_s.run, 4, 1)
+            st_s.prepare()
+            _, per_s = time_steps(torch, st_s.run_prepared, 8, 2)
+            assert st_s.status() == rb.RB_OK
+            path = rb.rb_last_path()
+            st_s.forget()
             ms_s = sum(per_s) / len(per_s)
-            skinny[f"T{Ts}" if prepared else f"T{Ts}_many_token_kernel"] = {
+            skinny[f"T{Ts}"] = {
                 "ms_per_pass": ms_s, "tokens_per_s": Ts / (ms_s * 1e-3), "GBps": packed_bytes / (ms_s * 1e-3) / 1e9,
-                "entry_point": "rb_stack_run" if prepared else "rb_layer_stack"}
+                "passes_over_the_weights": 1 if (Ts <= 2 or path == rb.RB_PATH_BATCH) else (Ts + 1) // 2,
+                "kernel": "small-batch kernel" if path == rb.RB_PATH_BATCH else "fused decode kernel",
+                "entry_point": "rb_stack_run"}
             del fbs, outs_s, st_s
+        # the dependent 7B-shaped chain at 8 and 16 tokens (the small-batch kernel)
+        for Ts in (8, 16):
+            ops_b, layers_b, bufs_b, op_list_b, _ = build_stack(rb, synth, torch, "7b", Ts)
+            st_b = rb.Stack(layers_b, op_list_b, bufs_b, Ts)
+            st_b.prepare()
+            _, per_b = time_steps(torch, st_b.run_prepared, 8, 2)
+            assert rb.rb_last_path() == rb.RB_PATH_BATCH and st_b.status() == rb.RB_OK
+            ms_b = sum(per_b) / len(per_b)
+            skinny[f"T{Ts}_dependent_chain"] = {"ms_per_pass": ms_b, "tokens_per_s": Ts / (ms_b * 1e-3),
+                                                "GBps": packed_bytes / (ms_b * 1e-3) / 1e9, "passes_over_the_weights": 1}
+            st_b.forget()
+            del ops_b, layers_b, bufs_b, st_b
         result["small_batch_stack"] = skinny
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)
     else:

@@ -49,9 +49,15 @@ constexpr int MAX_CONS = 3;            // ops that read one op's output inside a
 constexpr int WAVES = 16;              // wavefronts of a workgroup
 constexpr int THREADS = WAVES * 64;
 constexpr int MAX_STAGE_OPS = 8;       // independent ops that share a launch
-// wavefronts that share a row tile: each takes every S-th piece (128-column half x path) of a sign tile
-__host__ __device__ constexpr int pieces_split(int K) { return K == 2 ? 4 : 2; }
-__host__ __device__ constexpr int block_tiles(int K) { return WAVES / pieces_split(K); }      // row tiles of a workgroup
+// S wavefronts share a row tile, each taking every S-th piece (128-column half x path) of a sign
+// tile; a workgroup owns R = 16 / S row tiles.  Few row tiles per workgroup make many workgroups
+// out of a small op; many row tiles share the staged right operands among more rows, which is what
+// counts when a launch has workgroups enough anyway (at 16 tokens the operands of a column tile
+// are 32 KB, a sign tile 1 KB).  S is chosen per launch (see prepare_plan).
+__host__ __device__ constexpr int max_split(int K) { return K == 2 ? 4 : 2; }
+__host__ __device__ constexpr int min_split(int K) { return K == 2 ? 1 : 2; }     // three paths, all pieces in one wavefront: too many accumulators
+__host__ __device__ constexpr int block_tiles(int S) { return WAVES / S; }      // row tiles of a workgroup
+constexpr int WANT_GROUPS = 256;       // workgroups a launch should have before it takes larger row blocks
 constexpr size_t MAX_EXPAND = 1024;
 
 #define RB_LDS(p) ((__attribute__((address_space(3))) void *)(p))
@@ -87,7 +93,7 @@ struct Op {
     uint16_t *y;              // fp16 [T][out]
     uint8_t *up;              // expanded input of this op
     int out, in, K;
-    int RT, CT, RB;           // row tiles, column tiles, row blocks (workgroups)
+    int RT, CT;               // row tiles, column tiles
     int wg0;                  // first workgroup of this op inside its launch
     int n_cons;
     float sc[RB_MAX_K];       // power-of-two input scaling per path (max |h_k| * sc in [1/4, 1/2))
@@ -161,10 +167,10 @@ __global__ __launch_bounds__(256) void expand_kernel(const Op *ops, const int *w
 // ------------------------------------------------------------------- kernel ---
 // LDS ring of column tiles: a slot holds the tile's right operands and the sign tiles of the
 // workgroup's row tiles; as many slots as fit (at most 16)
-__host__ __device__ constexpr int slot_bytes(int K, int G) { return (int)tile_operand_bytes(K, G) + block_tiles(K) * tile_words(K) * 4; }
-__host__ __device__ constexpr int ring_depth(int K, int G)
+__host__ __device__ constexpr int slot_bytes(int K, int G, int S) { return (int)tile_operand_bytes(K, G) + block_tiles(S) * tile_words(K) * 4; }
+__host__ __device__ constexpr int ring_depth(int K, int G, int S)
 {
-    return (144 * 1024) / slot_bytes(K, G) < 16 ? (144 * 1024) / slot_bytes(K, G) : 16;
+    return (144 * 1024) / slot_bytes(K, G, S) < 16 ? (144 * 1024) / slot_bytes(K, G, S) : 16;
 }
 
 // "at most rem * LPI vector-memory loads outstanding" for a run-time rem in 0 .. R.  (KERNEL only
@@ -198,16 +204,17 @@ template <int KERNEL, int LPI> struct Copies {
     }
 };
 
-template <int K, int G>
+template <int K, int G, int S>
 __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict__ ops, int op0, int nops, int T)
 {
-    constexpr int S = pieces_split(K), R = block_tiles(K), NP = 2 * K / S;     // NP: pieces per wavefront and tile
+    constexpr int R = block_tiles(S), NP = 2 * K / S;        // NP: pieces per wavefront and tile
+    static_assert(2 * K % S == 0 && WAVES % S == 0, "pieces and wavefronts go round");
     constexpr int OPB = (int)tile_operand_bytes(K, G);
     constexpr int TB = tile_words(K) * 4;                    // bytes of a sign tile
-    constexpr int SLOT = slot_bytes(K, G);                   // [operands OPB][sign tiles R x TB]
+    constexpr int SLOT = slot_bytes(K, G, S);                 // [operands OPB][sign tiles R x TB]
     constexpr int COPIES = SLOT / 1024;                      // 1 KB per wavefront instruction
     constexpr int LPI = (COPIES + WAVES - 1) / WAVES;        // copies per wavefront and tile
-    constexpr int D = ring_depth(K, G);                      // slots in LDS; D - 1 tiles are requested ahead
+    constexpr int D = ring_depth(K, G, S);                    // slots in LDS; D - 1 tiles are requested ahead
     constexpr int PART = G * 4 * TILE_ROWS;                  // floats of one wavefront's partial outputs: [token][row]
     static_assert(SLOT % 1024 == 0 && D >= 2 && (D - 1) * LPI < 64, "the in-order wait counts on this");
     static_assert(WAVES * PART * 4 <= D * SLOT, "the partial outputs reuse the ring");
@@ -236,7 +243,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
     // temporal) follow in the slot as they are in memory, so that lane l finds its 2 K words
     // (word c * K + k = path k, columns 128 c + 32 (l / 16) ..) at 8 K l.  A row tile past the
     // end of the matrix copies the last one (nobody reads it).
-    Copies<16 * K + G, LPI> copies;
+    Copies<64 * K + 8 * G + S, LPI> copies;
 #pragma unroll
     for (int i = 0; i < LPI; ++i) {
         const int piece = (wave + WAVES * i) % COPIES;
@@ -271,7 +278,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
         // LPI times the number of younger tiles already requested are outstanding, tile ct is
         // here.  After the barrier it is here for every wavefront, and every wavefront is
         // through with the slot of tile ct - 1, which the next request overwrites.
-        WaitTiles<16 * K + G, LPI, D - 2>::run(min(CT - 1 - ct, D - 2));
+        WaitTiles<64 * K + 8 * G + S, LPI, D - 2>::run(min(CT - 1 - ct, D - 2));
         asm volatile("s_barrier" ::: "memory");               // the barrier alone: a fence would wait for every copy in flight
         if (ct + D - 1 < CT) copies.request(lds + (slot == 0 ? D - 1 : slot - 1) * SLOT, ct + D - 1);
         if (live) {
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
 }
 
 // ------------------------------------------------------------------ host ---
-struct Launch { int op0, nops, groups, K; };
+struct Launch { int op0, nops, groups, K, S; };
 struct Layout { size_t ops, cons, which, up, total; };
 
 static Layout make_layout(int n_ops, size_t up_total)
@@ -426,7 +433,6 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         o.y = bufs[sops[n].dst];
         o.out = L.out; o.in = L.in; o.K = L.K;
         o.RT = row_tiles(L.out); o.CT = col_tiles(L.in);
-        o.RB = (o.RT + block_tiles(L.K) - 1) / block_tiles(L.K);
         up_off[(size_t)n] = up_total;
         up_total += mx::align_up(operand_bytes(L.in, L.K, G), 256);
         int producer = -1;
@@ -447,17 +453,29 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     Prepared pr;
     pr.n_ops = n_ops; pr.T = T;
     for (int op0 = 0; op0 < n_ops;) {
-        int nops = 0, groups = 0;
+        int nops = 0;
+        const int K = ops[(size_t)op0].K;
         for (int n = op0; n < n_ops && nops < MAX_STAGE_OPS; ++n) {
-            bool conflict = ops[(size_t)n].K != ops[(size_t)op0].K;
+            bool conflict = ops[(size_t)n].K != K;
             for (int m = op0; m < n; ++m)
                 if (sops[m].dst == sops[n].src || sops[m].dst == sops[n].dst || sops[m].src == sops[n].dst) conflict = true;
             if (conflict) break;
-            ops[(size_t)n].wg0 = groups;
-            groups += ops[(size_t)n].RB;
             ++nops;
         }
-        pr.launches.push_back(Launch{op0, nops, groups, ops[(size_t)op0].K});
+        // the largest row blocks that still give the launch WANT_GROUPS workgroups, else the smallest
+        int S = max_split(K), groups = 0;
+        for (int s_try = min_split(K); s_try <= max_split(K); s_try *= 2) {
+            groups = 0;
+            for (int n = op0; n < op0 + nops; ++n) groups += (ops[(size_t)n].RT + block_tiles(s_try) - 1) / block_tiles(s_try);
+            S = s_try;
+            if (groups >= WANT_GROUPS) break;
+        }
+        groups = 0;
+        for (int n = op0; n < op0 + nops; ++n) {
+            ops[(size_t)n].wg0 = groups;
+            groups += (ops[(size_t)n].RT + block_tiles(S) - 1) / block_tiles(S);
+        }
+        pr.launches.push_back(Launch{op0, nops, groups, K, S});
         op0 += nops;
     }
     pr.n_expand = (int)expand_list.size();
@@ -483,19 +501,30 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     return RB_OK;
 }
 
-template <int K, int G>
+template <int K, int G, int S>
 static int launch_one(const Op *d_ops, const Launch &l, int T, hipStream_t stream)
 {
-    const int lds_bytes = ring_depth(K, G) * slot_bytes(K, G);
+    const int lds_bytes = ring_depth(K, G, S) * slot_bytes(K, G, S);
     static std::atomic<bool> configured{false};
     if (!configured.load()) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(batch_kernel<K, G>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(batch_kernel<K, G, S>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 lds_bytes) != hipSuccess)
             return RB_ERR_HIP;
         configured.store(true);
     }
-    hipLaunchKernelGGL((batch_kernel<K, G>), dim3((unsigned)l.groups), dim3(THREADS), lds_bytes, stream, d_ops, l.op0, l.nops, T);
+    hipLaunchKernelGGL((batch_kernel<K, G, S>), dim3((unsigned)l.groups), dim3(THREADS), lds_bytes, stream, d_ops, l.op0, l.nops, T);
     return RB_OK;
+}
+
+template <int K, int S>
+static int launch_groups(const Op *d_ops, const Launch &l, int T, hipStream_t stream)
+{
+    switch (groups_of(T)) {
+    case 1: return launch_one<K, 1, S>(d_ops, l, T, stream);
+    case 2: return launch_one<K, 2, S>(d_ops, l, T, stream);
+    case 3: return launch_one<K, 3, S>(d_ops, l, T, stream);
+    default: return launch_one<K, 4, S>(d_ops, l, T, stream);
+    }
 }
 
 // RB_ERR_UNSUPPORTED: the workspace holds no plan of this kind
@@ -508,16 +537,15 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (workspace_bytes_ < pr.lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const Op *d_ops = reinterpret_cast<const Op *>(ws + pr.lay.ops);
-    const int T = pr.T, G = groups_of(T);
+    const int T = pr.T;
     if (pr.n_expand > 0)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, T, (unsigned)pr.n_expand), dim3(256), 0,
                            stream, d_ops, reinterpret_cast<const int *>(ws + pr.lay.which), T);
     for (const Launch &l : pr.launches) {
         int rc = RB_ERR_UNSUPPORTED;
-        if (l.K == 2) rc = G == 1 ? launch_one<2, 1>(d_ops, l, T, stream) : G == 2 ? launch_one<2, 2>(d_ops, l, T, stream)
-                         : G == 3 ? launch_one<2, 3>(d_ops, l, T, stream) : launch_one<2, 4>(d_ops, l, T, stream);
-        else if (l.K == 3) rc = G == 1 ? launch_one<3, 1>(d_ops, l, T, stream) : G == 2 ? launch_one<3, 2>(d_ops, l, T, stream)
-                              : G == 3 ? launch_one<3, 3>(d_ops, l, T, stream) : launch_one<3, 4>(d_ops, l, T, stream);
+        if (l.K == 2) rc = l.S == 1 ? launch_groups<2, 1>(d_ops, l, T, stream) : l.S == 2 ? launch_groups<2, 2>(d_ops, l, T, stream)
+                                    : launch_groups<2, 4>(d_ops, l, T, stream);
+        else if (l.K == 3) rc = launch_groups<3, 2>(d_ops, l, T, stream);
         if (rc != RB_OK) return rc;
     }
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;

@@ -171,3 +171,20 @@ def test_full_width_7b_block_on_the_batch_kernel(T):
         worst = max(worst, err)
         assert err <= TOL, (op.name, err)
     print(f"  worst sampled rel_l2={worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("n_ops,T", [(8, 16), (4, 9), (8, 5)])
+def test_many_independent_rows_take_larger_row_blocks(n_ops, T):
+    """A launch with rows enough lets a workgroup own 16 (eight ops of 8192 rows) or 8 (four such
+    ops) row tiles instead of 4, so that the staged inputs are shared by more rows: the same
+    results, other instantiations of the kernel.  Every op reads the one stack input."""
+    rng = synth.child_rng(3, 506, n_ops, T)
+    out, inn = 8192 - 16 * 5 - 3, 288                 # part-filled last row tile and last row block
+    layers = []
+    for _ in range(n_ops):
+        signs, g, h = random_layer(rng, 2, out, inn)
+        gain = 1.0 / (np.sqrt(inn * 2) * (0.02 * 0.02))
+        layers.append((signs, (g.astype(np.float64) * gain).astype(np.float16), h))
+    x = synth.outlier_activations(rng, T, inn)
+    op_list = [(n, 0, 1 + n) for n in range(n_ops)]
+    _check_stack(layers, op_list, (inn,) + (out,) * n_ops, x, T, f"{n_ops} independent ops of {out} rows", prepared=(T >= 8))
