@@ -122,6 +122,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip comparators and the CPU baseline")
     ap.add_argument("--prefill-only", action="store_true",
                     help="only the prefill GEMM figures (for profiling that kernel)")
+    ap.add_argument("--batch-only", type=int, default=0, metavar="T",
+                    help="only the dependent 7B-shaped chain at T tokens (8..16) on the small-batch kernel (for profiling it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -137,6 +139,18 @@ def main() -> int:
 
     if args.prefill_only:
         print(json.dumps({"prefill_gemm_T2048": prefill_figures(rb, torch)}))
+        return 0
+
+    if args.batch_only:
+        Tb = args.batch_only
+        ops_b, layers_b, bufs_b, op_list_b, packed_b = build_stack(rb, synth, torch, "7b", Tb)
+        st_b = rb.Stack(layers_b, op_list_b, bufs_b, Tb)
+        st_b.prepare()
+        _, per_b = time_steps(torch, st_b.run_prepared, args.steps, args.warmup)
+        assert rb.rb_last_path() == rb.RB_PATH_BATCH and st_b.status() == rb.RB_OK
+        ms_b = sum(per_b) / len(per_b)
+        print(json.dumps({"small_batch_chain": {"tokens": Tb, "ms_per_pass": ms_b, "tokens_per_s": Tb / (ms_b * 1e-3),
+                                                "GBps": packed_b / (ms_b * 1e-3) / 1e9}}))
         return 0
 
     T = 1
