@@ -19,6 +19,11 @@ What each function follows:
                                Alg. 1: Gauss-Seidel sweeps of SVID over the
                                residuals of a preconditioned target, scales
                                mapped back to the original domain.
+* ``couple``                 - Alg. 2 forward loop ("on-the-fly residual coupling")
+                               with given scales, in fp32 as a training step holds
+                               the shared weight.
+* ``scale_grads``            - Eq. (RaBiT-grad-gh), gradients of the scales; with
+                               ``weight_grad`` Eq. (RaBiT-grad-wfp).
 * ``stack_forward``          - the layer applied op after op (fp16 between ops).
 
 All floating point is fp64.  Stored fp16 / bf16 values are widened exactly.
@@ -284,6 +289,59 @@ def derive_iterative(W: np.ndarray, K: int, T_max: int = 20, s_in=None, s_out=No
             What[i] = g[i][:, None] * signs[i].astype(np.float64) * h[i][None, :]
             err[t, i] = float(np.linalg.norm(Wp - What.sum(axis=0)))
     return signs, g / rows[None, :], h / cols[None, :], err
+
+
+# --------------------------------------------------------------------------
+# Training side (Alg. 2 and the backward-pass equations of Section 4.2)
+# --------------------------------------------------------------------------
+def couple(W: np.ndarray, g, h):
+    """Alg. 2, forward loop, with the scales given: R_0 = W; for i = 1..K:
+    B_i = sign(R_{i-1}); W_hat_i = g_i (.) B_i (.) h_i; R_i = R_{i-1} - W_hat_i.
+
+    The sign of a residual decides a stored bit, so the precision of the
+    residual is part of the definition: fp32 (the shared weight of a training
+    step), one rounding for the product g_i[r] * h_i[c] and one for the
+    subtraction (B_i only flips the sign of the product, which is exact).
+    g [K][out], h [K][in] are widened exactly to fp32.
+    Returns (signs int8 [K][out][in], R_K float32 [out][in])."""
+    R = np.array(W, dtype=np.float32, copy=True)
+    g32 = np.asarray(g).astype(np.float32)
+    h32 = np.asarray(h).astype(np.float32)
+    K = g32.shape[0]
+    signs = np.empty((K,) + R.shape, dtype=np.int8)
+    for i in range(K):
+        B = sign(R)
+        prod = (g32[i][:, None] * h32[i][None, :]).astype(np.float32)
+        R = (R - np.where(B > 0, prod, -prod)).astype(np.float32)
+        signs[i] = B
+    return signs, R
+
+
+def weight_grad(Delta, X) -> np.ndarray:
+    """Eq. (RaBiT-grad-wfp): dL/dW_hat = (dL/dY) X^T with X [in][N], Y [out][N];
+    here tokens are rows: Delta [N][out], X [N][in] -> [out][in], fp64."""
+    return _f64(Delta).T @ _f64(X)
+
+
+def scale_grads(signs: np.ndarray, g, h, X, Delta):
+    """Eq. (RaBiT-grad-gh), binary cores held constant:
+        grad g_i = sum_n Delta_n (.) (B_i (h_i (.) x_n))
+        grad h_i = sum_n (B_i^T (Delta_n (.) g_i)) (.) x_n
+    X [N][in], Delta [N][out]; returns (grad_g [K][out], grad_h [K][in]), fp64,
+    written sample by sample as the equation is."""
+    B = np.asarray(signs).astype(np.float64)
+    g = _f64(g)
+    h = _f64(h)
+    X = _f64(X)
+    D = _f64(Delta)
+    K = B.shape[0]
+    gg = np.zeros_like(g)
+    gh = np.zeros_like(h)
+    for n in range(X.shape[0]):
+        for i in range(K):
+            gg[i] += D[n] * (B[i] @ (h[i] * X[n]))
+            gh[i] += (B[i].T @ (D[n] * g[i])) * X[n]
+    return gg, gh
 
 
 # --------------------------------------------------------------------------

@@ -428,6 +428,73 @@ def test_preconditioning_formula_normalisation_and_mapping_back():
         oracle.precondition(W, np.zeros(28), s_out, 0.5, 0.5)
 
 
+# ---- Alg. 2 forward loop and the backward-pass equations of Section 4.2
+def test_couple_against_scalar_loops_and_the_residual_identity():
+    """The coupled derivation written with Python scalars (numpy.float32 arithmetic, one
+    rounding per operation), and R_K = W - sum_i g_i B_i h_i within fp32 rounding."""
+    rng = synth.child_rng(0, 46)
+    out, inn, K = 5, 64, 3
+    W = rng.standard_normal((out, inn)).astype(np.float32)
+    W[0, 0] = 0.0                                             # sign(0) = +1
+    g = np.abs(rng.standard_normal((K, out))).astype(np.float16) * np.float16(0.5)
+    h = np.abs(rng.standard_normal((K, inn))).astype(np.float16)
+    signs, R = oracle.couple(W, g, h)
+    assert signs.dtype == np.int8 and R.dtype == np.float32
+    for r in range(out):
+        for c in range(inn):
+            res = np.float32(W[r, c])
+            for i in range(K):
+                b = 1 if res >= 0 else -1
+                assert signs[i, r, c] == b, (i, r, c)
+                prod = np.float32(np.float32(g[i, r]) * np.float32(h[i, c]))
+                res = np.float32(res - prod) if b > 0 else np.float32(res + prod)
+            assert R[r, c] == res
+    assert signs[0, 0, 0] == 1
+    What = oracle.effective_weight(signs, g, h)
+    np.testing.assert_allclose(R.astype(np.float64), W.astype(np.float64) - What, atol=1e-5)
+    # one path: the core is the sign of the weight, whatever the scales
+    s1, _ = oracle.couple(W, g[:1], h[:1])
+    assert np.array_equal(s1[0], np.where(W >= 0, 1, -1))
+
+
+def test_couple_with_derived_scales_reproduces_the_derivation():
+    """With the scales the greedy derivation found, the coupled forward loop finds its cores again
+    (the two only differ in the precision of the residual, which moves no sign of a Gaussian weight
+    that is not within fp32 rounding of zero)."""
+    W = synth.gaussian_weight(synth.child_rng(0, 47), 48, 96, std=1.0)
+    signs, g, h, _ = oracle.derive(W, 2, round_scales=True)
+    s2, _ = oracle.couple(W.astype(np.float32), g, h)
+    assert np.mean(s2 != signs) < 1e-3
+
+
+def test_scale_gradients_are_the_derivatives_of_the_forward_pass():
+    """L = sum_n Delta_n . y_n is linear in each g_i and each h_i, so a difference quotient of the
+    (pinned) forward pass is its exact derivative: every entry of both gradients."""
+    rng = synth.child_rng(0, 48)
+    K, out, inn, N = 2, 6, 32, 3
+    signs = synth.uniform_signs(rng, K, out, inn)
+    g = rng.standard_normal((K, out))
+    h = rng.standard_normal((K, inn))
+    X = rng.standard_normal((N, inn))
+    D = rng.standard_normal((N, out))
+    gg, gh = oracle.scale_grads(signs, g, h, X, D)
+    loss = lambda g_, h_: float((D * oracle.forward(signs, g_, h_, X)).sum())
+    base = loss(g, h)
+    for i in range(K):
+        for r in range(out):
+            g2 = g.copy(); g2[i, r] += 1.0
+            assert loss(g2, h) - base == pytest.approx(gg[i, r], rel=1e-9, abs=1e-9)
+        for c in range(inn):
+            h2 = h.copy(); h2[i, c] += 1.0
+            assert loss(g, h2) - base == pytest.approx(gh[i, c], rel=1e-9, abs=1e-9)
+    # the same through the weight gradient (Eq. RaBiT-grad-wfp): grad g_i[r] = sum_c B_i[r][c] h_i[c] G[r][c]
+    G = oracle.weight_grad(D, X)
+    np.testing.assert_allclose(G, np.einsum("no,ni->oi", D, X), rtol=1e-12)
+    for i in range(K):
+        np.testing.assert_allclose(gg[i], (signs[i] * h[i][None, :] * G).sum(axis=1), rtol=1e-9, atol=1e-9)
+        np.testing.assert_allclose(gh[i], (signs[i] * g[i][:, None] * G).sum(axis=0), rtol=1e-9, atol=1e-9)
+
+
 # ------------------------------------------------------------------ stack ---
 def test_stack_forward_modes():
     rng = synth.child_rng(0, 14)
