@@ -364,6 +364,25 @@ def main() -> int:
             st_b.forget()
             del ops_b, layers_b, bufs_b, st_b
         result["small_batch_stack"] = skinny
+        # training-side kernels (Alg. 2): coupled derivation of the cores and the scale gradients
+        # of one 4096 x 11008 layer; both stream an fp32 matrix, so the figure is HBM bytes per second
+        o_t, i_t = 4096, 11008
+        Wt = torch.randn((o_t, i_t), device="cuda") * 0.02
+        gt = (torch.randn(2, o_t, device="cuda").abs() * 0.1).half()
+        ht = (torch.randn(2, i_t, device="cuda").abs() * 0.1).half()
+        _, per_c = time_steps(torch, lambda: rb.rb_couple(Wt, gt, ht), 10, 3)
+        pk, _, _ = rb.rb_couple(Wt, gt, ht)
+        ms_c = sum(per_c) / len(per_c)
+        bytes_c = 4 * o_t * i_t + 2 * (2 * o_t * i_t // 8)         # W read, canonical and native words written
+        _, per_g = time_steps(torch, lambda: rb.rb_scale_grads(Wt, pk, gt, ht), 10, 3)
+        ms_g = sum(per_g) / len(per_g)
+        bytes_g = 2 * (4 * o_t * i_t + 2 * o_t * i_t // 8)         # G and the packed cores, once per direction
+        result["training_side_4096x11008"] = {
+            "rb_couple": {"ms": ms_c, "GBps": bytes_c / (ms_c * 1e-3) / 1e9,
+                          "pct_of_hbm_peak": 100.0 * bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+            "rb_scale_grads": {"ms": ms_g, "GBps": bytes_g / (ms_g * 1e-3) / 1e9,
+                               "pct_of_hbm_peak": 100.0 * bytes_g / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
+        del Wt, pk
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)
     else:
         result["cpu_baseline"] = None

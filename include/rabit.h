@@ -205,6 +205,49 @@ int rb_stack_set_option(int option, int value);
 size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 
 /* ------------------------------------------------------------------------
+ * Training side (Section 4.2 "Backward Pass and Parameter Updates", Alg. 2).
+ * All pointers are device pointers; nothing allocates or synchronises.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * On-the-fly residual coupling (Alg. 2, forward loop): from the shared weight W
+ * (fp32 [out][in]) and the scales g (fp16 [K][out]), h (fp16 [K][in]) derive
+ *   R_0 = W;  B_i = sign(R_{i-1}) (sign(0) = +1);  R_i = R_{i-1} - g_i (.) B_i (.) h_i
+ * for i = 1..K.  The residual is fp32 with one rounding for g_i[r] * h_i[c] and
+ * one for the subtraction, so the stored bits are defined exactly.
+ * packed:   canonical words, uint32 [K][out][in/32], or NULL.
+ * native:   kernel-native tiles (rb_native_bytes(K, out, in) bytes, padding
+ *           written as +1), or NULL.  At least one of the two.
+ * residual: R_K, fp32 [out][in], or NULL.
+ */
+int rb_couple(const float *W, const uint16_t *g, const uint16_t *h, int K, int out, int in,
+              uint32_t *packed, void *native, float *residual, void *stream);
+
+/*
+ * Effective-weight gradient (Eq. RaBiT-grad-wfp), the straight-through gradient
+ * of the shared weight: G = (dL/dY) X^T.  Delta fp16 [N][out], X fp16 [N][in],
+ * G fp32 [out][in]; fp32 accumulation over the samples in order.  A plain
+ * kernel (one thread per element): for large N a dense GEMM library is faster
+ * and G may come from there.  out <= 65535.
+ */
+int rb_weight_grad(const uint16_t *Delta, const uint16_t *X, int N, int out, int in, float *G, void *stream);
+
+/*
+ * Gradients of the scales (Eq. RaBiT-grad-gh), binary cores held constant,
+ * summed over the samples:
+ *   grad_g[i][r] = sum_c B_i[r][c] h_i[c] G[r][c]
+ *   grad_h[i][c] = sum_r B_i[r][c] g_i[r] G[r][c]    (the transposed binary product)
+ * with G from rb_weight_grad (or any fp32 [out][in] = Delta^T X).  packed:
+ * canonical words as rb_couple writes them.  grad_g fp32 [K][out], grad_h fp32
+ * [K][in].  workspace: rb_scale_grads_workspace_bytes(K, out, in) bytes, 16-byte
+ * aligned (partial column sums; their order is fixed, results repeat bit for bit).
+ */
+size_t rb_scale_grads_workspace_bytes(int K, int out, int in);
+int rb_scale_grads(const float *G, const uint32_t *packed, const uint16_t *g, const uint16_t *h,
+                   int K, int out, int in, float *grad_g, float *grad_h,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * Measurement aids (not part of the layer): the comparators the benchmark
  * reports next to the binary path on the same GPU.
  * ------------------------------------------------------------------------ */

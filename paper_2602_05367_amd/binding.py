@@ -30,6 +30,7 @@ EXPORTS = [
     "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status", "rb_stack_waited",
     "rb_stack_set_option",
     "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
+    "rb_couple", "rb_weight_grad", "rb_scale_grads", "rb_scale_grads_workspace_bytes",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -76,13 +77,19 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_waited.argtypes = [p, p, ctypes.POINTER(ctypes.c_ulonglong)]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
+    lib.rb_couple.argtypes = [p, p, p, i, i, i, p, p, p, p]
+    lib.rb_weight_grad.argtypes = [p, p, i, i, i, p, p]
+    lib.rb_scale_grads_workspace_bytes.argtypes = [i, i, i]
+    lib.rb_scale_grads_workspace_bytes.restype = z
+    lib.rb_scale_grads.argtypes = [p, p, p, p, i, i, i, p, p, p, z, p]
     lib.rb_dense_gemv_f16.argtypes = [p, p, p, i, i, p]
     lib.rb_stream_read.argtypes = [p, z, p, p]
     lib.rb_stream_read_groups.argtypes = []
     lib.rb_version.argtypes = []
     lib.rb_last_path.argtypes = []
     for name in EXPORTS:
-        if name not in ("rb_native_bytes", "rb_workspace_bytes", "rb_noalloc_scratch_bytes"):
+        if name not in ("rb_native_bytes", "rb_workspace_bytes", "rb_noalloc_scratch_bytes",
+                        "rb_scale_grads_workspace_bytes"):
             getattr(lib, name).restype = i
     return lib
 
@@ -306,6 +313,49 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
 
 RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM, RB_PATH_BATCH = 0, 1, 2, 3, 4
 RB_OPT_HANDOVER_PAUSE = 1
+
+
+# -------------------------------------------------------------- training ---
+def rb_couple(W: torch.Tensor, g: torch.Tensor, h: torch.Tensor, want_native: bool = True,
+              want_residual: bool = False):
+    """Alg. 2 forward loop on the device: W fp32 [out][in], g fp16 [K][out], h fp16 [K][in] ->
+    (packed uint32 [K][out][in/32] as int32 tensor, native flat int32 tensor or None, residual or None)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    assert g.dtype == torch.float16 and h.dtype == torch.float16 and g.is_contiguous() and h.is_contiguous()
+    out, inn = W.shape
+    K = g.shape[0]
+    packed = torch.empty((K, out, inn // 32), dtype=torch.int32, device=W.device)
+    native = torch.empty(rb_native_bytes(K, out, inn) // 4, dtype=torch.int32, device=W.device) if want_native else None
+    residual = torch.empty_like(W) if want_residual else None
+    _check("rb_couple", lib.rb_couple(W.data_ptr(), g.data_ptr(), h.data_ptr(), K, out, inn, packed.data_ptr(),
+                                      native.data_ptr() if native is not None else None,
+                                      residual.data_ptr() if residual is not None else None, _stream()))
+    return packed, native, residual
+
+
+def rb_weight_grad(Delta: torch.Tensor, X: torch.Tensor) -> torch.Tensor:
+    """G = Delta^T X in fp32: Delta fp16 [N][out], X fp16 [N][in]."""
+    assert Delta.is_cuda and Delta.dtype == torch.float16 and X.dtype == torch.float16
+    assert Delta.is_contiguous() and X.is_contiguous() and Delta.shape[0] == X.shape[0]
+    N, out = Delta.shape
+    inn = X.shape[1]
+    G = torch.empty((out, inn), dtype=torch.float32, device=X.device)
+    _check("rb_weight_grad", lib.rb_weight_grad(Delta.data_ptr(), X.data_ptr(), N, out, inn, G.data_ptr(), _stream()))
+    return G
+
+
+def rb_scale_grads(G: torch.Tensor, packed: torch.Tensor, g: torch.Tensor, h: torch.Tensor):
+    """(grad_g fp32 [K][out], grad_h fp32 [K][in]) from G fp32 [out][in] and the canonical packed cores."""
+    assert G.is_cuda and G.dtype == torch.float32 and G.is_contiguous() and packed.is_contiguous()
+    out, inn = G.shape
+    K = g.shape[0]
+    n = int(lib.rb_scale_grads_workspace_bytes(K, out, inn))
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=G.device)
+    gg = torch.empty((K, out), dtype=torch.float32, device=G.device)
+    gh = torch.empty((K, inn), dtype=torch.float32, device=G.device)
+    _check("rb_scale_grads", lib.rb_scale_grads(G.data_ptr(), packed.data_ptr(), g.data_ptr(), h.data_ptr(), K, out, inn,
+                                                gg.data_ptr(), gh.data_ptr(), ws.data_ptr(), n, _stream()))
+    return gg, gh
 
 
 def rb_stack_set_option(option: int, value: int) -> None:
