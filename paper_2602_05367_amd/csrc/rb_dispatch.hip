@@ -64,6 +64,8 @@ static bool batch_supported(const rb_layer *layers, int n_layers, int T)
 
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
+    // one layer, one token: the single-call kernel keeps everything in LDS
+    if (n_layers == 1 && n_ops == 1 && T == 1 && gemv1::supported(&layers[0], 1)) return 0;
     if (batch_applies(layers, n_layers, T) && n_ops > 1) {
         size_t need = batch::plan_workspace_bytes(layers, n_layers, n_ops, T);
         // the ops of a stack the kernel turns down run one after the other on the general paths

@@ -2,7 +2,11 @@
 //
 // Section 4.1 / Eq. (stacked binary weight): Y[t][i] = sum_k g_k[i] * sum_j B_k[i][j] * (h_k[j] X[t][j]).
 // With T in the thousands this is a dense contraction and belongs on the MFMA units:
-//   * a pre-pass forms U_k = h_k (.) X once, in fp16 (input scaling, Section 4.1);
+//   * a pre-pass forms U_k = h_k (.) X once, in fp16 (input scaling, Section 4.1), times a power of
+//     two s_k per path that brings max|h_k| into [1/4, 1/2): how the magnitude of a path is split
+//     between g_k and h_k is not unique, and a layer that keeps it in g would otherwise push U into
+//     fp16 subnormals.  The left operand carries g_k * (s_min / s_k) (a power of two at most one:
+//     exact) and the result is multiplied by 1 / s_min;
 //   * the GEMM contracts over the pair (path, input column) with a single accumulator: the left
 //     operand element for row i is +-g_k[i] (an exact fp16 value: the stored scale with the sign
 //     bit of the weight), the right operand is U_k.  Both paths land in the same fp32 sum, so
@@ -32,6 +36,7 @@
 #include "rb_device.h"
 #include "rb_internal.h"
 #include "rb_layout.h"
+#include "rb_mx_device.h"
 
 namespace rb {
 namespace gemm {
@@ -61,10 +66,38 @@ __host__ __device__ inline int contraction_position(int col)
 }
 
 // ------------------------------------------------------------- pre-pass ---
-// U[k][t][j'] = fp16(h_k[j] * X[t][j]); rows t >= T and columns j >= in are zero.
+// Per call: the power-of-two input scaling of each path.  scl[k] = s_k, scl[2 + k] = s_min / s_k
+// (what the left operand's |g_k| is multiplied by), scl[4] = 1 / s_min.
+constexpr size_t SCALES_BYTES = 256;
+__global__ __launch_bounds__(256) void hscale_kernel(const __half *__restrict__ h, int in, float *__restrict__ scl)
+{
+    __shared__ float red[256];
+    __shared__ float sc[2];
+    for (int k = 0; k < 2; ++k) {
+        float m = 0.f;
+        for (int j = threadIdx.x; j < in; j += 256) m = fmaxf(m, fabsf(__half2float(h[(size_t)k * in + j])));
+        red[threadIdx.x] = m;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) sc[k] = mx::input_scale(red[0]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float s_min = fminf(sc[0], sc[1]);
+        scl[0] = sc[0]; scl[1] = sc[1];
+        scl[2] = s_min / sc[0]; scl[3] = s_min / sc[1];
+        scl[4] = 1.f / s_min;
+    }
+}
+
+// U[k][t][j'] = fp16(h_k[j] * s_k * X[t][j]); rows t >= T and columns j >= in are zero.
 template <typename ActT>
 __global__ __launch_bounds__(256) void scale_kernel(const ActT *__restrict__ X, const __half *__restrict__ h,
-                                                    _Float16 *__restrict__ U, int T, int T_pad, int in, int in_pad)
+                                                    const float *__restrict__ scl, _Float16 *__restrict__ U, int T,
+                                                    int T_pad, int in, int in_pad)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int t = blockIdx.y;
@@ -75,14 +108,15 @@ __global__ __launch_bounds__(256) void scale_kernel(const ActT *__restrict__ X, 
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const float hv = live ? __half2float(h[(size_t)k * in + j]) : 0.f;
-        U[((size_t)k * T_pad + t) * in_pad + jp] = (_Float16)(hv * x);
+        U[((size_t)k * T_pad + t) * in_pad + jp] = (_Float16)(hv * scl[k] * x);
     }
 }
 
 // split-contraction: sums the partial outputs of the `split` workgroups that share an output tile
 // and rounds to the output type.  part is [split][T][rows] for rows row0 .. row0 + rows - 1 of Y.
-__global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ part, void *__restrict__ Y, int out_dtype,
-                                                     int T, int out, int row0, int rows, int split)
+__global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ part, const float *__restrict__ scl,
+                                                     void *__restrict__ Y, int out_dtype, int T, int out, int row0,
+                                                     int rows, int split)
 {
     const size_t n = (size_t)T * rows;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -90,7 +124,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ p
     float s = 0.f;
     for (int k = 0; k < split; ++k) s += part[(size_t)k * n + i];
     const size_t t = i / rows, r = i % rows;
-    store_out(Y, out_dtype, t * out + row0 + r, s);
+    store_out(Y, out_dtype, t * out + row0 + r, s * scl[4]);
 }
 
 // ----------------------------------------------------------------- GEMM ---
@@ -115,8 +149,9 @@ __device__ __forceinline__ void wait_copies_and_sync()
 // of storing the output; finish_kernel adds the slices.
 template <int OUT_DT, int WM, int WN, int MP, int NT, int AHEAD>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bits, const __half *__restrict__ g,
-                                                      const _Float16 *__restrict__ U, void *__restrict__ Y,
-                                                      float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad,
+                                                      const float *__restrict__ scl, const _Float16 *__restrict__ U,
+                                                      void *__restrict__ Y, float *__restrict__ Acc, int out, int RT,
+                                                      int CT, int T, int T_pad,
                                                       int full_tiles, int tail_split, int tail_row0, int tail_rows)
 {
     static_assert(WM * WN == 4 && WM * MP * 32 == BLK_ROWS, "tile shape");
@@ -167,8 +202,9 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
         const int row = (rt_base + 2 * m + half_sel) * TILE_ROWS + r;
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-            const uint32_t gb = row < out ? (uint32_t)__half_as_ushort(g[(size_t)k * out + row]) : 0u;
-            const uint32_t mag = gb & 0x7fffu;
+            // |g| times s_min / s_k: a power of two at most one, exact short of fp16 underflow
+            const float gv = row < out ? fabsf(__half2float(g[(size_t)k * out + row])) * scl[2 + k] : 0.f;
+            const uint32_t mag = (uint32_t)__half_as_ushort(__float2half_rn(gv));
             G2[m][k] = mag | (mag << 16);
         }
     }
@@ -349,6 +385,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
     // none of the address arithmetic below is computed ahead of the main loop, where registers
     // are scarce.)
     asm volatile("" : "+s"(out));
+    const float inv_s = scl[4];
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
         const int t = tb * BLK_TOK + (wn * NT + n) * 32 + (lane & 31);
@@ -364,7 +401,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
                     if (partial)
                         Acc[((size_t)slice * T + t) * tail_rows + (row0 + e - tail_row0)] = acc[m][n][4 * a4 + e];
                     else
-                        store_out(Y, OUT_DT, (size_t)t * out + row0 + e, acc[m][n][4 * a4 + e]);
+                        store_out(Y, OUT_DT, (size_t)t * out + row0 + e, acc[m][n][4 * a4 + e] * inv_s);
                 }
             }
         }
@@ -423,7 +460,7 @@ static Plan make_plan(const rb_layer *L, int T)
 size_t workspace_bytes(const rb_layer *L, int T)
 {
     const Plan p = make_plan(L, T);
-    return p.u_bytes + p.acc_bytes;
+    return SCALES_BYTES + p.u_bytes + p.acc_bytes;
 }
 
 bool supported(const rb_layer *L, int T)
@@ -435,15 +472,17 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
            hipStream_t stream)
 {
     const Plan p = make_plan(L, T);
-    _Float16 *U = static_cast<_Float16 *>(workspace);
-    float *Acc = p.acc_bytes > 0 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + p.u_bytes) : nullptr;
+    float *scl = static_cast<float *>(workspace);
+    _Float16 *U = reinterpret_cast<_Float16 *>(static_cast<uint8_t *>(workspace) + SCALES_BYTES);
+    float *Acc = p.acc_bytes > 0 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + SCALES_BYTES + p.u_bytes) : nullptr;
     const __half *h = reinterpret_cast<const __half *>(L->h);
+    hipLaunchKernelGGL(hscale_kernel, dim3(1), dim3(256), 0, stream, h, L->in, scl);
     const dim3 sgrid(p.in_pad / 256, p.T_pad);
     if (act_dtype == RB_F16)
-        hipLaunchKernelGGL(scale_kernel<__half>, sgrid, dim3(256), 0, stream, static_cast<const __half *>(X), h, U,
+        hipLaunchKernelGGL(scale_kernel<__half>, sgrid, dim3(256), 0, stream, static_cast<const __half *>(X), h, scl, U,
                            T, p.T_pad, L->in, p.in_pad);
     else
-        hipLaunchKernelGGL(scale_kernel<bf16_t>, sgrid, dim3(256), 0, stream, static_cast<const bf16_t *>(X), h, U,
+        hipLaunchKernelGGL(scale_kernel<bf16_t>, sgrid, dim3(256), 0, stream, static_cast<const bf16_t *>(X), h, scl, U,
                            T, p.T_pad, L->in, p.in_pad);
     const v4u *bits = static_cast<const v4u *>(L->bits);
     const __half *g = reinterpret_cast<const __half *>(L->g);
@@ -452,12 +491,12 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
     const size_t lds = p.small ? (size_t)(AHEAD_SMALL + 1) * SMALL_TOKENS * 64 : (size_t)(AHEAD_LARGE + 1) * LARGE_TOKENS * 64;
 #define RB_GEMM(DT, WM, WN, MP, NT)                                                                              \
     hipLaunchKernelGGL((gemm_kernel<DT, WM, WN, MP, NT, (NT == 1 ? AHEAD_SMALL : AHEAD_LARGE)>), grid, dim3(256), lds, \
-                       stream, bits, g, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad, p.full_tiles, p.tail_split, p.tail_row0, \
+                       stream, bits, g, scl, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad, p.full_tiles, p.tail_split, p.tail_row0, \
                        p.tail_rows)
     if (p.small && p.split > 1) {
         RB_GEMM(RB_F32, 4, 1, 2, 1);
         const size_t n = (size_t)T * L->out;
-        hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype, T,
+        hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype, T,
                            L->out, 0, L->out, p.split);
     } else if (p.small) {
         if (out_dtype == RB_F16) RB_GEMM(RB_F16, 4, 1, 2, 1);
@@ -469,7 +508,7 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
         else RB_GEMM(RB_F32, 2, 2, 4, 4);
         if (p.tail_split > 1) {
             const size_t n = (size_t)T * p.tail_rows;
-            hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, Y, out_dtype,
+            hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype,
                                T, L->out, p.tail_row0, p.tail_rows, p.tail_split);
         }
     }

@@ -141,17 +141,18 @@ def test_batch_kernel_with_degenerate_scales_and_extreme_inputs():
     _check_stack([l1, l2], [(0, 0, 1), (1, 1, 2)], (d0, d1, d2), x, T, "edge cases", True)
 
 
-@pytest.mark.parametrize("T", [8, 16])
-def test_full_width_7b_block_on_the_batch_kernel(T):
+@pytest.mark.parametrize("T,K", [(8, 2), (16, 2), (1, 3), (8, 3)])
+def test_full_width_7b_block_on_the_batch_kernel(T, K):
     """One block of the 7B shape exactly as bench.py builds it (signs drawn on the device), at the
-    widths and launch shapes that are timed: sampled rows of every op against the oracle."""
+    widths and launch shapes that are timed, two and three paths: sampled rows of every op
+    against the oracle."""
     import bench
-    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T)
+    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T, K=K)
     ops, layers, op_list = ops[:7], layers[:7], op_list[:7]
     bufs[0].copy_(torch.from_numpy(synth.outlier_activations(synth.child_rng(3, 505, T), T, ops[0].inn)))
     stack = rb.Stack(layers, op_list, bufs, T)
     stack.prepare()
-    print(f"full-width 7B block on the batch kernel, T={T}", flush=True)
+    print(f"full-width 7B block on the batch kernel, T={T}, K={K}", flush=True)
     stack.run_prepared()
     torch.cuda.synchronize()
     assert rb.rb_last_path() == rb.RB_PATH_BATCH and stack.status() == rb.RB_OK
@@ -163,7 +164,7 @@ def test_full_width_7b_block_on_the_batch_kernel(T):
         y = bufs[op.dst].cpu().numpy().astype(np.float64)
         assert np.all(np.isfinite(y)) and np.any(y != 0), op.name
         native = L.bits.cpu().numpy().view(np.uint32)
-        packed = rb.rb_unpack_native(native, 2, L.out, L.inn)
+        packed = rb.rb_unpack_native(native, K, L.out, L.inn)
         rows = np.unique(np.concatenate([pick.integers(0, L.out, size=40), [0, L.out - 1]]))
         S = rb.rb_unpack(packed[:, rows, :])
         ref = oracle.forward(S, L.g.cpu().numpy()[:, rows], L.h.cpu().numpy(), bufs[op.src].cpu().numpy())

@@ -62,6 +62,25 @@ def test_gemm_negative_and_zero_scales():
     assert max_rel_l2(Y, oracle.forward(signs, g, h, X)) <= TOL
 
 
+@pytest.mark.parametrize("T", [16, 70])
+def test_gemm_when_the_magnitude_sits_in_g(T):
+    """Section 4.1 leaves the split of a path's magnitude between g and h open.  With h around 3e-5
+    and g around 10 the products h x are fp16 subnormals unless the kernel scales each path's h by
+    a power of two first (and takes it back out of g); path 2 gets another factor 1/8 on h."""
+    out, inn = 272, 1056
+    rng = synth.child_rng(5, 109, T)
+    signs, g, h = random_layer(rng, 2, out, inn)
+    g = (g.astype(np.float64) * 500.0 * np.array([1.0, 8.0])[:, None]).astype(np.float16)
+    h = (h.astype(np.float64) * 2.0e-3 * np.array([1.0, 1.0 / 8.0])[:, None]).astype(np.float16)
+    assert np.all(np.isfinite(g.astype(np.float64))) and np.count_nonzero(h) > 0.9 * h.size
+    X = synth.outlier_activations(rng, T, inn)
+    L = to_device_layer(signs, g, h)
+    Y = rb.rb_linear_gemm(L, torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_GEMM
+    assert max_rel_l2(Y, oracle.forward(signs, g, h, X)) <= TOL
+
+
 def test_gemm_rows_equal_single_token_calls():
     out, inn, T = 320, 1536, 70
     rng = synth.child_rng(5, 102)
