@@ -281,15 +281,15 @@ def main() -> int:
                                          "tiles_waited_per_pass": stack2.waited() / 35.0}
         stack2.forget()
         del ops2, layers2, bufs2, stack2
-        # three paths (the paper's 3-bit variant), the whole 7B-shaped chain: the small-batch kernel
-        # (one launch per group of independent ops) at one token and at eight
+        # three paths (the paper's 3-bit variant), the whole 7B-shaped chain: one token on the fused
+        # decode kernel (one launch), eight on the small-batch kernel (one launch per group of independent ops)
         three = {}
         for T3 in (1, 8):
             ops3, layers3, bufs3, op_list3, packed3 = build_stack(rb, synth, torch, "7b", T3, K=3)
             stack3 = rb.Stack(layers3, op_list3, bufs3, T3)
             stack3.prepare()
             _, per3 = time_steps(torch, stack3.run_prepared, 20, 3)
-            assert rb.rb_last_path() == rb.RB_PATH_BATCH and stack3.status() == rb.RB_OK
+            assert rb.rb_last_path() == (rb.RB_PATH_MX if T3 == 1 else rb.RB_PATH_BATCH) and stack3.status() == rb.RB_OK
             ms3 = sum(per3) / len(per3)
             three[f"T{T3}"] = {"ms_per_pass": ms3, "tokens_per_s": T3 / (ms3 * 1e-3), "packed_bytes": packed3,
                                "GBps": packed3 / (ms3 * 1e-3) / 1e9,

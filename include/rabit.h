@@ -43,8 +43,10 @@ extern "C" {
 #define RB_ERR_VALUE       -7   /* rb_pack: an entry is neither +1 nor -1             */
 #define RB_ERR_HANDOVER    -8   /* rb_stack_status: a run gave up waiting for another compute unit */
 
-/* K = 2 is the 2-bit layer every kernel here is built for; K = 1 and K = 3 (the 3-bit variant of
- * the paper's packing appendix) run on the generic sign-XOR + add kernel. */
+/* K = 2 is the 2-bit layer every kernel here is built for.  K = 3 (the 3-bit variant of the
+ * paper's packing appendix): stacks run on the matrix cores (one token on the fused decode kernel,
+ * 2..16 tokens on the small-batch kernel), single calls on the generic sign-XOR + add kernel,
+ * which also runs K = 1. */
 #define RB_MAX_K 3
 
 /* element types for rb_linear_gemm */
@@ -155,10 +157,14 @@ int rb_layer_stack(const rb_layer *layers, int n_layers,
  * between runs the caller must not write to the workspace nor change layers,
  * buffers addresses or T; rb_stack_forget drops the library's host-side record
  * of a workspace (call it before the memory is reused for something else).
- * T <= 2 runs as one launch; 3 <= T <= 16 as one launch per pair of consecutive
- * tokens (every layer's out a multiple of 8, at least two ops).
+ * Two paths: T <= 2 runs as one launch; 3 <= T <= 7 as one launch per pair of
+ * consecutive tokens (every layer's out a multiple of 8, at least two ops);
+ * 8 <= T <= 16 on the small-batch kernel (one pass over the weights for all
+ * tokens, one launch per group of independent ops).  Three paths in every
+ * layer: T = 1 as one launch, 2 <= T <= 16 on the small-batch kernel, which
+ * also takes stacks that mix two- and three-path layers.
  * rb_stack_prepare returns RB_ERR_UNSUPPORTED for stacks that only
- * rb_layer_stack's general path can run (K != 2, T > 16, an output read by more
+ * rb_layer_stack's general path can run (K = 1, T > 16, an output read by more
  * than three ops, more than 1024 ops fed from outside the stack).
  */
 int rb_stack_prepare(const rb_layer *layers, int n_layers,

@@ -47,12 +47,14 @@ static bool pairs_apply(const rb_layer *layers, int n_layers, int n_ops, int T)
 constexpr int BATCH_MIN_T = 8;
 bool batch_applies(const rb_layer *layers, int n_layers, int T)
 {
-    bool three = false;
+    bool any_three = false, all_three = true;
     for (int l = 0; l < n_layers; ++l) {
         if (!batch::layer_supported(&layers[l], T)) return false;
-        three = three || layers[l].K == 3;
+        any_three = any_three || layers[l].K == 3;
+        all_three = all_three && layers[l].K == 3;
     }
-    return three || T >= BATCH_MIN_T;
+    if (all_three && T == 1) return false;       // one token, three paths throughout: the fused decode kernel
+    return any_three || T >= BATCH_MIN_T;
 }
 
 static bool batch_supported(const rb_layer *layers, int n_layers, int T)
@@ -181,7 +183,7 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
         g_last_path = RB_PATH_MX;
         return gemv1::launch(L, X, Y, stream);
     }
-    if (act_dtype == RB_F16 && out_dtype == RB_F16 && mx::layer_supported(L, T) && workspace &&
+    if (act_dtype == RB_F16 && out_dtype == RB_F16 && L->K == 2 && mx::layer_supported(L, T) && workspace &&
         workspace_bytes >= mx::plan_workspace_bytes(L, 1, 1, T)) {
         const rb_stack_op op{0, 0, 1};
         uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};

@@ -37,21 +37,28 @@ constexpr int RING_D = 6;           // sign tiles requested ahead per compute wa
 constexpr int nb_of(int T) { return T == 1 ? 2 : 2; }
 // vector-memory loads per step: operand loads (16 bytes per lane each) and one sign tile
 constexpr int kop_of(int T) { return T == 1 ? 2 : 4; }
+// copies that bring in one sign tile (1 KB each; a three-path tile is 1.5 KB)
+constexpr int sign_loads_of(int K) { return K == 3 ? 2 : 1; }
 // Loads complete in order.  The operand of a tile is requested nb steps before its use, the sign
 // tile RING_D > nb steps before; when at most this many loads are outstanding both have arrived.
-constexpr int wait_of(int T) { return (nb_of(T) - 1) * (kop_of(T) + 1) + 1; }
+constexpr int wait_of(int T, int K) { return (nb_of(T) - 1) * (kop_of(T) + sign_loads_of(K)) + sign_loads_of(K); }
 constexpr int MAXSLOT = 8;         // (op, row tile) pairs one CU finishes per stage
 constexpr int MAX_CONS = 3;        // ops that read one op's output inside a fused stack
 constexpr int MAX_T = 2;           // tokens per call on this path
 constexpr int MAX_OPS = 4096;      // ops per launch
 constexpr size_t MAX_EXPAND = 1024;
-static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1) <= 63 && wait_of(2) <= 63,
+static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1, 2) <= 63 && wait_of(2, 2) <= 63 && wait_of(2, 3) <= 63,
               "the in-order wait counts on this");
+// Three paths, one token, ride on the two-token machinery: the 16 operand columns are 8 * token +
+// 4 * path + term for two paths; a three-path op puts its paths 0 and 1 where token 0 has them and
+// its path 2 where token 1 has path 0 (columns 8..11); columns 12..15 are zero.  LAYOUT_T is the
+// token count of the operand layout, not of the activations.
+constexpr int layout_tokens(int T, int K) { return K == 3 ? 2 : T; }
 
 // LDS map of the stack kernel with CW compute wavefronts
 constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
-template <int CW> struct LdsMap {
-    static constexpr int RING_BYTES = CW * RING_D * 1024;
+template <int CW, int K = 2> struct LdsMap {
+    static constexpr int RING_BYTES = CW * RING_D * 512 * K;
     // partial sums: [parity][slot][compute wavefront][path][token][row] fp32
     static constexpr int PART_SLOT_BYTES = CW * 2 * 2 * 16 * 4;
     static constexpr int PART_BYTES = 2 * MAXSLOT * PART_SLOT_BYTES;
@@ -93,15 +100,15 @@ struct Op {
     const uint16_t *x;        // fp16 [T][in]  input buffer (read by the expansion kernel only)
     uint16_t *y;              // fp16 [T][out] output buffer
     uint8_t *up;              // expanded input of this op (see up_group_offset)
-    int out, in;
+    int out, in, K;
     int RT, CT;               // row tiles (16 rows), column tiles (256 columns)
     int n_cons;               // ops that read y inside this call
     int cons[MAX_CONS];
     int expand_x;             // 1: x comes from outside the fused ops and must be expanded first
     int dep;                  // op of this launch that writes x (-1: none)
     int stage_op0;            // first op of the stage this op belongs to
-    float sc[2];              // power-of-two input scale per path (max |h| * sc <= 1/2)
-    float inv_sc[2];
+    float sc[RB_MAX_K];       // power-of-two input scale per path (max |h| * sc <= 1/2)
+    float inv_sc[RB_MAX_K];
 };
 
 // What a compute wavefront does, step by step (one step = one 1 KB sign tile), written out once per
@@ -140,11 +147,12 @@ struct SlotRec {
 };
 static_assert(sizeof(SlotRec) == 64, "four 16-byte loads");
 // per row of the slot: g_1 / sc_1, g_2 / sc_2 of the op (its output scales over the input scaling
-// it was fed with), then h_k * sc_k of each reading op (its input scales times its input scaling)
+// it was fed with), then h_k * sc_k (k = 1, 2) of each reading op (its input scales times its input
+// scaling); for three paths g_3 / sc_3 and the readers' h_3 * sc_3 follow
 struct SlotVals {
-    float v[16][2 + 2 * MAX_CONS];
+    float v[16][12];
 };
-static_assert(sizeof(SlotVals) == 512, "32 bytes per row");
+static_assert(sizeof(SlotVals) == 768 && 12 >= 3 + 3 * MAX_CONS, "48 bytes per row");
 
 struct Stage {
     int op0, nops;            // ops [op0, op0 + nops) are independent of each other
@@ -156,7 +164,9 @@ struct Stage {
 constexpr int WAITED_LDS_OFF = 240;   // lanes that waited for a tile not yet written
 
 struct Header {
-    int n_ops, n_stages, T, n_groups;
+    int n_ops, n_stages, T, n_groups;     // T: tokens of the operand layout (layout_tokens)
+    int K, tokens;                        // paths; tokens of the activations
+    int pad_[2];
 };
 
 // workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     const int o = blockIdx.x;
     Op &op = ops[o];
     __shared__ float red[256];
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < op.K; ++p) {
         float m = 0.f;
         for (int j = threadIdx.x; j < op.in; j += 256)
             m = fmaxf(m, fabsf(__half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j])));
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (size_t i = threadIdx.x; i < n16; i += 256) up[i] = make_uint4(0, 0, 0, 0);
     if (o == 0) {
-        zero_page[threadIdx.x] = 0;                       // 1 KB: what a padding step of the sign stream reads
+        zero_page[threadIdx.x] = 0;                       // 2 KB: what a padding step of the sign stream reads (up to 1.5 KB)
+        zero_page[256 + threadIdx.x] = 0;
         if (threadIdx.x < 2) error[threadIdx.x] = 0;      // the give-up mark and the count of tiles waited for
     }
 }
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             const uint32_t U = nrt * CT, u0 = run * U / CW, u1 = (run + 1) * U / CW;
             for (uint32_t u = u0 + lane; u < u1; u += 64) {
                 const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
-                put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * 1024);
+                put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * (size_t)(512 * hdr->K));
                 put_opnd(go + (u - u0), (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
                          STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) |
                              ((slot * CW + run) << STEP_PART_SHIFT) |
@@ -212,8 +213,8 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     sr.y = 0; sr.pad64_ = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
     sr.behind = most - mine;
     for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
-    float v[2 + 2 * MAX_CONS];
-    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) v[i] = 0.f;
+    float v[12];
+    for (int i = 0; i < 12; ++i) v[i] = 0.f;
     if (my_op >= 0) {
         const Op &op = ops[my_op];
         const int grow = row0 + row;
@@ -224,6 +225,7 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
         if (valid) {
             v[0] = __half2float(g[grow]) * op.inv_sc[0];
             v[1] = __half2float(g[(size_t)op.out + grow]) * op.inv_sc[1];
+            if (op.K == 3) v[8] = __half2float(g[2 * (size_t)op.out + grow]) * op.inv_sc[2];
         }
         for (int c = 0; c < op.n_cons; ++c) {
             const Op &m = ops[op.cons[c]];
@@ -232,10 +234,11 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
             if (valid) {
                 v[2 + 2 * c] = __half2float(h[grow]) * m.sc[0];
                 v[3 + 2 * c] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
+                if (m.K == 3) v[9 + c] = __half2float(h[2 * (size_t)m.in + grow]) * m.sc[2];
             }
         }
     }
-    for (int i = 0; i < 2 + 2 * MAX_CONS; ++i) vals[idx].v[row][i] = v[i];
+    for (int i = 0; i < 12; ++i) vals[idx].v[row][i] = v[i];
     if (row == 0) slots[idx] = sr;
 }
 
@@ -250,12 +253,13 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
     if (j >= op.in) return;
     const int T = hdr->T;
     const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < op.K; ++p) {
         const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
         const uint32_t terms = expand4(h * x * op.sc[p]);
+        // where path p of this token sits in the layout: three paths use token 1's path 0 for path 2
+        const int ltok = op.K == 3 ? p >> 1 : tok, lp = op.K == 3 ? p & 1 : p;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) op.up[up_offset(T, tok, p, t, j)] = (uint8_t)(terms >> (8 * t));
+        for (int t = 0; t < 4; ++t) op.up[up_offset(T, ltok, lp, t, j)] = (uint8_t)(terms >> (8 * t));
     }
 }
 
@@ -300,7 +304,8 @@ template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile:
 // What a producer stores carries its own validity (a 16-byte group of an expanded input is all 0xff
 // until it is written), so a producer neither waits for its stores to be acknowledged nor raises a
 // flag, and nobody polls memory for flags.
-template <int TT>
+// KK = 3 (with TT = 2, the layout; one token of activations): see layout_tokens in rb_mx.h.
+template <int TT, int KK = 2>
 __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
@@ -312,8 +317,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const SlotRec *__restrict__ slots_g,
                                                            const SlotVals *__restrict__ vals_g, int go_pause)
 {
+    static_assert(KK == 2 || (KK == 3 && TT == 2), "three paths use the two-token layout");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
-    using Lds = LdsMap<CW>;
+    constexpr int TILE_BYTES = 512 * KK, SL = sign_loads_of(KK);
+    using Lds = LdsMap<CW, KK>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     float *part = reinterpret_cast<float *>(lds + Lds::PART_OFF);
 
@@ -330,8 +337,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 
     if (wave < CW) {
         // ======================= compute wavefront ==========================
-        uint8_t *const ring = lds + Lds::RING_OFF + wave * (RING_D * 1024);
-        uint8_t *const ring_end = ring + RING_D * 1024;
+        uint8_t *const ring = lds + Lds::RING_OFF + wave * (RING_D * TILE_BYTES);
+        uint8_t *const ring_end = ring + RING_D * TILE_BYTES;
         const int col = lane & 15, qd = lane >> 4;
         const int scale_b = term_scale(col);
         const uint32_t lane_off = (uint32_t)lane * 16u;
@@ -431,7 +438,14 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             // non-temporal: every sign tile is read once (measured: the stream is ~13% faster)
             const uint64_t addr = next_sign();
             __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint8_t *>(addr) + lane * 16, RB_LDS(a_slot), 16, 0, 2);
-            a_slot += 1024;
+            if constexpr (KK == 3) {
+                // the last 512 bytes of a 1.5 KB tile: the first 32 lanes (an LDS copy lands at
+                // base + 16 * lane whichever lanes take part)
+                if (lane < 32)
+                    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint8_t *>(addr) + 1024 + lane * 16,
+                                                     RB_LDS(a_slot + 1024), 16, 0, 2);
+            }
+            a_slot += TILE_BYTES;
             if (a_slot == ring_end) a_slot = ring;
         };
 
@@ -528,7 +542,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 load_operand(dst, rsrc);
             };
 
-            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};
             const int parity = st & 1;
             // a quad of lanes holds the four terms of (path = quad & 1, token = quad >> 1); its
             // first lane writes rows 4*qd .. 4*qd+3 of that path and token
@@ -538,8 +552,12 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             auto flush = [&](uint32_t part_index) {       // slot * CW + run: 256 bytes each
                 v4f v;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)       // the four lanes of a quad hold terms of the same path
-                    v[r] = quad_sum((quad & 1) ? acc1[r] : acc0[r]);
+                for (int r = 0; r < 4; ++r) {     // the four lanes of a quad hold terms of the same path
+                    // two paths: quad = 2 * token + path.  Three paths: quads 0, 1, 2 are paths 0, 1, 2;
+                    // quad 3 takes path 1's signs times columns that are zero
+                    const float mine = (quad & 1) ? acc1[r] : (KK == 3 && quad == 2) ? acc2[r] : acc0[r];
+                    v[r] = quad_sum(mine);
+                }
                 if ((col & 3) == 0)
                     asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                  :
@@ -547,10 +565,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                  : "memory");
                 acc0 = (v4f){0, 0, 0, 0};
                 acc1 = (v4f){0, 0, 0, 0};
+                acc2 = (v4f){0, 0, 0, 0};
             };
 
 #pragma unroll
-            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], opnd_lo[i], opnd_hi[i]); issue_dummies(1); }
+            for (int i = 0; i < NB; ++i) { issue_b(B[i], meta[i], opnd_lo[i], opnd_hi[i]); issue_dummies(SL); }
 
             bool more = true;
             while (more) {
@@ -558,16 +577,31 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 for (int s = 0; s < NB; ++s) {
                     const uint32_t m = meta[s];
                     if (!(m & STEP_VALID)) { more = false; break; }
-                    // Every step issues exactly KOP + 1 vector-memory loads (the operand loads, one
-                    // sign tile or its stand-in) and loads complete in order.  The operand of this
+                    // Every step issues exactly KOP + SL vector-memory loads (the operand loads, the
+                    // copies of one sign tile or their stand-ins) and loads complete in order.  The operand of this
                     // tile was requested NB steps ago, followed by wait_of(T) younger loads; the
                     // sign tile is older still (RING_D > NB).  So "at most wait_of(T) outstanding"
                     // means both have arrived.
                     v4u w;
-                    asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                 : "=v"(w)
-                                 : "v"(lds_addr(c_slot_ptr) + lane * 16), "n"(wait_of(TT))
-                                 : "memory");
+                    uint2 w2 = make_uint2(0u, 0u);                // three paths: words 4 and 5 of the lane's six
+                    if constexpr (KK == 2) {
+                        asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(w)
+                                     : "v"(lds_addr(c_slot_ptr) + lane * 16), "n"(wait_of(TT, KK))
+                                     : "memory");
+                    } else {
+                        // 24 bytes per lane, 8-byte aligned
+                        uint2 wa, wb;
+                        asm volatile("s_waitcnt vmcnt(%4)\n\t"
+                                     "ds_read_b64 %0, %3\n\t"
+                                     "ds_read_b64 %1, %3 offset:8\n\t"
+                                     "ds_read_b64 %2, %3 offset:16\n\t"
+                                     "s_waitcnt lgkmcnt(0)"
+                                     : "=&v"(wa), "=&v"(wb), "=&v"(w2)
+                                     : "v"(lds_addr(c_slot_ptr) + lane * 24), "n"(wait_of(TT, KK))
+                                     : "memory");
+                        w = (v4u){wa.x, wa.y, wb.x, wb.y};
+                    }
 #pragma unroll
                     for (int r = 0; r < KOP; ++r) asm volatile("" : "+v"(B[s].r[r]));
                     // Each lane holds one 16-byte group per load.  No byte of a written group is 0xff,
@@ -681,7 +715,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                             if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
-                    c_slot_ptr += 1024;
+                    c_slot_ptr += TILE_BYTES;
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
                     const BTile<TT> bt = B[s];
                     v8i b0, b1;
@@ -703,10 +737,21 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                             b1[i] = bt.r[2 % KOP][i]; b1[4 + i] = bt.r[3 % KOP][i];
                         }
                     }
-                    acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
-                    acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
-                    acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
-                    acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
+                    if constexpr (KK == 2) {
+                        // lane words: (columns 0..127: path 0, path 1), (columns 128..255: path 0, path 1)
+                        acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
+                        acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
+                        acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
+                        acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
+                    } else {
+                        // (columns 0..127: paths 0, 1, 2), (columns 128..255: paths 0, 1, 2)
+                        acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
+                        acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
+                        acc2 = mfma_signs(w.z, b0, acc2, c22, scale_b);
+                        acc0 = mfma_signs(w.w, b1, acc0, c22, scale_b);
+                        acc1 = mfma_signs(w2.x, b1, acc1, c22, scale_b);
+                        acc2 = mfma_signs(w2.y, b1, acc2, c22, scale_b);
+                    }
                     if (m & STEP_FLUSH) flush((m >> STEP_PART_SHIFT) & 0xffu);
                     ++steps_done;
                     issue_b(B[s], meta[s], opnd_lo[s], opnd_hi[s]);
@@ -734,7 +779,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         // compiler can wait for exactly these and not for younger ones.
         struct Fin {
             SlotRec r;
-            v4f a, b;                       // the row's eight values
+            v4f a, b, c;                    // the row's values (c: the third path's, when there is one)
         };
         auto fetch = [&](int st) -> Fin {
             const size_t idx = ((size_t)min(st, n_stages - 1) * G + grp) * MAXSLOT + my_slot;
@@ -743,6 +788,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             const v4f *pv = reinterpret_cast<const v4f *>(&vals_g[idx].v[row][0]);
             f.a = pv[0];
             f.b = pv[1];
+            if constexpr (KK == 3) f.c = pv[2];
+            else f.c = (v4f){0.f, 0.f, 0.f, 0.f};
             if (st >= n_stages) f.r.op = -1;
             return f;
         };
@@ -765,7 +812,14 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             const int sub = tok;
             const bool active = have_slot && (SPLIT || tok < T) && grow < cur.r.out;
             const int n_cons = have_slot ? cur.r.n_cons : 0;
-            const float hs[MAX_CONS][2] = {{cur.a[2], cur.a[3]}, {cur.b[0], cur.b[1]}, {cur.b[2], cur.b[3]}};
+            // Three paths: the lane at a row's second-token position stands for path 2 (as that
+            // token's path 0, see layout_tokens): its output scale and its readers' input scales
+            // are the third path's, and its "path 1" is nothing.
+            const bool third = KK == 3 && tok == 1;
+            const float g_a = third ? cur.c[0] : cur.a[0], g_b = third ? 0.f : cur.a[1];
+            const float hs[MAX_CONS][2] = {{third ? cur.c[1] : cur.a[2], third ? 0.f : cur.a[3]},
+                                           {third ? cur.c[2] : cur.b[0], third ? 0.f : cur.b[1]},
+                                           {third ? cur.c[3] : cur.b[2], third ? 0.f : cur.b[3]}};
             // this lane's path of each reader's scales (selected value by value: an indexed array
             // would live in scratch memory)
             const float hsub[MAX_CONS] = {sub ? cur.a[3] : cur.a[2], sub ? cur.b[1] : cur.b[0], sub ? cur.b[3] : cur.b[2]};
@@ -789,8 +843,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         s1 += P[w * 64 + 32];
                     }
                 }
-                const _Float16 y16 = (_Float16)path_sum(cur.a[0], s0, cur.a[1], s1);   // round to nearest even
-                if (!SPLIT || sub == 0) RB_GLOBAL(_Float16, cur.r.y)[(size_t)(SPLIT ? 0 : tok) * cur.r.out + grow] = y16;
+                float ysum = path_sum(g_a, s0, g_b, s1);
+                if constexpr (KK == 3) ysum += __shfl_xor(ysum, 16);       // paths 0 and 1 in one lane of the row, path 2 in the other
+                const _Float16 y16 = (_Float16)ysum;                         // round to nearest even
+                if (KK == 3 ? tok == 0 : (!SPLIT || sub == 0))
+                    RB_GLOBAL(_Float16, cur.r.y)[(size_t)((SPLIT || KK == 3) ? 0 : tok) * cur.r.out + grow] = y16;
                 yf = (float)y16;
             }
             // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
@@ -899,7 +956,7 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, siz
     o = align_up(o, 128); L.ops = o; o += sizeof(Op) * (size_t)n_ops;
     o = align_up(o, 128); L.stages = o; o += sizeof(Stage) * (size_t)n_stages;
     o = align_up(o, 128); L.error = o; o += 128;
-    L.zero = o; o += 1024;
+    L.zero = o; o += 2048;
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
     o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * (size_t)cwaves;
     o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * (size_t)cwaves;
@@ -924,11 +981,14 @@ int device_groups()
 
 bool layer_supported(const rb_layer *L, int T)
 {
-    return L->K == 2 && T >= 1 && T <= MAX_T && L->in % 32 == 0 && L->in <= 65536;
+    // three paths: one token (its three paths take the place of two tokens' two paths in the operand)
+    return ((L->K == 2 && T >= 1 && T <= MAX_T) || (L->K == 3 && T == 1)) && L->in % 32 == 0 && L->in <= 65536;
 }
 
-size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T_in)
 {
+    int T = T_in;
+    for (int l = 0; l < n_layers; ++l) T = std::max(T, layout_tokens(T_in, layers[l].K));
     // upper bound: every op could use the widest layer
     size_t up_max = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -952,7 +1012,7 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
 // Host record of a prepared plan, keyed by the workspace that holds its device part.
 struct Prepared {
     Layout lay;
-    int n_ops = 0, n_stages = 0, G = 0, T = 0, max_expand_in = 0, n_expand = 0;
+    int n_ops = 0, n_stages = 0, G = 0, T = 0, K = 2, tokens = 0, max_expand_in = 0, n_expand = 0;   // T: of the operand layout
     uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
     bool chained = false;                   // some op reads what another op of the launch writes
     // host memory the plan's tables are copied from: pageable, so it must outlive the queued copies
@@ -966,11 +1026,16 @@ void set_pause(int clks) { g_pause_clks.store(clks < 0 ? -1 : std::min(clks, 1 <
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
 
-int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int T,
+int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int tokens,
                  void *workspace, size_t workspace_bytes_, hipStream_t stream)
 {
     const int G = device_groups();
     if (G <= 0) return RB_ERR_HIP;
+    // one kernel form per plan: every op has the same number of paths
+    const int K = layers[sops[0].layer].K;
+    for (int n = 0; n < n_ops; ++n)
+        if (layers[sops[n].layer].K != K || !layer_supported(&layers[sops[n].layer], tokens)) return RB_ERR_UNSUPPORTED;
+    const int T = layout_tokens(tokens, K);            // tokens of the operand layout
 
     // ---- ops, consumers, stages
     std::vector<Op> ops((size_t)n_ops);
@@ -985,7 +1050,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         o.g = L.g; o.h = L.h;
         o.x = bufs[sops[n].src];
         o.y = bufs[sops[n].dst];
-        o.out = L.out; o.in = L.in;
+        o.out = L.out; o.in = L.in; o.K = L.K;
         o.RT = row_tiles(L.out); o.CT = col_tiles(L.in);
         up_off[(size_t)n] = up_total;
         up_total += align_up(up_bytes(L.in, T), 256);
@@ -1030,7 +1095,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     for (const Stage &st : stages)
         for (int n = st.op0; n < st.op0 + st.nops; ++n) ops[(size_t)n].stage_op0 = st.op0;
     Prepared pr;
-    pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T;
+    pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T; pr.K = K; pr.tokens = tokens;
     pr.n_expand = (int)expand_list.size();
     for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
     for (int n = 0; n < n_ops; ++n) pr.chained = pr.chained || ops[(size_t)n].dep >= 0;
@@ -1055,7 +1120,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     for (int n = 0; n < n_ops; ++n) ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
 
     Header hdr{};
-    hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G;
+    hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G; hdr.K = K; hdr.tokens = tokens;
 
     // ---- upload: stream-ordered copies out of host memory that the plan's record keeps alive
     pr.blob = std::make_shared<std::vector<uint8_t>>(lay.error, (uint8_t)0);
@@ -1104,7 +1169,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     Header *d_hdr = reinterpret_cast<Header *>(ws);
     Op *d_ops = reinterpret_cast<Op *>(ws + lay.ops);
     if (pr.n_expand > 0)
-        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.T, (unsigned)pr.n_expand),
+        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.tokens, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
     if (pr.chained)
         hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops, pr.T);
@@ -1123,8 +1188,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            go_pause);
         return RB_OK;
     };
-    const int rc = pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
-                             : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
+    const int rc = pr.K == 3   ? launch(stack_kernel<2, 3>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)
+                   : pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+                               : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
     if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }

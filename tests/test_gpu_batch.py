@@ -1,5 +1,6 @@
-"""The small-batch kernel (one pass over the weights for up to 16 tokens, two or three paths)
-against the oracle: every op of a stack recomputed from the input the GPU run actually used."""
+"""The small-batch kernel (one pass over the weights for up to 16 tokens, two or three paths) and
+the three-path form of the fused decode kernel (one token) against the oracle: every op of a stack
+recomputed from the input the GPU run actually used."""
 import numpy as np
 import pytest
 import torch
@@ -28,6 +29,8 @@ def _branching_stack(rng, K, widths):
 
 
 def _check_stack(layers, op_list, widths, x, T, label, prepared):
+    # one token and three paths in every layer: the fused decode kernel; everything else here: the small-batch kernel
+    want_path = rb.RB_PATH_MX if (T == 1 and all(l[0].shape[0] == 3 for l in layers)) else rb.RB_PATH_BATCH
     dev_layers = [to_device_layer(*l) for l in layers]
     bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
     bufs[0].copy_(torch.from_numpy(x))
@@ -40,7 +43,7 @@ def _check_stack(layers, op_list, widths, x, T, label, prepared):
             stack.run_prepared()
             torch.cuda.synchronize()
             runs.append([b.clone() for b in bufs])
-        assert rb.rb_last_path() == rb.RB_PATH_BATCH
+        assert rb.rb_last_path() == want_path
         assert stack.status() == rb.RB_OK
         stack.forget()
         for a, b in zip(*runs):
@@ -48,7 +51,7 @@ def _check_stack(layers, op_list, widths, x, T, label, prepared):
     else:
         rb.rb_layer_stack(dev_layers, op_list, bufs, T)
         torch.cuda.synchronize()
-        assert rb.rb_last_path() == rb.RB_PATH_BATCH
+        assert rb.rb_last_path() == want_path
     got = [b.cpu().numpy() for b in bufs]
     worst = 0.0
     for n, (l, s, d) in enumerate(op_list):
@@ -155,7 +158,7 @@ def test_full_width_7b_block_on_the_batch_kernel(T, K):
     print(f"full-width 7B block on the batch kernel, T={T}, K={K}", flush=True)
     stack.run_prepared()
     torch.cuda.synchronize()
-    assert rb.rb_last_path() == rb.RB_PATH_BATCH and stack.status() == rb.RB_OK
+    assert rb.rb_last_path() == (rb.RB_PATH_MX if (K == 3 and T == 1) else rb.RB_PATH_BATCH) and stack.status() == rb.RB_OK
     stack.forget()
     pick = np.random.default_rng(11)
     worst = 0.0
@@ -189,3 +192,37 @@ def test_many_independent_rows_take_larger_row_blocks(n_ops, T):
     x = synth.outlier_activations(rng, T, inn)
     op_list = [(n, 0, 1 + n) for n in range(n_ops)]
     _check_stack(layers, op_list, (inn,) + (out,) * n_ops, x, T, f"{n_ops} independent ops of {out} rows", prepared=(T >= 8))
+
+
+@pytest.mark.parametrize("prepared", [True, False])
+def test_three_path_decode_kernel_one_token(prepared):
+    """Three paths, one token: the fused decode kernel (its three paths take the place of two
+    tokens' two paths in the right operand), a branching stack with ragged widths."""
+    rng = synth.child_rng(3, 507, int(prepared))
+    layers, op_list = _branching_stack(rng, 3, WIDTHS)
+    x = synth.outlier_activations(rng, 1, WIDTHS[0])
+    _check_stack(layers, op_list, WIDTHS, x, 1, "three paths, one token", prepared)
+
+
+def test_three_path_decode_kernel_early_reads_and_degenerate_scales():
+    """The same kernel with no hand-over pause at all (nearly every input tile is asked for before
+    it is written and has to be read again), negative and zero scales, an all-zero third path."""
+    rng = synth.child_rng(3, 508)
+    widths = (1056, 544, 288, 800)
+    layers = []
+    for n, (o, i) in enumerate([(544, 1056), (288, 544), (800, 288)]):
+        signs, g, h = random_layer(rng, 3, o, i)
+        g = g.astype(np.float64) / (np.sqrt(i * 3) * (0.02 * 0.02)); h = h.astype(np.float64)
+        g[:, rng.integers(0, o, 7)] *= -1.0
+        h[:, rng.integers(0, i, 9)] *= -1.0
+        g[2, rng.integers(0, o, 3)] = 0.0
+        if n == 1:
+            h[2] = 0.0
+        layers.append((signs, g.astype(np.float16), h.astype(np.float16)))
+    x = synth.outlier_activations(rng, 1, widths[0])
+    for pause in (0, -1):
+        rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, pause)
+        try:
+            _check_stack(layers, [(0, 0, 1), (1, 1, 2), (2, 2, 3)], widths, x, 1, f"three paths, pause {pause}", True)
+        finally:
+            rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, -1)

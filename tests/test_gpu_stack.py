@@ -252,8 +252,8 @@ def test_full_7b_stack_as_benchmarked_sampled_outputs():
 
 
 def test_three_path_layers_in_a_stack():
-    """K = 3 layers in a stack run on the small-batch matrix-core kernel (three right operands per
-    128 columns), every op checked against the oracle."""
+    """K = 3 layers in a stack of two tokens run on the small-batch matrix-core kernel (three right
+    operands per 128 columns), every op checked against the oracle."""
     rng = synth.child_rng(3, 88)
     shapes = [(192, 256), (320, 192), (192, 320)]              # x -> a -> b -> c
     layers = []
