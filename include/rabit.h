@@ -132,9 +132,9 @@ size_t rb_noalloc_scratch_bytes(void);
  * layers[ops[n].layer] to bufs[ops[n].src] and writes bufs[ops[n].dst]; every
  * buffer is device fp16 [T][width].  The result of each op equals
  * rb_linear_gemm on the same input (bit for bit for T <= 2 and T > 16; for
- * 3 <= T <= 16 a stack may run token pairs on the fused decode kernel while a
- * single call takes the many-token kernel, and the two agree to the accuracy
- * both are held to).  An op may read any buffer written by an
+ * 3 <= T <= 16 a stack runs on the fused decode kernel or the small-batch
+ * kernel while a single call takes the many-token kernel, and they agree to the
+ * accuracy all are held to).  An op may read any buffer written by an
  * earlier op (or never written: stack inputs); dst buffers must be distinct
  * from the op's src.  layers, ops and bufs are host arrays; bufs holds n_bufs
  * device pointers.  Activations are expected to be finite: an infinity or NaN
@@ -157,9 +157,9 @@ int rb_layer_stack(const rb_layer *layers, int n_layers,
  * between runs the caller must not write to the workspace nor change layers,
  * buffers addresses or T; rb_stack_forget drops the library's host-side record
  * of a workspace (call it before the memory is reused for something else).
- * Two paths: T <= 2 runs as one launch; 3 <= T <= 7 as one launch per pair of
- * consecutive tokens (every layer's out a multiple of 8, at least two ops);
- * 8 <= T <= 16 on the small-batch kernel (one pass over the weights for all
+ * Two paths: T <= 4 runs as one launch; 5 <= T <= 7 as one launch per group
+ * of four consecutive tokens (every layer's out a multiple of 8, at least two
+ * ops); 8 <= T <= 16 on the small-batch kernel (one pass over the weights for all
  * tokens, one launch per group of independent ops).  Three paths in every
  * layer: T = 1 as one launch, 2 <= T <= 16 on the small-batch kernel, which
  * also takes stacks that mix two- and three-path layers.

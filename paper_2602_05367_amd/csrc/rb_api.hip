@@ -63,7 +63,7 @@ extern "C" int rb_stack_prepare(const rb_layer *layers, int n_layers, const rb_s
     if (n_ops > 1 && rb::batch_applies(layers, n_layers, T))
         return rb::batch::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes,
                                        static_cast<hipStream_t>(stream));
-    if (T > 2)
+    if (T > 4)
         return rb::prepare_pairs(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes,
                                  static_cast<hipStream_t>(stream));
     for (int n = 0; n < n_ops; ++n)

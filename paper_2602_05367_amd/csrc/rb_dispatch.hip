@@ -14,36 +14,35 @@ namespace rb {
 thread_local int g_last_path = RB_PATH_NONE;
 void set_last_path(int path) { g_last_path = path; }
 
-// A stack of 3 to BATCH_MIN_T - 1 tokens runs as passes of the fused two-token kernel over
-// consecutive token pairs (the last pass takes one token if T is odd): one pass is one launch for
-// the whole op list.  A call that also has to set the plans up does so for up to
-// PAIRS_MAX_T_ONESHOT tokens.
+// The fused decode kernel takes up to four tokens per launch.  A two-path stack of 5 to
+// BATCH_MIN_T - 1 tokens runs as passes of that kernel over consecutive groups of four tokens (the
+// last pass takes what is left): one pass is one launch for the whole op list.
+constexpr int PASS_T = 4;
 constexpr int PAIRS_MAX_T = 16;
-constexpr int PAIRS_MAX_T_ONESHOT = 4;
 
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-// one slot per pass; the last pass of an odd T holds a one-token plan, whose step lists are longer
-// (more compute wavefronts), so a slot is sized for the larger of the two
+// one slot per pass, sized for the largest plan any pass may hold (a one-token plan has longer step
+// lists than a four-token one: more compute wavefronts)
 static size_t pair_stride(const rb_layer *layers, int n_layers, int n_ops)
 {
-    const size_t two = mx::plan_workspace_bytes(layers, n_layers, n_ops, 2);
-    const size_t one = mx::plan_workspace_bytes(layers, n_layers, n_ops, 1);
-    return round_up(two > one ? two : one, 256);
+    size_t need = 0;
+    for (int t = 1; t <= PASS_T; ++t) need = std::max(need, mx::plan_workspace_bytes(layers, n_layers, n_ops, t));
+    return round_up(need, 256);
 }
 static bool pairs_apply(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
-    if (n_ops < 2 || T <= 2 || T > PAIRS_MAX_T) return false;
+    if (n_ops < 2 || T <= PASS_T || T > PAIRS_MAX_T) return false;
     for (int l = 0; l < n_layers; ++l)
-        if (!mx::layer_supported(&layers[l], 2) || layers[l].out % 8 != 0) return false;   // rows of a pair stay 16-byte aligned
+        if (layers[l].K != 2 || !mx::layer_supported(&layers[l], PASS_T) || layers[l].out % 8 != 0) return false;   // rows of a pass stay 16-byte aligned
     return true;
 }
 
 // Which stacks take the small-batch kernel (one pass over the weights for all tokens): every stack
 // with a three-path layer, and two-path stacks of BATCH_MIN_T tokens or more.  Below that the passes
-// over token pairs on the fused decode kernel are faster (measured on the 7B-shaped stack: 1.2 ms
-// for two passes at 4 tokens against 2.1 ms; 2.4 against 2.5 ms at 8; 4.8 against 3.1 ms at 16):
-// the small-batch kernel is one launch per group of independent ops, and a launch of a few hundred
-// KB per workgroup is bound by memory latency, not by the bytes it streams.
+// over groups of four tokens on the fused decode kernel are faster (measured on the 7B-shaped
+// dependent chain: 1.3 ms for one pass at 4 tokens against 2.1 ms; 2.2 ms for two passes at 6;
+// 2.7 against 2.5 ms at 8): the small-batch kernel is one launch per group of independent ops, and
+// a launch of a few hundred KB per workgroup is bound by memory latency, not by the bytes it streams.
 constexpr int BATCH_MIN_T = 8;
 bool batch_applies(const rb_layer *layers, int n_layers, int T)
 {
@@ -75,24 +74,28 @@ size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
             if (T > 2 && gemm::supported(&layers[l], T)) need = std::max(need, gemm::workspace_bytes(&layers[l], T));
         return need;
     }
-    if (T > 2) {
+    if (T > PASS_T) {
         // ops run one after the other on the caller's stream and share the scratch of the GEMM path
         size_t need = 0;
         for (int l = 0; l < n_layers; ++l)
             if (gemm::supported(&layers[l], T)) need = need > gemm::workspace_bytes(&layers[l], T) ? need : gemm::workspace_bytes(&layers[l], T);
         if (pairs_apply(layers, n_layers, n_ops, T)) {
-            const size_t pairs = (size_t)((T + 1) / 2) * pair_stride(layers, n_layers, n_ops);
+            const size_t pairs = (size_t)((T + PASS_T - 1) / PASS_T) * pair_stride(layers, n_layers, n_ops);
             need = need > pairs ? need : pairs;
         }
-        // rb_layer_stack sets up pairs for up to PAIRS_MAX_T_ONESHOT tokens and takes the small-batch kernel above that
-        if (n_ops > 1 && T > PAIRS_MAX_T_ONESHOT && batch_supported(layers, n_layers, T))
+        // rb_layer_stack takes the small-batch kernel rather than set up several passes
+        if (n_ops > 1 && batch_supported(layers, n_layers, T))
             need = std::max(need, batch::plan_workspace_bytes(layers, n_layers, n_ops, T));
         return need;
     }
-    return mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
+    size_t need = mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
+    // three or four tokens: a single call (and whatever the fused kernel turns down) takes the many-token kernel
+    for (int l = 0; l < n_layers && T > 2; ++l)
+        if (gemm::supported(&layers[l], T)) need = std::max(need, gemm::workspace_bytes(&layers[l], T));
+    return need;
 }
 
-// host record of a workspace that holds one plan per token pair
+// host record of a workspace that holds one plan per pass
 struct PairPlans { int passes; size_t stride; };
 static std::mutex g_pairs_mutex;
 static std::map<const void *, PairPlans> g_pairs;
@@ -102,7 +105,7 @@ int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, 
 {
     if (!pairs_apply(layers, n_layers, n_ops, T)) return RB_ERR_UNSUPPORTED;
     const size_t stride = pair_stride(layers, n_layers, n_ops);
-    const int passes = (T + 1) / 2;
+    const int passes = (T + PASS_T - 1) / PASS_T;
     if (!workspace || workspace_bytes_ < stride * (size_t)passes) return RB_ERR_WORKSPACE;
     // width of every buffer an op touches
     std::vector<int> width((size_t)n_bufs, 0);
@@ -115,8 +118,8 @@ int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, 
     }
     std::vector<uint16_t *> sub((size_t)n_bufs);
     for (int p = 0; p < passes; ++p) {
-        for (int b = 0; b < n_bufs; ++b) sub[(size_t)b] = bufs[b] ? bufs[b] + (size_t)p * 2 * (size_t)width[(size_t)b] : nullptr;
-        const int rc = mx::prepare_plan(layers, ops, n_ops, sub.data(), p * 2 + 2 <= T ? 2 : 1,
+        for (int b = 0; b < n_bufs; ++b) sub[(size_t)b] = bufs[b] ? bufs[b] + (size_t)p * PASS_T * (size_t)width[(size_t)b] : nullptr;
+        const int rc = mx::prepare_plan(layers, ops, n_ops, sub.data(), std::min(PASS_T, T - p * PASS_T),
                                         static_cast<uint8_t *>(workspace) + (size_t)p * stride, stride, stream);
         if (rc != RB_OK) {
             // drop the records of the passes already prepared: the workspace holds no usable stack
@@ -183,7 +186,7 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
         g_last_path = RB_PATH_MX;
         return gemv1::launch(L, X, Y, stream);
     }
-    if (act_dtype == RB_F16 && out_dtype == RB_F16 && L->K == 2 && mx::layer_supported(L, T) && workspace &&
+    if (act_dtype == RB_F16 && out_dtype == RB_F16 && L->K == 2 && T <= 2 && mx::layer_supported(L, T) && workspace &&
         workspace_bytes >= mx::plan_workspace_bytes(L, 1, 1, T)) {
         const rb_stack_op op{0, 0, 1};
         uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};
@@ -201,17 +204,10 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
 int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    if (n_ops > 1 && (batch_applies(layers, n_layers, T) ||
-                      (T > PAIRS_MAX_T_ONESHOT && batch_supported(layers, n_layers, T)))) {
+    if (n_ops > 1 && (batch_applies(layers, n_layers, T) || (T > PASS_T && batch_supported(layers, n_layers, T)))) {
         int rc = batch::prepare_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes, stream);
         if (rc == RB_OK) rc = batch::launch_plan(workspace, workspace_bytes, stream);
         if (rc == RB_OK) g_last_path = RB_PATH_BATCH;
-        if (rc != RB_ERR_UNSUPPORTED && rc != RB_ERR_WORKSPACE) return rc;
-    }
-    if (T > 2 && T <= PAIRS_MAX_T_ONESHOT) {
-        int rc = prepare_pairs(layers, n_layers, ops, n_ops, bufs, n_bufs, T, workspace, workspace_bytes, stream);
-        if (rc == RB_OK) rc = run_pairs(workspace, workspace_bytes, stream);
-        if (rc == RB_OK) g_last_path = RB_PATH_MX;
         if (rc != RB_ERR_UNSUPPORTED && rc != RB_ERR_WORKSPACE) return rc;
     }
     bool fused = workspace && workspace_bytes >= mx::plan_workspace_bytes(layers, n_layers, n_ops, T);

@@ -25,7 +25,7 @@ int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops,
                    uint16_t *const *bufs, int n_bufs, int T, void *workspace, size_t workspace_bytes,
                    hipStream_t stream);
 
-// stacks of 3..8 tokens as passes of the fused two-token kernel over token pairs: one plan per pair
+// stacks of 5..7 tokens as passes of the fused kernel over groups of four tokens: one plan per pass
 // in consecutive parts of the workspace (RB_ERR_UNSUPPORTED where that does not apply)
 int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs,
                   int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
@@ -63,7 +63,7 @@ void forget_plan(const void *workspace);
 namespace mx {
 // workgroups of the decode kernels: one per compute unit of the current device (0: no device)
 int device_groups();
-// matrix-core path (K = 2, T <= 2): whole op lists run as one persistent kernel
+// matrix-core path (K = 2 and T <= 4, or K = 3 and T = 1): whole op lists run as one persistent kernel
 bool layer_supported(const rb_layer *L, int T);
 size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 int run_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint16_t *const *bufs, int T,

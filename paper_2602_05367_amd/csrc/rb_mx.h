@@ -36,7 +36,7 @@ constexpr int RING_D = 6;           // sign tiles requested ahead per compute wa
 // tile ahead no longer hides the latency (+9 %).
 constexpr int nb_of(int T) { return T == 1 ? 2 : 2; }
 // vector-memory loads per step: operand loads (16 bytes per lane each) and one sign tile
-constexpr int kop_of(int T) { return T == 1 ? 2 : 4; }
+constexpr int kop_of(int T) { return T == 1 ? 2 : T == 2 ? 4 : 8; }
 // copies that bring in one sign tile (1 KB each; a three-path tile is 1.5 KB)
 constexpr int sign_loads_of(int K) { return K == 3 ? 2 : 1; }
 // Loads complete in order.  The operand of a tile is requested nb steps before its use, the sign
@@ -44,23 +44,28 @@ constexpr int sign_loads_of(int K) { return K == 3 ? 2 : 1; }
 constexpr int wait_of(int T, int K) { return (nb_of(T) - 1) * (kop_of(T) + sign_loads_of(K)) + sign_loads_of(K); }
 constexpr int MAXSLOT = 8;         // (op, row tile) pairs one CU finishes per stage
 constexpr int MAX_CONS = 3;        // ops that read one op's output inside a fused stack
-constexpr int MAX_T = 2;           // tokens per call on this path
+constexpr int MAX_T = 4;           // tokens per launch on this path
+// Four tokens are two pairs: every 128-column block of the expanded input holds the two-token
+// operand of tokens 0, 1 and then that of tokens 2, 3; a sign tile is expanded once and multiplied
+// with both.  Three tokens use the same layout with the last token's columns left zero.
+constexpr int pairs_of(int T) { return T == 4 ? 2 : 1; }
 constexpr int MAX_OPS = 4096;      // ops per launch
 constexpr size_t MAX_EXPAND = 1024;
-static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && wait_of(1, 2) <= 63 && wait_of(2, 2) <= 63 && wait_of(2, 3) <= 63,
+static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && RING_D > nb_of(4) && wait_of(1, 2) <= 63 && wait_of(2, 2) <= 63 &&
+                  wait_of(2, 3) <= 63 && wait_of(4, 2) <= 63,
               "the in-order wait counts on this");
 // Three paths, one token, ride on the two-token machinery: the 16 operand columns are 8 * token +
 // 4 * path + term for two paths; a three-path op puts its paths 0 and 1 where token 0 has them and
 // its path 2 where token 1 has path 0 (columns 8..11); columns 12..15 are zero.  LAYOUT_T is the
 // token count of the operand layout, not of the activations.
-constexpr int layout_tokens(int T, int K) { return K == 3 ? 2 : T; }
+constexpr int layout_tokens(int T, int K) { return K == 3 ? 2 : T == 3 ? 4 : T; }
 
 // LDS map of the stack kernel with CW compute wavefronts
 constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
-template <int CW, int K = 2> struct LdsMap {
+template <int CW, int K = 2, int PAIRS = 1> struct LdsMap {
     static constexpr int RING_BYTES = CW * RING_D * 512 * K;
-    // partial sums: [parity][slot][compute wavefront][path][token][row] fp32
-    static constexpr int PART_SLOT_BYTES = CW * 2 * 2 * 16 * 4;
+    // partial sums: [parity][slot][compute wavefront][token pair][path][token of the pair][row] fp32
+    static constexpr int PART_SLOT_BYTES = CW * PAIRS * 2 * 2 * 16 * 4;
     static constexpr int PART_BYTES = 2 * MAXSLOT * PART_SLOT_BYTES;
     // go words and a counter, per-wavefront target of the stand-in loads, staging of the finishing wavefronts
     static constexpr int MISC_BYTES = 256 + CW * 256 + EWAVES * LDS_STAGE_BYTES;
@@ -78,19 +83,22 @@ template <int CW, int K = 2> struct LdsMap {
 // 64+16q..64+16q+15 in the next four.  Contraction index == input column inside a 128-column block
 // (see rb_layout.h), and the operand column is 8 * token + 4 * path + term.
 //   two tokens:  block b is 2 KB: [half j of the contraction][lane col + 16q][16 bytes]
+//   four tokens: block b is 4 KB: the two-token image of tokens 0, 1, then that of tokens 2, 3
+//                (operand column 8 * token + 4 * path + term runs to 31; its bit 4 picks the image)
 //   one token:   only columns 0..7 exist, so block b is 1 KB: [q][j][col][16 bytes]; lane
 //                col + 16q of the load gets (j = col / 8, column col % 8), i.e. lanes 0..7 of each
 //                row of 16 hold the first four registers of their column, and the next four
 //                registers come from eight lanes further on with one cross-lane move each.
 // A 16-byte group is the 16 input columns one row tile of the producing op writes.
-__host__ __device__ constexpr int up_block_bytes(int T) { return T == 1 ? 1024 : 2048; }
+__host__ __device__ constexpr int up_block_bytes(int T) { return T == 1 ? 1024 : T == 2 ? 2048 : 4096; }
 
 // byte offset of the 16-byte group of (input column block of 16 starting at j0, operand column c)
 __host__ __device__ inline size_t up_group_offset(int T, int j0, int c)
 {
     const int b = j0 >> 7, jj = j0 & 127, q = (jj & 63) >> 4, j = jj >> 6;
-    return T == 1 ? (size_t)b * 1024 + (size_t)(q * 16 + j * 8 + c) * 16
-                  : (size_t)b * 2048 + (size_t)j * 1024 + (size_t)(q * 16 + c) * 16;
+    return T == 1   ? (size_t)b * 1024 + (size_t)(q * 16 + j * 8 + c) * 16
+           : T == 2 ? (size_t)b * 2048 + (size_t)j * 1024 + (size_t)(q * 16 + c) * 16
+                    : (size_t)b * 4096 + (size_t)(c >> 4) * 2048 + (size_t)j * 1024 + (size_t)(q * 16 + (c & 15)) * 16;
 }
 
 struct Op {

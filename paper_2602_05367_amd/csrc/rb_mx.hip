@@ -276,9 +276,10 @@ __global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T)
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
     for (int i = blockIdx.y * 256 + threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
         // which 16 input columns group i holds (see up_group_offset): a block of 128 columns is
-        // [q][half j][operand column 0..7] for one token and [half j][q][operand column 0..15] for two
-        const int b = T == 1 ? i >> 6 : i >> 7;
-        const int q = T == 1 ? (i >> 4) & 3 : (i >> 4) & 3;
+        // [q][half j][operand column 0..7] for one token, [half j][q][operand column 0..15] for two
+        // and two such images for four
+        const int b = T == 1 ? i >> 6 : T == 2 ? i >> 7 : i >> 8;
+        const int q = (i >> 4) & 3;
         const int j = T == 1 ? (i >> 3) & 1 : (i >> 6) & 1;
         const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
         up[i] = make_uint4(v, v, v, v);
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
     static_assert(KK == 2 || (KK == 3 && TT == 2), "three paths use the two-token layout");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     constexpr int TILE_BYTES = 512 * KK, SL = sign_loads_of(KK);
-    using Lds = LdsMap<CW, KK>;
+    using Lds = LdsMap<CW, KK, pairs_of(TT)>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     float *part = reinterpret_cast<float *>(lds + Lds::PART_OFF);
 
@@ -497,7 +498,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                  : "+v"(dst.r[0]), "+v"(dst.r[1])
                                  : "v"(lane_off), "s"(rsrc)
                                  : "memory");
-                else
+                else if constexpr (TT == 2)
                     asm volatile("s_nop 4\n\t"
                                  "buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
                                  "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:1024\n\t"
@@ -506,6 +507,22 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                  : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2]), "+v"(dst.r[3])
                                  : "v"(lane_off), "s"(rsrc)
                                  : "memory");
+                else {
+                    // eight KB: the offset field holds 12 bits, the second half goes through a second address
+                    asm volatile("s_nop 4\n\t"
+                                 "buffer_load_dwordx4 %0, %8, %10, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %1, %8, %10, 0 offen offset:1024\n\t"
+                                 "buffer_load_dwordx4 %2, %8, %10, 0 offen offset:2048\n\t"
+                                 "buffer_load_dwordx4 %3, %8, %10, 0 offen offset:3072\n\t"
+                                 "buffer_load_dwordx4 %4, %9, %10, 0 offen\n\t"
+                                 "buffer_load_dwordx4 %5, %9, %10, 0 offen offset:1024\n\t"
+                                 "buffer_load_dwordx4 %6, %9, %10, 0 offen offset:2048\n\t"
+                                 "buffer_load_dwordx4 %7, %9, %10, 0 offen offset:3072"
+                                 : "+v"(dst.r[0]), "+v"(dst.r[1]), "+v"(dst.r[2 % KOP]), "+v"(dst.r[3 % KOP]), "+v"(dst.r[4 % KOP]),
+                                   "+v"(dst.r[5 % KOP]), "+v"(dst.r[6 % KOP]), "+v"(dst.r[7 % KOP])
+                                 : "v"(lane_off), "v"(lane_off + 4096u), "s"(rsrc)
+                                 : "memory");
+                }
             };
             // Hand-over: a finishing wavefront of this workgroup announces, with one word in LDS per
             // stage parity, that the inputs of this stage have probably been written.
@@ -542,14 +559,16 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 load_operand(dst, rsrc);
             };
 
-            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};
+            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};   // acc2: the third path, or path 0 of tokens 2, 3
+            [[maybe_unused]] v4f acc3 = {0, 0, 0, 0};                             // path 1 of tokens 2, 3
             const int parity = st & 1;
             // a quad of lanes holds the four terms of (path = quad & 1, token = quad >> 1); its
             // first lane writes rows 4*qd .. 4*qd+3 of that path and token
             const int quad = col >> 2;
             const uint32_t part_lane = lds_addr(part) + (uint32_t)(parity * MAXSLOT) * Lds::PART_SLOT_BYTES +
                                        (uint32_t)(((quad & 1) * 2 + (quad >> 1)) * 16 + 4 * qd) * 4;
-            auto flush = [&](uint32_t part_index) {       // slot * CW + run: 256 bytes each
+            constexpr int PAIRS = pairs_of(TT);
+            auto flush = [&](uint32_t part_index) {       // slot * CW + run: 256 bytes per token pair each
                 v4f v;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {     // the four lanes of a quad hold terms of the same path
@@ -561,8 +580,18 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 if ((col & 3) == 0)
                     asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                  :
-                                 : "v"(part_lane + part_index * 256u), "v"(v)
+                                 : "v"(part_lane + part_index * (256u * PAIRS)), "v"(v)
                                  : "memory");
+                if constexpr (TT == 4) {          // tokens 2, 3
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = quad_sum((quad & 1) ? acc3[r] : acc2[r]);
+                    if ((col & 3) == 0)
+                        asm volatile("ds_write_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     :
+                                     : "v"(part_lane + part_index * (256u * PAIRS) + 256u), "v"(v)
+                                     : "memory");
+                    acc3 = (v4f){0, 0, 0, 0};
+                }
                 acc0 = (v4f){0, 0, 0, 0};
                 acc1 = (v4f){0, 0, 0, 0};
                 acc2 = (v4f){0, 0, 0, 0};
@@ -660,6 +689,58 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                [un] "=&s"(unwritten), [left] "=&s"(left)
                                              : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
                                              : "vcc", "scc", "memory");
+                            } else if constexpr (TT == 4) {
+                                int c0, c1, c2, c3, c4, c5, c6, c7;
+                                asm volatile("s_mov_b32 %[left], 0x40000\n"
+                                             "1:\n\t"
+                                             "s_nop 4\n\t"
+                                             "buffer_load_dword %[c0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dword %[c2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dword %[c3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dword %[c4], %[off2], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dword %[c5], %[off2], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dword %[c6], %[off2], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dword %[c7], %[off2], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b4], %[off2], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b5], %[off2], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b6], %[off2], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b7], %[off2], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
+                                             "v_and_b32 %[c0], 0xff, %[c0]\n\t"
+                                             "v_and_b32 %[c1], 0xff, %[c1]\n\t"
+                                             "v_and_b32 %[c2], 0xff, %[c2]\n\t"
+                                             "v_and_b32 %[c3], 0xff, %[c3]\n\t"
+                                             "v_and_b32 %[c4], 0xff, %[c4]\n\t"
+                                             "v_and_b32 %[c5], 0xff, %[c5]\n\t"
+                                             "v_and_b32 %[c6], 0xff, %[c6]\n\t"
+                                             "v_and_b32 %[c7], 0xff, %[c7]\n\t"
+                                             "v_max3_u32 %[c0], %[c0], %[c1], %[c2]\n\t"
+                                             "v_max3_u32 %[c3], %[c3], %[c4], %[c5]\n\t"
+                                             "v_max3_u32 %[c0], %[c0], %[c3], %[c6]\n\t"
+                                             "v_max_u32 %[c0], %[c0], %[c7]\n\t"
+                                             "v_cmp_eq_u32 vcc, 0xff, %[c0]\n\t"
+                                             "s_mov_b64 %[un], vcc\n\t"
+                                             "s_cmp_eq_u64 %[un], 0\n\t"
+                                             "s_cbranch_scc1 2f\n\t"
+                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             "s_sub_u32 %[left], %[left], 1\n\t"
+                                             "s_cmp_lg_u32 %[left], 0\n\t"
+                                             "s_cbranch_scc1 1b\n"
+                                             "2:\n\t"
+                                             "v_mov_b32 %[c0], 1\n\t"
+                                             "ds_add_u32 %[cnt], %[c0]"
+                                             : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [b2] "+v"(B[s].r[2 % KOP]),
+                                               [b3] "+v"(B[s].r[3 % KOP]), [b4] "+v"(B[s].r[4 % KOP]), [b5] "+v"(B[s].r[5 % KOP]),
+                                               [b6] "+v"(B[s].r[6 % KOP]), [b7] "+v"(B[s].r[7 % KOP]), [c0] "=&v"(c0), [c1] "=&v"(c1),
+                                               [c2] "=&v"(c2), [c3] "=&v"(c3), [c4] "=&v"(c4), [c5] "=&v"(c5), [c6] "=&v"(c6),
+                                               [c7] "=&v"(c7), [un] "=&s"(unwritten), [left] "=&s"(left)
+                                             : [off] "v"(lane_off), [off2] "v"(lane_off + 4096u), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
+                                             : "vcc", "scc", "memory");
                             } else {
                                 int c0, c1, c2, c3;
                                 asm volatile("s_mov_b32 %[left], 0x40000\n"
@@ -719,6 +800,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     if (c_slot_ptr == ring_end) c_slot_ptr = ring;
                     const BTile<TT> bt = B[s];
                     v8i b0, b1;
+                    [[maybe_unused]] v8i c0, c1;                  // four tokens: the operands of tokens 2, 3
                     if constexpr (TT == 1) {
                         // lanes 0..7 of a row of 16 hold the first four registers of their column; the
                         // other four sit eight lanes further on (row_shl:8).  Lanes 8..15 end up with
@@ -729,6 +811,15 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                             b0[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[0][i], 0x108, 0xf, 0xf, true);
                             b1[i] = bt.r[1][i];
                             b1[4 + i] = __builtin_amdgcn_update_dpp(0, bt.r[1][i], 0x108, 0xf, 0xf, true);
+                        }
+                    } else if constexpr (TT == 4) {
+                        // per 128-column block: the image of tokens 0, 1 (two loads), then that of tokens 2, 3
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            b0[i] = bt.r[0][i]; b0[4 + i] = bt.r[1][i];
+                            c0[i] = bt.r[2 % KOP][i]; c0[4 + i] = bt.r[3 % KOP][i];
+                            b1[i] = bt.r[4 % KOP][i]; b1[4 + i] = bt.r[5 % KOP][i];
+                            c1[i] = bt.r[6 % KOP][i]; c1[4 + i] = bt.r[7 % KOP][i];
                         }
                     } else {
 #pragma unroll
@@ -743,6 +834,12 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         acc1 = mfma_signs(w.y, b0, acc1, c22, scale_b);
                         acc0 = mfma_signs(w.z, b1, acc0, c22, scale_b);
                         acc1 = mfma_signs(w.w, b1, acc1, c22, scale_b);
+                        if constexpr (TT == 4) {
+                            acc2 = mfma_signs(w.x, c0, acc2, c22, scale_b);
+                            acc3 = mfma_signs(w.y, c0, acc3, c22, scale_b);
+                            acc2 = mfma_signs(w.z, c1, acc2, c22, scale_b);
+                            acc3 = mfma_signs(w.w, c1, acc3, c22, scale_b);
+                        }
                     } else {
                         // (columns 0..127: paths 0, 1, 2), (columns 128..255: paths 0, 1, 2)
                         acc0 = mfma_signs(w.x, b0, acc0, c22, scale_b);
@@ -770,6 +867,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         const int half = lane >> 5;
         const int my_slot = ew + EWAVES * half;
         const int row = lane & 15, tok = (lane >> 4) & 1;
+        const int tokens = hdr_p->tokens;                 // of the activations (three use the layout of four)
         // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
         uint8_t *stage_bytes = lds + Lds::MISC_OFF + 256 + CW * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
 
@@ -810,7 +908,6 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             // row split the paths between them (sub = which path) for the sums and the expansion.
             constexpr bool SPLIT = TT == 1;
             const int sub = tok;
-            const bool active = have_slot && (SPLIT || tok < T) && grow < cur.r.out;
             const int n_cons = have_slot ? cur.r.n_cons : 0;
             // Three paths: the lane at a row's second-token position stands for path 2 (as that
             // token's path 0, see layout_tokens): its output scale and its readers' input scales
@@ -823,31 +920,36 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             // this lane's path of each reader's scales (selected value by value: an indexed array
             // would live in scratch memory)
             const float hsub[MAX_CONS] = {sub ? cur.a[3] : cur.a[2], sub ? cur.b[1] : cur.b[0], sub ? cur.b[3] : cur.b[2]};
+            // four tokens: the pair of tokens 0, 1, then the pair 2, 3 (this lane's token is 2 * pair + tok)
+            constexpr int PAIRS = pairs_of(TT);
+#pragma unroll
+            for (int pair = 0; pair < PAIRS; ++pair) {
+            const bool active = have_slot && (SPLIT || KK == 3 || 2 * pair + tok < tokens) && grow < cur.r.out;
             float yf = 0.f;
-            // partial sums of this lane's row: [run][path][token][row]
-            float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * 64 + (SPLIT ? 0 : tok * 16) + row;
+            // partial sums of this lane's row: [run][token pair][path][token][row]
+            float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * (64 * PAIRS) + pair * 64 + (SPLIT ? 0 : tok * 16) + row;
             if (active) {
                 // sum the partial sums of the runs in run order
                 float s0 = 0.f, s1 = 0.f;
                 if constexpr (SPLIT) {
                     float mine = 0.f;
 #pragma unroll
-                    for (int w = 0; w < CW; ++w) mine += P[w * 64 + sub * 32];
+                    for (int w = 0; w < CW; ++w) mine += P[w * (64 * PAIRS) + sub * 32];
                     const float other = __shfl_xor(mine, 16);      // the lane with the same row and the other path
                     s0 = sub ? other : mine;
                     s1 = sub ? mine : other;
                 } else {
 #pragma unroll
                     for (int w = 0; w < CW; ++w) {
-                        s0 += P[w * 64];
-                        s1 += P[w * 64 + 32];
+                        s0 += P[w * (64 * PAIRS)];
+                        s1 += P[w * (64 * PAIRS) + 32];
                     }
                 }
                 float ysum = path_sum(g_a, s0, g_b, s1);
                 if constexpr (KK == 3) ysum += __shfl_xor(ysum, 16);       // paths 0 and 1 in one lane of the row, path 2 in the other
                 const _Float16 y16 = (_Float16)ysum;                         // round to nearest even
                 if (KK == 3 ? tok == 0 : (!SPLIT || sub == 0))
-                    RB_GLOBAL(_Float16, cur.r.y)[(size_t)((SPLIT || KK == 3) ? 0 : tok) * cur.r.out + grow] = y16;
+                    RB_GLOBAL(_Float16, cur.r.y)[(size_t)((SPLIT || KK == 3) ? 0 : 2 * pair + tok) * cur.r.out + grow] = y16;
                 yf = (float)y16;
             }
             // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
@@ -895,7 +997,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     if (v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T) {
                         const v4i bytes = *reinterpret_cast<const v4i *>(
                             stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
-                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + (8 * vtok + vpt) * 16;
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + pair * 2048 + (8 * vtok + vpt) * 16;
                                                 asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
@@ -905,15 +1007,16 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             if (active) {
                 if constexpr (SPLIT) {
 #pragma unroll
-                    for (int w = 0; w < CW; ++w) P[w * 64 + sub * 32] = 0.f;
+                    for (int w = 0; w < CW; ++w) P[w * (64 * PAIRS) + sub * 32] = 0.f;
                 } else {
 #pragma unroll
                     for (int w = 0; w < CW; ++w) {
-                        P[w * 64] = 0.f;
-                        P[w * 64 + 32] = 0.f;
+                        P[w * (64 * PAIRS)] = 0.f;
+                        P[w * (64 * PAIRS) + 32] = 0.f;
                     }
                 }
             }
+            }   // token pairs
             // ---- tell the compute wavefronts, which may already be in the next stage, when that
             // stage's inputs have probably been written (one wavefront per workgroup)
             if (ew == 0 && st + 1 < n_stages) {
@@ -1190,7 +1293,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     };
     const int rc = pr.K == 3   ? launch(stack_kernel<2, 3>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)
                    : pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
-                               : launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES);
+                   : pr.T == 2 ? launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES)
+                               : launch(stack_kernel<4>, threads_of(4), LdsMap<cwaves_of(4), 2, 2>::BYTES);
     if (rc != RB_OK) return rc;
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }

@@ -324,11 +324,13 @@ def _sampled_rows_check(rb_mod, ops, layers, bufs, op_numbers, rows_per_op, seed
     return worst
 
 
-def test_one_full_width_7b_block_two_tokens_chained():
-    """The two-token kernel at the real 7B widths (43 column tiles, 688 row tiles, two or three per
-    workgroup), ops in dependency order, outlier channels in the stack input."""
-    ops, widths, layers, bufs = build_stack("7b", 1, 3, 2, derived=False, outliers=True, gain=100.0)
-    _run_and_check(ops, widths, layers, bufs, 2, "one full-width 7B block, T=2, chained", prepared=True)
+@pytest.mark.parametrize("T", [2, 3, 4])
+def test_one_full_width_7b_block_small_batches_chained(T):
+    """The two- and four-token forms of the fused kernel (three tokens use the layout of four) at
+    the real 7B widths (43 column tiles, 688 row tiles, two or three per workgroup), ops in
+    dependency order, outlier channels in the stack input."""
+    ops, widths, layers, bufs = build_stack("7b", 1, 3, T, derived=False, outliers=True, gain=100.0)
+    _run_and_check(ops, widths, layers, bufs, T, f"one full-width 7B block, T={T}, chained", prepared=True)
 
 
 @pytest.mark.parametrize("T", [2, 4, 8, 16])
