@@ -25,6 +25,14 @@ What each function follows:
 * ``scale_grads``            - Eq. (RaBiT-grad-gh), gradients of the scales; with
                                ``weight_grad`` Eq. (RaBiT-grad-wfp).
 * ``stack_forward``          - the layer applied op after op (fp16 between ops).
+* ``rmsnorm`` / ``silu`` / ``block_forward``
+                             - the operations that sit between the linear layers of
+                               the Llama-2 decoder block the end-to-end decoding
+                               figures are measured on (Section 5.4, inference
+                               table): root-mean-square normalisation with a weight
+                               in front of a layer, gate(x) -> SiLU, times up(x),
+                               and the addition of the residual stream, each by its
+                               textbook definition.
 
 All floating point is fp64.  Stored fp16 / bf16 values are widened exactly.
 """
@@ -366,5 +374,63 @@ def stack_forward(layers: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]],
         y = forward(signs, g, h, x)
         outs.append(y)
         if forced_inputs is None:
+            bufs[dst] = y.astype(np.float16)
+    return outs
+
+
+# --------------------------------------------------------------------------
+# The decoder block around the layers (Section 5.4: Llama-2 decoding)
+# --------------------------------------------------------------------------
+EPI_NONE, EPI_ADD, EPI_SILU_MUL = 0, 1, 2
+
+
+def rmsnorm(X, w, eps: float) -> np.ndarray:
+    """x / sqrt(mean_j x_j^2 + eps) (.) w for every row of X [T][n]; fp64."""
+    X = _f64(X)
+    X = X.reshape(-1, X.shape[-1])
+    w = _f64(w).reshape(-1)
+    ms = (X * X).sum(axis=1, keepdims=True) / X.shape[1]
+    return X / np.sqrt(ms + eps) * w[None, :]
+
+
+def silu(z) -> np.ndarray:
+    """z * sigmoid(z) = z / (1 + exp(-z)); fp64."""
+    z = _f64(z)
+    with np.errstate(over="ignore"):
+        return z / (1.0 + np.exp(-z))
+
+
+def block_forward(layers: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]],
+                  norm_weights: Sequence[np.ndarray], eps: float,
+                  ops: Sequence[Tuple[int, int, int, int, int, int]],
+                  bufs: List[Optional[np.ndarray]], write_back: bool = True) -> List[np.ndarray]:
+    """Run ops (layer, src, dst, norm, epilogue, aux) in order; returns each op's fp64 output.
+
+    The layer's input is ``bufs[src]`` (fp16 [T][in]), normalised with
+    ``norm_weights[norm]`` first when ``norm >= 0``.  Epilogues on the layer's
+    output y: EPI_NONE: y;  EPI_ADD: y + bufs[aux] (the residual stream);
+    EPI_SILU_MUL: silu(y) * y_up, where y_up is layer ``aux`` applied to the
+    same input (the gate and up projections of the feed-forward part).
+    With ``write_back`` the result, rounded to fp16, becomes ``bufs[dst]``
+    (free-running); without it ``bufs`` is only read, so a caller can hand in
+    the buffers another implementation produced (teacher-forced).
+    """
+    outs = []
+    for layer, src, dst, norm, epilogue, aux in ops:
+        x = _f64(bufs[src])
+        x = x.reshape(-1, x.shape[-1])
+        if norm >= 0:
+            x = rmsnorm(x, norm_weights[norm], eps)
+        signs, g, h = layers[layer]
+        y = forward(signs, g, h, x)
+        if epilogue == EPI_ADD:
+            y = y + _f64(bufs[aux]).reshape(y.shape)
+        elif epilogue == EPI_SILU_MUL:
+            signs_u, g_u, h_u = layers[aux]
+            y = silu(y) * forward(signs_u, g_u, h_u, x)
+        elif epilogue != EPI_NONE:
+            raise ValueError("unknown epilogue")
+        outs.append(y)
+        if write_back:
             bufs[dst] = y.astype(np.float16)
     return outs

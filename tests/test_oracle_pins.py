@@ -2,6 +2,7 @@
 other than itself - brute force on tiny inputs, closed forms, an independent
 library routine, or a number the paper prints."""
 import itertools
+import math
 import os
 
 import numpy as np
@@ -519,6 +520,137 @@ def test_stack_forward_modes():
     outs_tf = oracle.stack_forward(layers, op_list, [None] * len(widths), forced_inputs=forced)
     for a, b in zip(outs, outs_tf):
         assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------- decoder block ---
+def test_rmsnorm_closed_forms_and_library():
+    rng = synth.child_rng(0, 31)
+    # a worked case: x = (3, 4): mean square 12.5
+    y = oracle.rmsnorm(np.array([[3.0, 4.0]]), np.array([1.0, 2.0]), 0.0)
+    np.testing.assert_allclose(y, [[3 / math.sqrt(12.5), 8 / math.sqrt(12.5)]], rtol=1e-15)
+    X = rng.standard_normal((3, 40)) * np.array([[0.01], [1.0], [300.0]])
+    w = rng.standard_normal(40)
+    one = np.ones(40)
+    # without eps the output has mean square exactly 1 and does not depend on the input's scale
+    n0 = oracle.rmsnorm(X, one, 0.0)
+    np.testing.assert_allclose((n0 ** 2).mean(axis=1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(oracle.rmsnorm(7.5 * X, one, 0.0), n0, rtol=1e-13)
+    # eps sits under the root, added to the mean (not the sum) of the squares
+    eps = 0.5
+    ms = (X ** 2).mean(axis=1, keepdims=True)
+    np.testing.assert_allclose(oracle.rmsnorm(X, one, eps) * np.sqrt(ms + eps), X, rtol=1e-13)
+    assert np.all(oracle.rmsnorm(np.zeros((1, 8)), np.ones(8), 1e-5) == 0.0)
+    # the weight multiplies per channel, after the normalisation
+    np.testing.assert_allclose(oracle.rmsnorm(X, w, eps), oracle.rmsnorm(X, one, eps) * w[None, :], rtol=1e-15)
+    # library routine
+    import torch
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(X), (40,), torch.from_numpy(w), eps).numpy()
+    np.testing.assert_allclose(oracle.rmsnorm(X, w, eps), ref, rtol=1e-12)
+
+
+def test_silu_closed_forms_and_library():
+    z = np.array([-800.0, -30.0, -2.5, -1.0, 0.0, 1.0, 2.5, 30.0, 800.0])
+    s = oracle.silu(z)
+    assert s[4] == 0.0 and np.all(np.isfinite(s))
+    np.testing.assert_allclose(s[5], 1.0 / (1.0 + math.exp(-1.0)), rtol=1e-15)      # sigmoid(1) = 0.7310585786...
+    assert abs(s[5] - 0.7310585786300049) < 1e-15
+    # sigmoid(z) + sigmoid(-z) = 1  =>  silu(z) - silu(-z) = z
+    np.testing.assert_allclose(s - s[::-1], z, rtol=1e-13, atol=1e-300)
+    # far out it is the identity on the right and zero on the left; its minimum is about -0.27846 near z = -1.2785
+    assert s[-1] == 800.0 and abs(s[0]) < 1e-300
+    grid = np.linspace(-3, 0, 300001)
+    v = oracle.silu(grid)
+    assert abs(v.min() + 0.27846454276107374) < 1e-9 and abs(grid[v.argmin()] + 1.2784645427610738) < 1e-4
+    # slope 1/2 at the origin
+    assert abs((oracle.silu(np.array([1e-6])) - oracle.silu(np.array([-1e-6])))[0] / 2e-6 - 0.5) < 1e-9
+    import torch
+    np.testing.assert_allclose(s, torch.nn.functional.silu(torch.from_numpy(z)).numpy(), rtol=1e-13, atol=1e-300)
+
+
+def _tiny_block(rng, T=2, d=32, f=64):
+    mk = lambda o, i: (synth.uniform_signs(rng, 2, o, i),
+                       (synth.halfnormal_scales(rng, 2, o).astype(np.float64) * 50).astype(np.float16),
+                       synth.halfnormal_scales(rng, 2, i))
+    layers = [mk(d, d), mk(d, d), mk(f, d), mk(f, d), mk(d, f)]      # v, o, gate, up, down
+    norms = [(1.0 + 0.1 * rng.standard_normal(d)).astype(np.float16) for _ in range(2)]
+    # buffers: 0 x, 1 v_out, 2 x + o_out, 3 act, 4 x' = (2) + down_out
+    ops = [(0, 0, 1, 0, oracle.EPI_NONE, -1),
+           (1, 1, 2, -1, oracle.EPI_ADD, 0),
+           (2, 2, 3, 1, oracle.EPI_SILU_MUL, 3),
+           (4, 3, 4, -1, oracle.EPI_ADD, 2)]
+    bufs = [synth.gaussian_activations(rng, T, d), None, None, None, None]
+    return layers, norms, ops, bufs
+
+
+def test_block_forward_against_scalar_loops():
+    """Every op of a small block recomputed with explicit loops over rows and columns."""
+    rng = synth.child_rng(0, 32)
+    layers, norms, ops, bufs = _tiny_block(rng)
+    eps = 1e-5
+    outs = oracle.block_forward(layers, norms, eps, ops, bufs)
+
+    def lin(layer, x):
+        signs, g, h = layers[layer]
+        K, out, inn = signs.shape
+        y = [0.0] * out
+        for i in range(out):
+            for k in range(K):
+                acc = 0.0
+                for j in range(inn):
+                    acc += float(signs[k, i, j]) * float(h[k, j]) * x[j]
+                y[i] += float(g[k, i]) * acc
+        return y
+
+    def norm(x, w):
+        ms = sum(v * v for v in x) / len(x)
+        return [v / math.sqrt(ms + eps) * float(wj) for v, wj in zip(x, w)]
+
+    T = bufs[0].shape[0]
+    for t in range(T):
+        x0 = [float(v) for v in bufs[0][t]]
+        v = lin(0, norm(x0, norms[0]))
+        np.testing.assert_allclose(outs[0][t], v, rtol=1e-11, atol=1e-13)
+        v16 = [float(np.float16(a)) for a in v]
+        x1 = [a + b for a, b in zip(lin(1, v16), x0)]
+        np.testing.assert_allclose(outs[1][t], x1, rtol=1e-11, atol=1e-13)
+        x1_16 = [float(np.float16(a)) for a in x1]
+        n1 = norm(x1_16, norms[1])
+        gate, up = lin(2, n1), lin(3, n1)
+        act = [a / (1.0 + math.exp(-a)) * b for a, b in zip(gate, up)]
+        np.testing.assert_allclose(outs[2][t], act, rtol=1e-11, atol=1e-13)
+        act16 = [float(np.float16(a)) for a in act]
+        x2 = [a + b for a, b in zip(lin(4, act16), x1_16)]
+        np.testing.assert_allclose(outs[3][t], x2, rtol=1e-11, atol=1e-13)
+    # what was stored is the fp16 rounding of each result
+    for n, op in enumerate(ops):
+        assert np.array_equal(bufs[op[2]], outs[n].astype(np.float16))
+
+
+def test_block_forward_roles_and_modes():
+    rng = synth.child_rng(0, 33)
+    layers, norms, ops, bufs = _tiny_block(rng)
+    outs = oracle.block_forward(layers, norms, 1e-5, ops, bufs)
+    # reading the stored buffers back without writing gives the same results, and leaves them alone
+    before = [b.copy() for b in bufs]
+    again = oracle.block_forward(layers, norms, 1e-5, ops, bufs, write_back=False)
+    for a, b in zip(outs, again):
+        assert np.array_equal(a, b)
+    for a, b in zip(before, bufs):
+        assert np.array_equal(a, b)
+    # the activation goes on the op's own layer (gate), not on the second one (up)
+    swapped = list(ops)
+    swapped[2] = (3, 2, 3, 1, oracle.EPI_SILU_MUL, 2)
+    other = oracle.block_forward(layers, norms, 1e-5, swapped, [b.copy() for b in before], write_back=False)
+    assert oracle.relative_l2(other[2], outs[2]).min() > 0.05
+    # no norm, no epilogue: the plain stack
+    plain = oracle.block_forward(layers, norms, 1e-5, [(0, 0, 1, -1, oracle.EPI_NONE, -1)], [before[0], None])
+    assert np.array_equal(plain[0], oracle.forward(*layers[0], before[0]))
+    # a layer with zero output scales leaves the residual stream as it was
+    signs, g, h = layers[1]
+    dead = list(layers)
+    dead[1] = (signs, np.zeros_like(g), h)
+    res = oracle.block_forward(dead, norms, 1e-5, ops[:2], [b.copy() if b is not None else None for b in before])
+    assert np.array_equal(res[1], before[0].astype(np.float64))
 
 
 # ------------------------------------------------------------ paper values ---
