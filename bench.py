@@ -52,6 +52,31 @@ def build_stack(rb, synth, torch, which: str, T: int, seed: int = 20260205, K: i
     return ops, layers, bufs, op_list, packed_bytes
 
 
+def build_block_stack(rb, synth, torch, which: str, T: int, seed: int = 20260206):
+    """The same synthetic layers as build_stack with what sits between them in a decoder block
+    (normalised q/k/v and gate/up inputs, silu(gate) * up, residual additions; attention left out),
+    the residual stream kept in buffer 0."""
+    ops, shapes, widths, norms = synth.llama_block_stack(which, synth.LLAMA_SHAPES[which][2], in_place=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    layers, packed_bytes = [], 0
+    gh = [0.0160, 0.0097]
+    a = torch.tensor(gh, device="cuda").sqrt()[:, None]
+    for name, out, inn in shapes:
+        bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (rb.rb_native_bytes(2, out, inn) // 4,), dtype=torch.int32,
+                             device="cuda", generator=gen)
+        c = 1.0 / (inn * sum(v ** 2 for v in gh)) ** 0.5 * (2.0 if name.endswith("down") else 1.0)
+        g = (a * c * (1 + 0.01 * torch.randn(2, out, device="cuda", generator=gen))).half()
+        h = (a * (1 + 0.01 * torch.randn(2, inn, device="cuda", generator=gen))).half()
+        layers.append(rb.Layer(bits, g, h, 2, out, inn))
+        packed_bytes += 2 * out * inn // 8
+    norm_w = [(1 + 0.1 * torch.randn(w, device="cuda", generator=gen)).half() for w in norms]
+    bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in widths]
+    x0 = torch.randn(T, widths[0], device="cuda", generator=gen).half()
+    op_list = [(o.layer, o.src, o.dst, o.norm, o.epilogue, o.aux) for o in ops]
+    return ops, layers, norm_w, bufs, x0, op_list, packed_bytes
+
+
 def time_steps(torch, fn, steps: int, warmup: int):
     for _ in range(warmup):
         fn()
@@ -297,6 +322,43 @@ def main() -> int:
             stack3.forget()
             del ops3, layers3, bufs3, stack3
         result["three_path_stack_7b"] = three
+        # whole decoder blocks in the same single launch: RMS normalisation in front of q/k/v and
+        # gate/up, silu(gate) * up, both residual additions, all in the kernel's finishing step;
+        # against the same block run op by op (a launch per layer and per elementwise operation)
+        blocks = {}
+        for Tb in (1, 4):
+            bops, blayers, bnorms, bbufs, bx0, bop_list, bpacked = build_block_stack(rb, synth, torch, "7b", Tb)
+            block = rb.Block(blayers, bnorms, 1e-5, bop_list, bbufs, Tb)
+            block.prepare()
+
+            def fused_step():
+                bbufs[0].copy_(bx0)          # the residual stream lives in buffer 0: a fresh token every pass
+                block.run_prepared()
+            _, per_b = time_steps(torch, fused_step, 20, 3)
+            assert rb.rb_last_path() == rb.RB_PATH_MX and block.status() == rb.RB_OK
+            ms_b = sum(per_b) / len(per_b)
+            blocks[f"T{Tb}"] = {"ms_per_pass": ms_b, "tokens_per_s": Tb / (ms_b * 1e-3), "GBps": bpacked / (ms_b * 1e-3) / 1e9,
+                                "pct_of_hbm_peak": 100.0 * bpacked / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                "ops": len(bop_list), "matrices": len(blayers), "launches_per_pass": 1,
+                                "entry_point": "rb_block_prepare + rb_stack_run"}
+            if Tb == 1:
+                def op_by_op():
+                    x = bx0.clone()
+                    for l in range(len(blayers) // 7):
+                        L = blayers[7 * l: 7 * l + 7]
+                        n1 = rb.rb_rmsnorm(x, bnorms[2 * l], 1e-5)
+                        rb.rb_linear_gemm(L[0], n1); rb.rb_linear_gemm(L[1], n1)
+                        v = rb.rb_linear_gemm(L[2], n1)
+                        x = rb.rb_add(rb.rb_linear_gemm(L[3], v), x)
+                        n2 = rb.rb_rmsnorm(x, bnorms[2 * l + 1], 1e-5)
+                        act = rb.rb_silu_mul(rb.rb_linear_gemm(L[4], n2), rb.rb_linear_gemm(L[5], n2))
+                        x = rb.rb_add(rb.rb_linear_gemm(L[6], act), x)
+                _, per_u = time_steps(torch, op_by_op, 5, 2)
+                blocks["T1"]["op_by_op_ms"] = sum(per_u) / len(per_u)
+                blocks["T1"]["op_by_op_launches"] = 12 * (len(blayers) // 7)
+            block.forget()
+            del bops, blayers, bnorms, bbufs, block
+        result["decoder_block_stack_7b"] = blocks
         # one-call form (set-up inside the call)
         _, per_o = time_steps(torch, stack.run, 20, 3)
         ms_o = sum(per_o) / len(per_o)

@@ -288,6 +288,48 @@ int rb_last_path(void);
 /* Library version: major*10000 + minor*100 + patch. */
 int rb_version(void);
 
+/*
+ * The decoder block around the layers (the end-to-end decoding setting of
+ * Section 5.4 and the inference table: a Llama-2 block), fused into the stack
+ * kernel's finishing step so that a whole model's blocks stay one launch.
+ * Op n applies layers[layer] to bufs[src] and writes bufs[dst] (device fp16
+ * [T][width], as in rb_layer_stack), with
+ *   norm >= 0:         the layer reads x / sqrt(mean_j x_j^2 + eps) (.) w with
+ *                      w = norm_weights[norm] (device fp16 [in]) in place of x;
+ *   RB_EPI_ADD:        dst = y + bufs[aux] (the residual stream; aux may equal dst);
+ *   RB_EPI_SILU_MUL:   dst = silu(y) * y_up, y_up = layers[aux] applied to the
+ *                      same (normalised) input: the gate and up projections of
+ *                      the feed-forward part as one op (same out, in, K);
+ * silu(z) = z / (1 + exp(-z)).  Sums, normalisation and epilogues are fp32; only
+ * dst is rounded to fp16 (gate and up outputs are never stored).  Ops that share
+ * an input and do not depend on each other (q, k, v) run side by side.
+ * rb_block_prepare is to a block what rb_stack_prepare is to a plain stack
+ * (same rules, may block the host); the prepared ops are run, checked and
+ * dropped with rb_stack_run, rb_stack_status and rb_stack_forget.  Two-path
+ * layers, T <= 4; RB_ERR_UNSUPPORTED otherwise (run such a block op by op with
+ * rb_layer_stack and the three kernels below).  norm_weights is a host array
+ * of n_norms device pointers.
+ */
+#define RB_EPI_NONE 0
+#define RB_EPI_ADD 1
+#define RB_EPI_SILU_MUL 2
+typedef struct rb_block_op { int layer; int src; int dst; int norm; int epilogue; int aux; } rb_block_op;
+
+size_t rb_block_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
+int rb_block_prepare(const rb_layer *layers, int n_layers,
+                     const uint16_t *const *norm_weights, int n_norms, float eps,
+                     const rb_block_op *ops, int n_ops,
+                     uint16_t *const *bufs, int n_bufs, int T,
+                     void *workspace, size_t workspace_bytes, void *stream);
+/*
+ * The same three operations as kernels of their own (device fp16, fp32
+ * arithmetic, one rounding at the end): y[t] = rmsnorm(x[t]) (.) w for T rows
+ * of n; y = silu(gate) * up and y = a + b over n elements.  y may be an input.
+ */
+int rb_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int T, int n, float eps, void *stream);
+int rb_silu_mul(const uint16_t *gate, const uint16_t *up, uint16_t *y, size_t n, void *stream);
+int rb_add(const uint16_t *a, const uint16_t *b, uint16_t *y, size_t n, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

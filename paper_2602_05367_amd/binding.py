@@ -31,6 +31,7 @@ EXPORTS = [
     "rb_stack_set_option",
     "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
     "rb_couple", "rb_weight_grad", "rb_scale_grads", "rb_scale_grads_workspace_bytes",
+    "rb_block_prepare", "rb_block_workspace_bytes", "rb_rmsnorm", "rb_silu_mul", "rb_add",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -48,6 +49,11 @@ class rb_layer(ctypes.Structure):
 
 class rb_stack_op(ctypes.Structure):
     _fields_ = [("layer", ctypes.c_int), ("src", ctypes.c_int), ("dst", ctypes.c_int)]
+
+
+class rb_block_op(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_int), ("src", ctypes.c_int), ("dst", ctypes.c_int),
+                ("norm", ctypes.c_int), ("epilogue", ctypes.c_int), ("aux", ctypes.c_int)]
 
 
 def _load() -> ctypes.CDLL:
@@ -77,6 +83,13 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_waited.argtypes = [p, p, ctypes.POINTER(ctypes.c_ulonglong)]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
+    lib.rb_block_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
+    lib.rb_block_workspace_bytes.restype = z
+    lib.rb_block_prepare.argtypes = [ctypes.POINTER(rb_layer), i, ctypes.POINTER(ctypes.c_void_p), i, ctypes.c_float,
+                                     ctypes.POINTER(rb_block_op), i, ctypes.POINTER(ctypes.c_void_p), i, i, p, z, p]
+    lib.rb_rmsnorm.argtypes = [p, p, p, i, i, ctypes.c_float, p]
+    lib.rb_silu_mul.argtypes = [p, p, p, z, p]
+    lib.rb_add.argtypes = [p, p, p, z, p]
     lib.rb_couple.argtypes = [p, p, p, i, i, i, p, p, p, p]
     lib.rb_weight_grad.argtypes = [p, p, i, i, i, p, p]
     lib.rb_scale_grads_workspace_bytes.argtypes = [i, i, i]
@@ -89,7 +102,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_last_path.argtypes = []
     for name in EXPORTS:
         if name not in ("rb_native_bytes", "rb_workspace_bytes", "rb_noalloc_scratch_bytes",
-                        "rb_scale_grads_workspace_bytes"):
+                        "rb_scale_grads_workspace_bytes", "rb_block_workspace_bytes"):
             getattr(lib, name).restype = i
     return lib
 
@@ -285,6 +298,66 @@ class Stack:
 
     def forget(self) -> None:
         _check("rb_stack_forget", lib.rb_stack_forget(self.ws.data_ptr()))
+
+
+RB_EPI_NONE, RB_EPI_ADD, RB_EPI_SILU_MUL = 0, 1, 2
+
+
+class Block(Stack):
+    """Marshalled arguments of rb_block_prepare; run, status, waited and forget are the stack's."""
+
+    def __init__(self, layers: Sequence[Layer], norm_weights: Sequence[torch.Tensor], eps: float,
+                 ops: Sequence[Tuple[int, int, int, int, int, int]], bufs: Sequence[torch.Tensor], T: int):
+        self.layers, self.bufs, self.T = list(layers), list(bufs), T
+        self.norm_weights, self.eps = list(norm_weights), float(eps)
+        for b in self.bufs + self.norm_weights:
+            assert b.is_cuda and b.dtype == torch.float16 and b.is_contiguous()
+        self._layers = _layer_array(self.layers)
+        self._ops = (rb_block_op * len(ops))(*[rb_block_op(*o) for o in ops])
+        self._bufs = (ctypes.c_void_p * len(bufs))(*[b.data_ptr() for b in self.bufs])
+        self._norms = (ctypes.c_void_p * max(len(self.norm_weights), 1))(*[w.data_ptr() for w in self.norm_weights])
+        self.n_ops = len(ops)
+        self.ws_bytes = int(lib.rb_block_workspace_bytes(self._layers, len(self.layers), self.n_ops, T))
+        self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=self.bufs[0].device)
+
+    def run(self) -> None:
+        self.prepare()
+        self.run_prepared()
+
+    def prepare(self) -> None:
+        """rb_block_prepare: everything that does not depend on the activations."""
+        _check("rb_block_prepare", lib.rb_block_prepare(
+            self._layers, len(self.layers), self._norms, len(self.norm_weights), self.eps, self._ops, self.n_ops,
+            self._bufs, len(self.bufs), self.T, self.ws.data_ptr(), self.ws_bytes, _stream()))
+
+
+def rb_rmsnorm(x: torch.Tensor, w: torch.Tensor, eps: float, y: torch.Tensor = None) -> torch.Tensor:
+    """y[t] = x[t] / sqrt(mean(x[t]^2) + eps) * w for fp16 x [T][n]."""
+    assert x.is_cuda and x.dtype == torch.float16 and x.is_contiguous() and x.dim() == 2
+    assert w.dtype == torch.float16 and w.numel() == x.shape[1]
+    if y is None:
+        y = torch.empty_like(x)
+    _check("rb_rmsnorm", lib.rb_rmsnorm(x.data_ptr(), w.data_ptr(), y.data_ptr(), x.shape[0], x.shape[1], float(eps),
+                                        _stream()))
+    return y
+
+
+def rb_silu_mul(gate: torch.Tensor, up: torch.Tensor, y: torch.Tensor = None) -> torch.Tensor:
+    assert gate.is_cuda and gate.dtype == torch.float16 and up.dtype == torch.float16
+    assert gate.is_contiguous() and up.is_contiguous() and gate.shape == up.shape
+    if y is None:
+        y = torch.empty_like(gate)
+    _check("rb_silu_mul", lib.rb_silu_mul(gate.data_ptr(), up.data_ptr(), y.data_ptr(), gate.numel(), _stream()))
+    return y
+
+
+def rb_add(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor = None) -> torch.Tensor:
+    assert a.is_cuda and a.dtype == torch.float16 and b.dtype == torch.float16
+    assert a.is_contiguous() and b.is_contiguous() and a.shape == b.shape
+    if y is None:
+        y = torch.empty_like(a)
+    _check("rb_add", lib.rb_add(a.data_ptr(), b.data_ptr(), y.data_ptr(), a.numel(), _stream()))
+    return y
 
 
 def rb_layer_stack(layers: Sequence[Layer], ops: Sequence[Tuple[int, int, int]],

@@ -74,6 +74,11 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *ops, int n_ops, uint
                  void *workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_plan(void *workspace, size_t workspace_bytes, hipStream_t stream);
 void forget_plan(const void *workspace);
+// decoder blocks (norms, gate times up, residual additions in the kernel's finishing step); run,
+// checked and forgotten like any other plan of this kernel
+size_t block_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
+int prepare_block(const rb_layer *layers, const uint16_t *const *norm_w, float eps, const rb_block_op *ops, int n_ops,
+                  uint16_t *const *bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
 // waits for the stream; RB_ERR_HANDOVER if a run of this plan gave up a wait, RB_ERR_WORKSPACE: no plan
 // waited (optional): += input tiles that compute wavefronts found not yet written and waited for, since the plan was made
 int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);

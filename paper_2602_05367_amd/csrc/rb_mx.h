@@ -117,7 +117,23 @@ struct Op {
     int stage_op0;            // first op of the stage this op belongs to
     float sc[RB_MAX_K];       // power-of-two input scale per path (max |h| * sc <= 1/2)
     float inv_sc[RB_MAX_K];
+    // ---- the decoder block around the layer (all unused, zero, in a plain stack)
+    int pos;                  // which rotation of the workgroups the row tiles are dealt by (position in the stage)
+    int slot0;                // first finishing slot of this op in every workgroup (< 0: right after the op before it)
+    int role;                 // ROLE_*
+    int resid_kind;           // RESID_*
+    const uint16_t *norm_w;   // fp16 [in]: the input is normalised (root mean square) and multiplied by this
+    const float *ssq_in;      // [4][n_part]: per token, sums of squares of 16 input rows each
+    float *ssq_out;           // [4][RT]: the same of this op's output, for readers that normalise it
+    uint32_t *rcopy;          // [T][out]: the fp16 output once more, one word each, for an op that adds it later
+    const void *resid;        // what is added to the result: fp16 [T][out] of the caller or another op's rcopy
+    int n_part;
+    float eps;
 };
+// the gate and the up projection of a feed-forward part run as two ops of one stage whose row tiles
+// meet in the two halves of a finishing wavefront: y = silu(gate) * up leaves through the gate op
+constexpr int ROLE_PLAIN = 0, ROLE_GATE = 1, ROLE_UP = 2;
+constexpr int RESID_NONE = 0, RESID_CALLER = 1, RESID_COPY = 2;
 
 // What a compute wavefront does, step by step (one step = one 1 KB sign tile), written out once per
 // plan so that the kernel's loop is a walk over two lists and not a search through op tables:
@@ -162,6 +178,19 @@ struct SlotVals {
 };
 static_assert(sizeof(SlotVals) == 768 && 12 >= 3 + 3 * MAX_CONS, "48 bytes per row");
 
+// More per slot, read only by the form of the kernel that runs decoder blocks.
+struct SlotExt {
+    uint64_t resid;           // element (token 0, row 0 of the op) of what is added to the result
+    uint64_t ssq_in;          // sums of squares of the input, [4][n_part]
+    uint64_t ssq_out;         // this row tile's entry of the op's own sums of squares (0: nobody reads them)
+    uint64_t rcopy;           // element (token 0, row 0) of the op's copy of its output (0: none)
+    int n_part, role, resid_kind;
+    float inv_n, eps;         // 1 / in
+    int ssq_stride;           // entries per token of the op's own sums of squares
+    int pad_[2];
+};
+static_assert(sizeof(SlotExt) == 64, "four 16-byte loads");
+
 struct Stage {
     int op0, nops;            // ops [op0, op0 + nops) are independent of each other
     int n_deps;               // ops of this stage whose input an earlier stage of the launch writes
@@ -181,8 +210,11 @@ struct Header {
 //            [indices of the ops whose input is expanded by a kernel of its own]
 //            [sign lists, operand lists: blocks x n_groups x cwaves_of(T) each]
 //            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
+//            decoder blocks: [SlotExt x the same][sums of squares and output copies of ops]
+//                            [sums of squares of inputs from outside]
 struct Layout {
-    size_t ops, stages, error, zero, which, sdesc, odesc, slots, vals, up, total;
+    size_t ops, stages, error, zero, which, sdesc, odesc, slots, vals, up, ext, aux, total;
+    size_t aux_poison;        // bytes at the start of aux that every launch marks as not yet written
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

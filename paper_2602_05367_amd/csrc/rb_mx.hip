@@ -66,6 +66,13 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
     return (uint32_t)(size_t)RB_LDS(p);
 }
 
+// weight of the normalisation in front of the op at input column j (1 where there is none): it is
+// folded into the op's input scales
+__device__ __forceinline__ float norm_weight(const Op &op, int j)
+{
+    return op.norm_w ? __half2float(reinterpret_cast<const __half *>(op.norm_w)[j]) : 1.f;
+}
+
 // ------------------------------------------------------------ prep kernel ---
 // One workgroup per op: power-of-two scale of each path's input scales and the zero fill of the
 // expanded-input array (padding columns and unused operand columns must read as zero).
@@ -77,7 +84,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
     for (int p = 0; p < op.K; ++p) {
         float m = 0.f;
         for (int j = threadIdx.x; j < op.in; j += 256)
-            m = fmaxf(m, fabsf(__half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j])));
+            m = fmaxf(m, fabsf(__half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]) * norm_weight(op, j)));
         red[threadIdx.x] = m;
         __syncthreads();
         for (int s = 128; s > 0; s >>= 1) {
@@ -138,7 +145,8 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
             const Op &op = ops[o];
             const uint32_t CT = (uint32_t)op.CT;
             uint32_t rt0, nrt;
-            group_rows((uint32_t)op.RT, grp, G, o - stage.op0, rt0, nrt);
+            group_rows((uint32_t)op.RT, grp, G, op.pos, rt0, nrt);
+            if (op.slot0 >= 0) slot_base = (uint32_t)op.slot0;
             // Run `run` of the share goes to this wavefront.  Runs differ by one tile when CW does not
             // divide the share, and the longer ones sit at the same positions for every op of equal
             // shape; dealing op number n of the stage from wavefront n on spreads them.  The partial
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
 // Second set-up pass (needs the scales of every op): the tables of the finishing wavefronts.
 // One workgroup per (stage, pair of workgroups of the stack kernel); a thread per (slot, row).
 __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *ops, const Stage *stages,
-                                                   SlotRec *slots, SlotVals *vals)
+                                                   SlotRec *slots, SlotVals *vals, SlotExt *ext)
 {
     const int G = hdr->n_groups, T = hdr->T;
     const int st = blockIdx.x;
@@ -180,7 +188,7 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
         uint32_t tiles = 0;
         for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
             uint32_t rt0, nrt;
-            group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, o - stage.op0, rt0, nrt);
+            group_rows((uint32_t)ops[o].RT, (uint32_t)gg, (uint32_t)G, ops[o].pos, rt0, nrt);
             tiles += nrt * (uint32_t)ops[o].CT;
         }
         return tiles;
@@ -201,7 +209,8 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     int my_op = -1, row0 = 0, slot_base = 0;
     for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
         uint32_t rt0, nrt;
-        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, o - stage.op0, rt0, nrt);
+        group_rows((uint32_t)ops[o].RT, (uint32_t)grp, (uint32_t)G, ops[o].pos, rt0, nrt);
+        if (ops[o].slot0 >= 0) slot_base = ops[o].slot0;
         if (slot >= slot_base && slot < slot_base + (int)nrt) {
             my_op = o;
             row0 = (int)(rt0 + (uint32_t)(slot - slot_base)) * 16;
@@ -215,9 +224,18 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
     for (int c = 0; c < MAX_CONS; ++c) sr.up[c] = 0;
     float v[12];
     for (int i = 0; i < 12; ++i) v[i] = 0.f;
+    SlotExt sx;
+    sx.resid = 0; sx.ssq_in = 0; sx.ssq_out = 0; sx.rcopy = 0; sx.n_part = 0; sx.role = ROLE_PLAIN;
+    sx.resid_kind = RESID_NONE; sx.inv_n = 0.f; sx.eps = 0.f; sx.ssq_stride = 0; sx.pad_[0] = sx.pad_[1] = 0;
     if (my_op >= 0) {
         const Op &op = ops[my_op];
         const int grow = row0 + row;
+        sx.resid = (uint64_t)op.resid; sx.resid_kind = op.resid_kind;
+        sx.ssq_in = (uint64_t)op.ssq_in; sx.n_part = op.ssq_in ? op.n_part : 0;
+        sx.ssq_out = op.ssq_out ? (uint64_t)(op.ssq_out + row0 / 16) : 0;
+        sx.ssq_stride = op.RT;
+        sx.rcopy = (uint64_t)op.rcopy;
+        sx.role = op.role; sx.inv_n = 1.f / (float)op.in; sx.eps = op.eps;
         sr.y = (uint64_t)op.y;
         sr.out = op.out; sr.n_cons = op.n_cons; sr.row0 = row0; sr.op = my_op;
         const bool valid = grow < op.out;
@@ -232,14 +250,18 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
             sr.up[c] = (uint64_t)(m.up + up_group_offset(T, row0, 0));
             const __half *h = reinterpret_cast<const __half *>(m.h);
             if (valid) {
-                v[2 + 2 * c] = __half2float(h[grow]) * m.sc[0];
-                v[3 + 2 * c] = __half2float(h[(size_t)m.in + grow]) * m.sc[1];
-                if (m.K == 3) v[9 + c] = __half2float(h[2 * (size_t)m.in + grow]) * m.sc[2];
+                const float w = norm_weight(m, grow);
+                v[2 + 2 * c] = __half2float(h[grow]) * w * m.sc[0];
+                v[3 + 2 * c] = __half2float(h[(size_t)m.in + grow]) * w * m.sc[1];
+                if (m.K == 3) v[9 + c] = __half2float(h[2 * (size_t)m.in + grow]) * w * m.sc[2];
             }
         }
     }
     for (int i = 0; i < 12; ++i) vals[idx].v[row][i] = v[i];
-    if (row == 0) slots[idx] = sr;
+    if (row == 0) {
+        slots[idx] = sr;
+        if (ext) ext[idx] = sx;
+    }
 }
 
 // --------------------------------------------------------- expand kernel ---
@@ -255,11 +277,29 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
     const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
     for (int p = 0; p < op.K; ++p) {
         const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
-        const uint32_t terms = expand4(h * x * op.sc[p]);
+        const uint32_t terms = expand4(h * norm_weight(op, j) * x * op.sc[p]);
         // where path p of this token sits in the layout: three paths use token 1's path 0 for path 2
         const int ltok = op.K == 3 ? p >> 1 : tok, lp = op.K == 3 ? p & 1 : p;
 #pragma unroll
         for (int t = 0; t < 4; ++t) op.up[up_offset(T, ltok, lp, t, j)] = (uint8_t)(terms >> (8 * t));
+    }
+}
+
+// Sums of squares of an input from outside that an op normalises: 16 columns per entry, [token][entry], as the
+// finishing wavefronts file them for inputs written inside a launch.  One workgroup per (op, token).
+__global__ __launch_bounds__(256) void ssq_kernel(const Op *ops, const int *which)
+{
+    const Op &op = ops[which[blockIdx.x]];
+    if (!op.norm_w || op.dep >= 0) return;
+    const int tok = blockIdx.y;
+    float *out = const_cast<float *>(op.ssq_in);
+    for (int e = threadIdx.x; e < op.n_part; e += 256) {
+        float sum = 0.f;
+        for (int j = 16 * e; j < min(16 * e + 16, op.in); ++j) {
+            const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
+            sum += x * x;
+        }
+        out[(size_t)tok * op.n_part + e] = sum;
     }
 }
 
@@ -268,8 +308,15 @@ __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op
 // columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  POISON_SPLIT
 // workgroups per op.
 constexpr int POISON_SPLIT = 4;
-__global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T)
+__global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T, int n_ops, uint4 *aux, size_t aux16)
 {
+    if ((int)blockIdx.x == n_ops) {
+        // what finishing wavefronts hand to each other in a decoder block: no sum of squares and
+        // no fp16 value in a word of its own is all ones
+        for (size_t i = blockIdx.y * 256 + threadIdx.x; i < aux16; i += 256 * POISON_SPLIT)
+            aux[i] = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+        return;
+    }
     const Op &op = ops[blockIdx.x];
     if (op.dep < 0) return;
     const int groups = (int)(up_bytes(op.in, T) / 16);
@@ -294,6 +341,13 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// a store that passes the L2 of this XCD (for another XCD's wavefront to read with a device-scope load)
+__device__ __forceinline__ void store_sc1_u32(uint64_t addr, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, off sc1" : : "v"(addr), "v"(v) : "memory");
+}
+constexpr uint32_t BLOCK_POLLS = 0x40000;     // looks at a value another workgroup has yet to write, before giving up
+
 __device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
 {
     return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32) |
@@ -306,7 +360,9 @@ template <int TT> struct BTile { v4i r[kop_of(TT)]; };   // operand of one tile:
 // until it is written), so a producer neither waits for its stores to be acknowledged nor raises a
 // flag, and nobody polls memory for flags.
 // KK = 3 (with TT = 2, the layout; one token of activations): see layout_tokens in rb_mx.h.
-template <int TT, int KK = 2>
+// BLK: the form that runs decoder blocks (normalised inputs, gate times up, residual additions in
+// the finishing wavefronts; the compute wavefronts are the same).
+template <int TT, int KK = 2, bool BLK = false>
 __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *__restrict__ hdr_p,
                                                            const Op *__restrict__ ops,
                                                            const Stage *__restrict__ stages,
@@ -316,9 +372,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const uint32_t *__restrict__ odesc_g,
                                                            uint32_t sblocks, uint32_t oblocks,
                                                            const SlotRec *__restrict__ slots_g,
-                                                           const SlotVals *__restrict__ vals_g, int go_pause)
+                                                           const SlotVals *__restrict__ vals_g, int go_pause,
+                                                           const SlotExt *__restrict__ ext_g)
 {
     static_assert(KK == 2 || (KK == 3 && TT == 2), "three paths use the two-token layout");
+    static_assert(!BLK || KK == 2, "decoder blocks: two paths");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     constexpr int TILE_BYTES = 512 * KK, SL = sign_loads_of(KK);
     using Lds = LdsMap<CW, KK, pairs_of(TT)>;
@@ -878,6 +936,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         struct Fin {
             SlotRec r;
             v4f a, b, c;                    // the row's values (c: the third path's, when there is one)
+            SlotExt x;                      // decoder blocks only
         };
         auto fetch = [&](int st) -> Fin {
             const size_t idx = ((size_t)min(st, n_stages - 1) * G + grp) * MAXSLOT + my_slot;
@@ -888,6 +947,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             f.b = pv[1];
             if constexpr (KK == 3) f.c = pv[2];
             else f.c = (v4f){0.f, 0.f, 0.f, 0.f};
+            if constexpr (BLK) f.x = ext_g[idx];
             if (st >= n_stages) f.r.op = -1;
             return f;
         };
@@ -901,9 +961,96 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 const uint32_t a = ready_lds + (uint32_t)(((st + 1) & 1) * 8);
                 asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(0u) : "memory");
             }
-            lds_barrier();                                    // partial sums complete
             const bool have_slot = cur.r.op >= 0;
             const int grow = cur.r.row0 + row;
+            // ---- decoder blocks: what the epilogue takes from other workgroups' finishing
+            // wavefronts is fetched while the compute wavefronts work.  Both are marked "not yet
+            // written" (all ones) before the launch and looked at until they are not.
+            [[maybe_unused]] float rinv[pairs_of(TT)], radd[pairs_of(TT)];
+#pragma unroll
+            for (int pr = 0; pr < pairs_of(TT); ++pr) { rinv[pr] = 1.f; radd[pr] = 0.f; }
+            if constexpr (BLK) {
+                const int tok_in_pair = TT == 1 ? 0 : tok;
+                // 1 / root mean square of the input, per token: the sums of squares of 16 columns
+                // each, added up by the 32 lanes of this slot's half in a fixed order
+                const int n_part = have_slot ? cur.x.n_part : 0;
+                // the residual stream's values at this lane's row
+                const int kind = have_slot && grow < cur.r.out ? cur.x.resid_kind : RESID_NONE;
+                if (__any(n_part > 0 || kind != RESID_NONE)) {
+                    // not before this stage's inputs have been announced: a look that comes too
+                    // early costs a trip to memory and back
+                    if (st > 0) {
+                        const uint32_t go_word = ready_lds + (uint32_t)((st & 1) * 8);
+                        for (int spins = 0; spins < (1 << 22); ++spins) {
+                            uint32_t v;
+                            asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(go_word) : "memory");
+                            if (__builtin_amdgcn_readfirstlane((int)v) != 0) break;
+                            __builtin_amdgcn_s_sleep(2);
+                        }
+                    }
+                    v4f tot;
+                    // sums of squares come two at a time (their number is even: in % 32 == 0), four
+                    // loads per lane in flight
+                    const int n2 = n_part >> 1;
+                    for (uint32_t left = BLOCK_POLLS;;) {
+                        tot = (v4f){0.f, 0.f, 0.f, 0.f};
+                        bool unwritten = false;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            if (t < tokens) {
+                                const auto *row_t = RB_GLOBAL(const uint64_t, cur.x.ssq_in) + (size_t)t * n2;
+                                for (int base = 0; base < n2; base += 128) {
+                                    uint64_t two[4];
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u) {
+                                        const int i = base + 32 * u + (lane & 31);
+                                        two[u] = i < n2 ? __hip_atomic_load(row_t + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                                    }
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u) {
+                                        const uint32_t lo = (uint32_t)two[u], hi = (uint32_t)(two[u] >> 32);
+                                        unwritten |= lo == 0xffffffffu || hi == 0xffffffffu;
+                                        tot[t] += __uint_as_float(lo) + __uint_as_float(hi);
+                                    }
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int pr = 0; pr < pairs_of(TT); ++pr) {
+                            const int tk = 2 * pr + tok_in_pair;
+                            const size_t e = (size_t)tk * cur.r.out + grow;
+                            if (kind == RESID_CALLER && tk < tokens) radd[pr] = (float)RB_GLOBAL(_Float16, cur.x.resid)[e];
+                            if (kind == RESID_COPY && tk < tokens) {
+                                const uint32_t word = __hip_atomic_load(RB_GLOBAL(const uint32_t, cur.x.resid) + e, __ATOMIC_RELAXED,
+                                                                        __HIP_MEMORY_SCOPE_AGENT);
+                                unwritten |= word == 0xffffffffu;
+                                radd[pr] = (float)__builtin_bit_cast(_Float16, (uint16_t)word);
+                            }
+                        }
+                        if (!__any(unwritten)) break;
+                        if (--left == 0) {
+                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+                    // 1 / root mean square of the input, per token: the 32 lanes of this slot's half
+                    // add up their shares in a fixed order
+                    if (__any(n_part > 0)) {
+#pragma unroll
+                        for (int m = 1; m < 32; m <<= 1)
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) tot[t] += __shfl_xor(tot[t], m);
+#pragma unroll
+                        for (int pr = 0; pr < pairs_of(TT); ++pr) {
+                            const int tk = 2 * pr + tok_in_pair;
+                            const float sum = tk == 0 ? tot[0] : tk == 1 ? tot[1] : tk == 2 ? tot[2] : tot[3];
+                            if (n_part > 0 && tk < tokens) rinv[pr] = rsqrtf(sum * cur.x.inv_n + cur.x.eps);
+                        }
+                    }
+                }
+            }
+            lds_barrier();                                    // partial sums complete
             // One token: the lanes of a row's second-token position are free, so the two lanes of a
             // row split the paths between them (sub = which path) for the sums and the expansion.
             constexpr bool SPLIT = TT == 1;
@@ -925,7 +1072,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 #pragma unroll
             for (int pair = 0; pair < PAIRS; ++pair) {
             const bool active = have_slot && (SPLIT || KK == 3 || 2 * pair + tok < tokens) && grow < cur.r.out;
-            float yf = 0.f;
+            float yf = 0.f, ysum = 0.f;
             // partial sums of this lane's row: [run][token pair][path][token][row]
             float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * (64 * PAIRS) + pair * 64 + (SPLIT ? 0 : tok * 16) + row;
             if (active) {
@@ -945,12 +1092,39 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         s1 += P[w * (64 * PAIRS) + 32];
                     }
                 }
-                float ysum = path_sum(g_a, s0, g_b, s1);
+                ysum = path_sum(g_a, s0, g_b, s1);
                 if constexpr (KK == 3) ysum += __shfl_xor(ysum, 16);       // paths 0 and 1 in one lane of the row, path 2 in the other
+            }
+            if constexpr (BLK) {
+                ysum *= rinv[pair];                                          // the input was x / rms(x) (.) w
+                const int role = have_slot ? cur.x.role : ROLE_PLAIN;
+                if (__any(role != ROLE_PLAIN)) {
+                    // the same rows of the up projection sit in the other half of the wavefront
+                    const float other = __shfl_xor(ysum, 32);
+                    if (role == ROLE_GATE) ysum = ysum / (1.f + __expf(-ysum)) * other;
+                }
+                ysum += radd[pair];
+            }
+            if (active) {
                 const _Float16 y16 = (_Float16)ysum;                         // round to nearest even
-                if (KK == 3 ? tok == 0 : (!SPLIT || sub == 0))
-                    RB_GLOBAL(_Float16, cur.r.y)[(size_t)((SPLIT || KK == 3) ? 0 : 2 * pair + tok) * cur.r.out + grow] = y16;
+                const bool writes = (KK == 3 ? tok == 0 : (!SPLIT || sub == 0)) && (!BLK || cur.x.role != ROLE_UP);
+                const size_t e = (size_t)((SPLIT || KK == 3) ? 0 : 2 * pair + tok) * cur.r.out + grow;
+                if (writes) RB_GLOBAL(_Float16, cur.r.y)[e] = y16;
                 yf = (float)y16;
+                if constexpr (BLK)
+                    if (writes && cur.x.rcopy != 0) store_sc1_u32(cur.x.rcopy + e * 4u, (uint32_t)__builtin_bit_cast(uint16_t, y16));
+            }
+            if constexpr (BLK) {
+                // this row tile's sum of squares, for the ops that normalise what they read
+                const bool files = have_slot && cur.x.ssq_out != 0;
+                if (__any(files)) {
+                    float sq = yf * yf;
+#pragma unroll
+                    for (int m = 1; m < 16; m <<= 1) sq += __shfl_xor(sq, m);
+                    const int tk = SPLIT ? 0 : 2 * pair + tok;
+                    if (files && row == 0 && (!SPLIT || sub == 0) && tk < tokens)
+                        store_sc1_u32(cur.x.ssq_out + (uint64_t)tk * (uint32_t)cur.x.ssq_stride * 4u, __float_as_uint(sq));
+                }
             }
             // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
             // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
@@ -1052,7 +1226,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 
 // ------------------------------------------------------------------ host ---
 static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, size_t up_total,
-                          size_t sblocks, size_t oblocks)
+                          size_t sblocks, size_t oblocks, bool block = false, size_t aux_poison = 0, size_t aux_rest = 0)
 {
     Layout L;
     size_t o = sizeof(Header);
@@ -1066,6 +1240,12 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, siz
     o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
     o = align_up(o, 256); L.up = o; o += up_total;
+    L.ext = L.aux = o; L.aux_poison = 0;
+    if (block) {
+        o = align_up(o, 128); L.ext = o; o += sizeof(SlotExt) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+        o = align_up(o, 256); L.aux = o; o += align_up(aux_poison, 256) + align_up(aux_rest, 256);
+        L.aux_poison = align_up(aux_poison, 256);
+    }
     L.total = align_up(o, 256);
     return L;
 }
@@ -1088,7 +1268,18 @@ bool layer_supported(const rb_layer *L, int T)
     return ((L->K == 2 && T >= 1 && T <= MAX_T) || (L->K == 3 && T == 1)) && L->in % 32 == 0 && L->in <= 65536;
 }
 
-size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T_in)
+// per op of a decoder block, at most: sums of squares of its output and of an input from outside,
+// and the copy of its output that a later op adds
+static size_t block_aux_bound(const rb_layer *layers, int n_layers, int tokens)
+{
+    size_t most = 0;
+    for (int l = 0; l < n_layers; ++l)
+        most = std::max(most, align_up((size_t)row_tiles(layers[l].out) * 16, 256) + align_up((size_t)tokens * layers[l].out * 4, 256) +
+                                  align_up((size_t)((layers[l].in + 15) / 16) * 16, 256));
+    return most;
+}
+
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T_in, bool block)
 {
     int T = T_in;
     for (int l = 0; l < n_layers; ++l) T = std::max(T, layout_tokens(T_in, layers[l].K));
@@ -1108,8 +1299,18 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
     }
     const size_t steps = per_op * (size_t)n_ops;
     return make_layout(n_ops, n_ops, G, (int)CW, align_up(up_max, 256) * (size_t)n_ops,
-                       desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)))
+                       desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)),
+                       block, block ? block_aux_bound(layers, n_layers, T_in) * (size_t)n_ops : 0, 0)
         .total;
+}
+size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
+{
+    return plan_workspace_bytes(layers, n_layers, n_ops, T, false);
+}
+// a gate-times-up op of the caller is two ops of the plan
+size_t block_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
+{
+    return plan_workspace_bytes(layers, n_layers, 2 * n_ops, T, true);
 }
 
 // Host record of a prepared plan, keyed by the workspace that holds its device part.
@@ -1118,6 +1319,8 @@ struct Prepared {
     int n_ops = 0, n_stages = 0, G = 0, T = 0, K = 2, tokens = 0, max_expand_in = 0, n_expand = 0;   // T: of the operand layout
     uint32_t sblocks = 0, oblocks = 0;      // blocks per step list of a compute wavefront
     bool chained = false;                   // some op reads what another op of the launch writes
+    bool block = false;                     // a decoder block: the kernel form with the epilogues
+    bool ext_norm = false;                  // some op normalises an input from outside
     // host memory the plan's tables are copied from: pageable, so it must outlive the queued copies
     std::shared_ptr<std::vector<uint8_t>> blob;
     std::shared_ptr<std::vector<int>> which;
@@ -1129,15 +1332,26 @@ void set_pause(int clks) { g_pause_clks.store(clks < 0 ? -1 : std::min(clks, 1 <
 static std::mutex g_mutex;
 static std::map<const void *, Prepared> g_prepared;
 
-int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int tokens,
-                 void *workspace, size_t workspace_bytes_, hipStream_t stream)
+// one op of a plan: a layer between two buffers and, in a decoder block, what surrounds it
+struct PlanOp {
+    int layer, src, dst;      // dst < 0: the result leaves through another op (ROLE_UP)
+    int norm;                 // >= 0: which weight vector normalises the input
+    int add;                  // >= 0: the buffer added to the result
+    int role;
+};
+
+static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, uint16_t *const *bufs,
+                       const uint16_t *const *norm_w, float eps, bool block, int tokens, void *workspace,
+                       size_t workspace_bytes_, hipStream_t stream)
 {
     const int G = device_groups();
     if (G <= 0) return RB_ERR_HIP;
+    if (block && tokens > MAX_T) return RB_ERR_UNSUPPORTED;
     // one kernel form per plan: every op has the same number of paths
     const int K = layers[sops[0].layer].K;
     for (int n = 0; n < n_ops; ++n)
         if (layers[sops[n].layer].K != K || !layer_supported(&layers[sops[n].layer], tokens)) return RB_ERR_UNSUPPORTED;
+    if (block && K != 2) return RB_ERR_UNSUPPORTED;
     const int T = layout_tokens(tokens, K);            // tokens of the operand layout
 
     // ---- ops, consumers, stages
@@ -1145,6 +1359,8 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     std::vector<int> expand_list;
     size_t up_total = 0;
     std::vector<size_t> up_off((size_t)n_ops);
+    std::vector<bool> need_ssq((size_t)n_ops, false), need_rcopy((size_t)n_ops, false);
+    std::vector<int> resid_from((size_t)n_ops, -1);
     for (int n = 0; n < n_ops; ++n) {
         const rb_layer &L = layers[sops[n].layer];
         Op &o = ops[(size_t)n];
@@ -1152,7 +1368,11 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         o.bits = static_cast<const uint32_t *>(L.bits);
         o.g = L.g; o.h = L.h;
         o.x = bufs[sops[n].src];
-        o.y = bufs[sops[n].dst];
+        o.y = sops[n].dst >= 0 ? bufs[sops[n].dst] : nullptr;
+        o.slot0 = -1;
+        o.role = sops[n].role;
+        o.norm_w = sops[n].norm >= 0 ? norm_w[sops[n].norm] : nullptr;
+        o.eps = eps;
         o.out = L.out; o.in = L.in; o.K = L.K;
         o.RT = row_tiles(L.out); o.CT = col_tiles(L.in);
         up_off[(size_t)n] = up_total;
@@ -1162,6 +1382,25 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         for (int m = n - 1; m >= 0; --m)
             if (sops[m].dst == sops[n].src) { producer = m; break; }
         o.dep = producer;
+        if (o.norm_w) {
+            o.n_part = (L.in + 15) / 16;
+            if (producer >= 0) need_ssq[(size_t)producer] = true;
+        }
+        // what is added: the caller's buffer as it was before the launch, or what an earlier op wrote there
+        if (sops[n].add >= 0) {
+            int writer = -1;
+            for (int m = n - 1; m >= 0; --m)
+                if (sops[m].dst == sops[n].add) { writer = m; break; }
+            if (writer >= 0) {
+                if (ops[(size_t)writer].out != L.out) return RB_ERR_SHAPE;
+                need_rcopy[(size_t)writer] = true;
+                resid_from[(size_t)n] = writer;
+                o.resid_kind = RESID_COPY;
+            } else {
+                o.resid = bufs[sops[n].add];
+                o.resid_kind = RESID_CALLER;
+            }
+        }
         if (producer < 0) {
             o.expand_x = 1;
             expand_list.push_back(n);
@@ -1181,12 +1420,27 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             int slots = 0;
             for (int n = op0; n < n_ops; ++n) {
                 bool conflict = false;
-                for (int m = op0; m < n; ++m)
-                    if (sops[m].dst == sops[n].src || sops[m].dst == sops[n].dst || sops[m].src == sops[n].dst)
+                for (int m = op0; m < n; ++m) {
+                    if (sops[m].dst < 0 || sops[n].dst < 0) continue;
+                    if (sops[m].dst == sops[n].src || sops[m].dst == sops[n].dst || sops[m].src == sops[n].dst ||
+                        sops[m].dst == sops[n].add || sops[m].add == sops[n].dst)
                         conflict = true;
+                }
                 const int per_group = (ops[(size_t)n].RT + G - 1) / G;
                 if (per_group > MAXSLOT) return RB_ERR_UNSUPPORTED;
+                if (sops[n].role == ROLE_GATE) {
+                    // gate and up: a stage of their own; the row tiles of the two are dealt alike and
+                    // finish in the two halves of the same wavefronts (slots s and s + 4)
+                    if (n > op0) break;
+                    if (per_group > MAXSLOT / 2) return RB_ERR_UNSUPPORTED;
+                    ops[(size_t)n].slot0 = 0;
+                    ops[(size_t)n + 1].slot0 = MAXSLOT / 2;
+                    if (ops[(size_t)n].dep >= 0) s.n_deps += 2;
+                    s.nops = 2;
+                    break;
+                }
                 if (conflict || slots + per_group > MAXSLOT) break;
+                ops[(size_t)n].pos = n - op0;
                 if (ops[(size_t)n].dep >= 0) ++s.n_deps;
                 slots += per_group;
                 ++s.nops;
@@ -1201,7 +1455,7 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     pr.n_ops = n_ops; pr.n_stages = (int)stages.size(); pr.G = G; pr.T = T; pr.K = K; pr.tokens = tokens;
     pr.n_expand = (int)expand_list.size();
     for (int n : expand_list) pr.max_expand_in = std::max(pr.max_expand_in, ops[(size_t)n].in);
-    for (int n = 0; n < n_ops; ++n) pr.chained = pr.chained || ops[(size_t)n].dep >= 0;
+    for (int n = 0; n < n_ops; ++n) pr.chained = pr.chained || ops[(size_t)n].dep >= 0 || resid_from[(size_t)n] >= 0;
     // an upper bound on the step list of a compute wavefront: the largest share of every op, cut in
     // CW runs, rounded up (the exact maximum over workgroups and wavefronts costs more host time than
     // the few blocks it saves)
@@ -1216,11 +1470,37 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
         pr.sblocks = desc_blocks((uint32_t)(longest + RING_D));
         pr.oblocks = desc_blocks((uint32_t)(longest + (size_t)nb_of(T) * (size_t)pr.n_stages));
     }
-    pr.lay = make_layout(n_ops, pr.n_stages, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks);
+    // decoder blocks: what finishing wavefronts hand to each other (marked unwritten before every
+    // launch), then the sums of squares of inputs from outside
+    std::vector<size_t> ssq_off((size_t)n_ops, 0), rcopy_off((size_t)n_ops, 0), ext_off((size_t)n_ops, 0);
+    size_t aux_poison = 0, aux_rest = 0;
+    for (int n = 0; n < n_ops && block; ++n) {
+        if (need_ssq[(size_t)n]) { ssq_off[(size_t)n] = aux_poison; aux_poison += align_up((size_t)ops[(size_t)n].RT * 16, 256); }
+        if (need_rcopy[(size_t)n]) { rcopy_off[(size_t)n] = aux_poison; aux_poison += align_up((size_t)tokens * ops[(size_t)n].out * 4, 256); }
+        if (ops[(size_t)n].norm_w && ops[(size_t)n].dep < 0) {
+            ext_off[(size_t)n] = aux_rest;
+            aux_rest += align_up((size_t)ops[(size_t)n].n_part * 16, 256);
+            pr.ext_norm = true;
+        }
+    }
+    pr.block = block;
+    pr.lay = make_layout(n_ops, pr.n_stages, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks, block, aux_poison, aux_rest);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     for (int n = 0; n < n_ops; ++n) ops[(size_t)n].up = ws + lay.up + up_off[(size_t)n];
+    for (int n = 0; n < n_ops && block; ++n) {
+        Op &o = ops[(size_t)n];
+        if (need_ssq[(size_t)n]) o.ssq_out = reinterpret_cast<float *>(ws + lay.aux + ssq_off[(size_t)n]);
+        if (need_rcopy[(size_t)n]) o.rcopy = reinterpret_cast<uint32_t *>(ws + lay.aux + rcopy_off[(size_t)n]);
+    }
+    for (int n = 0; n < n_ops && block; ++n) {
+        Op &o = ops[(size_t)n];
+        if (o.norm_w)
+            o.ssq_in = o.dep >= 0 ? ops[(size_t)o.dep].ssq_out
+                                  : reinterpret_cast<const float *>(ws + lay.aux + lay.aux_poison + ext_off[(size_t)n]);
+        if (resid_from[(size_t)n] >= 0) o.resid = ops[(size_t)resid_from[(size_t)n]].rcopy;
+    }
 
     Header hdr{};
     hdr.n_ops = n_ops; hdr.n_stages = pr.n_stages; hdr.T = T; hdr.n_groups = G; hdr.K = K; hdr.tokens = tokens;
@@ -1253,8 +1533,33 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + 1) / 2), dim3(256), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
-                       reinterpret_cast<SlotVals *>(ws + lay.vals));
+                       reinterpret_cast<SlotVals *>(ws + lay.vals), block ? reinterpret_cast<SlotExt *>(ws + lay.ext) : nullptr);
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+}
+
+int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uint16_t *const *bufs, int tokens,
+                 void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    std::vector<PlanOp> pops((size_t)n_ops);
+    for (int n = 0; n < n_ops; ++n) pops[(size_t)n] = PlanOp{sops[n].layer, sops[n].src, sops[n].dst, -1, -1, ROLE_PLAIN};
+    return prepare_any(layers, pops.data(), n_ops, bufs, nullptr, 0.f, false, tokens, workspace, workspace_bytes_, stream);
+}
+
+int prepare_block(const rb_layer *layers, const uint16_t *const *norm_w, float eps, const rb_block_op *bops, int n_bops,
+                  uint16_t *const *bufs, int tokens, void *workspace, size_t workspace_bytes_, hipStream_t stream)
+{
+    std::vector<PlanOp> pops;
+    for (int n = 0; n < n_bops; ++n) {
+        const rb_block_op &b = bops[n];
+        if (b.epilogue == RB_EPI_SILU_MUL) {
+            pops.push_back(PlanOp{b.layer, b.src, b.dst, b.norm, -1, ROLE_GATE});
+            pops.push_back(PlanOp{b.aux, b.src, -1, b.norm, -1, ROLE_UP});
+        } else {
+            pops.push_back(PlanOp{b.layer, b.src, b.dst, b.norm, b.epilogue == RB_EPI_ADD ? b.aux : -1, ROLE_PLAIN});
+        }
+    }
+    return prepare_any(layers, pops.data(), (int)pops.size(), bufs, norm_w, eps, true, tokens, workspace, workspace_bytes_,
+                       stream);
 }
 
 int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
@@ -1274,8 +1579,12 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     if (pr.n_expand > 0)
         hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.tokens, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
+    if (pr.ext_norm)
+        hipLaunchKernelGGL(ssq_kernel, dim3((unsigned)pr.n_expand, pr.tokens), dim3(256), 0, stream, d_ops,
+                           reinterpret_cast<const int *>(ws + lay.which));
     if (pr.chained)
-        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops, POISON_SPLIT), dim3(256), 0, stream, d_ops, pr.T);
+        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops + (lay.aux_poison ? 1 : 0), POISON_SPLIT), dim3(256), 0, stream, d_ops,
+                           pr.T, pr.n_ops, reinterpret_cast<uint4 *>(ws + lay.aux), lay.aux_poison / 16);
     const int pause_clks = g_pause_clks.load();
     const int go_pause = pause_clks < 0 ? -1 : pause_clks / 64;      // s_sleep units
     auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
@@ -1288,10 +1597,13 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
                            pr.sblocks, pr.oblocks,
                            reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals),
-                           go_pause);
+                           go_pause, pr.block ? reinterpret_cast<const SlotExt *>(ws + lay.ext) : nullptr);
         return RB_OK;
     };
-    const int rc = pr.K == 3   ? launch(stack_kernel<2, 3>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)
+    const int rc = pr.block    ? (pr.T == 1   ? launch(stack_kernel<1, 2, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+                                  : pr.T == 2 ? launch(stack_kernel<2, 2, true>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES)
+                                              : launch(stack_kernel<4, 2, true>, threads_of(4), LdsMap<cwaves_of(4), 2, 2>::BYTES))
+                   : pr.K == 3 ? launch(stack_kernel<2, 3>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)
                    : pr.T == 1 ? launch(stack_kernel<1>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
                    : pr.T == 2 ? launch(stack_kernel<2>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES)
                                : launch(stack_kernel<4>, threads_of(4), LdsMap<cwaves_of(4), 2, 2>::BYTES);

@@ -20,6 +20,7 @@ from .workloads import (  # noqa: F401
     gaussian_weight,
     StackOp,
     llama_stack,
+    llama_block_stack,
     LLAMA_SHAPES,
     single_layer_config,
     prefill_shapes,

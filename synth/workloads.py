@@ -96,6 +96,64 @@ def llama_stack(which: str, n_layers: int | None = None) -> Tuple[List[StackOp],
     return ops, widths
 
 
+@dataclass(frozen=True)
+class BlockOp:
+    """One op of a decoder block: layer `layer` between buffers `src` and `dst`; `norm` >= 0: the
+    input is normalised with that weight vector first; `epilogue` 0: nothing, 1: buffer `aux` is
+    added, 2: the op is gate-times-up and `aux` is the layer of the up projection."""
+    name: str
+    layer: int
+    src: int
+    dst: int
+    norm: int
+    epilogue: int
+    aux: int
+
+
+def llama_block_stack(which: str, n_layers: int, in_place: bool = False
+                      ) -> Tuple[List[BlockOp], List[Tuple[str, int, int]], List[int], List[int]]:
+    """The linear layers of a Llama-shaped decoder with what sits between them, attention left out.
+
+    Per block: q, k, v read the normalised block input x; o reads v's output and x is added to it;
+    gate and up read the normalised result x1, silu(gate) * up feeds down, and x1 is added to
+    down's output, which is the next block's input.  Returns (ops in issue order, (name, out, in)
+    of every layer, width of every buffer, width of every norm weight); buffer 0 is the stack
+    input.  Every op writes a buffer of its own unless `in_place`, where the residual stream lives
+    in buffer 0 throughout.
+    """
+    d, f, _ = LLAMA_SHAPES[which]
+    ops: List[BlockOp] = []
+    shapes: List[Tuple[str, int, int]] = []
+    widths: List[int] = [d]
+    norms: List[int] = []
+    x = 0
+
+    def new_buf(w: int) -> int:
+        widths.append(w)
+        return len(widths) - 1
+
+    def new_layer(name: str, out: int, inn: int) -> int:
+        shapes.append((name, out, inn))
+        return len(shapes) - 1
+
+    for l in range(n_layers):
+        n1, n2 = len(norms), len(norms) + 1
+        norms += [d, d]
+        for name in ("q", "k"):
+            ops.append(BlockOp(f"l{l}.{name}", new_layer(f"l{l}.{name}", d, d), x, new_buf(d), n1, 0, -1))
+        v = new_buf(d)
+        ops.append(BlockOp(f"l{l}.v", new_layer(f"l{l}.v", d, d), x, v, n1, 0, -1))
+        x1 = x if in_place else new_buf(d)
+        ops.append(BlockOp(f"l{l}.o", new_layer(f"l{l}.o", d, d), v, x1, -1, 1, x))
+        gate, up = new_layer(f"l{l}.gate", f, d), new_layer(f"l{l}.up", f, d)
+        act = new_buf(f)
+        ops.append(BlockOp(f"l{l}.gate_up", gate, x1, act, n2, 2, up))
+        x2 = x1 if in_place else new_buf(d)
+        ops.append(BlockOp(f"l{l}.down", new_layer(f"l{l}.down", d, f), act, x2, -1, 1, x1))
+        x = x2
+    return ops, shapes, widths, norms
+
+
 def single_layer_config() -> Tuple[int, int, int]:
     """(out, in, K) of the small single-layer case."""
     return 2048, 2048, 2

@@ -111,6 +111,38 @@ def test_compute_entry_points_reject_bad_arguments_without_a_gpu():
     assert rb.lib.rb_stream_read(0x10, 24, 0x20, None) == rb.RB_ERR_SHAPE
 
 
+def test_block_entry_points_reject_bad_arguments_without_a_gpu():
+    B = rb.binding.rb_block_op
+    ref = ctypes.byref
+    layers = (rb.binding.rb_layer * 2)(rb.binding.rb_layer(64, 256, 2, 0x1000, 0x2000, 0x3000),
+                                       rb.binding.rb_layer(32, 256, 2, 0x1000, 0x2000, 0x3000))
+    bufs = (ctypes.c_void_p * 3)(0x100, 0x200, 0x300)
+    norms = (ctypes.c_void_p * 1)(0x400)
+    prep = rb.lib.rb_block_prepare
+
+    def call(op, n_norms=1, eps=1e-5, T=1):
+        ops = (B * 1)(op)
+        return prep(layers, 2, norms, n_norms, eps, ops, 1, bufs, 3, T, 0x10000, 1 << 40, None)
+    assert call(B(0, 0, 0, -1, rb.RB_EPI_NONE, -1)) == rb.RB_ERR_SHAPE            # src == dst
+    assert call(B(0, 0, 1, 1, rb.RB_EPI_NONE, -1)) == rb.RB_ERR_SHAPE             # norm index
+    assert call(B(0, 0, 1, 0, rb.RB_EPI_NONE, -1), n_norms=0) == rb.RB_ERR_SHAPE
+    assert call(B(0, 0, 1, -1, 7, -1)) == rb.RB_ERR_SHAPE                         # unknown epilogue
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_ADD, 3)) == rb.RB_ERR_SHAPE              # buffer index of the addend
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_ADD, 0)) == rb.RB_ERR_SHAPE              # adding the op's own input
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_SILU_MUL, 2)) == rb.RB_ERR_SHAPE         # layer index of up
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_SILU_MUL, 1)) == rb.RB_ERR_SHAPE         # gate and up differ in shape
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_NONE, -1), eps=-1.0) == rb.RB_ERR_SHAPE
+    assert call(B(0, 0, 1, -1, rb.RB_EPI_NONE, -1), T=0) == rb.RB_ERR_SHAPE
+    ops = (B * 1)(B(0, 0, 1, -1, rb.RB_EPI_NONE, -1))
+    assert prep(layers, 2, norms, 1, 1e-5, ops, 1, bufs, 3, 1, 0x10000, 16, None) == rb.RB_ERR_WORKSPACE
+    assert prep(None, 2, norms, 1, 1e-5, ops, 1, bufs, 3, 1, 0x10000, 1 << 40, None) == rb.RB_ERR_NULL
+    assert rb.lib.rb_block_workspace_bytes(layers, 2, 1, 1) > rb.lib.rb_workspace_bytes(layers, 2, 1, 1)
+    assert rb.lib.rb_rmsnorm(None, 0x10, 0x20, 1, 8, 1e-5, None) == rb.RB_ERR_NULL
+    assert rb.lib.rb_rmsnorm(0x10, 0x10, 0x20, 0, 8, 1e-5, None) == rb.RB_ERR_SHAPE
+    assert rb.lib.rb_silu_mul(0x10, None, 0x20, 8, None) == rb.RB_ERR_NULL
+    assert rb.lib.rb_add(0x10, 0x10, 0x20, 0, None) == rb.RB_ERR_SHAPE
+
+
 def test_storage_accounting_reproduces_effective_bits():
     """K*out*in/8 sign bytes + fp16 scales: ~2.02 bits per weight at 4096x4096
     (Section 4.1) and ~2.01 over the whole 7B-shaped stack."""
