@@ -444,6 +444,18 @@ def main() -> int:
                           "pct_of_hbm_peak": 100.0 * bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS},
             "rb_scale_grads": {"ms": ms_g, "GBps": bytes_g / (ms_g * 1e-3) / 1e9,
                                "pct_of_hbm_peak": 100.0 * bytes_g / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
+        # initialisation (Alg. 1): Iterative Residual SVID of the same layer on the device, fp64;
+        # wall clock of the call (it follows the power iteration's stopping rule from the host)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, _, _, err_i = rb.rb_derive_iterative(Wt, 2, 5)
+        torch.cuda.synchronize()
+        s_i = time.perf_counter() - t0
+        err_i = err_i.cpu().numpy()
+        result["initialisation_4096x11008"] = {
+            "rb_derive_iterative": {"K": 2, "T_max": 5, "seconds": s_i, "seconds_per_sweep": s_i / 5,
+                                    "error_after_greedy_over_norm": float(err_i[0, 1] / Wt.double().norm().item()),
+                                    "error_after_5_sweeps_over_norm": float(err_i[4, 1] / Wt.double().norm().item())}}
         del Wt, pk
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)
     else:

@@ -288,6 +288,35 @@ int rb_last_path(void);
 /* Library version: major*10000 + minor*100 + patch. */
 int rb_version(void);
 
+/* ------------------------------------------------------------------------
+ * Initialisation of the paths from a full-precision weight (Section 4.3,
+ * Alg. 1: Iterative Residual SVID with preconditioning).
+ * ------------------------------------------------------------------------ */
+
+/*
+ * With W' = row_factors (.) W (.) col_factors (Eq. init-calib; the caller forms
+ * the factors (s / max s)^alpha from its channel statistics; NULL means 1):
+ *   What_i = 0;  for t = 1..T_max, for i = 1..K:
+ *     R_i = W' - sum_{j != i} What_j                            (Eq. init-iter)
+ *     B_i = sign(R_i) (sign(0) = +1);  (sigma, a, b) = leading singular triplet of |R_i|
+ *     g_i' = sqrt(sigma) a;  h_i' = sqrt(sigma) b;  What_i = g_i' (.) B_i (.) h_i'
+ *   g_i = g_i' / row_factors;  h_i = h_i' / col_factors.
+ * T_max = 1 is the greedy pass.  fp64 throughout; the triplet comes from a power
+ * iteration from the all-ones vector until sigma changes by less than 1e-13
+ * relative and b by less than 1e-10 (at most 200 iterations).
+ * W fp32 [out][in]; factors fp64 [out], [in]; packed: canonical words, uint32
+ * [K][out][in/32]; g fp64 [K][out], h fp64 [K][in]; err: NULL or fp64
+ * [T_max][K], the error ||W' - sum_j What_j||_F right after each update.  All
+ * device pointers.  workspace: rb_derive_workspace_bytes(out, in) bytes of
+ * device memory.  An offline step: it waits for `stream` several times (the
+ * host follows the iteration's stopping rule) and has finished when it returns.
+ */
+size_t rb_derive_workspace_bytes(int out, int in);
+int rb_derive_iterative(const float *W, const double *row_factors, const double *col_factors,
+                        int K, int T_max, int out, int in,
+                        uint32_t *packed, double *g, double *h, double *err,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
 /*
  * The decoder block around the layers (the end-to-end decoding setting of
  * Section 5.4 and the inference table: a Llama-2 block), fused into the stack

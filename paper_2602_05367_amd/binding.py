@@ -32,6 +32,7 @@ EXPORTS = [
     "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
     "rb_couple", "rb_weight_grad", "rb_scale_grads", "rb_scale_grads_workspace_bytes",
     "rb_block_prepare", "rb_block_workspace_bytes", "rb_rmsnorm", "rb_silu_mul", "rb_add",
+    "rb_derive_iterative", "rb_derive_workspace_bytes",
     "rb_dense_gemv_f16", "rb_stream_read", "rb_stream_read_groups", "rb_version", "rb_last_path",
 ]
 
@@ -90,6 +91,9 @@ def _load() -> ctypes.CDLL:
     lib.rb_rmsnorm.argtypes = [p, p, p, i, i, ctypes.c_float, p]
     lib.rb_silu_mul.argtypes = [p, p, p, z, p]
     lib.rb_add.argtypes = [p, p, p, z, p]
+    lib.rb_derive_workspace_bytes.argtypes = [i, i]
+    lib.rb_derive_workspace_bytes.restype = z
+    lib.rb_derive_iterative.argtypes = [p, p, p, i, i, i, i, p, p, p, p, p, z, p]
     lib.rb_couple.argtypes = [p, p, p, i, i, i, p, p, p, p]
     lib.rb_weight_grad.argtypes = [p, p, i, i, i, p, p]
     lib.rb_scale_grads_workspace_bytes.argtypes = [i, i, i]
@@ -102,7 +106,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_last_path.argtypes = []
     for name in EXPORTS:
         if name not in ("rb_native_bytes", "rb_workspace_bytes", "rb_noalloc_scratch_bytes",
-                        "rb_scale_grads_workspace_bytes", "rb_block_workspace_bytes"):
+                        "rb_scale_grads_workspace_bytes", "rb_block_workspace_bytes", "rb_derive_workspace_bytes"):
             getattr(lib, name).restype = i
     return lib
 
@@ -386,6 +390,29 @@ def rb_stream_read(src: torch.Tensor, sink: torch.Tensor = None) -> torch.Tensor
 
 RB_PATH_NONE, RB_PATH_SIGNADD, RB_PATH_MX, RB_PATH_GEMM, RB_PATH_BATCH = 0, 1, 2, 3, 4
 RB_OPT_HANDOVER_PAUSE = 1
+
+
+# -------------------------------------------------------- initialisation ---
+def rb_derive_iterative(W: torch.Tensor, K: int, T_max: int, row_factors: torch.Tensor = None,
+                        col_factors: torch.Tensor = None, want_err: bool = True):
+    """Alg. 1 on the device: returns (packed int32 [K][out][in/32], g fp64 [K][out], h fp64 [K][in],
+    err fp64 [T_max][K] or None)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
+    out, inn = W.shape
+    for f, n in ((row_factors, out), (col_factors, inn)):
+        assert f is None or (f.is_cuda and f.dtype == torch.float64 and f.is_contiguous() and f.numel() == n)
+    packed = torch.empty((K, out, inn // 32), dtype=torch.int32, device=W.device)
+    g = torch.empty((K, out), dtype=torch.float64, device=W.device)
+    h = torch.empty((K, inn), dtype=torch.float64, device=W.device)
+    err = torch.empty((T_max, K), dtype=torch.float64, device=W.device) if want_err else None
+    n = int(lib.rb_derive_workspace_bytes(out, inn))
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=W.device)
+    _check("rb_derive_iterative", lib.rb_derive_iterative(
+        W.data_ptr(), row_factors.data_ptr() if row_factors is not None else None,
+        col_factors.data_ptr() if col_factors is not None else None, K, T_max, out, inn,
+        packed.data_ptr(), g.data_ptr(), h.data_ptr(), err.data_ptr() if err is not None else None,
+        ws.data_ptr(), n, _stream()))
+    return packed, g, h, err
 
 
 # -------------------------------------------------------------- training ---

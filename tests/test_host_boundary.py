@@ -143,6 +143,24 @@ def test_block_entry_points_reject_bad_arguments_without_a_gpu():
     assert rb.lib.rb_add(0x10, 0x10, 0x20, 0, None) == rb.RB_ERR_SHAPE
 
 
+def test_derivation_entry_point_rejects_bad_arguments_without_a_gpu():
+    d = rb.lib.rb_derive_iterative
+    ok = dict(W=0x1000, rf=None, cf=None, K=2, T=3, out=16, inn=64, packed=0x2000, g=0x3000, h=0x4000, err=None,
+              ws=0x10000, n=1 << 30)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return d(a["W"], a["rf"], a["cf"], a["K"], a["T"], a["out"], a["inn"], a["packed"], a["g"], a["h"], a["err"],
+                 a["ws"], a["n"], None)
+    assert call(W=None) == rb.RB_ERR_NULL and call(g=None) == rb.RB_ERR_NULL
+    assert call(K=0) == rb.RB_ERR_SHAPE and call(K=4) == rb.RB_ERR_SHAPE and call(T=0) == rb.RB_ERR_SHAPE
+    assert call(inn=40) == rb.RB_ERR_SHAPE and call(out=0) == rb.RB_ERR_SHAPE
+    assert call(g=0x3004) == rb.RB_ERR_ALIGN and call(packed=0x2002) == rb.RB_ERR_ALIGN
+    assert call(n=64) == rb.RB_ERR_WORKSPACE and call(ws=None) == rb.RB_ERR_WORKSPACE
+    assert rb.lib.rb_derive_workspace_bytes(16, 40) == 0
+    assert rb.lib.rb_derive_workspace_bytes(4096, 4096) > 4096 * 4096 // 8
+
+
 def test_storage_accounting_reproduces_effective_bits():
     """K*out*in/8 sign bytes + fp16 scales: ~2.02 bits per weight at 4096x4096
     (Section 4.1) and ~2.01 over the whole 7B-shaped stack."""
