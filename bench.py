@@ -202,7 +202,8 @@ def main() -> int:
         "config": {"workload": "configs[1]: Llama-7B-shaped decode stack, batch 1, K=2, 32 blocks x "
                                "(q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008); i.i.d. sign bits, "
                                "scales as the paper's derivation gives for Gaussian weights",
-                   "tokens": T, "packed_bytes": packed_bytes, "entry_point": "rb_stack_run"},
+                   "tokens": T, "packed_bytes": packed_bytes, "workspace_bytes": stack.ws_bytes,
+                   "entry_point": "rb_stack_run"},
         "tokens_per_s": T / (ms * 1e-3),
         "pct_of_hbm_peak": 100.0 * packed_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "us_per_layer": ms * 1e3 / len(ops),

@@ -158,8 +158,9 @@ constexpr int STEP_CT_SHIFT = 20;            // 12 bits: column tile
 __host__ __device__ constexpr uint32_t desc_blocks(uint32_t n) { return n / DESC_BLOCK + 2; }
 
 // What a finishing wavefront needs for finishing slot `slot` of workgroup `grp` in stage `st`
-// (one row tile of one op), laid out flat so that its address follows from (st, grp, slot) alone:
-// nothing on the path from the partial sums to the stores waits for a chain of dependent loads.
+// (one row tile of one op), laid out flat: record stages[st].rec0 + grp * stages[st].n_slots + slot,
+// so that its address follows from the stage's entry and (grp, slot) alone and nothing on the path
+// from the partial sums to the stores waits for a chain of dependent loads.
 struct SlotRec {
     uint64_t y;               // fp16 output: row 0 of token 0
     uint64_t pad64_;
@@ -194,8 +195,11 @@ static_assert(sizeof(SlotExt) == 64, "four 16-byte loads");
 struct Stage {
     int op0, nops;            // ops [op0, op0 + nops) are independent of each other
     int n_deps;               // ops of this stage whose input an earlier stage of the launch writes
-    int pad_;
+    int n_slots;              // finishing slots a workgroup may use in this stage (the tables hold that many per workgroup)
+    uint32_t rec0;            // index of the stage's first record in the slot tables
+    int pad_[3];
 };
+static_assert(sizeof(Stage) == 32, "two 16-byte loads");
 // First 256 bytes of the miscellaneous LDS area: one "go" word per stage parity at bytes 0 and 8
 // (set = the inputs of that stage have probably been written), and a counter.
 constexpr int WAITED_LDS_OFF = 240;   // lanes that waited for a tile not yet written
@@ -209,7 +213,7 @@ struct Header {
 // workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]
 //            [indices of the ops whose input is expanded by a kernel of its own]
 //            [sign lists, operand lists: blocks x n_groups x cwaves_of(T) each]
-//            [SlotRec x n_stages x n_groups x MAXSLOT][SlotVals x the same][up arrays]
+//            [SlotRec x records][SlotVals x the same][up arrays]   (records: see Stage)
 //            decoder blocks: [SlotExt x the same][sums of squares and output copies of ops]
 //                            [sums of squares of inputs from outside]
 struct Layout {

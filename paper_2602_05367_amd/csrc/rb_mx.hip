@@ -217,7 +217,8 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
         }
         slot_base += (int)nrt;
     }
-    const size_t idx = ((size_t)st * G + grp) * MAXSLOT + slot;
+    if (slot >= stage.n_slots) return;
+    const size_t idx = (size_t)stage.rec0 + (size_t)grp * stage.n_slots + slot;
     SlotRec sr;
     sr.y = 0; sr.pad64_ = 0; sr.out = 1; sr.n_cons = 0; sr.row0 = 0; sr.op = -1; sr.pad_ = 0;
     sr.behind = most - mine;
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int grp = blockIdx.x, G = gridDim.x;
+    const int grp = blockIdx.x;
     const int n_stages = hdr_p->n_stages;
     constexpr int T = TT, NB = nb_of(TT), KOP = kop_of(TT);
 
@@ -939,7 +940,9 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             SlotExt x;                      // decoder blocks only
         };
         auto fetch = [&](int st) -> Fin {
-            const size_t idx = ((size_t)min(st, n_stages - 1) * G + grp) * MAXSLOT + my_slot;
+            // a slot the stage does not have reads the record of one it has, and is marked unused
+            const Stage sg = stages[min(st, n_stages - 1)];
+            const size_t idx = (size_t)sg.rec0 + (size_t)grp * sg.n_slots + min(my_slot, sg.n_slots - 1);
             Fin f;
             f.r = slots_g[idx];
             const v4f *pv = reinterpret_cast<const v4f *>(&vals_g[idx].v[row][0]);
@@ -948,7 +951,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             if constexpr (KK == 3) f.c = pv[2];
             else f.c = (v4f){0.f, 0.f, 0.f, 0.f};
             if constexpr (BLK) f.x = ext_g[idx];
-            if (st >= n_stages) f.r.op = -1;
+            if (st >= n_stages || my_slot >= sg.n_slots) f.r.op = -1;
             return f;
         };
         Fin cur = fetch(0);
@@ -1225,7 +1228,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 }
 
 // ------------------------------------------------------------------ host ---
-static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, size_t up_total,
+static Layout make_layout(int n_ops, int n_stages, size_t n_records, int n_groups, int cwaves, size_t up_total,
                           size_t sblocks, size_t oblocks, bool block = false, size_t aux_poison = 0, size_t aux_rest = 0)
 {
     Layout L;
@@ -1237,12 +1240,12 @@ static Layout make_layout(int n_ops, int n_stages, int n_groups, int cwaves, siz
     L.which = o; o += align_up(sizeof(int) * MAX_EXPAND, 128);
     o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * (size_t)cwaves;
     o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * (size_t)cwaves;
-    o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
-    o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+    o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * n_records;
+    o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * n_records;
     o = align_up(o, 256); L.up = o; o += up_total;
     L.ext = L.aux = o; L.aux_poison = 0;
     if (block) {
-        o = align_up(o, 128); L.ext = o; o += sizeof(SlotExt) * (size_t)n_stages * (size_t)n_groups * MAXSLOT;
+        o = align_up(o, 128); L.ext = o; o += sizeof(SlotExt) * n_records;
         o = align_up(o, 256); L.aux = o; o += align_up(aux_poison, 256) + align_up(aux_rest, 256);
         L.aux_poison = align_up(aux_poison, 256);
     }
@@ -1298,7 +1301,13 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
         per_op = std::max(per_op, (share + CW - 1) / CW + 1);
     }
     const size_t steps = per_op * (size_t)n_ops;
-    return make_layout(n_ops, n_ops, G, (int)CW, align_up(up_max, 256) * (size_t)n_ops,
+    // slots: a stage holds what its ops need (the two ops of a gate-times-up stage sit at slots s
+    // and s + MAXSLOT / 2, which may leave a gap)
+    int slots_per_op = 1;
+    for (int l = 0; l < n_layers; ++l) slots_per_op = std::max(slots_per_op, (row_tiles(layers[l].out) + G - 1) / G);
+    if (block) slots_per_op = std::max(slots_per_op, MAXSLOT / 2);
+    slots_per_op = std::min(slots_per_op, MAXSLOT);
+    return make_layout(n_ops, n_ops, (size_t)n_ops * (size_t)G * (size_t)slots_per_op, G, (int)CW, align_up(up_max, 256) * (size_t)n_ops,
                        desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)),
                        block, block ? block_aux_bound(layers, n_layers, T_in) * (size_t)n_ops : 0, 0)
         .total;
@@ -1413,10 +1422,12 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
     }
     if (expand_list.size() > MAX_EXPAND || n_ops > MAX_OPS) return RB_ERR_UNSUPPORTED;
     std::vector<Stage> stages;
+    size_t n_records = 0;
     {
         int op0 = 0;
         while (op0 < n_ops) {
-            Stage s{op0, 0, 0, 0};
+            Stage s{};
+            s.op0 = op0;
             int slots = 0;
             for (int n = op0; n < n_ops; ++n) {
                 bool conflict = false;
@@ -1437,6 +1448,7 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
                     ops[(size_t)n + 1].slot0 = MAXSLOT / 2;
                     if (ops[(size_t)n].dep >= 0) s.n_deps += 2;
                     s.nops = 2;
+                    slots = MAXSLOT / 2 + per_group;
                     break;
                 }
                 if (conflict || slots + per_group > MAXSLOT) break;
@@ -1445,6 +1457,9 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
                 slots += per_group;
                 ++s.nops;
             }
+            s.n_slots = slots;
+            s.rec0 = (uint32_t)n_records;
+            n_records += (size_t)G * (size_t)slots;
             stages.push_back(s);
             op0 += s.nops;
         }
@@ -1484,7 +1499,9 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
         }
     }
     pr.block = block;
-    pr.lay = make_layout(n_ops, pr.n_stages, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks, block, aux_poison, aux_rest);
+    if (n_records > 0xffffffffull) return RB_ERR_UNSUPPORTED;
+    pr.lay = make_layout(n_ops, pr.n_stages, n_records, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks, block, aux_poison,
+                         aux_rest);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
