@@ -52,11 +52,11 @@ def build_stack(rb, synth, torch, which: str, T: int, seed: int = 20260205, K: i
     return ops, layers, bufs, op_list, packed_bytes
 
 
-def build_block_stack(rb, synth, torch, which: str, T: int, seed: int = 20260206):
+def build_block_stack(rb, synth, torch, which: str, T: int, seed: int = 20260206, in_place: bool = True):
     """The same synthetic layers as build_stack with what sits between them in a decoder block
     (normalised q/k/v and gate/up inputs, silu(gate) * up, residual additions; attention left out),
-    the residual stream kept in buffer 0."""
-    ops, shapes, widths, norms = synth.llama_block_stack(which, synth.LLAMA_SHAPES[which][2], in_place=True)
+    the residual stream kept in buffer 0 (`in_place`; otherwise every op writes a buffer of its own)."""
+    ops, shapes, widths, norms = synth.llama_block_stack(which, synth.LLAMA_SHAPES[which][2], in_place=in_place)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     layers, packed_bytes = [], 0

@@ -236,3 +236,62 @@ def test_block_beyond_the_fused_kernel_is_refused():
     with pytest.raises(rb.RabitError) as e:
         block.prepare()
     assert e.value.code == rb.RB_ERR_UNSUPPORTED
+
+
+def test_full_7b_block_stack_as_benchmarked_sampled_outputs():
+    """The 32-block stack exactly as bench.py builds and times it (residual stream in one buffer):
+    status clean, and bit for bit the run of the same ops with a buffer per op, whose sampled rows
+    (first, a middle and the last block) are recomputed by the oracle from the stored bits and the
+    buffers that run read."""
+    import bench
+    T = 1
+    ops_ip, layers, norms, bufs_ip, x0, list_ip, packed = bench.build_block_stack(rb, synth, torch, "7b", T)
+    ops, layers2, norms2, bufs, x0b, op_list, _ = bench.build_block_stack(rb, synth, torch, "7b", T, in_place=False)
+    assert len(ops) == 192 and len(layers) == 224 and packed == 1619001344
+    assert torch.equal(x0, x0b) and all(torch.equal(a.bits, b.bits) for a, b in zip(layers, layers2))
+    results = []
+    for name, o_list, bb in (("in place", list_ip, bufs_ip), ("a buffer per op", op_list, bufs)):
+        print(f"full 7B-shaped block stack, {name}", flush=True)
+        block = rb.Block(layers, norms, 1e-5, o_list, bb, T)
+        block.prepare()
+        for run in range(2):                        # scratch state must not leak between runs
+            bb[0].copy_(x0)
+            block.run_prepared()
+            torch.cuda.synchronize()
+            assert rb.rb_last_path() == rb.RB_PATH_MX and block.status() == rb.RB_OK
+            results.append([b.clone() for b in bb])
+        block.forget()
+    for a, b in zip(results[0], results[1]):
+        assert torch.equal(a, b)
+    for a, b in zip(results[2], results[3]):
+        assert torch.equal(a, b)
+    assert torch.equal(results[0][0], results[2][ops[-1].dst])           # the residual stream after the last block
+    for a, b in zip(ops, ops_ip):
+        if b.dst != 0:
+            assert torch.equal(results[2][a.dst], results[0][b.dst]), a.name
+    # sampled rows against the oracle
+    pick = np.random.default_rng(77)
+    host = [b.cpu().numpy() for b in bufs]
+    worst = 0.0
+
+    def rows_of(L, rows):
+        packed_words = rb.rb_unpack_native(L.bits.cpu().numpy().view(np.uint32), 2, L.out, L.inn)
+        return rb.rb_unpack(packed_words[:, rows, :]), L.g.cpu().numpy()[:, rows], L.h.cpu().numpy()
+    for blk in (0, 15, 31):
+        for op in ops[6 * blk: 6 * blk + 6]:
+            L = layers[op.layer]
+            rows = np.unique(pick.integers(0, L.out, size=40))
+            x = host[op.src].astype(np.float64)
+            if op.norm >= 0:
+                x = oracle.rmsnorm(x, norms[op.norm].cpu().numpy(), 1e-5)
+            ref = oracle.forward(*rows_of(L, rows), x)
+            if op.epilogue == rb.RB_EPI_SILU_MUL:
+                ref = oracle.silu(ref) * oracle.forward(*rows_of(layers[op.aux], rows), x)
+            elif op.epilogue == rb.RB_EPI_ADD:
+                ref = ref + host[op.aux].astype(np.float64)[:, rows]
+            got = host[op.dst].astype(np.float64)[:, rows]
+            assert np.all(np.isfinite(got)) and np.any(got != 0), op.name
+            err = float(oracle.relative_l2(got, ref).max())
+            worst = max(worst, err)
+            assert err <= TOL, (op.name, err)
+    print(f"  worst sampled rel_l2={worst:.3e}", flush=True)
