@@ -408,6 +408,395 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
     }
 }
 
+// ------------------------------------------------- one contraction (prefill) ---
+// With hundreds of tokens per weight the dense form of the layer, Y = W_hat X with
+// W_hat = sum_k g_k (.) B_k (.) h_k (Alg. 2, "compute layer output"), needs half the matrix
+// instructions of the two contractions above: the left operand is the effective weight itself,
+// built in registers from the packed signs on the way to the matrix instruction and never stored.
+// Per pair of fp16 elements: |g_1| |h_1| (packed multiply), its sign from the sign word (shift,
+// and-or), the signed |h_2| (shift, and-or), and one packed fused multiply-add with |g_2|: six
+// vector instructions, two roundings to fp16 (the product of path 1 and the sum).  Signs of g are
+// folded into the sign words per row, signs of h per 32-column group (a word the pre-pass writes),
+// so the magnitudes are non-negative and the and-or can place the sign.  Magnitudes are scaled by
+// powers of two (h_k by s_k as above, g_k by S / s_k with one S for both paths) so that the
+// products sit in fp16's normal range however the layer splits its magnitude; the result is
+// multiplied by 1 / S.  The right operand is X itself in fp16, in the contraction order of the
+// sign words.  A workgroup tile is 256 rows x 256 tokens; each of the four wavefronts owns 64 rows
+// and all 256 tokens, so no two wavefronts build the same left operand.
+constexpr int ONE_NBUF = 5;                    // ring of right-operand buffers (three steps of copies in flight)
+constexpr int ONE_BUF_BYTES = LARGE_TOKENS * 64 + 256;     // 256 tokens x 32 columns of X, then the step's h block
+constexpr int HBLOCK_BYTES = 256;              // per 32-column group: [path][32 magnitudes fp16][2 sign words][padding]
+
+// Largest |h_k| and |g_k|: ABSMAX_GROUPS workgroups take a slice each and write their four maxima
+// to part[group][4] (scratch that the next kernels overwrite)
+constexpr int ABSMAX_GROUPS = 64;
+__global__ __launch_bounds__(256) void absmax_kernel(const __half *__restrict__ g, const __half *__restrict__ h, int out,
+                                                     int in, float *__restrict__ part)
+{
+    __shared__ float red[4][256];
+    float m[4] = {0.f, 0.f, 0.f, 0.f};
+    const int tid = blockIdx.x * 256 + threadIdx.x, stride = ABSMAX_GROUPS * 256;
+    for (int j = tid; j < in; j += stride) {
+        m[0] = fmaxf(m[0], fabsf(__half2float(h[j])));
+        m[1] = fmaxf(m[1], fabsf(__half2float(h[(size_t)in + j])));
+    }
+    for (int j = tid; j < out; j += stride) {
+        m[2] = fmaxf(m[2], fabsf(__half2float(g[j])));
+        m[3] = fmaxf(m[3], fabsf(__half2float(g[(size_t)out + j])));
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = m[q];
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = fmaxf(red[q][threadIdx.x], red[q][threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x < 4) part[blockIdx.x * 4 + threadIdx.x] = red[threadIdx.x][0];
+}
+
+// scl[0..1] = s_k (h), scl[2..3] = S / s_k (g), scl[4] = 1 / S
+__global__ __launch_bounds__(64) void scales1_kernel(const float *__restrict__ part, float *__restrict__ scl)
+{
+    float m[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        m[q] = part[threadIdx.x * 4 + q];                   // ABSMAX_GROUPS = 64 = one per lane
+        for (int s = 32; s > 0; s >>= 1) m[q] = fmaxf(m[q], __shfl_xor(m[q], s));
+    }
+    if (threadIdx.x == 0) {
+        const float s0 = mx::input_scale(m[0]), s1 = mx::input_scale(m[1]);
+        const float S = fminf(s0 * mx::input_scale(m[2]), s1 * mx::input_scale(m[3]));
+        scl[0] = s0; scl[1] = s1;
+        scl[2] = S / s0; scl[3] = S / s1;
+        scl[4] = 1.f / S;
+    }
+}
+
+// the h block of every 32-column group, and X in fp16 in contraction order (rows t >= T and columns
+// j >= in are zero)
+__global__ __launch_bounds__(64) void hblock_kernel(const __half *__restrict__ h, const float *__restrict__ scl, int in,
+                                                    uint8_t *__restrict__ Hblk)
+{
+    const int group = blockIdx.x, lane = threadIdx.x, k = lane >> 5, col = lane & 31;
+    const int j = group * 32 + col;
+    const float hv = j < in ? __half2float(h[(size_t)k * in + j]) : 0.f;
+    uint8_t *blk = Hblk + (size_t)group * HBLOCK_BYTES;
+    reinterpret_cast<_Float16 *>(blk)[k * 32 + contraction_position(col)] = (_Float16)(fabsf(hv) * scl[k]);
+    // sign word in the bit order of the stored sign words: native bit of column col
+    const unsigned long long neg = __ballot(hv < 0.f);
+    uint32_t word = 0;
+    const uint32_t mine = (uint32_t)(neg >> (32 * k));
+    for (int b = 0; b < 32; ++b) word |= ((mine >> b) & 1u) << native_bit(b);
+    if (col == 0) reinterpret_cast<uint32_t *>(blk + 128)[k] = word;
+    if (lane < 30) reinterpret_cast<uint32_t *>(blk + 136)[lane] = 0u;
+}
+
+// a thread writes eight consecutive positions (16 bytes) of a 32-column group and gathers their
+// eight columns from the group's 64 bytes of X
+template <typename ActT>
+__global__ __launch_bounds__(256) void xperm_kernel(const ActT *__restrict__ X, _Float16 *__restrict__ Xp, int T, int T_pad,
+                                                    int in, int in_pad)
+{
+    const int p8 = blockIdx.x * 256 + threadIdx.x;          // which run of eight positions of the row
+    const int t = blockIdx.y;
+    if (p8 * 8 >= in_pad) return;
+    const int group = p8 >> 2, pos0 = (p8 & 3) * 8;
+    v8h o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        // position 2n + hi holds the column of native bit n + 16 hi
+        const int pos = pos0 + e, bit = (pos >> 1) + 16 * (pos & 1);
+        const int j = group * 32 + column_of_native_bit(bit);
+        o[e] = (_Float16)((t < T && j < in) ? to_float(X[(size_t)t * in + j]) : 0.f);
+    }
+    *reinterpret_cast<v8h *>(Xp + (size_t)t * in_pad + (size_t)p8 * 8) = o;
+}
+
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+template <int OUT_DT>
+__global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ bits, const __half *__restrict__ g,
+                                                       const float *__restrict__ scl, const uint8_t *__restrict__ Hblk,
+                                                       const _Float16 *__restrict__ Xp, void *__restrict__ Y,
+                                                       float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad,
+                                                       int full_tiles, int tail_split, int tail_row0, int tail_rows)
+{
+    constexpr int MP = 2, NT = 8, BLK_TOK = LARGE_TOKENS, NBUF = ONE_NBUF, BUF_BYTES = ONE_BUF_BYTES;
+    constexpr int COPIES = 4;                              // 16 groups of 16 tokens over four wavefronts
+    constexpr int CP = COPIES + 1;                         // copies per wavefront and step: X, and the h block
+    extern __shared__ __attribute__((aligned(16))) uint8_t Bs[];       // NBUF * BUF_BYTES
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, half_sel = (lane >> 4) & 1, kg = lane >> 5;
+    const int in_pad = CT * TILE_COLS;
+    const int TB = T_pad / BLK_TOK;
+    int tile = (int)blockIdx.x, slice = 0, n_slices = 1;
+    if (tile >= full_tiles) {
+        const int u = tile - full_tiles;
+        tile = full_tiles + u / tail_split;
+        slice = u % tail_split;
+        n_slices = tail_split;
+    }
+    const bool partial = n_slices > 1;
+    const int tb = tile % TB, rb = tile / TB;
+    const int rt_base = rb * (BLK_ROWS / TILE_ROWS) + wave * MP * 2;           // first row tile of this wavefront
+    const int ct_begin = (int)((long)CT * slice / n_slices);
+    const int ct_end = (int)((long)CT * (slice + 1) / n_slices);
+
+    // ---- per-row constants: |g_k| S / s_k as a packed pair, and the sign of g_k as a mask on the sign words
+    // (both for the row this lane feeds to the matrix instruction: row pair m, row l % 32)
+    uint32_t G2[MP][2], flip[MP][2];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+        const int row = (rt_base + 2 * m + half_sel) * TILE_ROWS + r;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const __half gk = row < out ? g[(size_t)k * out + row] : __float2half(0.f);
+            flip[m][k] = (__half_as_ushort(gk) & 0x8000u) ? 0xffffffffu : 0u;
+            const float gv = fabsf(__half2float(gk)) * scl[2 + k];
+            const uint32_t mag = (uint32_t)__half_as_ushort(__float2half_rn(gv));
+            G2[m][k] = mag | (mag << 16);
+        }
+    }
+    // lane (row, k group kg) holds positions 16 kk + 8 kg .. + 7: register e of half kk gets native
+    // bits n and n + 16, n = 8 kk + 4 kg + e, on bits 15 and 31.  The words are shifted right by
+    // 4 kg once per step; what is left of the shift is a constant.
+    const uint32_t kg4 = 4u * (uint32_t)kg;
+
+    auto load_words = [&](int ct, v4u (&w)[2 * MP]) {
+#pragma unroll
+        for (int i = 0; i < 2 * MP; ++i) {
+            const int rt = rt_base + i;
+            v4u v = {0u, 0u, 0u, 0u};
+            if (rt < RT) v = bits[((size_t)rt * CT + ct) * 64 + lane];
+            w[i] = v;
+        }
+    };
+    // the two words (both paths) of column half c again, for the next column tile
+    auto reload_half = [&](int ct, int c, v4u (&w)[2 * MP]) {
+        const uint2 *words = reinterpret_cast<const uint2 *>(bits);
+#pragma unroll
+        for (int i = 0; i < 2 * MP; ++i) {
+            const int rt = rt_base + i;
+            uint2 v = make_uint2(0u, 0u);
+            if (rt < RT) v = words[(((size_t)rt * CT + ct) * 64 + lane) * 2 + c];
+            w[i][2 * c] = v.x;
+            w[i][2 * c + 1] = v.y;
+        }
+    };
+
+    // right-operand staging, as in the kernel above, plus the 256-byte h block of the step (every
+    // wavefront copies it: four bytes per lane, the same bytes to the same place)
+    // (a base the wavefront shares plus a 32-bit offset per lane: a token block of X is < 4 GB)
+    const uint8_t *stage_base = reinterpret_cast<const uint8_t *>(Xp + (size_t)tb * BLK_TOK * in_pad);
+    uint32_t stage_off[COPIES];
+#pragma unroll
+    for (int j = 0; j < COPIES; ++j) {
+        const int token = 16 * (wave * COPIES + j) + (lane >> 2);
+        const int chunk = (lane & 3) ^ swizzle(token);
+        stage_off[j] = (uint32_t)(((size_t)token * in_pad + chunk * 8) * sizeof(_Float16));
+    }
+    // step s = 8 (ct - ct_begin) + 4 column half + 32-column group; its operands live in buffer s % NBUF
+    const int n_steps = (ct_end - ct_begin) * 8;
+    auto stage_step = [&](int s) {
+        const int sc = s < n_steps ? s : 0;               // past the end: repeat the first copy
+        const int group = ct_begin * 8 + sc;              // 32-column group of the matrix
+        uint8_t *buf = &Bs[(s % NBUF) * BUF_BYTES];
+        const uint8_t *src = stage_base + (size_t)group * 64;
+#pragma unroll
+        for (int j = 0; j < COPIES; ++j)
+            __builtin_amdgcn_global_load_lds(static_cast<const void *>(src + stage_off[j]),
+                                             RB_LDS(buf + (wave * COPIES + j) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(static_cast<const void *>(Hblk + (size_t)group * HBLOCK_BYTES + lane * 4),
+                                         RB_LDS(buf + LARGE_TOKENS * 64), 4, 0, 0);
+    };
+    // LDS addresses of this lane's operand reads inside a buffer: token tile n adds n * 2048
+    uint32_t b_addr[2];
+    {
+        const int token = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) b_addr[kk] = (uint32_t)(size_t)RB_LDS(&Bs[token * 64 + (((2 * kk + kg) ^ swizzle(token)) * 16)]);
+    }
+    const uint32_t h_addr = (uint32_t)(size_t)RB_LDS(&Bs[LARGE_TOKENS * 64 + 16 * kg]);
+
+    v16f acc[MP][NT];
+#pragma unroll
+    for (int m = 0; m < MP; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[m][n][e] = 0.f;
+
+    v4u cur[2 * MP];
+    v8h a[2][MP][2], b[NT][2];
+    v8h hm[2][2];                                             // [path][half]: |h| of this lane's eight positions
+    uint32_t hs[2];                                           // sign words of h for the step
+    uint32_t wq[MP][2];
+    const uint32_t sel_mask = half_sel ? 0xffffffffu : 0u;
+    // (addresses: one register per half and ring buffer, everything else in the instruction's offset)
+    auto read_b = [&](uint32_t addr, int n, int kk) {
+        switch (n) {
+        case 0: asm volatile("ds_read_b128 %0, %1" : "=v"(b[0][kk]) : "v"(addr) : "memory"); break;
+        case 1: asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(b[1][kk]) : "v"(addr) : "memory"); break;
+        case 2: asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(b[2][kk]) : "v"(addr) : "memory"); break;
+        case 3: asm volatile("ds_read_b128 %0, %1 offset:6144" : "=v"(b[3][kk]) : "v"(addr) : "memory"); break;
+        case 4: asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(b[4][kk]) : "v"(addr) : "memory"); break;
+        case 5: asm volatile("ds_read_b128 %0, %1 offset:10240" : "=v"(b[5][kk]) : "v"(addr) : "memory"); break;
+        case 6: asm volatile("ds_read_b128 %0, %1 offset:12288" : "=v"(b[6][kk]) : "v"(addr) : "memory"); break;
+        default: asm volatile("ds_read_b128 %0, %1 offset:14336" : "=v"(b[7][kk]) : "v"(addr) : "memory"); break;
+        }
+    };
+    // addr: this lane's 16 bytes of path 0, half 0 of the step's h block
+    auto read_h = [&](uint32_t addr, int i) {
+        uint2 v;
+        switch (i) {
+        case 0: asm volatile("ds_read_b128 %0, %1" : "=v"(hm[0][0]) : "v"(addr) : "memory"); break;
+        case 1: asm volatile("ds_read_b128 %0, %1 offset:32" : "=v"(hm[0][1]) : "v"(addr) : "memory"); break;
+        case 2: asm volatile("ds_read_b128 %0, %1 offset:64" : "=v"(hm[1][0]) : "v"(addr) : "memory"); break;
+        case 3: asm volatile("ds_read_b128 %0, %1 offset:96" : "=v"(hm[1][1]) : "v"(addr) : "memory"); break;
+        default:
+            // the two sign words sit 128 bytes into the block (addr carries 16 bytes per k group)
+            asm volatile("ds_read_b64 %0, %1 offset:128" : "=v"(v) : "v"(addr - 16u * (uint32_t)kg) : "memory");
+            hs[0] = v.x; hs[1] = v.y;
+            break;
+        }
+    };
+    auto ring = [&](int s) { return (uint32_t)((s % NBUF) * BUF_BYTES); };
+    // The word of this lane's row (row tile 2m + half_sel, row r) sits in lane (r, q) of that
+    // tile's register.  The lane exchange is written as instructions, like the operand reads: its
+    // results are taken up after the step's common wait, not one by one.
+    uint32_t wf[MP][2][2];
+    const uint32_t bp_addr = 4u * (uint32_t)r;
+    auto fetch_a = [&](const v4u (&w)[2 * MP], int c, int q, int m, int k) {
+        const uint32_t a0 = bp_addr + 64u * (uint32_t)q;
+        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][0]) : "v"(a0), "v"(w[2 * m][c * 2 + k]) : "memory");
+        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][1]) : "v"(a0), "v"(w[2 * m + 1][c * 2 + k]) : "memory");
+    };
+    // after the wait: pick the word of this lane's row tile, put the signs of g and h into it, and
+    // move it so that this lane's first position sits at bit 0 (and 16)
+    auto sign_a = [&](int m, int k) {
+        asm volatile("" : "+v"(wf[m][k][0]), "+v"(wf[m][k][1]));
+        const uint32_t w = (wf[m][k][0] & ~sel_mask) | (wf[m][k][1] & sel_mask);
+        wq[m][k] = (w ^ hs[k] ^ flip[m][k]) >> kg4;
+    };
+    auto expand_a = [&](int i, v8h (&aa)[MP][2]) {
+        // register e of the four of (row pair m, half kk): two elements of the effective weight
+        const int m = i >> 3, kk = (i >> 2) & 1, e = i & 3;
+        union { v8h h; uint32_t u[4]; v2h p[4]; } f, h0, h1;
+        f.h = aa[m][kk];
+        h0.h = hm[0][kk];
+        h1.h = hm[1][kk];
+        union { uint32_t u; v2h p; } g0, g1, p1, s2;
+        g0.u = G2[m][0];
+        g1.u = G2[m][1];
+        p1.p = g0.p * h0.p[e];                                                 // |g_1| |h_1|
+        p1.u = ((wq[m][0] << (15 - 8 * kk - e)) & 0x80008000u) | p1.u;          // its sign
+        s2.u = ((wq[m][1] << (15 - 8 * kk - e)) & 0x80008000u) | h1.u[e];       // signed |h_2|
+        f.p[e] = __builtin_elementwise_fma(g1.p, s2.p, p1.p);
+        aa[m][kk] = f.h;
+    };
+    auto wait_lds = [&]() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
+    auto touch_b = [&](int kk) {
+#pragma unroll
+        for (int n = 0; n < NT; ++n) asm volatile("" : "+v"(b[n][kk]));
+    };
+
+    if (n_steps > 0) {
+        // ---- prologue: NBUF - 1 steps of copies in flight; operands of step 0 in registers
+        load_words(ct_begin, cur);
+#pragma unroll
+        for (int s = 0; s < NBUF - 1; ++s) stage_step(s);
+        wait_copies_and_sync<CP * (NBUF - 2)>();               // step 0 has landed
+#pragma unroll
+        for (int i = 0; i < 5; ++i) read_h(h_addr, i);
+#pragma unroll
+        for (int m = 0; m < MP; ++m) { fetch_a(cur, 0, 0, m, 0); fetch_a(cur, 0, 0, m, 1); }
+#pragma unroll
+        for (int n = 0; n < NT; ++n) read_b(b_addr[0], n, 0);
+        wait_lds();
+        asm volatile("" : "+v"(hm[0][0]), "+v"(hm[0][1]), "+v"(hm[1][0]), "+v"(hm[1][1]), "+v"(hs[0]), "+v"(hs[1]));
+        touch_b(0);
+#pragma unroll
+        for (int m = 0; m < MP; ++m) { sign_a(m, 0); sign_a(m, 1); }
+#pragma unroll
+        for (int i = 0; i < MP * 8; ++i) expand_a(i, a[0]);
+    }
+
+    // ---- main loop: 32 matrix instructions per step (2 row pairs x 8 token tiles x 2 halves).  In
+    // between: the second half of this step's right operand (slots 0-7), everything the next
+    // step's left operand needs (h block, sign words, expansion) and the first half of its right
+    // operand (slots 16-23, after that half's last use).
+    for (int ct = ct_begin; ct < ct_end; ++ct) {
+#pragma unroll
+        for (int step = 0; step < 8; ++step) {
+            const int s = (ct - ct_begin) * 8 + step;
+            const int p = step & 1, pn = p ^ 1;
+            const int ns = (step + 1) & 7;
+            const int c_ = ns >> 2, q_ = ns & 3;
+            const uint32_t here = ring(s), next = ring(s + 1);
+            const uint32_t b1_here = b_addr[1] + here, b0_next = b_addr[0] + next, h_next = h_addr + next;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int kk = j >> 4, n = (j >> 1) & 7, m = j & 1;
+                if (j == 16) {                                  // this step's second half, and the next step's words and h
+                    wait_lds();
+                    touch_b(1);
+                    asm volatile("" : "+v"(hm[0][0]), "+v"(hm[0][1]), "+v"(hm[1][0]), "+v"(hm[1][1]), "+v"(hs[0]), "+v"(hs[1]));
+#pragma unroll
+                    for (int mm = 0; mm < MP; ++mm) { sign_a(mm, 0); sign_a(mm, 1); }
+                }
+                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[p][m][kk], b[n][kk], acc[m][n], 0, 0, 0);
+                if (j == 0) {
+                    // the copies of step s + 1 were requested NBUF - 2 steps before it, and
+                    // CP * (NBUF - 3) copies came after them; behind the barrier every wavefront has
+                    // read what it needed from the buffer of step s - 1, which the next copies fill
+                    wait_copies_and_sync<CP * (NBUF - 3)>();
+                    stage_step(s + NBUF - 1);
+                }
+                if (j < 8) read_b(b1_here, j, 1);
+                if (j >= 1 && j < 6) read_h(h_next, j - 1);
+                if (j >= 6 && j < 10) fetch_a(cur, c_, q_, (j - 6) >> 1, (j - 6) & 1);
+                if (j >= 16 && j < 24) read_b(b0_next, j - 16, 0);
+                if (j >= 16) expand_a(j - 16, a[pn]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_lds();
+            touch_b(0);
+            // the words of column half c were last fetched for its fourth step, one step ahead
+            if ((step & 3) == 2 && ct + 1 < ct_end) reload_half(ct + 1, step >> 2, cur);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no copy may land in LDS after the end
+
+    // ---- epilogue: lane l of tile (m, n) holds token 32n + l % 32 and, in register 4a + e, row
+    // 8a + 4 (l / 32) + e of the 32
+    asm volatile("" : "+s"(out));
+    const float inv_s = scl[4];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int t = tb * BLK_TOK + n * 32 + (lane & 31);
+        if (t >= T) continue;
+#pragma unroll
+        for (int m = 0; m < MP; ++m) {
+#pragma unroll
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const int row0 = (rt_base + 2 * m) * TILE_ROWS + 8 * a4 + 4 * kg;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (row0 + e >= out) continue;
+                    if (partial)
+                        Acc[((size_t)slice * T + t) * tail_rows + (row0 + e - tail_row0)] = acc[m][n][4 * a4 + e];
+                    else
+                        store_out(Y, OUT_DT, (size_t)t * out + row0 + e, acc[m][n][4 * a4 + e] * inv_s);
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host ---
 struct Plan {
     bool small;          // 32-token tiles with the contraction split over workgroups
@@ -415,6 +804,7 @@ struct Plan {
     // 256-token tiles: the tiles of the last, partly filled round are shared by tail_split workgroups each
     int full_tiles, tail_split, tail_row0, tail_rows;
     size_t u_bytes, acc_bytes;
+    size_t hblk_bytes;   // 256-token tiles (one contraction): the h blocks; u_bytes then holds X in fp16
 };
 
 static Plan make_plan(const rb_layer *L, int T)
@@ -430,7 +820,8 @@ static Plan make_plan(const rb_layer *L, int T)
     p.TB = p.T_pad / blk_tok;
     // enough workgroups for every compute unit of an MI355X (256), never less than one column tile each
     p.split = p.small ? std::max(1, std::min(p.CT, (256 + p.RB * p.TB - 1) / (p.RB * p.TB))) : 1;
-    p.u_bytes = (2 * (size_t)p.T_pad * p.in_pad * sizeof(_Float16) + 255) / 256 * 256;
+    p.hblk_bytes = p.small ? 0 : (size_t)p.CT * 8 * HBLOCK_BYTES;
+    p.u_bytes = ((p.small ? 2 : 1) * (size_t)p.T_pad * p.in_pad * sizeof(_Float16) + 255) / 256 * 256;
     p.acc_bytes = p.split > 1 ? (size_t)p.split * T * L->out * sizeof(float) : 0;
     const int tiles = p.RB * p.TB;
     p.full_tiles = tiles;
@@ -460,7 +851,7 @@ static Plan make_plan(const rb_layer *L, int T)
 size_t workspace_bytes(const rb_layer *L, int T)
 {
     const Plan p = make_plan(L, T);
-    return SCALES_BYTES + p.u_bytes + p.acc_bytes;
+    return SCALES_BYTES + p.hblk_bytes + p.u_bytes + p.acc_bytes;
 }
 
 bool supported(const rb_layer *L, int T)
@@ -473,11 +864,48 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
 {
     const Plan p = make_plan(L, T);
     float *scl = static_cast<float *>(workspace);
-    _Float16 *U = reinterpret_cast<_Float16 *>(static_cast<uint8_t *>(workspace) + SCALES_BYTES);
-    float *Acc = p.acc_bytes > 0 ? reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + SCALES_BYTES + p.u_bytes) : nullptr;
+    uint8_t *Hblk = static_cast<uint8_t *>(workspace) + SCALES_BYTES;
+    _Float16 *U = reinterpret_cast<_Float16 *>(Hblk + p.hblk_bytes);
+    float *Acc = p.acc_bytes > 0 ? reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(U) + p.u_bytes) : nullptr;
     const __half *h = reinterpret_cast<const __half *>(L->h);
-    hipLaunchKernelGGL(hscale_kernel, dim3(1), dim3(256), 0, stream, h, L->in, scl);
     const dim3 sgrid(p.in_pad / 256, p.T_pad);
+    if (!p.small) {
+        // one contraction on the effective weight built in registers
+        const v4u *bits = static_cast<const v4u *>(L->bits);
+        const __half *g = reinterpret_cast<const __half *>(L->g);
+        static_assert(ABSMAX_GROUPS == 64 && ABSMAX_GROUPS * 4 * sizeof(float) <= LARGE_TOKENS * TILE_COLS * sizeof(_Float16), "partials fit in U");
+        hipLaunchKernelGGL(absmax_kernel, dim3(ABSMAX_GROUPS), dim3(256), 0, stream, g, h, L->out, L->in, reinterpret_cast<float *>(U));
+        hipLaunchKernelGGL(scales1_kernel, dim3(1), dim3(64), 0, stream, reinterpret_cast<const float *>(U), scl);
+        hipLaunchKernelGGL(hblock_kernel, dim3(p.CT * 8), dim3(64), 0, stream, h, scl, L->in, Hblk);
+        const dim3 xgrid((p.in_pad / 8 + 255) / 256, p.T_pad);
+        if (act_dtype == RB_F16)
+            hipLaunchKernelGGL(xperm_kernel<__half>, xgrid, dim3(256), 0, stream, static_cast<const __half *>(X), U, T, p.T_pad,
+                               L->in, p.in_pad);
+        else
+            hipLaunchKernelGGL(xperm_kernel<bf16_t>, xgrid, dim3(256), 0, stream, static_cast<const bf16_t *>(X), U, T, p.T_pad,
+                               L->in, p.in_pad);
+        const int tail_tiles = p.RB * p.TB - p.full_tiles;
+        const dim3 grid((unsigned)(p.full_tiles + tail_tiles * p.tail_split));
+        constexpr int lds1 = ONE_NBUF * ONE_BUF_BYTES;
+        auto run = [&](auto kernel) -> int {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds1) !=
+                hipSuccess)
+                return RB_ERR_HIP;
+            hipLaunchKernelGGL(kernel, grid, dim3(256), lds1, stream, bits, g, scl, Hblk, U, Y, Acc, L->out, p.RT, p.CT, T, p.T_pad,
+                               p.full_tiles, p.tail_split, p.tail_row0, p.tail_rows);
+            return RB_OK;
+        };
+        const int rc = out_dtype == RB_F16 ? run(gemm1_kernel<RB_F16>) : out_dtype == RB_BF16 ? run(gemm1_kernel<RB_BF16>)
+                                                                                               : run(gemm1_kernel<RB_F32>);
+        if (rc != RB_OK) return rc;
+        if (p.tail_split > 1) {
+            const size_t n = (size_t)T * p.tail_rows;
+            hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype, T,
+                               L->out, p.tail_row0, p.tail_rows, p.tail_split);
+        }
+        return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
+    }
+    hipLaunchKernelGGL(hscale_kernel, dim3(1), dim3(256), 0, stream, h, L->in, scl);
     if (act_dtype == RB_F16)
         hipLaunchKernelGGL(scale_kernel<__half>, sgrid, dim3(256), 0, stream, static_cast<const __half *>(X), h, scl, U,
                            T, p.T_pad, L->in, p.in_pad);

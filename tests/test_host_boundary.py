@@ -178,15 +178,16 @@ def test_storage_accounting_reproduces_effective_bits():
 
 
 def test_many_token_workspace_counts_the_shared_last_round():
-    """The many-token GEMM needs 256 bytes for the per-path input scaling, the scaled input
-    (2 paths x T x in fp16) and, when the output
-    tiles (256 rows x 256 tokens) do not fill whole rounds of the device's 256 compute units, fp32
-    partial sums for the row blocks of the last round, one copy per workgroup that shares a tile."""
+    """The many-token GEMM needs 256 bytes for the power-of-two scalings, 256 bytes per 32-column
+    group for the input scales in operand order, the input in fp16 in contraction order (T x in)
+    and, when the output tiles (256 rows x 256 tokens) do not fill whole rounds of the device's 256
+    compute units, fp32 partial sums for the row blocks of the last round, one copy per workgroup
+    that shares a tile."""
     def need(out, inn, T):
         L = rb.binding.rb_layer(out, inn, 2, 0x1000, 0x2000, 0x3000)
         return rb.lib.rb_workspace_bytes(ctypes.byref(L), 1, 1, T)
     T = 2048
-    u = lambda inn: 256 + 2 * T * inn * 2
+    u = lambda inn: 256 + (inn // 32) * 256 + T * inn * 2
     # 112 x 8 = 896 tiles = 3.5 rounds: the last 16 row blocks (4096 rows), two workgroups per tile
     assert need(28672, 8192, T) == u(8192) + 2 * T * 4096 * 4
     # 32 x 8 = 256 tiles: one full round, nothing shared
