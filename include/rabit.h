@@ -103,7 +103,11 @@ int rb_linear_gemv(const rb_layer *L, const uint16_t *x, uint16_t *y,
  * Batched form, T tokens: Y[t] = layer(X[t]).  X device [T][in] of act_dtype
  * (RB_F16 or RB_BF16), Y device [T][out] of out_dtype (RB_F16, RB_BF16, RB_F32).
  * Small T streams the weights once for all tokens; large T runs as a dense
- * contraction on the matrix cores.
+ * contraction on the matrix cores: beyond 32 tokens as Y = W_hat X with the
+ * effective weight W_hat = sum_k g_k (.) B_k (.) h_k (the form Alg. 2 gives for
+ * batched inputs), which the kernel builds in fp16 registers from the packed
+ * signs (two roundings per weight, a few 1e-4 relative on the output; fp32
+ * accumulation).
  */
 int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
                    int act_dtype, int out_dtype,
