@@ -22,11 +22,12 @@
 //     into a ring of four buffers with one barrier per step; rows are 64 bytes and the four
 //     16-byte chunks of a row are XOR-swizzled with the token index so that neither the copy nor
 //     the operand reads collide on LDS banks;
-//   * two tile shapes: 256 rows x 256 tokens (a wavefront owns 128 x 128 in sixteen 32 x 32
-//     accumulator tiles) for prefill, and 256 rows x 32 tokens for small batches, where the
-//     contraction is also split over workgroups (fp32 partial outputs in scratch, one more
-//     small kernel sums and rounds them) so that a 4096-row matrix still fills
-//     the chip.  Either way the packed weights are read once per block of tokens.
+//   * the tile is 256 rows x 32 tokens (single calls of up to 32 tokens), and the contraction
+//     is also split over workgroups (fp32 partial outputs in scratch, one more small kernel sums
+//     and rounds them) so that a 4096-row matrix still fills the chip.  The kernel is written
+//     for any split of a 256-row tile over its four wavefronts; beyond 32 tokens the
+//     one-contraction kernel further down takes over, whose 256 x 256 tile shares this one's
+//     staging of the right operand and its cut of the device's last round.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -926,19 +927,10 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
         const size_t n = (size_t)T * L->out;
         hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype, T,
                            L->out, 0, L->out, p.split);
-    } else if (p.small) {
+    } else {
         if (out_dtype == RB_F16) RB_GEMM(RB_F16, 4, 1, 2, 1);
         else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 4, 1, 2, 1);
         else RB_GEMM(RB_F32, 4, 1, 2, 1);
-    } else {
-        if (out_dtype == RB_F16) RB_GEMM(RB_F16, 2, 2, 4, 4);
-        else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 2, 2, 4, 4);
-        else RB_GEMM(RB_F32, 2, 2, 4, 4);
-        if (p.tail_split > 1) {
-            const size_t n = (size_t)T * p.tail_rows;
-            hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype,
-                               T, L->out, p.tail_row0, p.tail_rows, p.tail_split);
-        }
     }
 #undef RB_GEMM
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;

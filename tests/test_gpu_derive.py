@@ -100,3 +100,35 @@ def test_derived_paths_run_through_the_inference_kernel():
     torch.cuda.synchronize()
     ref = oracle.forward(signs, g.astype(np.float16), h.astype(np.float16), x)
     assert oracle.relative_l2(y.cpu().numpy().astype(np.float64)[None], ref).max() <= 1e-3
+
+
+def test_full_size_layer_as_benchmarked_last_update_against_the_oracle():
+    """4096 x 11008, K = 2, the size bench.py times.  The oracle cannot run the whole iteration at
+    this size in test time, but the last update of the last sweep is an SVID of one residual that
+    numpy can form from what the device returned for the other path: its signs must be the stored
+    bits of path 2, the oracle's leading singular pair of its magnitudes the stored scales, and the
+    remaining error the last entry of the error table.  The errors must fall from update to update
+    and start at the greedy values of a Gaussian weight (residual fractions 1 - 2/pi and 0.130)."""
+    out, inn, K, T_max = 4096, 11008, 2, 2
+    W = (torch.randn((out, inn), device="cuda", generator=torch.Generator(device="cuda").manual_seed(7)) * 0.02)
+    print("derive 4096x11008 on the device", flush=True)
+    packed, g, h, err = rb.rb_derive_iterative(W, K, T_max)
+    torch.cuda.synchronize()
+    Wh = W.cpu().numpy().astype(np.float64)
+    packed, g, h, err = packed.cpu().numpy().view(np.uint32), g.cpu().numpy(), h.cpu().numpy(), err.cpu().numpy()
+    norm = np.linalg.norm(Wh)
+    flat = err.reshape(-1)
+    assert np.all(np.diff(flat) < 0)
+    assert abs((flat[0] / norm) ** 2 - (1 - 2 / np.pi)) < 0.003 and abs((flat[1] / norm) ** 2 - 0.130) < 0.003
+    print("  residual of path 2 in numpy", flush=True)
+    B0 = oracle.unpack(packed[0:1])[0]
+    R = Wh - g[0][:, None] * B0 * h[0][None, :]
+    del B0
+    B1 = oracle.sign(R)
+    differing = int(np.unpackbits((oracle.pack(B1[None]) ^ packed[1:2]).view(np.uint8)).sum())
+    assert differing == 0, differing
+    sigma, a, b = oracle.leading_singular_pair(np.abs(R))
+    np.testing.assert_allclose(g[1], np.sqrt(sigma) * a, rtol=1e-8)
+    np.testing.assert_allclose(h[1], np.sqrt(sigma) * b, rtol=1e-8)
+    left = np.linalg.norm(R - g[1][:, None] * B1 * h[1][None, :])
+    np.testing.assert_allclose(flat[-1], left, rtol=1e-9)
