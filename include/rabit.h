@@ -339,7 +339,8 @@ int rb_derive_iterative(const float *W, const double *row_factors, const double 
  * rb_block_prepare is to a block what rb_stack_prepare is to a plain stack
  * (same rules, may block the host); the prepared ops are run, checked and
  * dropped with rb_stack_run, rb_stack_status and rb_stack_forget.  Two-path
- * layers, T <= 4; RB_ERR_UNSUPPORTED otherwise (run such a block op by op with
+ * layers at T <= 4 or three-path layers at T = 1 (the same number of paths in
+ * every layer); RB_ERR_UNSUPPORTED otherwise (run such a block op by op with
  * rb_layer_stack and the three kernels below).  norm_weights is a host array
  * of n_norms device pointers.
  */

@@ -377,7 +377,6 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const SlotExt *__restrict__ ext_g)
 {
     static_assert(KK == 2 || (KK == 3 && TT == 2), "three paths use the two-token layout");
-    static_assert(!BLK || KK == 2, "decoder blocks: two paths");
     constexpr int CW = cwaves_of(TT), THREADS = threads_of(TT);
     constexpr int TILE_BYTES = 512 * KK, SL = sign_loads_of(KK);
     using Lds = LdsMap<CW, KK, pairs_of(TT)>;
@@ -973,7 +972,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 #pragma unroll
             for (int pr = 0; pr < pairs_of(TT); ++pr) { rinv[pr] = 1.f; radd[pr] = 0.f; }
             if constexpr (BLK) {
-                const int tok_in_pair = TT == 1 ? 0 : tok;
+                const int tok_in_pair = (TT == 1 || KK == 3) ? 0 : tok;       // three paths: both lanes of a row hold token 0
                 // 1 / root mean square of the input, per token: the sums of squares of 16 columns
                 // each, added up by the 32 lanes of this slot's half in a fixed order
                 const int n_part = have_slot ? cur.x.n_part : 0;
@@ -1124,8 +1123,8 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     float sq = yf * yf;
 #pragma unroll
                     for (int m = 1; m < 16; m <<= 1) sq += __shfl_xor(sq, m);
-                    const int tk = SPLIT ? 0 : 2 * pair + tok;
-                    if (files && row == 0 && (!SPLIT || sub == 0) && tk < tokens)
+                    const int tk = (SPLIT || KK == 3) ? 0 : 2 * pair + tok;
+                    if (files && row == 0 && ((SPLIT || KK == 3) ? tok == 0 : true) && tk < tokens)
                         store_sc1_u32(cur.x.ssq_out + (uint64_t)tk * (uint32_t)cur.x.ssq_stride * 4u, __float_as_uint(sq));
                 }
             }
@@ -1360,7 +1359,7 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
     const int K = layers[sops[0].layer].K;
     for (int n = 0; n < n_ops; ++n)
         if (layers[sops[n].layer].K != K || !layer_supported(&layers[sops[n].layer], tokens)) return RB_ERR_UNSUPPORTED;
-    if (block && K != 2) return RB_ERR_UNSUPPORTED;
+    if (block && K == 3 && tokens != 1) return RB_ERR_UNSUPPORTED;
     const int T = layout_tokens(tokens, K);            // tokens of the operand layout
 
     // ---- ops, consumers, stages
@@ -1617,7 +1616,8 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            go_pause, pr.block ? reinterpret_cast<const SlotExt *>(ws + lay.ext) : nullptr);
         return RB_OK;
     };
-    const int rc = pr.block    ? (pr.T == 1   ? launch(stack_kernel<1, 2, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
+    const int rc = pr.block    ? (pr.K == 3   ? launch(stack_kernel<2, 3, true>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)
+                                  : pr.T == 1 ? launch(stack_kernel<1, 2, true>, threads_of(1), LdsMap<cwaves_of(1)>::BYTES)
                                   : pr.T == 2 ? launch(stack_kernel<2, 2, true>, threads_of(2), LdsMap<cwaves_of(2)>::BYTES)
                                               : launch(stack_kernel<4, 2, true>, threads_of(4), LdsMap<cwaves_of(4), 2, 2>::BYTES))
                    : pr.K == 3 ? launch(stack_kernel<2, 3>, threads_of(2), LdsMap<cwaves_of(2), 3>::BYTES)

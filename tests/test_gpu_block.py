@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-5
 
 
-def build_block(which, n_layers, config, T, shrink=None, outliers=False, in_place=False, gain=None):
+def build_block(which, n_layers, config, T, shrink=None, outliers=False, in_place=False, gain=None, K=2):
     """Layers, norm weights and the stack input of a Llama-shaped block stack: uniform signs,
     half-normal scales with a gain on g that keeps every op's output near RMS 1 for a normalised
     input, norm weights around 1 (a few negative, one zero)."""
@@ -29,7 +29,7 @@ def build_block(which, n_layers, config, T, shrink=None, outliers=False, in_plac
         g_gain = gain if gain is not None else 1.0 / (0.02 * 0.02 * np.sqrt(m(inn)))
         if name.endswith("down"):
             g_gain *= 2.0           # its input, silu(gate) * up, has RMS near 1/2
-        layers.append(random_layer(rng, 2, m(out), m(inn), gain=g_gain))
+        layers.append(random_layer(rng, K, m(out), m(inn), gain=g_gain))
     norm_w = []
     for n, w in enumerate(norms):
         rng = synth.child_rng(config, 2, n)
@@ -101,6 +101,27 @@ def test_full_width_7b_blocks(T):
     print(f"two full-width 7B blocks, T={T}", flush=True)
     got, _, _ = _run(ops, widths, layers, norm_w, x0, T)
     _check(ops, layers, norm_w, got, f"full-width 7B blocks T={T}")
+
+
+def test_three_path_blocks_one_token():
+    """The 3-bit variant: three paths in every layer, one token (the third path rides in the lanes
+    of a second token), at 1/8 width over three blocks and at full 7B width."""
+    ops, widths, layers, norm_w, x0 = build_block("7b", 3, 58, 1, shrink=SHRINK, outliers=True, K=3)
+    print("three-path block stack at 1/8 width", flush=True)
+    got, _, _ = _run(ops, widths, layers, norm_w, x0, 1)
+    _check(ops, layers, norm_w, got, "three-path small block stack")
+    ops, widths, layers, norm_w, x0 = build_block("7b", 1, 59, 1, K=3)
+    print("one full-width three-path 7B block", flush=True)
+    got, _, _ = _run(ops, widths, layers, norm_w, x0, 1)
+    _check(ops, layers, norm_w, got, "three-path full-width block")
+    # two tokens of three paths: not on this kernel
+    ops, widths, layers, norm_w, x0 = build_block("7b", 1, 59, 2, shrink=SHRINK, K=3)
+    dev_layers = [to_device_layer(*l) for l in layers]
+    dev_norms = [torch.from_numpy(w).cuda() for w in norm_w]
+    dev_bufs = [torch.zeros((2, w), dtype=torch.float16, device="cuda") for w in widths]
+    with pytest.raises(rb.RabitError) as e:
+        rb.Block(dev_layers, dev_norms, EPS, _op_tuples(ops), dev_bufs, 2).prepare()
+    assert e.value.code == rb.RB_ERR_UNSUPPORTED
 
 
 def test_one_13b_block():
