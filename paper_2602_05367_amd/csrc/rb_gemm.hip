@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void scale_kernel(const ActT *__restrict__ X, 
 // and rounds to the output type.  part is [split][T][rows] for rows row0 .. row0 + rows - 1 of Y.
 __global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ part, const float *__restrict__ scl,
                                                      void *__restrict__ Y, int out_dtype, int T, int out, int row0,
-                                                     int rows, int split)
+                                                     int rows, int split, int factor)
 {
     const size_t n = (size_t)T * rows;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const float *__restrict__ p
     float s = 0.f;
     for (int k = 0; k < split; ++k) s += part[(size_t)k * n + i];
     const size_t t = i / rows, r = i % rows;
-    store_out(Y, out_dtype, t * out + row0 + r, s * scl[4]);
+    store_out(Y, out_dtype, t * out + row0 + r, s * scl[factor]);
 }
 
 // ----------------------------------------------------------------- GEMM ---
@@ -426,72 +426,85 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const v4u *__restrict__ bi
 // and all 256 tokens, so no two wavefronts build the same left operand.
 constexpr int ONE_NBUF = 5;                    // ring of right-operand buffers (three steps of copies in flight)
 constexpr int ONE_BUF_BYTES = LARGE_TOKENS * 64 + 256;     // 256 tokens x 32 columns of X, then the step's h block
-constexpr int HBLOCK_BYTES = 256;              // per 32-column group: [path][32 magnitudes fp16][2 sign words][padding]
+constexpr int HBLOCK_BYTES = 256;              // per 32-column group: [path][32 magnitudes fp16][K sign words][padding]
 
 // Largest |h_k| and |g_k|: ABSMAX_GROUPS workgroups take a slice each and write their four maxima
 // to part[group][4] (scratch that the next kernels overwrite)
 constexpr int ABSMAX_GROUPS = 64;
-__global__ __launch_bounds__(256) void absmax_kernel(const __half *__restrict__ g, const __half *__restrict__ h, int out,
+// (part[group][2 k] for |h_k|, part[group][2 k + 1] for |g_k|, eight floats per group)
+__global__ __launch_bounds__(256) void absmax_kernel(const __half *__restrict__ g, const __half *__restrict__ h, int K, int out,
                                                      int in, float *__restrict__ part)
 {
-    __shared__ float red[4][256];
-    float m[4] = {0.f, 0.f, 0.f, 0.f};
+    __shared__ float red[2 * RB_MAX_K][256];
+    float m[2 * RB_MAX_K];
+#pragma unroll
+    for (int q = 0; q < 2 * RB_MAX_K; ++q) m[q] = 0.f;
     const int tid = blockIdx.x * 256 + threadIdx.x, stride = ABSMAX_GROUPS * 256;
-    for (int j = tid; j < in; j += stride) {
-        m[0] = fmaxf(m[0], fabsf(__half2float(h[j])));
-        m[1] = fmaxf(m[1], fabsf(__half2float(h[(size_t)in + j])));
-    }
-    for (int j = tid; j < out; j += stride) {
-        m[2] = fmaxf(m[2], fabsf(__half2float(g[j])));
-        m[3] = fmaxf(m[3], fabsf(__half2float(g[(size_t)out + j])));
+#pragma unroll
+    for (int k = 0; k < RB_MAX_K; ++k) {
+        if (k < K) {
+            for (int j = tid; j < in; j += stride) m[2 * k] = fmaxf(m[2 * k], fabsf(__half2float(h[(size_t)k * in + j])));
+            for (int j = tid; j < out; j += stride) m[2 * k + 1] = fmaxf(m[2 * k + 1], fabsf(__half2float(g[(size_t)k * out + j])));
+        }
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = m[q];
+    for (int q = 0; q < 2 * RB_MAX_K; ++q) red[q][threadIdx.x] = m[q];
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = fmaxf(red[q][threadIdx.x], red[q][threadIdx.x + s]);
+            for (int q = 0; q < 2 * RB_MAX_K; ++q) red[q][threadIdx.x] = fmaxf(red[q][threadIdx.x], red[q][threadIdx.x + s]);
         __syncthreads();
     }
-    if (threadIdx.x < 4) part[blockIdx.x * 4 + threadIdx.x] = red[threadIdx.x][0];
+    if (threadIdx.x < 2 * RB_MAX_K) part[blockIdx.x * 8 + threadIdx.x] = red[threadIdx.x][0];
 }
 
-// scl[0..1] = s_k (h), scl[2..3] = S / s_k (g), scl[4] = 1 / S
-__global__ __launch_bounds__(64) void scales1_kernel(const float *__restrict__ part, float *__restrict__ scl)
+// scl[k] = s_k (h), scl[3 + k] = S / s_k (g), scl[6] = 1 / S, with S the largest common power of two
+// that keeps every path's |g_k| S / s_k at or below 1/2
+__global__ __launch_bounds__(64) void scales1_kernel(const float *__restrict__ part, int K, float *__restrict__ scl)
 {
-    float m[4];
+    float m[2 * RB_MAX_K];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        m[q] = part[threadIdx.x * 4 + q];                   // ABSMAX_GROUPS = 64 = one per lane
+    for (int q = 0; q < 2 * RB_MAX_K; ++q) {
+        m[q] = part[threadIdx.x * 8 + q];                   // ABSMAX_GROUPS = 64 = one per lane
         for (int s = 32; s > 0; s >>= 1) m[q] = fmaxf(m[q], __shfl_xor(m[q], s));
     }
     if (threadIdx.x == 0) {
-        const float s0 = mx::input_scale(m[0]), s1 = mx::input_scale(m[1]);
-        const float S = fminf(s0 * mx::input_scale(m[2]), s1 * mx::input_scale(m[3]));
-        scl[0] = s0; scl[1] = s1;
-        scl[2] = S / s0; scl[3] = S / s1;
-        scl[4] = 1.f / S;
+        float sk[RB_MAX_K], S = 0.f;
+        for (int k = 0; k < K; ++k) {
+            sk[k] = mx::input_scale(m[2 * k]);
+            const float cand = sk[k] * mx::input_scale(m[2 * k + 1]);
+            S = k == 0 ? cand : fminf(S, cand);
+        }
+        for (int k = 0; k < K; ++k) { scl[k] = sk[k]; scl[3 + k] = S / sk[k]; }
+        scl[6] = 1.f / S;
     }
 }
 
 // the h block of every 32-column group, and X in fp16 in contraction order (rows t >= T and columns
 // j >= in are zero)
-__global__ __launch_bounds__(64) void hblock_kernel(const __half *__restrict__ h, const float *__restrict__ scl, int in,
-                                                    uint8_t *__restrict__ Hblk)
+__global__ __launch_bounds__(32 * RB_MAX_K) void hblock_kernel(const __half *__restrict__ h, const float *__restrict__ scl, int K,
+                                                               int in, uint8_t *__restrict__ Hblk)
 {
-    const int group = blockIdx.x, lane = threadIdx.x, k = lane >> 5, col = lane & 31;
+    // one thread per (path, column) of the group: threads 0..31 path 0, 32..63 path 1, 64..95 path 2
+    const int group = blockIdx.x, k = threadIdx.x >> 5, col = threadIdx.x & 31;
+    uint8_t *blk = Hblk + (size_t)group * HBLOCK_BYTES;
+    if (k >= K) {
+        // the rest of the block: nobody reads it, but it is copied
+        for (int i = K * 64 + K * 4 + 4 * col; i < HBLOCK_BYTES; i += 128) *reinterpret_cast<uint32_t *>(blk + i) = 0u;
+        return;
+    }
     const int j = group * 32 + col;
     const float hv = j < in ? __half2float(h[(size_t)k * in + j]) : 0.f;
-    uint8_t *blk = Hblk + (size_t)group * HBLOCK_BYTES;
     reinterpret_cast<_Float16 *>(blk)[k * 32 + contraction_position(col)] = (_Float16)(fabsf(hv) * scl[k]);
     // sign word in the bit order of the stored sign words: native bit of column col
-    const unsigned long long neg = __ballot(hv < 0.f);
+    const unsigned long long neg = __ballot(hv < 0.f);       // a wavefront holds two paths (or path 2 alone)
+    const uint32_t mine = (uint32_t)(neg >> (32 * (threadIdx.x >> 5 & 1)));
     uint32_t word = 0;
-    const uint32_t mine = (uint32_t)(neg >> (32 * k));
     for (int b = 0; b < 32; ++b) word |= ((mine >> b) & 1u) << native_bit(b);
-    if (col == 0) reinterpret_cast<uint32_t *>(blk + 128)[k] = word;
-    if (lane < 30) reinterpret_cast<uint32_t *>(blk + 136)[lane] = 0u;
+    if (col == 0) reinterpret_cast<uint32_t *>(blk + K * 64)[k] = word;
+    if (K == RB_MAX_K && k == 0)
+        for (int i = K * 64 + K * 4 + 4 * col; i < HBLOCK_BYTES; i += 128) *reinterpret_cast<uint32_t *>(blk + i) = 0u;
 }
 
 // a thread writes eight consecutive positions (16 bytes) of a 32-column group and gathers their
@@ -517,8 +530,8 @@ __global__ __launch_bounds__(256) void xperm_kernel(const ActT *__restrict__ X, 
 
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
-template <int OUT_DT>
-__global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ bits, const __half *__restrict__ g,
+template <int OUT_DT, int K>
+__global__ __launch_bounds__(256, 1) void gemm1_kernel(const uint32_t *__restrict__ bits, const __half *__restrict__ g,
                                                        const float *__restrict__ scl, const uint8_t *__restrict__ Hblk,
                                                        const _Float16 *__restrict__ Xp, void *__restrict__ Y,
                                                        float *__restrict__ Acc, int out, int RT, int CT, int T, int T_pad,
@@ -549,15 +562,15 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
 
     // ---- per-row constants: |g_k| S / s_k as a packed pair, and the sign of g_k as a mask on the sign words
     // (both for the row this lane feeds to the matrix instruction: row pair m, row l % 32)
-    uint32_t G2[MP][2], flip[MP][2];
+    uint32_t G2[MP][K], flip[MP][K];
 #pragma unroll
     for (int m = 0; m < MP; ++m) {
         const int row = (rt_base + 2 * m + half_sel) * TILE_ROWS + r;
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < K; ++k) {
             const __half gk = row < out ? g[(size_t)k * out + row] : __float2half(0.f);
             flip[m][k] = (__half_as_ushort(gk) & 0x8000u) ? 0xffffffffu : 0u;
-            const float gv = fabsf(__half2float(gk)) * scl[2 + k];
+            const float gv = fabsf(__half2float(gk)) * scl[3 + k];
             const uint32_t mag = (uint32_t)__half_as_ushort(__float2half_rn(gv));
             G2[m][k] = mag | (mag << 16);
         }
@@ -567,27 +580,24 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
     // 4 kg once per step; what is left of the shift is a constant.
     const uint32_t kg4 = 4u * (uint32_t)kg;
 
-    auto load_words = [&](int ct, v4u (&w)[2 * MP]) {
+    // sign words of this wavefront's row tiles for one column tile: lane (r, q) holds, for row r,
+    // the 2 K words [column half c][path k] of columns 128c + 32q .. +31
+    struct Words { uint32_t w[2 * K]; };
+    auto load_half = [&](int ct, int c, Words (&w)[2 * MP]) {
 #pragma unroll
         for (int i = 0; i < 2 * MP; ++i) {
             const int rt = rt_base + i;
-            v4u v = {0u, 0u, 0u, 0u};
-            if (rt < RT) v = bits[((size_t)rt * CT + ct) * 64 + lane];
-            w[i] = v;
-        }
-    };
-    // the two words (both paths) of column half c again, for the next column tile
-    auto reload_half = [&](int ct, int c, v4u (&w)[2 * MP]) {
-        const uint2 *words = reinterpret_cast<const uint2 *>(bits);
+            const uint32_t *src = bits + (((size_t)rt * CT + ct) * 64 + lane) * (2 * K) + c * K;
 #pragma unroll
-        for (int i = 0; i < 2 * MP; ++i) {
-            const int rt = rt_base + i;
-            uint2 v = make_uint2(0u, 0u);
-            if (rt < RT) v = words[(((size_t)rt * CT + ct) * 64 + lane) * 2 + c];
-            w[i][2 * c] = v.x;
-            w[i][2 * c + 1] = v.y;
+            for (int k = 0; k < K; ++k) w[i].w[c * K + k] = rt < RT ? src[k] : 0u;
         }
     };
+    auto load_words = [&](int ct, Words (&w)[2 * MP]) {
+        load_half(ct, 0, w);
+        load_half(ct, 1, w);
+    };
+    // the words of column half c again, for the next column tile
+    auto reload_half = [&](int ct, int c, Words (&w)[2 * MP]) { load_half(ct, c, w); };
 
     // right-operand staging, as in the kernel above, plus the 256-byte h block of the step (every
     // wavefront copies it: four bytes per lane, the same bytes to the same place)
@@ -631,11 +641,11 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[m][n][e] = 0.f;
 
-    v4u cur[2 * MP];
+    Words cur[2 * MP];
     v8h a[2][MP][2], b[NT][2];
-    v8h hm[2][2];                                             // [path][half]: |h| of this lane's eight positions
-    uint32_t hs[2];                                           // sign words of h for the step
-    uint32_t wq[MP][2];
+    v8h hm[K][2];                                             // [path][half]: |h| of this lane's eight positions
+    uint32_t hs[K];                                           // sign words of h for the step
+    uint32_t wq[MP][K];
     const uint32_t sel_mask = half_sel ? 0xffffffffu : 0u;
     // (addresses: one register per half and ring buffer, everything else in the instruction's offset)
     auto read_b = [&](uint32_t addr, int n, int kk) {
@@ -650,18 +660,27 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
         default: asm volatile("ds_read_b128 %0, %1 offset:14336" : "=v"(b[7][kk]) : "v"(addr) : "memory"); break;
         }
     };
-    // addr: this lane's 16 bytes of path 0, half 0 of the step's h block
+    // addr: this lane's 16 bytes of path 0, half 0 of the step's h block; reads 0 .. 2K - 1 are the
+    // magnitudes [path][half], read 2K the sign words (K * 64 bytes into the block; addr carries
+    // 16 bytes per k group)
     auto read_h = [&](uint32_t addr, int i) {
-        uint2 v;
         switch (i) {
         case 0: asm volatile("ds_read_b128 %0, %1" : "=v"(hm[0][0]) : "v"(addr) : "memory"); break;
         case 1: asm volatile("ds_read_b128 %0, %1 offset:32" : "=v"(hm[0][1]) : "v"(addr) : "memory"); break;
         case 2: asm volatile("ds_read_b128 %0, %1 offset:64" : "=v"(hm[1][0]) : "v"(addr) : "memory"); break;
         case 3: asm volatile("ds_read_b128 %0, %1 offset:96" : "=v"(hm[1][1]) : "v"(addr) : "memory"); break;
         default:
-            // the two sign words sit 128 bytes into the block (addr carries 16 bytes per k group)
-            asm volatile("ds_read_b64 %0, %1 offset:128" : "=v"(v) : "v"(addr - 16u * (uint32_t)kg) : "memory");
-            hs[0] = v.x; hs[1] = v.y;
+            if constexpr (K == 3) {
+                if (i == 4) { asm volatile("ds_read_b128 %0, %1 offset:128" : "=v"(hm[K - 1][0]) : "v"(addr) : "memory"); break; }
+                if (i == 5) { asm volatile("ds_read_b128 %0, %1 offset:160" : "=v"(hm[K - 1][1]) : "v"(addr) : "memory"); break; }
+                v4u v;
+                asm volatile("ds_read_b128 %0, %1 offset:192" : "=v"(v) : "v"(addr - 16u * (uint32_t)kg) : "memory");
+                hs[0] = v[0]; hs[1] = v[1]; hs[K - 1] = v[2];
+            } else {
+                uint2 v;
+                asm volatile("ds_read_b64 %0, %1 offset:128" : "=v"(v) : "v"(addr - 16u * (uint32_t)kg) : "memory");
+                hs[0] = v.x; hs[1] = v.y;
+            }
             break;
         }
     };
@@ -669,12 +688,12 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
     // The word of this lane's row (row tile 2m + half_sel, row r) sits in lane (r, q) of that
     // tile's register.  The lane exchange is written as instructions, like the operand reads: its
     // results are taken up after the step's common wait, not one by one.
-    uint32_t wf[MP][2][2];
+    uint32_t wf[MP][K][2];
     const uint32_t bp_addr = 4u * (uint32_t)r;
-    auto fetch_a = [&](const v4u (&w)[2 * MP], int c, int q, int m, int k) {
+    auto fetch_a = [&](const Words (&w)[2 * MP], int c, int q, int m, int k) {
         const uint32_t a0 = bp_addr + 64u * (uint32_t)q;
-        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][0]) : "v"(a0), "v"(w[2 * m][c * 2 + k]) : "memory");
-        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][1]) : "v"(a0), "v"(w[2 * m + 1][c * 2 + k]) : "memory");
+        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][0]) : "v"(a0), "v"(w[2 * m].w[c * K + k]) : "memory");
+        asm volatile("ds_bpermute_b32 %0, %1, %2" : "=v"(wf[m][k][1]) : "v"(a0), "v"(w[2 * m + 1].w[c * K + k]) : "memory");
     };
     // after the wait: pick the word of this lane's row tile, put the signs of g and h into it, and
     // move it so that this lane's first position sits at bit 0 (and 16)
@@ -686,20 +705,30 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
     auto expand_a = [&](int i, v8h (&aa)[MP][2]) {
         // register e of the four of (row pair m, half kk): two elements of the effective weight
         const int m = i >> 3, kk = (i >> 2) & 1, e = i & 3;
-        union { v8h h; uint32_t u[4]; v2h p[4]; } f, h0, h1;
+        union { v8h h; uint32_t u[4]; v2h p[4]; } f, h0;
         f.h = aa[m][kk];
         h0.h = hm[0][kk];
-        h1.h = hm[1][kk];
-        union { uint32_t u; v2h p; } g0, g1, p1, s2;
+        union { uint32_t u; v2h p; } g0, p1;
         g0.u = G2[m][0];
-        g1.u = G2[m][1];
         p1.p = g0.p * h0.p[e];                                                 // |g_1| |h_1|
         p1.u = ((wq[m][0] << (15 - 8 * kk - e)) & 0x80008000u) | p1.u;          // its sign
-        s2.u = ((wq[m][1] << (15 - 8 * kk - e)) & 0x80008000u) | h1.u[e];       // signed |h_2|
-        f.p[e] = __builtin_elementwise_fma(g1.p, s2.p, p1.p);
+#pragma unroll
+        for (int k = 1; k < K; ++k) {
+            union { v8h h; uint32_t u[4]; } hk;
+            union { uint32_t u; v2h p; } gk, sk;
+            hk.h = hm[k][kk];
+            gk.u = G2[m][k];
+            sk.u = ((wq[m][k] << (15 - 8 * kk - e)) & 0x80008000u) | hk.u[e];   // signed |h_k|
+            p1.p = __builtin_elementwise_fma(gk.p, sk.p, p1.p);
+        }
+        f.p[e] = p1.p;
         aa[m][kk] = f.h;
     };
     auto wait_lds = [&]() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
+    auto touch_h = [&]() {
+#pragma unroll
+        for (int k = 0; k < K; ++k) asm volatile("" : "+v"(hm[k][0]), "+v"(hm[k][1]), "+v"(hs[k]));
+    };
     auto touch_b = [&](int kk) {
 #pragma unroll
         for (int n = 0; n < NT; ++n) asm volatile("" : "+v"(b[n][kk]));
@@ -712,16 +741,20 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
         for (int s = 0; s < NBUF - 1; ++s) stage_step(s);
         wait_copies_and_sync<CP * (NBUF - 2)>();               // step 0 has landed
 #pragma unroll
-        for (int i = 0; i < 5; ++i) read_h(h_addr, i);
+        for (int i = 0; i < 2 * K + 1; ++i) read_h(h_addr, i);
 #pragma unroll
-        for (int m = 0; m < MP; ++m) { fetch_a(cur, 0, 0, m, 0); fetch_a(cur, 0, 0, m, 1); }
+        for (int m = 0; m < MP; ++m)
+#pragma unroll
+            for (int k = 0; k < K; ++k) fetch_a(cur, 0, 0, m, k);
 #pragma unroll
         for (int n = 0; n < NT; ++n) read_b(b_addr[0], n, 0);
         wait_lds();
-        asm volatile("" : "+v"(hm[0][0]), "+v"(hm[0][1]), "+v"(hm[1][0]), "+v"(hm[1][1]), "+v"(hs[0]), "+v"(hs[1]));
+        touch_h();
         touch_b(0);
 #pragma unroll
-        for (int m = 0; m < MP; ++m) { sign_a(m, 0); sign_a(m, 1); }
+        for (int m = 0; m < MP; ++m)
+#pragma unroll
+            for (int k = 0; k < K; ++k) sign_a(m, k);
 #pragma unroll
         for (int i = 0; i < MP * 8; ++i) expand_a(i, a[0]);
     }
@@ -745,9 +778,11 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
                 if (j == 16) {                                  // this step's second half, and the next step's words and h
                     wait_lds();
                     touch_b(1);
-                    asm volatile("" : "+v"(hm[0][0]), "+v"(hm[0][1]), "+v"(hm[1][0]), "+v"(hm[1][1]), "+v"(hs[0]), "+v"(hs[1]));
+                    touch_h();
 #pragma unroll
-                    for (int mm = 0; mm < MP; ++mm) { sign_a(mm, 0); sign_a(mm, 1); }
+                    for (int mm = 0; mm < MP; ++mm)
+#pragma unroll
+                        for (int k = 0; k < K; ++k) sign_a(mm, k);
                 }
                 acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[p][m][kk], b[n][kk], acc[m][n], 0, 0, 0);
                 if (j == 0) {
@@ -758,8 +793,8 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
                     stage_step(s + NBUF - 1);
                 }
                 if (j < 8) read_b(b1_here, j, 1);
-                if (j >= 1 && j < 6) read_h(h_next, j - 1);
-                if (j >= 6 && j < 10) fetch_a(cur, c_, q_, (j - 6) >> 1, (j - 6) & 1);
+                if (j >= 1 && j < 2 * K + 2) read_h(h_next, j - 1);
+                if (j >= 8 && j < 8 + MP * K) fetch_a(cur, c_, q_, (j - 8) / K, (j - 8) % K);
                 if (j >= 16 && j < 24) read_b(b0_next, j - 16, 0);
                 if (j >= 16) expand_a(j - 16, a[pn]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -775,7 +810,7 @@ __global__ __launch_bounds__(256, 1) void gemm1_kernel(const v4u *__restrict__ b
     // ---- epilogue: lane l of tile (m, n) holds token 32n + l % 32 and, in register 4a + e, row
     // 8a + 4 (l / 32) + e of the 32
     asm volatile("" : "+s"(out));
-    const float inv_s = scl[4];
+    const float inv_s = scl[6];
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
         const int t = tb * BLK_TOK + n * 32 + (lane & 31);
@@ -857,7 +892,8 @@ size_t workspace_bytes(const rb_layer *L, int T)
 
 bool supported(const rb_layer *L, int T)
 {
-    return L->K == 2 && T >= 1;
+    // three paths: the one-contraction kernel only (more than 32 tokens)
+    return (L->K == 2 && T >= 1) || (L->K == 3 && T > SMALL_TOKENS);
 }
 
 int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype, void *workspace,
@@ -872,12 +908,12 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
     const dim3 sgrid(p.in_pad / 256, p.T_pad);
     if (!p.small) {
         // one contraction on the effective weight built in registers
-        const v4u *bits = static_cast<const v4u *>(L->bits);
+        const uint32_t *bits = static_cast<const uint32_t *>(L->bits);
         const __half *g = reinterpret_cast<const __half *>(L->g);
-        static_assert(ABSMAX_GROUPS == 64 && ABSMAX_GROUPS * 4 * sizeof(float) <= LARGE_TOKENS * TILE_COLS * sizeof(_Float16), "partials fit in U");
-        hipLaunchKernelGGL(absmax_kernel, dim3(ABSMAX_GROUPS), dim3(256), 0, stream, g, h, L->out, L->in, reinterpret_cast<float *>(U));
-        hipLaunchKernelGGL(scales1_kernel, dim3(1), dim3(64), 0, stream, reinterpret_cast<const float *>(U), scl);
-        hipLaunchKernelGGL(hblock_kernel, dim3(p.CT * 8), dim3(64), 0, stream, h, scl, L->in, Hblk);
+        static_assert(ABSMAX_GROUPS == 64 && ABSMAX_GROUPS * 8 * sizeof(float) <= LARGE_TOKENS * TILE_COLS * sizeof(_Float16), "partials fit in U");
+        hipLaunchKernelGGL(absmax_kernel, dim3(ABSMAX_GROUPS), dim3(256), 0, stream, g, h, L->K, L->out, L->in, reinterpret_cast<float *>(U));
+        hipLaunchKernelGGL(scales1_kernel, dim3(1), dim3(64), 0, stream, reinterpret_cast<const float *>(U), L->K, scl);
+        hipLaunchKernelGGL(hblock_kernel, dim3(p.CT * 8), dim3(32 * RB_MAX_K), 0, stream, h, scl, L->K, L->in, Hblk);
         const dim3 xgrid((p.in_pad / 8 + 255) / 256, p.T_pad);
         if (act_dtype == RB_F16)
             hipLaunchKernelGGL(xperm_kernel<__half>, xgrid, dim3(256), 0, stream, static_cast<const __half *>(X), U, T, p.T_pad,
@@ -896,13 +932,17 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
                                p.full_tiles, p.tail_split, p.tail_row0, p.tail_rows);
             return RB_OK;
         };
-        const int rc = out_dtype == RB_F16 ? run(gemm1_kernel<RB_F16>) : out_dtype == RB_BF16 ? run(gemm1_kernel<RB_BF16>)
-                                                                                               : run(gemm1_kernel<RB_F32>);
+        const int rc = L->K == 3 ? (out_dtype == RB_F16    ? run(gemm1_kernel<RB_F16, 3>)
+                                    : out_dtype == RB_BF16 ? run(gemm1_kernel<RB_BF16, 3>)
+                                                           : run(gemm1_kernel<RB_F32, 3>))
+                                 : (out_dtype == RB_F16    ? run(gemm1_kernel<RB_F16, 2>)
+                                    : out_dtype == RB_BF16 ? run(gemm1_kernel<RB_BF16, 2>)
+                                                           : run(gemm1_kernel<RB_F32, 2>));
         if (rc != RB_OK) return rc;
         if (p.tail_split > 1) {
             const size_t n = (size_t)T * p.tail_rows;
             hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype, T,
-                               L->out, p.tail_row0, p.tail_rows, p.tail_split);
+                               L->out, p.tail_row0, p.tail_rows, p.tail_split, 6);
         }
         return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
     }
@@ -926,7 +966,7 @@ int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int 
         RB_GEMM(RB_F32, 4, 1, 2, 1);
         const size_t n = (size_t)T * L->out;
         hipLaunchKernelGGL(finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Acc, scl, Y, out_dtype, T,
-                           L->out, 0, L->out, p.split);
+                           L->out, 0, L->out, p.split, 4);
     } else {
         if (out_dtype == RB_F16) RB_GEMM(RB_F16, 4, 1, 2, 1);
         else if (out_dtype == RB_BF16) RB_GEMM(RB_BF16, 4, 1, 2, 1);

@@ -45,6 +45,25 @@ def test_gemm_matches_oracle(out, inn, T):
     assert err <= TOL
 
 
+@pytest.mark.parametrize("out,inn,T", [(272, 320, 33), (1000, 2080, 517), (4096, 1024, 256), (8400, 1024, 300)])
+def test_three_path_gemm_matches_oracle(out, inn, T):
+    """The 3-bit variant beyond 32 tokens: the same one-contraction kernel with a third path in
+    the effective weight (ragged shapes, tiles cut along the contraction, scales of either sign)."""
+    rng = synth.child_rng(5, 110, out, inn, T)
+    signs, g, h = random_layer(rng, 3, out, inn)
+    g = g.copy(); h = h.copy()
+    g[2, ::7] *= -1; h[1, ::5] *= -1; h[2, 3::4] *= -1; g[0, 11] = 0
+    X = synth.outlier_activations(rng, T, inn)
+    _say(f"three-path gemm out={out} in={inn} T={T}")
+    L = to_device_layer(signs, g, h)
+    Y = rb.rb_linear_gemm(L, torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_GEMM
+    err = max_rel_l2(Y, oracle.forward(signs, g, h, X))
+    _say(f"  rel_l2={err:.3e}")
+    assert err <= TOL
+
+
 def test_gemm_negative_and_zero_scales():
     """Stored output scales of either sign and zero: the kernel folds the sign of g into the
     sign bits and keeps |g| as the magnitude of its left operand."""
