@@ -247,7 +247,7 @@ int rb_weight_grad(const uint16_t *Delta, const uint16_t *X, int N, int out, int
  * summed over the samples:
  *   grad_g[i][r] = sum_c B_i[r][c] h_i[c] G[r][c]
  *   grad_h[i][c] = sum_r B_i[r][c] g_i[r] G[r][c]    (the transposed binary product)
- * with G from rb_weight_grad (or any fp32 [out][in] = Delta^T X).  packed:
+ * with G from rb_weight_grad (or any fp32 [out][in] = Delta^T X; 16-byte aligned).  packed:
  * canonical words as rb_couple writes them.  grad_g fp32 [K][out], grad_h fp32
  * [K][in].  workspace: rb_scale_grads_workspace_bytes(K, out, in) bytes, 16-byte
  * aligned (partial column sums; their order is fixed, results repeat bit for bit).

@@ -51,10 +51,21 @@ __global__ __launch_bounds__(256) void couple_kernel(const float *__restrict__ W
     float gr[RB_MAX_K];
     for (int k = 0; k < K; ++k) gr[k] = __half2float(g[(size_t)k * out + row]);
     const int chunk0 = blockIdx.y * COUPLE_CHUNK, chunk1 = min(in, chunk0 + COUPLE_CHUNK);
-    for (int c0 = chunk0; c0 < chunk1; c0 += 64) {
+    // the chunk's weights first, all loads in flight at once: a wavefront that asked for them one
+    // step at a time would spend its life waiting for memory
+    float wv[COUPLE_CHUNK / 64];
+#pragma unroll
+    for (int i = 0; i < COUPLE_CHUNK / 64; ++i) {
+        const int c = chunk0 + 64 * i + lane;
+        wv[i] = c < in ? W[(size_t)row * in + c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < COUPLE_CHUNK / 64; ++i) {
+        const int c0 = chunk0 + 64 * i;
+        if (c0 >= chunk1) break;
         const int c = c0 + lane;
         const bool real = c < in;
-        float r = real ? W[(size_t)row * in + c] : 0.f;
+        float r = wv[i];
         for (int k = 0; k < K; ++k) {
             const bool neg = real && !(r >= 0.f);                 // sign(0) = +1; columns past the end read as +1
             const unsigned long long bal = __ballot(neg);
@@ -90,8 +101,9 @@ __global__ __launch_bounds__(256) void weight_grad_kernel(const __half *__restri
     G[(size_t)r * in + c] = s;
 }
 
-// grad g: one wavefront per row, lanes across the columns, K sums per lane, then a butterfly over
-// the wavefront (a fixed order for a given width).
+// grad g: one wavefront per row; a lane takes four consecutive columns at a time (one 16-byte load
+// of G, four bits of one sign word per path), four such steps in flight; K sums per lane, then a
+// butterfly over the wavefront (a fixed order for a given width).
 __global__ __launch_bounds__(256) void grad_rows_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
                                                         const __half *__restrict__ h, int K, int out, int in,
                                                         float *__restrict__ grad_g)
@@ -100,13 +112,30 @@ __global__ __launch_bounds__(256) void grad_rows_kernel(const float *__restrict_
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= out) return;
     const int W32 = in / 32;
+    const float4 *Grow = reinterpret_cast<const float4 *>(G + (size_t)row * in);     // in % 32 == 0: 16-byte aligned rows
     float s[RB_MAX_K] = {0.f, 0.f, 0.f};
-    for (int c = lane; c < in; c += 64) {
-        const float gv = G[(size_t)row * in + c];
-        for (int k = 0; k < K; ++k) {
-            const uint32_t word = packed[((size_t)k * out + row) * W32 + (c >> 5)];
-            const float t = __half2float(h[(size_t)k * in + c]) * gv;
-            s[k] += (word >> (c & 31)) & 1u ? -t : t;
+    for (int c0 = 0; c0 < in; c0 += 4 * 256) {
+        float4 gv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 256 * u + 4 * lane;
+            gv[u] = c < in ? Grow[c >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 256 * u + 4 * lane;
+            if (c < in) {
+                const float v[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+                for (int k = 0; k < K; ++k) {
+                    const uint32_t bits4 = packed[((size_t)k * out + row) * W32 + (c >> 5)] >> (c & 31);
+                    const __half *hk = h + (size_t)k * in + c;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float t = __half2float(hk[e]) * v[e];
+                        s[k] += (bits4 >> e) & 1u ? -t : t;
+                    }
+                }
+            }
         }
     }
     for (int k = 0; k < K; ++k) {
@@ -116,25 +145,43 @@ __global__ __launch_bounds__(256) void grad_rows_kernel(const float *__restrict_
     }
 }
 
-// grad h, first pass: a thread per column walks ROW_SLICE rows of its slice in order; partial sums
-// [slice][K][in].  Second pass: the slices are added in order.
-__global__ __launch_bounds__(256) void grad_cols_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
-                                                        const __half *__restrict__ g, int K, int out, int in,
-                                                        float *__restrict__ part)
+// grad h, first pass: a thread takes four consecutive columns and walks the ROW_SLICE rows of its
+// slice in order, eight rows in flight; partial sums [slice][K][in].  Second pass: the slices are
+// added in order.
+__global__ __launch_bounds__(64) void grad_cols_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
+                                                       const __half *__restrict__ g, int K, int out, int in,
+                                                       float *__restrict__ part)
 {
-    const int c = blockIdx.x * 256 + threadIdx.x, slice = blockIdx.y;
+    const int c = (blockIdx.x * 64 + threadIdx.x) * 4, slice = blockIdx.y;
     if (c >= in) return;
     const int W32 = in / 32, r0 = slice * ROW_SLICE, r1 = min(out, r0 + ROW_SLICE);
-    float s[RB_MAX_K] = {0.f, 0.f, 0.f};
-    for (int r = r0; r < r1; ++r) {
-        const float gv = G[(size_t)r * in + c];
-        for (int k = 0; k < K; ++k) {
-            const uint32_t word = packed[((size_t)k * out + r) * W32 + (c >> 5)];
-            const float t = __half2float(g[(size_t)k * out + r]) * gv;
-            s[k] += (word >> (c & 31)) & 1u ? -t : t;
+    float s[RB_MAX_K][4];
+    for (int k = 0; k < RB_MAX_K; ++k)
+        for (int e = 0; e < 4; ++e) s[k][e] = 0.f;
+    for (int rb = r0; rb < r1; rb += 8) {
+        float4 gv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            gv[u] = rb + u < r1 ? *reinterpret_cast<const float4 *>(G + (size_t)(rb + u) * in + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = rb + u;
+            if (r < r1) {
+                const float v[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+                for (int k = 0; k < K; ++k) {
+                    const uint32_t bits4 = packed[((size_t)k * out + r) * W32 + (c >> 5)] >> (c & 31);
+                    const float gk = __half2float(g[(size_t)k * out + r]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float t = gk * v[e];
+                        s[k][e] += (bits4 >> e) & 1u ? -t : t;
+                    }
+                }
+            }
         }
     }
-    for (int k = 0; k < K; ++k) part[((size_t)slice * K + k) * in + c] = s[k];
+    for (int k = 0; k < K; ++k)
+        *reinterpret_cast<float4 *>(part + ((size_t)slice * K + k) * in + c) = make_float4(s[k][0], s[k][1], s[k][2], s[k][3]);
 }
 
 __global__ __launch_bounds__(256) void grad_cols_finish_kernel(const float *__restrict__ part, int slices, int K, int in,
@@ -205,11 +252,11 @@ extern "C" int rb_scale_grads(const float *G, const uint32_t *packed, const uint
     const int slices = (out + ROW_SLICE - 1) / ROW_SLICE;
     if (slices > 65535) return RB_ERR_SHAPE;
     if (!workspace || workspace_bytes < rb_scale_grads_workspace_bytes(K, out, in)) return RB_ERR_WORKSPACE;
-    if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
+    if (((uintptr_t)workspace | (uintptr_t)G) & 15) return RB_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     hipLaunchKernelGGL(grad_rows_kernel, dim3((unsigned)((out + 3) / 4)), dim3(256), 0, stream, G, packed,
                        reinterpret_cast<const __half *>(h), K, out, in, grad_g);
-    hipLaunchKernelGGL(grad_cols_kernel, dim3((unsigned)((in + 255) / 256), (unsigned)slices), dim3(256), 0, stream, G,
+    hipLaunchKernelGGL(grad_cols_kernel, dim3((unsigned)((in + 255) / 256), (unsigned)slices), dim3(64), 0, stream, G,
                        packed, reinterpret_cast<const __half *>(g), K, out, in, static_cast<float *>(workspace));
     hipLaunchKernelGGL(grad_cols_finish_kernel, dim3((unsigned)((K * in + 255) / 256)), dim3(256), 0, stream,
                        static_cast<const float *>(workspace), slices, K, in, grad_h);
