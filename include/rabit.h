@@ -190,6 +190,13 @@ int rb_stack_forget(const void *workspace);
  */
 int rb_stack_status(const void *workspace, void *stream);
 /*
+ * Diagnostic: which bounded wait a run gave up, for a workspace whose rb_stack_status is
+ * RB_ERR_HANDOVER (waits for `stream`; *reason, host: 0 none, 1 an input tile was never written,
+ * 2 a tile kept reading as unwritten after its first bytes had arrived, 3 a stage was never
+ * announced inside a workgroup, 4 a value of a decoder block's epilogue never arrived).
+ */
+int rb_stack_gave_up(const void *workspace, void *stream, int *reason);
+/*
  * Diagnostic of the hand-over pacing: like rb_stack_status (waits for `stream`,
  * same return values), and stores in *tiles (host) how many input tiles, over
  * all runs since rb_stack_prepare, a wavefront found not yet written when it

@@ -28,7 +28,7 @@ EXPORTS = [
     "rb_pack", "rb_unpack", "rb_native_bytes", "rb_repack_native", "rb_unpack_native",
     "rb_linear_gemv", "rb_linear_gemm", "rb_layer_stack", "rb_workspace_bytes",
     "rb_stack_prepare", "rb_stack_run", "rb_stack_forget", "rb_stack_status", "rb_stack_waited",
-    "rb_stack_set_option",
+    "rb_stack_set_option", "rb_stack_gave_up",
     "rb_linear_gemm_noalloc", "rb_noalloc_scratch_bytes",
     "rb_couple", "rb_weight_grad", "rb_scale_grads", "rb_scale_grads_workspace_bytes",
     "rb_block_prepare", "rb_block_workspace_bytes", "rb_rmsnorm", "rb_silu_mul", "rb_add",
@@ -82,6 +82,7 @@ def _load() -> ctypes.CDLL:
     lib.rb_stack_set_option.argtypes = [i, i]
     lib.rb_stack_status.argtypes = [p, p]
     lib.rb_stack_waited.argtypes = [p, p, ctypes.POINTER(ctypes.c_ulonglong)]
+    lib.rb_stack_gave_up.argtypes = [p, p, ctypes.POINTER(ctypes.c_int)]
     lib.rb_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
     lib.rb_workspace_bytes.restype = z
     lib.rb_block_workspace_bytes.argtypes = [ctypes.POINTER(rb_layer), i, i, i]
@@ -299,6 +300,12 @@ class Stack:
         n = ctypes.c_ulonglong(0)
         _check("rb_stack_waited", lib.rb_stack_waited(self.ws.data_ptr(), _stream(), ctypes.byref(n)))
         return int(n.value)
+
+    def gave_up(self) -> int:
+        """rb_stack_gave_up: which bounded wait a run gave up (0: none); waits for the stream."""
+        r = ctypes.c_int(0)
+        _check("rb_stack_gave_up", lib.rb_stack_gave_up(self.ws.data_ptr(), _stream(), ctypes.byref(r)))
+        return int(r.value)
 
     def forget(self) -> None:
         _check("rb_stack_forget", lib.rb_stack_forget(self.ws.data_ptr()))

@@ -107,6 +107,17 @@ extern "C" int rb_stack_waited(const void *workspace, void *stream, unsigned lon
     return rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream), tiles);
 }
 
+extern "C" int rb_stack_gave_up(const void *workspace, void *stream, int *reason)
+{
+    if (!workspace || !reason) return RB_ERR_NULL;
+    *reason = 0;
+    if (rb::batch::has_plan(workspace)) return RB_OK;
+    const int rc = rb::pairs_status(workspace, static_cast<hipStream_t>(stream), nullptr, reason);
+    if (rc != RB_ERR_UNSUPPORTED) return rc == RB_ERR_HANDOVER ? RB_OK : rc;
+    const int rc2 = rb::mx::plan_status(workspace, static_cast<hipStream_t>(stream), nullptr, reason);
+    return rc2 == RB_ERR_HANDOVER ? RB_OK : rc2;
+}
+
 extern "C" int rb_stack_set_option(int option, int value)
 {
     if (option == RB_OPT_HANDOVER_PAUSE) {

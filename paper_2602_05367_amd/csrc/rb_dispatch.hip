@@ -150,7 +150,7 @@ int run_pairs(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return RB_OK;
 }
 
-int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited)
+int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited, int *reason)
 {
     PairPlans pp;
     {
@@ -160,7 +160,7 @@ int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *
         pp = it->second;
     }
     for (int p = 0; p < pp.passes; ++p) {
-        const int rc = mx::plan_status(static_cast<const uint8_t *>(workspace) + (size_t)p * pp.stride, stream, waited);
+        const int rc = mx::plan_status(static_cast<const uint8_t *>(workspace) + (size_t)p * pp.stride, stream, waited, reason);
         if (rc != RB_OK) return rc;
     }
     return RB_OK;

@@ -31,7 +31,7 @@ int prepare_pairs(const rb_layer *layers, int n_layers, const rb_stack_op *ops, 
                   int n_bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
 int run_pairs(void *workspace, size_t workspace_bytes, hipStream_t stream);
 void forget_pairs(const void *workspace);
-int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);     // RB_ERR_UNSUPPORTED: no plans of this kind
+int pairs_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr, int *reason = nullptr);     // RB_ERR_UNSUPPORTED: no plans of this kind
 
 namespace gemm {
 // many-token matrix-core GEMM (K = 2): workspace holds the scaled input of both paths
@@ -81,7 +81,7 @@ int prepare_block(const rb_layer *layers, const uint16_t *const *norm_w, float e
                   uint16_t *const *bufs, int T, void *workspace, size_t workspace_bytes, hipStream_t stream);
 // waits for the stream; RB_ERR_HANDOVER if a run of this plan gave up a wait, RB_ERR_WORKSPACE: no plan
 // waited (optional): += input tiles that compute wavefronts found not yet written and waited for, since the plan was made
-int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr);
+int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited = nullptr, int *reason = nullptr);
 // pause between a workgroup's last stores of a stage and the moment its compute wavefronts ask for
 // that stage's outputs, in clocks (< 0: the built-in timing); launches made afterwards use it
 void set_pause(int clks);

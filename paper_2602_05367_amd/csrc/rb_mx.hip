@@ -111,14 +111,15 @@ __global__ __launch_bounds__(256) void prep_kernel(Header *hdr, Op *ops, uint32_
 // The step lists of the compute wavefronts; one thread per (workgroup, wavefront).  Row tiles of an
 // op are dealt to the workgroups in contiguous, nearly equal shares, and a share (row tiles x column
 // tiles, contiguous in the native layout) is cut into one contiguous run per compute wavefront.
-__global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *ops, const Stage *stages,
-                                                  const uint32_t *zero_page, uint32_t *sdesc, uint32_t *odesc,
-                                                  uint32_t sblocks, uint32_t oblocks)
+// (T is a template argument so that the divisions by the number of compute wavefronts are by a
+// constant; the walk over the ops is integer arithmetic from end to end, and runs once per plan)
+template <int T>
+__global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *ops, const uint32_t *zero_page,
+                                                  uint32_t *sdesc, uint32_t *odesc, uint32_t sblocks, uint32_t oblocks)
 {
     // one wavefront per list; its lanes write the entries of an op's run side by side
     const uint32_t G = (uint32_t)hdr->n_groups, id = blockIdx.x, lane = threadIdx.x;
-    const int T = hdr->T, n_stages = hdr->n_stages;
-    const uint32_t CW = (uint32_t)cwaves_of(T);
+    constexpr uint32_t CW = (uint32_t)cwaves_of(T);
     if (id >= G * CW) return;
     const uint32_t grp = id / CW, wave = id % CW;
     uint32_t *sd = sdesc + (size_t)id * sblocks * (SIGN_FIELDS * DESC_BLOCK);
@@ -138,36 +139,61 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
         b[2 * DESC_BLOCK] = meta;
     };
     uint32_t gs = 0, go = 0;                  // entries written so far (the same in every lane)
-    for (int st = 0; st < n_stages; ++st) {
-        const Stage stage = stages[st];
+    // 64 ops at a time, one op per lane: a lane works out its op's run for this wavefront, a scan
+    // over the lanes places the runs one after the other (a stage is a run of consecutive ops and
+    // ends with nb_of(T) empty operand entries), and every lane writes the entries of its own op.
+    // (A walk op by op costs a few hundred instructions per op and wavefront whether the run has
+    // an entry or not: a quarter of a millisecond for a 7B-shaped plan.)
+    const int n_ops = hdr->n_ops, K = hdr->K;
+    auto share = [&](uint32_t RT, int pos, uint32_t &rt0, uint32_t &nrt) { group_rows(RT, grp, G, pos, rt0, nrt); };
+    for (int chunk = 0; chunk < n_ops; chunk += 64) {
+        const int o = chunk + (int)lane;
+        const bool live = o < n_ops;
+        const Op &mo = ops[live ? o : n_ops - 1];
+        const uint64_t bits = (uint64_t)mo.bits, up = (uint64_t)mo.up;
+        const uint32_t RT = (uint32_t)mo.RT, CT = (uint32_t)mo.CT;
+        const int first = mo.stage_op0, dep = mo.dep;
+        const bool ends_stage = live && (o == n_ops - 1 || ops[o + 1].stage_op0 != first);
+        uint32_t rt0, nrt;
+        share(RT, mo.pos, rt0, nrt);
+        // first finishing slot of the op: behind the ops of its stage that come before it
         uint32_t slot_base = 0;
-        for (int o = stage.op0; o < stage.op0 + stage.nops; ++o) {
-            const Op &op = ops[o];
-            const uint32_t CT = (uint32_t)op.CT;
-            uint32_t rt0, nrt;
-            group_rows((uint32_t)op.RT, grp, G, op.pos, rt0, nrt);
-            if (op.slot0 >= 0) slot_base = (uint32_t)op.slot0;
-            // Run `run` of the share goes to this wavefront.  Runs differ by one tile when CW does not
-            // divide the share, and the longer ones sit at the same positions for every op of equal
-            // shape; dealing op number n of the stage from wavefront n on spreads them.  The partial
-            // sums are filed under the run, not the wavefront, so the order of the final sum is the
-            // single-op kernel's whichever wavefront worked on a run.
-            const uint32_t run = (wave + (uint32_t)(o - stage.op0)) % CW;
-            const uint32_t U = nrt * CT, u0 = run * U / CW, u1 = (run + 1) * U / CW;
-            for (uint32_t u = u0 + lane; u < u1; u += 64) {
-                const uint32_t ct = u % CT, rt = rt0 + u / CT, slot = slot_base + u / CT;
-                put_sign(gs + (u - u0), (uint64_t)op.bits + ((size_t)rt * CT + ct) * (size_t)(512 * hdr->K));
-                put_opnd(go + (u - u0), (uint64_t)op.up + (size_t)ct * 2 * up_block_bytes(T),
-                         STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) |
-                             ((slot * CW + run) << STEP_PART_SHIFT) |
-                             ((op.dep >= 0 ? 1u : 0u) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
-            }
-            gs += u1 - u0;
-            go += u1 - u0;
-            slot_base += nrt;
+        for (int m = first; m < o && live; ++m) {
+            uint32_t a, n;
+            share((uint32_t)ops[m].RT, ops[m].pos, a, n);
+            if (ops[m].slot0 >= 0) slot_base = (uint32_t)ops[m].slot0;
+            slot_base += n;
         }
-        if (lane < (uint32_t)nb_of(T)) put_opnd(go + lane, 0, 0u);      // the empty entries that end the stage
-        go += (uint32_t)nb_of(T);
+        if (mo.slot0 >= 0) slot_base = (uint32_t)mo.slot0;
+        // Run `run` of the share goes to this wavefront.  Runs differ by one tile when CW does not
+        // divide the share, and the longer ones sit at the same positions for every op of equal
+        // shape; dealing op number n of the stage from wavefront n on spreads them.  The partial
+        // sums are filed under the run, not the wavefront, so the order of the final sum is the
+        // single-op kernel's whichever wavefront worked on a run.
+        const uint32_t run = (wave + (uint32_t)(o - first)) % CW;
+        const uint32_t U = nrt * CT, u0 = run * U / CW, u1 = (run + 1) * U / CW;
+        const uint32_t n_sign = live ? u1 - u0 : 0u;
+        const uint32_t n_opnd = n_sign + (ends_stage ? (uint32_t)nb_of(T) : 0u);
+        // where this lane's entries start: exclusive sums over the lanes before it
+        uint32_t s_at = n_sign, o_at = n_opnd;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t a = __shfl_up(s_at, d), b = __shfl_up(o_at, d);
+            if ((int)lane >= d) { s_at += a; o_at += b; }
+        }
+        const uint32_t s_total = __shfl(s_at, 63), o_total = __shfl(o_at, 63);
+        s_at = gs + s_at - n_sign;
+        o_at = go + o_at - n_opnd;
+        for (uint32_t e = 0; e < n_sign; ++e) {
+            const uint32_t u = u0 + e, row = u / CT, ct = u - row * CT, rt = rt0 + row, slot = slot_base + row;
+            put_sign(s_at + e, bits + ((size_t)rt * CT + ct) * (size_t)(512 * K));
+            put_opnd(o_at + e, up + (size_t)ct * 2 * up_block_bytes(T),
+                     STEP_VALID | ((ct == CT - 1 || u == u1 - 1) ? STEP_FLUSH : 0u) | ((slot * CW + run) << STEP_PART_SHIFT) |
+                         ((dep >= 0 ? 1u : 0u) << STEP_DEP_SHIFT) | (ct << STEP_CT_SHIFT));
+        }
+        if (ends_stage)
+            for (uint32_t e = 0; e < (uint32_t)nb_of(T); ++e) put_opnd(o_at + n_sign + e, 0, 0u);
+        gs += s_total;
+        go += o_total;
     }
     // past the last tile: a sign request reads a page of zeros, an operand entry is empty
     for (uint32_t e = gs + lane; e < s_cap; e += 64) put_sign(e, (uint64_t)zero_page);
@@ -175,13 +201,13 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
 }
 
 // Second set-up pass (needs the scales of every op): the tables of the finishing wavefronts.
-// One workgroup per (stage, pair of workgroups of the stack kernel); a thread per (slot, row).
+// One workgroup per (stage, LINK_GROUPS workgroups of the stack kernel); a thread per (slot, row).
+constexpr int LINK_GROUPS = 8;
 __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *ops, const Stage *stages,
                                                    SlotRec *slots, SlotVals *vals, SlotExt *ext)
 {
     const int G = hdr->n_groups, T = hdr->T;
     const int st = blockIdx.x;
-    const int grp = blockIdx.y * 2 + (threadIdx.x >> 7);
     const Stage stage = stages[st];
     // sign tiles of workgroup gg in this stage; the most any workgroup has (all threads take part)
     auto stage_tiles = [&](int gg) {
@@ -203,6 +229,9 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
         __syncthreads();
     }
     most = most_of[0];
+    // LINK_GROUPS workgroups of the stack kernel per workgroup of this one, two at a time (what a
+    // thread reads hangs on a chain of dependent loads: fewer, longer workgroups wait for it less often)
+    auto one_group = [&](int grp) {
     if (grp >= G) return;
     const uint32_t mine = stage_tiles(grp);
     const int slot = (threadIdx.x >> 4) & 7, row = threadIdx.x & 15;
@@ -258,11 +287,16 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
             }
         }
     }
-    for (int i = 0; i < 12; ++i) vals[idx].v[row][i] = v[i];
+    float4 *vrow = reinterpret_cast<float4 *>(&vals[idx].v[row][0]);      // 48 bytes per row: three 16-byte stores
+    vrow[0] = make_float4(v[0], v[1], v[2], v[3]);
+    vrow[1] = make_float4(v[4], v[5], v[6], v[7]);
+    vrow[2] = make_float4(v[8], v[9], v[10], v[11]);
     if (row == 0) {
         slots[idx] = sr;
         if (ext) ext[idx] = sx;
     }
+    };
+    for (int sub = 0; sub < LINK_GROUPS / 2; ++sub) one_group((int)blockIdx.y * LINK_GROUPS + 2 * sub + (int)(threadIdx.x >> 7));
 }
 
 // --------------------------------------------------------- expand kernel ---
@@ -347,6 +381,12 @@ __device__ __forceinline__ void store_sc1_u32(uint64_t addr, uint32_t v)
 {
     asm volatile("global_store_dword %0, %1, off sc1" : : "v"(addr), "v"(v) : "memory");
 }
+// what a wavefront that gave up a bounded wait leaves in the plan's error word (rb_stack_status
+// reports any of them as RB_ERR_HANDOVER; rb_stack_gave_up tells which)
+constexpr int GAVE_UP_TILE = 1;       // an input tile was never written
+constexpr int GAVE_UP_TORN = 2;       // a tile whose first bytes had arrived kept reading as unwritten
+constexpr int GAVE_UP_GO = 3;         // a stage was never announced inside the workgroup
+constexpr int GAVE_UP_BLOCK = 4;      // a sum of squares or a residual value of a decoder block never arrived
 constexpr uint32_t BLOCK_POLLS = 0x40000;     // looks at a value another workgroup has yet to write, before giving up
 
 __device__ __forceinline__ uint64_t uniform64(uint32_t lo, uint32_t hi)
@@ -604,7 +644,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     int spins = 0;
                     while (!go_given()) {
                         __builtin_amdgcn_s_sleep(2);
-                        if (++spins > (1 << 24)) { failed = true; break; }
+                        if (++spins > (1 << 24)) {
+                            failed = true;
+                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), (uint32_t)GAVE_UP_GO, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
                     }
                     go_seen = true;
                 }
@@ -845,13 +889,15 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         // Each look reads the first word of every group and then, with later loads of
                         // the same wavefront from the same addresses, the groups themselves.  A group
                         // whose store had landed in part is complete one look later; should a word
-                        // still read as unwritten after that, the run is reported, not trusted.
-                        uint32_t left = look_again();
-                        if (left != 0 && unwritten_word()) left = look_again();
-                        if (left != 0 && unwritten_word()) left = 0;
-                        if (left == 0) {                      // a producer never delivered: report, stop checking
+                        // still read as unwritten after a few more, the run is reported, not trusted.
+                        uint32_t reason = look_again() == 0 ? (uint32_t)GAVE_UP_TILE : 0u;
+                        for (int again = 0; reason == 0 && unwritten_word(); ++again) {
+                            if (again == 4) reason = GAVE_UP_TORN;
+                            else if (look_again() == 0) reason = GAVE_UP_TILE;
+                        }
+                        if (reason != 0) {                    // a producer never delivered: report, stop checking
                             failed = true;
-                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), reason, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
                     c_slot_ptr += TILE_BYTES;
@@ -1031,7 +1077,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         }
                         if (!__any(unwritten)) break;
                         if (--left == 0) {
-                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), (uint32_t)GAVE_UP_BLOCK, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(8);
@@ -1541,12 +1587,16 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
     hipLaunchKernelGGL(prep_kernel, dim3(n_ops), dim3(256), 0, stream, reinterpret_cast<Header *>(ws),
                        reinterpret_cast<Op *>(ws + lay.ops),
                        reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<uint32_t *>(ws + lay.zero));
-    hipLaunchKernelGGL(desc_kernel, dim3(G * cwaves_of(T)), dim3(64), 0, stream,
-                       reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
-                       reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<const uint32_t *>(ws + lay.zero),
-                       reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc),
-                       pr.sblocks, pr.oblocks);
-    hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + 1) / 2), dim3(256), 0, stream,
+    auto lists = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(G * cwaves_of(T)), dim3(64), 0, stream, reinterpret_cast<const Header *>(ws),
+                           reinterpret_cast<const Op *>(ws + lay.ops), reinterpret_cast<const uint32_t *>(ws + lay.zero),
+                           reinterpret_cast<uint32_t *>(ws + lay.sdesc), reinterpret_cast<uint32_t *>(ws + lay.odesc), pr.sblocks,
+                           pr.oblocks);
+    };
+    if (T == 1) lists(desc_kernel<1>);
+    else if (T == 2) lists(desc_kernel<2>);
+    else lists(desc_kernel<4>);
+    hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + LINK_GROUPS - 1) / LINK_GROUPS), dim3(256), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
                        reinterpret_cast<SlotVals *>(ws + lay.vals), block ? reinterpret_cast<SlotExt *>(ws + lay.ext) : nullptr);
@@ -1628,7 +1678,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
-int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited)
+int plan_status(const void *workspace, hipStream_t stream, unsigned long long *waited, int *reason)
 {
     Prepared pr;
     {
@@ -1643,6 +1693,7 @@ int plan_status(const void *workspace, hipStream_t stream, unsigned long long *w
         hipStreamSynchronize(stream) != hipSuccess)
         return RB_ERR_HIP;
     if (waited) *waited += mark[1];
+    if (reason && mark[0]) *reason = (int)mark[0];
     return mark[0] ? RB_ERR_HANDOVER : RB_OK;
 }
 

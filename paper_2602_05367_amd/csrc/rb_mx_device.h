@@ -61,6 +61,13 @@ __device__ __forceinline__ size_t up_offset(int T, int tok, int p, int t, int j)
 // of a stage fall on different workgroups where they can.
 __host__ __device__ inline void group_rows(uint32_t RT, uint32_t grp, uint32_t G, int pos, uint32_t &rt0, uint32_t &nrt)
 {
+    if ((G & (G - 1)) == 0) {                 // the usual number of workgroups is a power of two
+        const int shift = __builtin_ctz(G);
+        const uint32_t g = (grp + (uint32_t)pos) & (G - 1);
+        rt0 = (g * RT) >> shift;
+        nrt = (((g + 1) * RT) >> shift) - rt0;
+        return;
+    }
     const uint32_t g = (grp + (uint32_t)pos) % G;
     rt0 = g * RT / G;
     nrt = (g + 1) * RT / G - rt0;

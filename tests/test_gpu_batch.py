@@ -44,7 +44,7 @@ def _check_stack(layers, op_list, widths, x, T, label, prepared):
             torch.cuda.synchronize()
             runs.append([b.clone() for b in bufs])
         assert rb.rb_last_path() == want_path
-        assert stack.status() == rb.RB_OK
+        assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
         stack.forget()
         for a, b in zip(*runs):
             assert torch.equal(a, b)

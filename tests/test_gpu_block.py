@@ -60,7 +60,7 @@ def _run(ops, widths, layers, norm_w, x0, T, pause=-1, runs=1):
     finally:
         rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, -1)
     assert rb.rb_last_path() == rb.RB_PATH_MX
-    assert block.status() == rb.RB_OK
+    assert block.status() == rb.RB_OK, f"gave up: reason {block.gave_up()}"
     waited = block.waited()
     block.forget()
     return [b.cpu().numpy() for b in dev_bufs], waited, (dev_layers, dev_norms, dev_bufs)

@@ -30,7 +30,7 @@ def _run_and_check(ops, widths, layers, bufs0, T, label, prepared=False):
         stack.run_prepared()
         torch.cuda.synchronize()
         assert rb.rb_last_path() == (rb.RB_PATH_MX if T < 8 else rb.RB_PATH_BATCH)
-        assert stack.status() == rb.RB_OK
+        assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
         stack.forget()
     else:
         rb.rb_layer_stack(dev_layers, op_list, dev_bufs, T)
@@ -141,7 +141,7 @@ def test_non_finite_activation_propagates_and_ends():
     stack.prepare()
     print("non-finite input through a dependent stack", flush=True)
     stack.run_prepared()
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     stack.forget()
     for op in ops:
         assert not torch.isfinite(dev_bufs[op.dst]).any(), op.name
@@ -174,7 +174,7 @@ def test_requests_ahead_of_the_writes_are_caught(T):
                 stack.run_prepared()
                 torch.cuda.synchronize()
                 runs.append([b.clone() for b in dev_bufs])
-            assert stack.status() == rb.RB_OK
+            assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
             waited.append(stack.waited())
             print(f"  tiles read again: {waited[-1]}", flush=True)
             stack.forget()
@@ -296,7 +296,7 @@ def test_hand_over_at_full_scale_many_tokens():
         torch.cuda.synchronize()
         bad = [op.name for n, op in enumerate(ops) if not torch.equal(ys[n], bufs[op.dst])]
         assert not bad, (token, bad[:5])
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     stack.forget()
 
 
@@ -351,11 +351,11 @@ def test_full_width_7b_block_small_batches_own_inputs(T):
     stack.prepare()
     stack.run_prepared()
     torch.cuda.synchronize()
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     first = [b.clone() for b in bufs]
     stack.run_prepared()                                 # scratch state must not leak between runs
     torch.cuda.synchronize()
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     stack.forget()
     for a, b in zip(first, bufs):
         assert torch.equal(a, b)
@@ -380,12 +380,12 @@ def test_full_13b_stack_as_benchmarked_sampled_outputs():
     stack.run_prepared()
     torch.cuda.synchronize()
     assert rb.rb_last_path() == rb.RB_PATH_MX
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     first = [b.clone() for b in bufs]
     print("full 13B-shaped stack, run 2", flush=True)
     stack.run_prepared()
     torch.cuda.synchronize()
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     for a, b in zip(first, bufs):
         assert torch.equal(a, b)
     stack.forget()
@@ -506,7 +506,7 @@ def test_prepared_odd_batches_on_pure_chains(T, n_chain):
     stack.prepare()
     stack.run_prepared()
     torch.cuda.synchronize()
-    assert stack.status() == rb.RB_OK
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     stack.forget()
     got = [b.cpu().numpy() for b in bufs]
     for n in range(n_chain):
