@@ -156,6 +156,8 @@ def main() -> int:
                     help="only the prefill GEMM figures (for profiling that kernel)")
     ap.add_argument("--batch-only", type=int, default=0, metavar="T",
                     help="only the dependent 7B-shaped chain at T tokens (8..16) on the small-batch kernel (for profiling it)")
+    ap.add_argument("--block-only", type=int, default=0, metavar="T",
+                    help="only the 7B-shaped decoder-block stack at T tokens (1..4) on the fused kernel (for profiling it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -183,6 +185,22 @@ def main() -> int:
         ms_b = sum(per_b) / len(per_b)
         print(json.dumps({"small_batch_chain": {"tokens": Tb, "ms_per_pass": ms_b, "tokens_per_s": Tb / (ms_b * 1e-3),
                                                 "GBps": packed_b / (ms_b * 1e-3) / 1e9}}))
+        return 0
+
+    if args.block_only:
+        Tb = args.block_only
+        bops, blayers, bnorms, bbufs, bx0, bop_list, bpacked = build_block_stack(rb, synth, torch, "7b", Tb)
+        block = rb.Block(blayers, bnorms, 1e-5, bop_list, bbufs, Tb)
+        block.prepare()
+
+        def fused_step():
+            bbufs[0].copy_(bx0)
+            block.run_prepared()
+        _, per_b = time_steps(torch, fused_step, args.steps, args.warmup)
+        assert rb.rb_last_path() == rb.RB_PATH_MX and block.status() == rb.RB_OK
+        ms_b = sum(per_b) / len(per_b)
+        print(json.dumps({"decoder_block_stack_7b": {"tokens": Tb, "ms_per_pass": ms_b, "tokens_per_s": Tb / (ms_b * 1e-3),
+                                                     "GBps": bpacked / (ms_b * 1e-3) / 1e9}}))
         return 0
 
     T = 1
