@@ -324,6 +324,39 @@ def _sampled_rows_check(rb_mod, ops, layers, bufs, op_numbers, rows_per_op, seed
     return worst
 
 
+@pytest.mark.parametrize("T,runs", [(1, 10000), (3, 3000)])
+def test_determinism_canary_and_hand_over_stress(T, runs):
+    """The 7B-shaped stack as the benchmark builds it, run after run on the same input: the first
+    100 runs must reproduce every buffer bit for bit, and after thousands of runs (every one of
+    them 128 hand-overs between all compute units) the outputs are still those bits and no wait
+    was ever given up."""
+    import bench
+    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T)
+    stack = rb.Stack(layers, op_list, bufs, T)
+    stack.prepare()
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    first = [b.clone() for b in bufs]
+    print(f"determinism canary, T={T}: 100 runs, every buffer", flush=True)
+    for run in range(100):
+        stack.run_prepared()
+        torch.cuda.synchronize()
+        bad = [n for n, (a, b) in enumerate(zip(first, bufs)) if not torch.equal(a, b)]
+        assert not bad, (run, bad[:5])
+    print(f"hand-over stress, T={T}: {runs} runs", flush=True)
+    for run in range(runs):
+        stack.run_prepared()
+        if run % 1000 == 999:
+            torch.cuda.synchronize()
+            assert torch.equal(first[ops[-1].dst], bufs[ops[-1].dst]), run
+            print(f"  {run + 1} runs", flush=True)
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
+    bad = [n for n, (a, b) in enumerate(zip(first, bufs)) if not torch.equal(a, b)]
+    assert not bad, bad[:5]
+    stack.forget()
+
+
 @pytest.mark.parametrize("T", [2, 3, 4])
 def test_one_full_width_7b_block_small_batches_chained(T):
     """The two- and four-token forms of the fused kernel (three tokens use the layout of four) at
