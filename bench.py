@@ -464,7 +464,7 @@ def main() -> int:
         bytes_c = 4 * o_t * i_t + 2 * (2 * o_t * i_t // 8)         # W read, canonical and native words written
         _, per_g = time_steps(torch, lambda: rb.rb_scale_grads(Wt, pk, gt, ht), 10, 3)
         ms_g = sum(per_g) / len(per_g)
-        bytes_g = 2 * (4 * o_t * i_t + 2 * o_t * i_t // 8)         # G and the packed cores, once per direction
+        bytes_g = 4 * o_t * i_t + 2 * o_t * i_t // 8               # G and the packed cores, read once for both gradients
         result["training_side_4096x11008"] = {
             "rb_couple": {"ms": ms_c, "GBps": bytes_c / (ms_c * 1e-3) / 1e9,
                           "pct_of_hbm_peak": 100.0 * bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS},

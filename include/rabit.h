@@ -228,7 +228,8 @@ size_t rb_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T
 
 /*
  * On-the-fly residual coupling (Alg. 2, forward loop): from the shared weight W
- * (fp32 [out][in]) and the scales g (fp16 [K][out]), h (fp16 [K][in]) derive
+ * (fp32 [out][in], 16-byte aligned) and the scales g (fp16 [K][out]), h (fp16
+ * [K][in], 8-byte aligned) derive
  *   R_0 = W;  B_i = sign(R_{i-1}) (sign(0) = +1);  R_i = R_{i-1} - g_i (.) B_i (.) h_i
  * for i = 1..K.  The residual is fp32 with one rounding for g_i[r] * h_i[c] and
  * one for the subtraction, so the stored bits are defined exactly.
@@ -257,7 +258,8 @@ int rb_weight_grad(const uint16_t *Delta, const uint16_t *X, int N, int out, int
  * with G from rb_weight_grad (or any fp32 [out][in] = Delta^T X; 16-byte aligned).  packed:
  * canonical words as rb_couple writes them.  grad_g fp32 [K][out], grad_h fp32
  * [K][in].  workspace: rb_scale_grads_workspace_bytes(K, out, in) bytes, 16-byte
- * aligned (partial column sums; their order is fixed, results repeat bit for bit).
+ * aligned (partial column and row sums of the one pass over G that serves both
+ * gradients; their order is fixed, results repeat bit for bit).
  */
 size_t rb_scale_grads_workspace_bytes(int K, int out, int in);
 int rb_scale_grads(const float *G, const uint32_t *packed, const uint16_t *g, const uint16_t *h,

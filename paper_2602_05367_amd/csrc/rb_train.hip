@@ -35,10 +35,25 @@ __global__ __launch_bounds__(256) void zero_kernel(uint32_t *p, size_t n)
     if (i < n) p[i] = 0u;
 }
 
-// One wavefront per row and chunk of COUPLE_CHUNK columns; a step covers 64 consecutive columns,
-// lane l holding column 64 m + l, so that a ballot of "residual is negative" is two canonical words at once (bit b = column 32 w + b,
-// 1 means -1).  The residual is fp32 with one rounding for g * h and one for the subtraction, the
-// arithmetic the definition fixes (the sign of the product is exact).
+// OR over each group of eight consecutive lanes, left in all eight: two exchanges inside the quad,
+// then one with the mirrored lane of the group (7 - i, which sits in the other quad).  Data-parallel
+// moves: every lane of the wavefront must be active.
+__device__ __forceinline__ uint32_t or_over_8(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);   // row_half_mirror
+    return v;
+}
+
+// One wavefront per row and chunk of COUPLE_CHUNK columns.  A lane takes four consecutive columns
+// at a time (one 16-byte load of W; the chunk's loads are all requested before the first is used),
+// so a step of the wavefront covers 256 columns and eight lanes hold one sign word between them:
+// lane i of the eight has columns 4 i .. 4 i + 3 of the word, bits 4 i + j of the canonical word
+// (bit b = column 32 w + b, 1 means -1) and bits 16 (i % 2) + 4 j + i / 2 of the native one (native
+// bit 4 e + s is column 8 s + e); each lane shifts its four bits into place in both and an OR over
+// the eight lanes gives the words.  The residual is fp32 with one rounding for g * h and one for
+// the subtraction, the arithmetic the definition fixes (the sign of the product is exact).
 __global__ __launch_bounds__(256) void couple_kernel(const float *__restrict__ W, const __half *__restrict__ g,
                                                      const __half *__restrict__ h, int K, int out, int in,
                                                      uint32_t *__restrict__ packed, uint32_t *__restrict__ native,
@@ -50,42 +65,52 @@ __global__ __launch_bounds__(256) void couple_kernel(const float *__restrict__ W
     const int W32 = in / 32, CT = col_tiles(in);
     float gr[RB_MAX_K];
     for (int k = 0; k < K; ++k) gr[k] = __half2float(g[(size_t)k * out + row]);
-    const int chunk0 = blockIdx.y * COUPLE_CHUNK, chunk1 = min(in, chunk0 + COUPLE_CHUNK);
-    // the chunk's weights first, all loads in flight at once: a wavefront that asked for them one
-    // step at a time would spend its life waiting for memory
-    float wv[COUPLE_CHUNK / 64];
+    const int chunk0 = blockIdx.y * COUPLE_CHUNK;
+    constexpr int STEPS = COUPLE_CHUNK / 256;
+    float4 wv[STEPS];
 #pragma unroll
-    for (int i = 0; i < COUPLE_CHUNK / 64; ++i) {
-        const int c = chunk0 + 64 * i + lane;
-        wv[i] = c < in ? W[(size_t)row * in + c] : 0.f;
+    for (int i = 0; i < STEPS; ++i) {
+        const int c = chunk0 + 256 * i + 4 * lane;
+        wv[i] = c < in ? *reinterpret_cast<const float4 *>(W + (size_t)row * in + c) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int i = 0; i < COUPLE_CHUNK / 64; ++i) {
-        const int c0 = chunk0 + 64 * i;
-        if (c0 >= chunk1) break;
-        const int c = c0 + lane;
-        const bool real = c < in;
-        float r = wv[i];
+    for (int i = 0; i < STEPS; ++i) {
+        const int c0 = chunk0 + 256 * i;
+        if (c0 >= in) break;
+        const int c = c0 + 4 * lane;
+        const bool real = c < in;                              // in % 32 == 0: all four columns or none
+        float r[4] = {wv[i].x, wv[i].y, wv[i].z, wv[i].w};
+        const int i8 = lane & 7;
+        const int w = (c0 >> 5) + (lane >> 3);                 // the word this group of eight lanes holds
         for (int k = 0; k < K; ++k) {
-            const bool neg = real && !(r >= 0.f);                 // sign(0) = +1; columns past the end read as +1
-            const unsigned long long bal = __ballot(neg);
-            const float prod = __fmul_rn(gr[k], real ? __half2float(h[(size_t)k * in + c]) : 0.f);
-            r = neg ? __fadd_rn(r, prod) : __fsub_rn(r, prod);
-            const int w = (c0 >> 5) + (lane >> 5);                // the word this half of the wavefront covers
-            const uint32_t word = lane < 32 ? (uint32_t)bal : (uint32_t)(bal >> 32);
-            if (packed && (lane & 31) == 0 && w < W32) packed[((size_t)k * out + row) * W32 + w] = word;
-            if (native) {
-                // native bit p of a word is column 8 (p % 4) + p / 4: every lane supplies one bit
-                const int p = lane & 31;
-                const unsigned long long nat = __ballot((word >> column_of_native_bit(p)) & 1u);
-                const uint32_t nword = lane < 32 ? (uint32_t)nat : (uint32_t)(nat >> 32);
-                if ((lane & 31) == 0 && w < W32) {
+            float hv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (real) {
+                const uint2 hb = *reinterpret_cast<const uint2 *>(h + (size_t)k * in + c);
+                hv[0] = __half2float(__ushort_as_half((unsigned short)(hb.x & 0xffffu)));
+                hv[1] = __half2float(__ushort_as_half((unsigned short)(hb.x >> 16)));
+                hv[2] = __half2float(__ushort_as_half((unsigned short)(hb.y & 0xffffu)));
+                hv[3] = __half2float(__ushort_as_half((unsigned short)(hb.y >> 16)));
+            }
+            uint32_t can = 0, nat = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool neg = real && !(r[j] >= 0.f);       // sign(0) = +1; columns past the end read as +1
+                const float prod = __fmul_rn(gr[k], hv[j]);
+                r[j] = neg ? __fadd_rn(r[j], prod) : __fsub_rn(r[j], prod);
+                can |= neg ? 1u << j : 0u;
+                nat |= neg ? 1u << (4 * j) : 0u;
+            }
+            const uint32_t word = or_over_8(can << (4 * i8));
+            const uint32_t nword = or_over_8(nat << (16 * (i8 & 1) + (i8 >> 1)));
+            if (i8 == 0 && w < W32) {
+                if (packed) packed[((size_t)k * out + row) * W32 + w] = word;
+                if (native) {
                     const int rt = row / TILE_ROWS, ct = w / 8, cc = (w % 8) / 4, q = w % 4;
                     native[((size_t)rt * CT + ct) * tile_words(K) + lane_word((row % TILE_ROWS) + 16 * q, cc, k, K)] = nword;
                 }
             }
         }
-        if (residual && real) residual[(size_t)row * in + c] = r;
+        if (residual && real) *reinterpret_cast<float4 *>(residual + (size_t)row * in + c) = make_float4(r[0], r[1], r[2], r[3]);
     }
 }
 
@@ -101,97 +126,90 @@ __global__ __launch_bounds__(256) void weight_grad_kernel(const __half *__restri
     G[(size_t)r * in + c] = s;
 }
 
-// grad g: one wavefront per row; a lane takes four consecutive columns at a time (one 16-byte load
-// of G, four bits of one sign word per path), four such steps in flight; K sums per lane, then a
-// butterfly over the wavefront (a fixed order for a given width).
-__global__ __launch_bounds__(256) void grad_rows_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
-                                                        const __half *__restrict__ h, int K, int out, int in,
-                                                        float *__restrict__ grad_g)
+// Both scale gradients from one pass over G.  A wavefront takes a slab of ROW_SLICE rows by 256
+// columns, a lane four consecutive columns (one 16-byte load of G and four bits of a sign word per
+// row and path), eight rows in flight.  The column sums of grad h stay in the lane (rows in order);
+// the row sums of grad g need the whole wavefront: the eight rows of a group are summed together,
+// three exchanges that each halve the number of rows a lane carries (after them lane l holds row
+// 4 (l & 1) + 2 (l >> 1 & 1) + (l >> 2 & 1) of the group, summed over its eight lanes) and three
+// more over the eight-lane groups.  Partial sums: [slice][K][in] and [column block][K][out]; the
+// second kernel adds them in order, so results repeat bit for bit.
+__global__ __launch_bounds__(64) void grad_slab_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
+                                                       const __half *__restrict__ g, const __half *__restrict__ h, int K,
+                                                       int out, int in, float *__restrict__ part_h,
+                                                       float *__restrict__ part_g)
 {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= out) return;
-    const int W32 = in / 32;
-    const float4 *Grow = reinterpret_cast<const float4 *>(G + (size_t)row * in);     // in % 32 == 0: 16-byte aligned rows
-    float s[RB_MAX_K] = {0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < in; c0 += 4 * 256) {
-        float4 gv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + 256 * u + 4 * lane;
-            gv[u] = c < in ? Grow[c >> 2] : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + 256 * u + 4 * lane;
-            if (c < in) {
-                const float v[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
-                for (int k = 0; k < K; ++k) {
-                    const uint32_t bits4 = packed[((size_t)k * out + row) * W32 + (c >> 5)] >> (c & 31);
-                    const __half *hk = h + (size_t)k * in + c;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float t = __half2float(hk[e]) * v[e];
-                        s[k] += (bits4 >> e) & 1u ? -t : t;
-                    }
-                }
-            }
-        }
-    }
-    for (int k = 0; k < K; ++k) {
-        float v = s[k];
-        for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d);
-        if (lane == 0) grad_g[(size_t)k * out + row] = v;
-    }
-}
-
-// grad h, first pass: a thread takes four consecutive columns and walks the ROW_SLICE rows of its
-// slice in order, eight rows in flight; partial sums [slice][K][in].  Second pass: the slices are
-// added in order.
-__global__ __launch_bounds__(64) void grad_cols_kernel(const float *__restrict__ G, const uint32_t *__restrict__ packed,
-                                                       const __half *__restrict__ g, int K, int out, int in,
-                                                       float *__restrict__ part)
-{
-    const int c = (blockIdx.x * 64 + threadIdx.x) * 4, slice = blockIdx.y;
-    if (c >= in) return;
+    const int lane = threadIdx.x;
+    const int c = (blockIdx.x * 64 + lane) * 4, slice = blockIdx.y;
+    const bool real = c < in;                                  // in % 32 == 0: all four columns or none
+    const int cs = real ? c : 0;
     const int W32 = in / 32, r0 = slice * ROW_SLICE, r1 = min(out, r0 + ROW_SLICE);
-    float s[RB_MAX_K][4];
+    float sh[RB_MAX_K][4], hv[RB_MAX_K][4];
     for (int k = 0; k < RB_MAX_K; ++k)
-        for (int e = 0; e < 4; ++e) s[k][e] = 0.f;
+        for (int e = 0; e < 4; ++e) {
+            sh[k][e] = 0.f;
+            hv[k][e] = k < K && real ? __half2float(h[(size_t)k * in + c + e]) : 0.f;
+        }
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+    const int my_row = 4 * (int)b0 + 2 * (int)b1 + (int)b2;
     for (int rb = r0; rb < r1; rb += 8) {
         float4 gv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            gv[u] = rb + u < r1 ? *reinterpret_cast<const float4 *>(G + (size_t)(rb + u) * in + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+            gv[u] = real && rb + u < r1 ? *reinterpret_cast<const float4 *>(G + (size_t)(rb + u) * in + c)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < K; ++k) {
+            float rp[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = rb + u;
-            if (r < r1) {
+            for (int u = 0; u < 8; ++u) {
+                const int r = min(rb + u, r1 - 1);             // rows past the end: G read as zero above
                 const float v[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
-                for (int k = 0; k < K; ++k) {
-                    const uint32_t bits4 = packed[((size_t)k * out + r) * W32 + (c >> 5)] >> (c & 31);
-                    const float gk = __half2float(g[(size_t)k * out + r]);
+                const uint32_t bits4 = packed[((size_t)k * out + r) * W32 + (cs >> 5)] >> (cs & 31);
+                const float gk = __half2float(g[(size_t)k * out + r]);
+                float rs = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float t = gk * v[e];
-                        s[k][e] += (bits4 >> e) & 1u ? -t : t;
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float sv = (bits4 >> e) & 1u ? -v[e] : v[e];
+                    sh[k][e] = __builtin_fmaf(gk, sv, sh[k][e]);
+                    rs = __builtin_fmaf(hv[k][e], sv, rs);
                 }
+                rp[u] = rs;
             }
+            float q[4], p2[2];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[u] = (b0 ? rp[u + 4] : rp[u]) + __shfl_xor(b0 ? rp[u] : rp[u + 4], 1);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) p2[u] = (b1 ? q[u + 2] : q[u]) + __shfl_xor(b1 ? q[u] : q[u + 2], 2);
+            float o = (b2 ? p2[1] : p2[0]) + __shfl_xor(b2 ? p2[0] : p2[1], 4);
+            o += __shfl_xor(o, 8);
+            o += __shfl_xor(o, 16);
+            o += __shfl_xor(o, 32);
+            if (lane < 8 && rb + my_row < r1) part_g[((size_t)blockIdx.x * K + k) * out + rb + my_row] = o;
         }
     }
-    for (int k = 0; k < K; ++k)
-        *reinterpret_cast<float4 *>(part + ((size_t)slice * K + k) * in + c) = make_float4(s[k][0], s[k][1], s[k][2], s[k][3]);
+    if (real)
+        for (int k = 0; k < K; ++k)
+            *reinterpret_cast<float4 *>(part_h + ((size_t)slice * K + k) * in + c) =
+                make_float4(sh[k][0], sh[k][1], sh[k][2], sh[k][3]);
 }
 
-__global__ __launch_bounds__(256) void grad_cols_finish_kernel(const float *__restrict__ part, int slices, int K, int in,
-                                                               float *__restrict__ grad_h)
+// element i < K * in of grad h: the slices in order; the rest, grad g: the column blocks in order
+__global__ __launch_bounds__(256) void grad_finish_kernel(const float *__restrict__ part_h, int slices,
+                                                          const float *__restrict__ part_g, int col_blocks, int K,
+                                                          int out, int in, float *__restrict__ grad_g,
+                                                          float *__restrict__ grad_h)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= K * in) return;
-    float s = 0.f;
-    for (int sl = 0; sl < slices; ++sl) s += part[(size_t)sl * K * in + i];
-    grad_h[i] = s;
+    if (i < K * in) {
+        float s = 0.f;
+        for (int sl = 0; sl < slices; ++sl) s += part_h[(size_t)sl * K * in + i];
+        grad_h[i] = s;
+    } else if (i < K * in + K * out) {
+        const int j = i - K * in;
+        float s = 0.f;
+        for (int cb = 0; cb < col_blocks; ++cb) s += part_g[(size_t)cb * K * out + j];
+        grad_g[j] = s;
+    }
 }
 
 static int check_shape(int K, int out, int in)
@@ -211,7 +229,9 @@ extern "C" int rb_couple(const float *W, const uint16_t *g, const uint16_t *h, i
     if (!packed && !native) return RB_ERR_NULL;
     const int rc = check_shape(K, out, in);
     if (rc != RB_OK) return rc;
-    if (((uintptr_t)W | (uintptr_t)packed | (uintptr_t)native | (uintptr_t)residual) & 3) return RB_ERR_ALIGN;
+    if (((uintptr_t)packed | (uintptr_t)native) & 3) return RB_ERR_ALIGN;
+    if (((uintptr_t)W | (uintptr_t)residual) & 15) return RB_ERR_ALIGN;
+    if ((uintptr_t)h & 7) return RB_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (native) {
         // rows and columns of padding read as +1 (bit 0); a kernel, not a memset, so that a caller may capture the call
@@ -239,7 +259,8 @@ extern "C" int rb_weight_grad(const uint16_t *Delta, const uint16_t *X, int N, i
 extern "C" size_t rb_scale_grads_workspace_bytes(int K, int out, int in)
 {
     if (check_shape(K, out, in) != RB_OK) return 0;
-    return (size_t)((out + ROW_SLICE - 1) / ROW_SLICE) * K * in * sizeof(float);
+    // [slice][K][in] partial sums of grad h, then [column block][K][out] partial sums of grad g
+    return ((size_t)((out + ROW_SLICE - 1) / ROW_SLICE) * K * in + (size_t)((in + 255) / 256) * K * out) * sizeof(float);
 }
 
 extern "C" int rb_scale_grads(const float *G, const uint32_t *packed, const uint16_t *g, const uint16_t *h, int K,
@@ -254,11 +275,11 @@ extern "C" int rb_scale_grads(const float *G, const uint32_t *packed, const uint
     if (!workspace || workspace_bytes < rb_scale_grads_workspace_bytes(K, out, in)) return RB_ERR_WORKSPACE;
     if (((uintptr_t)workspace | (uintptr_t)G) & 15) return RB_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    hipLaunchKernelGGL(grad_rows_kernel, dim3((unsigned)((out + 3) / 4)), dim3(256), 0, stream, G, packed,
-                       reinterpret_cast<const __half *>(h), K, out, in, grad_g);
-    hipLaunchKernelGGL(grad_cols_kernel, dim3((unsigned)((in + 255) / 256), (unsigned)slices), dim3(64), 0, stream, G,
-                       packed, reinterpret_cast<const __half *>(g), K, out, in, static_cast<float *>(workspace));
-    hipLaunchKernelGGL(grad_cols_finish_kernel, dim3((unsigned)((K * in + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<const float *>(workspace), slices, K, in, grad_h);
+    const int col_blocks = (in + 255) / 256;
+    float *part_h = static_cast<float *>(workspace), *part_g = part_h + (size_t)slices * K * in;
+    hipLaunchKernelGGL(grad_slab_kernel, dim3((unsigned)col_blocks, (unsigned)slices), dim3(64), 0, stream, G, packed,
+                       reinterpret_cast<const __half *>(g), reinterpret_cast<const __half *>(h), K, out, in, part_h, part_g);
+    hipLaunchKernelGGL(grad_finish_kernel, dim3((unsigned)((K * (in + out) + 255) / 256)), dim3(256), 0, stream, part_h,
+                       slices, part_g, col_blocks, K, out, in, grad_g, grad_h);
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
