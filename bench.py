@@ -146,6 +146,43 @@ def prefill_figures(rb, torch):
     return prefill
 
 
+def training_figures(rb, torch):
+    """Training-side kernels (Alg. 2) and the initialisation (Alg. 1) on one 4096 x 11008 layer."""
+    out = {}
+    # training-side kernels (Alg. 2): coupled derivation of the cores and the scale gradients
+    # of one 4096 x 11008 layer; both stream an fp32 matrix, so the figure is HBM bytes per second
+    o_t, i_t = 4096, 11008
+    Wt = torch.randn((o_t, i_t), device="cuda") * 0.02
+    gt = (torch.randn(2, o_t, device="cuda").abs() * 0.1).half()
+    ht = (torch.randn(2, i_t, device="cuda").abs() * 0.1).half()
+    _, per_c = time_steps(torch, lambda: rb.rb_couple(Wt, gt, ht), 10, 3)
+    pk, _, _ = rb.rb_couple(Wt, gt, ht)
+    ms_c = sum(per_c) / len(per_c)
+    bytes_c = 4 * o_t * i_t + 2 * (2 * o_t * i_t // 8)         # W read, canonical and native words written
+    _, per_g = time_steps(torch, lambda: rb.rb_scale_grads(Wt, pk, gt, ht), 10, 3)
+    ms_g = sum(per_g) / len(per_g)
+    bytes_g = 4 * o_t * i_t + 2 * o_t * i_t // 8               # G and the packed cores, read once for both gradients
+    out["training_side_4096x11008"] = {
+        "rb_couple": {"ms": ms_c, "GBps": bytes_c / (ms_c * 1e-3) / 1e9,
+                      "pct_of_hbm_peak": 100.0 * bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "rb_scale_grads": {"ms": ms_g, "GBps": bytes_g / (ms_g * 1e-3) / 1e9,
+                           "pct_of_hbm_peak": 100.0 * bytes_g / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
+    # initialisation (Alg. 1): Iterative Residual SVID of the same layer on the device, fp64;
+    # wall clock of the call (it follows the power iteration's stopping rule from the host)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, _, _, err_i = rb.rb_derive_iterative(Wt, 2, 5)
+    torch.cuda.synchronize()
+    s_i = time.perf_counter() - t0
+    err_i = err_i.cpu().numpy()
+    out["initialisation_4096x11008"] = {
+        "rb_derive_iterative": {"K": 2, "T_max": 5, "seconds": s_i, "seconds_per_sweep": s_i / 5,
+                                "error_after_greedy_over_norm": float(err_i[0, 1] / Wt.double().norm().item()),
+                                "error_after_5_sweeps_over_norm": float(err_i[4, 1] / Wt.double().norm().item())}}
+    del Wt, pk
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,6 +195,8 @@ def main() -> int:
                     help="only the dependent 7B-shaped chain at T tokens (8..16) on the small-batch kernel (for profiling it)")
     ap.add_argument("--block-only", type=int, default=0, metavar="T",
                     help="only the 7B-shaped decoder-block stack at T tokens (1..4) on the fused kernel (for profiling it)")
+    ap.add_argument("--train-only", action="store_true",
+                    help="only the training-side kernels and the initialisation (for profiling them)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -173,6 +212,10 @@ def main() -> int:
 
     if args.prefill_only:
         print(json.dumps({"prefill_gemm_T2048": prefill_figures(rb, torch)}))
+        return 0
+
+    if args.train_only:
+        print(json.dumps(training_figures(rb, torch)))
         return 0
 
     if args.batch_only:
@@ -452,37 +495,7 @@ def main() -> int:
             st_b.forget()
             del ops_b, layers_b, bufs_b, st_b
         result["small_batch_stack"] = skinny
-        # training-side kernels (Alg. 2): coupled derivation of the cores and the scale gradients
-        # of one 4096 x 11008 layer; both stream an fp32 matrix, so the figure is HBM bytes per second
-        o_t, i_t = 4096, 11008
-        Wt = torch.randn((o_t, i_t), device="cuda") * 0.02
-        gt = (torch.randn(2, o_t, device="cuda").abs() * 0.1).half()
-        ht = (torch.randn(2, i_t, device="cuda").abs() * 0.1).half()
-        _, per_c = time_steps(torch, lambda: rb.rb_couple(Wt, gt, ht), 10, 3)
-        pk, _, _ = rb.rb_couple(Wt, gt, ht)
-        ms_c = sum(per_c) / len(per_c)
-        bytes_c = 4 * o_t * i_t + 2 * (2 * o_t * i_t // 8)         # W read, canonical and native words written
-        _, per_g = time_steps(torch, lambda: rb.rb_scale_grads(Wt, pk, gt, ht), 10, 3)
-        ms_g = sum(per_g) / len(per_g)
-        bytes_g = 4 * o_t * i_t + 2 * o_t * i_t // 8               # G and the packed cores, read once for both gradients
-        result["training_side_4096x11008"] = {
-            "rb_couple": {"ms": ms_c, "GBps": bytes_c / (ms_c * 1e-3) / 1e9,
-                          "pct_of_hbm_peak": 100.0 * bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS},
-            "rb_scale_grads": {"ms": ms_g, "GBps": bytes_g / (ms_g * 1e-3) / 1e9,
-                               "pct_of_hbm_peak": 100.0 * bytes_g / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
-        # initialisation (Alg. 1): Iterative Residual SVID of the same layer on the device, fp64;
-        # wall clock of the call (it follows the power iteration's stopping rule from the host)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        _, _, _, err_i = rb.rb_derive_iterative(Wt, 2, 5)
-        torch.cuda.synchronize()
-        s_i = time.perf_counter() - t0
-        err_i = err_i.cpu().numpy()
-        result["initialisation_4096x11008"] = {
-            "rb_derive_iterative": {"K": 2, "T_max": 5, "seconds": s_i, "seconds_per_sweep": s_i / 5,
-                                    "error_after_greedy_over_norm": float(err_i[0, 1] / Wt.double().norm().item()),
-                                    "error_after_5_sweeps_over_norm": float(err_i[4, 1] / Wt.double().norm().item())}}
-        del Wt, pk
+        result.update(training_figures(rb, torch))
         result["cpu_baseline"] = cpu_baseline(synth, packed_bytes)
     else:
         result["cpu_baseline"] = None

@@ -320,8 +320,9 @@ int rb_version(void);
  * W fp32 [out][in]; factors fp64 [out], [in]; packed: canonical words, uint32
  * [K][out][in/32]; g fp64 [K][out], h fp64 [K][in]; err: NULL or fp64
  * [T_max][K], the error ||W' - sum_j What_j||_F right after each update.  All
- * device pointers.  workspace: rb_derive_workspace_bytes(out, in) bytes of
- * device memory.  An offline step: it waits for `stream` several times (the
+ * device pointers; W, h and col_factors 16-byte aligned (RB_ERR_ALIGN otherwise).
+ * workspace: rb_derive_workspace_bytes(out, in) bytes of device memory, 16-byte
+ * aligned.  An offline step: it waits for `stream` several times (the
  * host follows the iteration's stopping rule) and has finished when it returns.
  */
 size_t rb_derive_workspace_bytes(int out, int in);

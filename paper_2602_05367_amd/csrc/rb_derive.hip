@@ -12,20 +12,21 @@
 // from W (4 bytes per weight) and the other paths (a bit and two cached scale values each), so a
 // pass is bound by the HBM read of W.  The singular triplet comes from a power iteration from the
 // all-ones vector (the matrix is non-negative): two passes per iteration, a = |R| b by rows (one
-// wavefront per row) and b = |R|^T a by columns (a thread per column over slices of rows, partial
-// sums added in slice order).  Every sum has a fixed order.  The iteration's stopping rule is
+// wavefront per row) and b = |R|^T a by columns (slices of rows, partial sums added in slice
+// order); in both a lane takes four consecutive columns, one 16-byte load of W.  Every sum has a fixed order.  The iteration's stopping rule is
 // evaluated on the device; the host reads one flag every few iterations, so the call synchronises.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 
 #include "rabit.h"
+#include "rb_device.h"
 #include "rb_internal.h"
 
 namespace rb {
 namespace derive {
 
-constexpr int ROW_SLICE = 128;         // rows one workgroup of the column pass walks
+constexpr int ROW_SLICE = 64;          // rows one workgroup of the column pass walks
 constexpr int CHECK_EVERY = 4;         // power iterations between two looks at the flag
 constexpr int MAX_ITER = 200;
 constexpr double TOL_SIGMA = 1e-13, TOL_B = 1e-10;
@@ -38,20 +39,31 @@ struct Problem {
     int K, out, in;
 };
 
-// R_i[r][c] for path `skip` (skip < 0: the error of the whole approximation, no path left out)
-__device__ __forceinline__ double residual(const Problem &p, int r, int c, int skip, const double *g_r)
+// R_i[r][c .. c + 3] for path `skip` (skip < 0: the error of the whole approximation, no path left
+// out); c % 4 == 0.  One 16-byte load of W, four bits of one sign word per path.
+__device__ __forceinline__ void residual4(const Problem &p, int r, int c, int skip, const double *g_r, double rows_r,
+                                          double v[4])
 {
-    double v = (double)p.W[(size_t)r * p.in + c];
-    if (p.rows) v = p.rows[r] * v;
-    if (p.cols) v = v * p.cols[c];
+    const float4 w = *reinterpret_cast<const float4 *>(p.W + (size_t)r * p.in + c);
+    v[0] = (double)w.x; v[1] = (double)w.y; v[2] = (double)w.z; v[3] = (double)w.w;
+    if (p.rows)
+        for (int e = 0; e < 4; ++e) v[e] = rows_r * v[e];
+    if (p.cols) {
+        const double2 c01 = *reinterpret_cast<const double2 *>(p.cols + c), c23 = *reinterpret_cast<const double2 *>(p.cols + c + 2);
+        v[0] = v[0] * c01.x; v[1] = v[1] * c01.y; v[2] = v[2] * c23.x; v[3] = v[3] * c23.y;
+    }
     const int W32 = p.in / 32;
     for (int j = 0; j < p.K; ++j) {
         if (j == skip) continue;
-        const uint32_t word = p.packed[((size_t)j * p.out + r) * W32 + (c >> 5)];
-        const double gs = (word >> (c & 31)) & 1u ? -g_r[j] : g_r[j];
-        v -= gs * p.h[(size_t)j * p.in + c];
+        const uint32_t bits4 = p.packed[((size_t)j * p.out + r) * W32 + (c >> 5)] >> (c & 31);
+        const double2 h01 = *reinterpret_cast<const double2 *>(p.h + (size_t)j * p.in + c);
+        const double2 h23 = *reinterpret_cast<const double2 *>(p.h + (size_t)j * p.in + c + 2);
+        const double hv[4] = {h01.x, h01.y, h23.x, h23.y};
+        for (int e = 0; e < 4; ++e) {
+            const double gs = (bits4 >> e) & 1u ? -g_r[j] : g_r[j];
+            v[e] -= gs * hv[e];
+        }
     }
-    return v;
 }
 
 struct Scalars {
@@ -89,7 +101,8 @@ __global__ __launch_bounds__(256) void start_kernel(double *b, int in, Scalars *
     }
 }
 
-// a_raw[r] = sum_c |R[r][c]| b[c]; one wavefront per row, lanes stride the columns
+// a_raw[r] = sum_c |R[r][c]| b[c]; one wavefront per row, a lane takes four consecutive columns at
+// a time (256 columns per step of the wavefront)
 __global__ __launch_bounds__(256) void rows_kernel(Problem p, int skip, const double *b, double *a_raw, const Scalars *sc,
                                                    bool final_pass)
 {
@@ -99,8 +112,18 @@ __global__ __launch_bounds__(256) void rows_kernel(Problem p, int skip, const do
     if (r >= p.out) return;
     double g_r[RB_MAX_K];
     for (int j = 0; j < p.K; ++j) g_r[j] = p.g[(size_t)j * p.out + r];
+    const double rows_r = p.rows ? p.rows[r] : 1.0;
     double s = 0.0;
-    for (int c = lane; c < p.in; c += 64) s += fabs(residual(p, r, c, skip, g_r)) * b[c];
+#pragma unroll 2
+    for (int c = 4 * lane; c < p.in; c += 256) {
+        double v[4];
+        residual4(p, r, c, skip, g_r, rows_r, v);
+        const double2 b01 = *reinterpret_cast<const double2 *>(b + c), b23 = *reinterpret_cast<const double2 *>(b + c + 2);
+        s += fabs(v[0]) * b01.x;
+        s += fabs(v[1]) * b01.y;
+        s += fabs(v[2]) * b23.x;
+        s += fabs(v[3]) * b23.y;
+    }
     for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m);
     if (lane == 0) a_raw[r] = s;
 }
@@ -118,34 +141,46 @@ __global__ __launch_bounds__(1024) void unit_a_kernel(const double *a_raw, doubl
     }
 }
 
-// partial[slice][c] = sum over the slice's rows of |R[r][c]| a[r]; a thread per column
-__global__ __launch_bounds__(256) void cols_kernel(Problem p, int skip, const double *a, double *partial, const Scalars *sc)
+// partial[slice][c] = sum over the slice's rows of |R[r][c]| a[r]; a thread per four consecutive
+// columns, the rows of the slice in order
+__global__ __launch_bounds__(64) void cols_kernel(Problem p, int skip, const double *a, double *partial, const Scalars *sc)
 {
     if (sc->done) return;
-    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int c = (blockIdx.x * 64 + threadIdx.x) * 4;
     const int r0 = blockIdx.y * ROW_SLICE, r1 = min(p.out, r0 + ROW_SLICE);
     if (c >= p.in) return;
-    double s = 0.0;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 8
     for (int r = r0; r < r1; ++r) {
         double g_r[RB_MAX_K];
         for (int j = 0; j < p.K; ++j) g_r[j] = p.g[(size_t)j * p.out + r];
-        s += fabs(residual(p, r, c, skip, g_r)) * a[r];
+        double v[4];
+        residual4(p, r, c, skip, g_r, p.rows ? p.rows[r] : 1.0, v);
+        const double a_r = a[r];
+        for (int e = 0; e < 4; ++e) s[e] += fabs(v[e]) * a_r;
     }
-    partial[(size_t)blockIdx.y * p.in + c] = s;
+    double *dst = partial + (size_t)blockIdx.y * p.in + c;
+    *reinterpret_cast<double2 *>(dst) = make_double2(s[0], s[1]);
+    *reinterpret_cast<double2 *>(dst + 2) = make_double2(s[2], s[3]);
 }
 
-// b_new = sum of the slices, its norm, the change of b, the stopping rule  (one workgroup)
-__global__ __launch_bounds__(1024) void unit_b_kernel(const double *partial, int n_slices, double *b, double *scratch,
-                                                      int in, Scalars *sc)
+// sum[c] = the slices of partial[.][c] in order
+__global__ __launch_bounds__(256) void slices_kernel(const double *partial, int n_slices, int in, double *sum, const Scalars *sc)
+{
+    if (sc->done) return;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= in) return;
+    double s = 0.0;
+#pragma unroll 8
+    for (int k = 0; k < n_slices; ++k) s += partial[(size_t)k * in + c];
+    sum[c] = s;
+}
+
+// b_new = scratch / its norm, the change of b, the stopping rule  (one workgroup; scratch is used up)
+__global__ __launch_bounds__(1024) void unit_b_kernel(double *b, double *scratch, int in, Scalars *sc)
 {
     if (sc->done) return;
     __shared__ double red[1024];
-    for (int c = threadIdx.x; c < in; c += 1024) {
-        double s = 0.0;
-        for (int k = 0; k < n_slices; ++k) s += partial[(size_t)k * in + c];
-        scratch[c] = s;
-    }
-    __syncthreads();
     const double s_new = sqrt(block_sumsq(scratch, in, red));
     for (int c = threadIdx.x; c < in; c += 1024) {
         const double bn = scratch[c] / s_new;
@@ -176,6 +211,8 @@ __global__ __launch_bounds__(1024) void scales_kernel(const double *a_raw, const
 // B_i = sign(R_i) (sign(0) = +1), packed 32 columns per word, bit b = column 32 w + b, 1 means -1.
 // Written to a buffer of its own: the other kernels of this step still read path i's old signs
 // nowhere (it is the path left out), but a wavefront must not read words another has replaced.
+// Eight lanes hold the 32 columns of a word, four each: every lane shifts its four bits into place
+// and an OR over the eight gives the word.
 __global__ __launch_bounds__(256) void sign_kernel(Problem p, int skip, uint32_t *words)
 {
     const int lane = threadIdx.x & 63;
@@ -183,13 +220,19 @@ __global__ __launch_bounds__(256) void sign_kernel(Problem p, int skip, uint32_t
     if (r >= p.out) return;
     double g_r[RB_MAX_K];
     for (int j = 0; j < p.K; ++j) g_r[j] = p.g[(size_t)j * p.out + r];
+    const double rows_r = p.rows ? p.rows[r] : 1.0;
     const int W32 = p.in / 32;
-    for (int c0 = 0; c0 < p.in; c0 += 64) {
-        const int c = c0 + lane;
-        const bool neg = c < p.in && !(residual(p, r, c, skip, g_r) >= 0.0);
-        const unsigned long long bal = __ballot(neg);
-        const int w = (c0 >> 5) + (lane >> 5);
-        if ((lane & 31) == 0 && w < W32) words[(size_t)r * W32 + w] = lane < 32 ? (uint32_t)bal : (uint32_t)(bal >> 32);
+    for (int c0 = 0; c0 < p.in; c0 += 256) {
+        const int c = c0 + 4 * lane;
+        uint32_t four = 0;
+        if (c < p.in) {                                        // in % 32 == 0: all four columns or none
+            double v[4];
+            residual4(p, r, c, skip, g_r, rows_r, v);
+            for (int e = 0; e < 4; ++e) four |= !(v[e] >= 0.0) ? 1u << e : 0u;
+        }
+        const uint32_t word = or_over_8(four << (4 * (lane & 7)));
+        const int w = (c0 >> 5) + (lane >> 3);
+        if ((lane & 7) == 0 && w < W32) words[(size_t)r * W32 + w] = word;
     }
 }
 
@@ -201,10 +244,13 @@ __global__ __launch_bounds__(256) void err_rows_kernel(Problem p, double *row_sq
     if (r >= p.out) return;
     double g_r[RB_MAX_K];
     for (int j = 0; j < p.K; ++j) g_r[j] = p.g[(size_t)j * p.out + r];
+    const double rows_r = p.rows ? p.rows[r] : 1.0;
     double s = 0.0;
-    for (int c = lane; c < p.in; c += 64) {
-        const double v = residual(p, r, c, -1, g_r);
-        s += v * v;
+#pragma unroll 2
+    for (int c = 4 * lane; c < p.in; c += 256) {
+        double v[4];
+        residual4(p, r, c, -1, g_r, rows_r, v);
+        for (int e = 0; e < 4; ++e) s += v[e] * v[e];
     }
     for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m);
     if (lane == 0) row_sq[r] = s;
@@ -278,8 +324,9 @@ extern "C" int rb_derive_iterative(const float *W, const double *row_factors, co
     using namespace rb::derive;
     if (!W || !packed || !g || !h) return RB_ERR_NULL;
     if (K < 1 || K > RB_MAX_K || T_max < 1 || out < 1 || in < 32 || in % 32 != 0) return RB_ERR_SHAPE;
-    if (((uintptr_t)W | (uintptr_t)packed) & 3) return RB_ERR_ALIGN;
-    if (((uintptr_t)g | (uintptr_t)h | (uintptr_t)row_factors | (uintptr_t)col_factors | (uintptr_t)err) & 7) return RB_ERR_ALIGN;
+    if ((uintptr_t)packed & 3) return RB_ERR_ALIGN;
+    if (((uintptr_t)g | (uintptr_t)row_factors | (uintptr_t)err) & 7) return RB_ERR_ALIGN;
+    if (((uintptr_t)W | (uintptr_t)h | (uintptr_t)col_factors) & 15) return RB_ERR_ALIGN;      // read 16 bytes at a time
     const Layout lay = make_layout(out, in);
     if (!workspace || workspace_bytes < lay.total) return RB_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 15) return RB_ERR_ALIGN;
@@ -292,7 +339,7 @@ extern "C" int rb_derive_iterative(const float *W, const double *row_factors, co
     uint32_t *words = reinterpret_cast<uint32_t *>(ws + lay.words);
     const int W32 = in / 32;
     const int n_slices = (out + ROW_SLICE - 1) / ROW_SLICE;
-    const dim3 by_rows((out + 3) / 4), by_cols((in + 255) / 256, n_slices);
+    const dim3 by_rows((out + 3) / 4), by_cols((in + 255) / 256, n_slices);      // the column pass: 64 threads of 4 columns
 
     // What_i^(0) = 0: zero scales (and all-plus signs, which the zero scales make irrelevant)
     const size_t nv = (size_t)K * std::max(out, in), nw = (size_t)K * out * W32;
@@ -309,8 +356,9 @@ extern "C" int rb_derive_iterative(const float *W, const double *row_factors, co
                 for (int n = 0; n < CHECK_EVERY; ++n) {
                     hipLaunchKernelGGL(rows_kernel, by_rows, dim3(256), 0, stream, p, i, b, a_raw, sc, false);
                     hipLaunchKernelGGL(unit_a_kernel, dim3(1), dim3(1024), 0, stream, a_raw, a, out, sc, false);
-                    hipLaunchKernelGGL(cols_kernel, by_cols, dim3(256), 0, stream, p, i, a, partial, sc);
-                    hipLaunchKernelGGL(unit_b_kernel, dim3(1), dim3(1024), 0, stream, partial, n_slices, b, scratch, in, sc);
+                    hipLaunchKernelGGL(cols_kernel, by_cols, dim3(64), 0, stream, p, i, a, partial, sc);
+                    hipLaunchKernelGGL(slices_kernel, dim3((in + 255) / 256), dim3(256), 0, stream, partial, n_slices, in, scratch, sc);
+                    hipLaunchKernelGGL(unit_b_kernel, dim3(1), dim3(1024), 0, stream, b, scratch, in, sc);
                 }
                 Scalars host;
                 if (hipMemcpyAsync(&host, sc, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess ||

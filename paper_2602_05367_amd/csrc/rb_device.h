@@ -34,4 +34,15 @@ __device__ __forceinline__ void store_out(void *Y, int out_dtype, size_t idx, fl
     }
 }
 
+// OR over each group of eight consecutive lanes, left in all eight: two exchanges inside the quad,
+// then one with the mirrored lane of the group (7 - i, which sits in the other quad).  Data-parallel
+// moves: every lane of the wavefront must be active.
+__device__ __forceinline__ uint32_t or_over_8(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);   // row_half_mirror
+    return v;
+}
+
 }  // namespace rb

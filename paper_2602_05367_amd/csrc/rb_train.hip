@@ -19,6 +19,7 @@
 #include <hip/hip_fp16.h>
 
 #include "rabit.h"
+#include "rb_device.h"
 #include "rb_internal.h"
 #include "rb_layout.h"
 
@@ -33,17 +34,6 @@ __global__ __launch_bounds__(256) void zero_kernel(uint32_t *p, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = 0u;
-}
-
-// OR over each group of eight consecutive lanes, left in all eight: two exchanges inside the quad,
-// then one with the mirrored lane of the group (7 - i, which sits in the other quad).  Data-parallel
-// moves: every lane of the wavefront must be active.
-__device__ __forceinline__ uint32_t or_over_8(uint32_t v)
-{
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);   // row_half_mirror
-    return v;
 }
 
 // One wavefront per row and chunk of COUPLE_CHUNK columns.  A lane takes four consecutive columns
@@ -202,11 +192,13 @@ __global__ __launch_bounds__(256) void grad_finish_kernel(const float *__restric
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < K * in) {
         float s = 0.f;
+#pragma unroll 8
         for (int sl = 0; sl < slices; ++sl) s += part_h[(size_t)sl * K * in + i];
         grad_h[i] = s;
     } else if (i < K * in + K * out) {
         const int j = i - K * in;
         float s = 0.f;
+#pragma unroll 8
         for (int cb = 0; cb < col_blocks; ++cb) s += part_g[(size_t)cb * K * out + j];
         grad_g[j] = s;
     }

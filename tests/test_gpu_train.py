@@ -91,6 +91,9 @@ def test_training_entry_points_reject_bad_arguments():
     assert lib.rb_couple(None, g.data_ptr(), h.data_ptr(), 2, 4, 32, out.data_ptr(), None, None, None) == rb.RB_ERR_NULL
     assert lib.rb_couple(W.data_ptr(), g.data_ptr(), h.data_ptr(), 4, 4, 32, out.data_ptr(), None, None, None) == rb.RB_ERR_SHAPE
     assert lib.rb_couple(W.data_ptr(), g.data_ptr(), h.data_ptr(), 2, 4, 33, out.data_ptr(), None, None, None) == rb.RB_ERR_SHAPE
+    # the kernels read W sixteen and h eight bytes at a time
+    assert lib.rb_couple(W.data_ptr() + 4, g.data_ptr(), h.data_ptr(), 2, 3, 32, out.data_ptr(), None, None, None) == rb.RB_ERR_ALIGN
+    assert lib.rb_couple(W.data_ptr(), g.data_ptr(), h.data_ptr() + 2, 1, 4, 32, out.data_ptr(), None, None, None) == rb.RB_ERR_ALIGN
     assert lib.rb_scale_grads(W.data_ptr(), out.data_ptr(), g.data_ptr(), h.data_ptr(), 2, 4, 32, W.data_ptr(), W.data_ptr(),
                               None, 0, None) == rb.RB_ERR_WORKSPACE
     assert lib.rb_scale_grads_workspace_bytes(2, 4, 31) == 0
