@@ -45,8 +45,9 @@ extern "C" {
 
 /* K = 2 is the 2-bit layer every kernel here is built for.  K = 3 (the 3-bit variant of the
  * paper's packing appendix): stacks run on the matrix cores (one token on the fused decode kernel,
- * 2..16 tokens on the small-batch kernel), single calls of more than 32 tokens on the many-token
- * kernel, shorter single calls on the generic sign-XOR + add kernel, which also runs K = 1. */
+ * 2..16 tokens on the small-batch kernel), single calls of 6 tokens or more too (the small-batch
+ * kernel up to 12 fp16 tokens, the many-token kernel otherwise), shorter single calls on the
+ * generic sign-XOR + add kernel, which also runs K = 1. */
 #define RB_MAX_K 3
 
 /* element types for rb_linear_gemm */

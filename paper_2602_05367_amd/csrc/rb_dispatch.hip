@@ -63,10 +63,31 @@ static bool batch_supported(const rb_layer *layers, int n_layers, int T)
     return true;
 }
 
+// A single call on a three-path layer reads the weights once from K3_ONE_PASS_MIN_T tokens on: the
+// small-batch kernel as a plan of one op up to K3_BATCH_MAX_T fp16 tokens, the many-token kernel
+// beyond that and for other element types.  Below, the generic kernel's one launch (its passes
+// over the weights, one per token, come out of the caches) beats their four or five.  Measured per
+// call at 4096x4096 / 11008x4096 / 4096x11008: generic 26 / 52 / 64 us at 4 tokens, 43 / 95 / 99
+// at 8, 76 / 175 / 188 at 16; small-batch 38 / 38 / 66, 46 / 47 / 86, 60 / 61 / 124; many-token
+// 57 / 58 / 111 whatever the count.
+constexpr int K3_ONE_PASS_MIN_T = 6, K3_BATCH_MAX_T = 12;
+static bool single_batch_applies(const rb_layer *L, int T)
+{
+    return L->K == 3 && T >= K3_ONE_PASS_MIN_T && T <= K3_BATCH_MAX_T && batch::layer_supported(L, T);
+}
+bool single_gemm_applies(const rb_layer *L, int T)
+{
+    return T > 2 && (L->K != 3 || T >= K3_ONE_PASS_MIN_T) && gemm::supported(L, T);
+}
+
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T)
 {
     // one layer, one token: the single-call kernel keeps everything in LDS
     if (n_layers == 1 && n_ops == 1 && T == 1 && gemv1::supported(&layers[0], 1)) return 0;
+    // one three-path layer at a few tokens: the small-batch kernel as a plan of one op; other
+    // element types than fp16 in and out: the many-token kernel
+    if (n_layers == 1 && n_ops == 1 && single_batch_applies(&layers[0], T))
+        return std::max(batch::plan_workspace_bytes(layers, 1, 1, T), gemm::workspace_bytes(&layers[0], T));
     if (batch_applies(layers, n_layers, T) && n_ops > 1) {
         size_t need = batch::plan_workspace_bytes(layers, n_layers, n_ops, T);
         // the ops of a stack the kernel turns down run one after the other on the general paths
@@ -190,10 +211,19 @@ int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dt
         workspace_bytes >= mx::plan_workspace_bytes(L, 1, 1, T)) {
         const rb_stack_op op{0, 0, 1};
         uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};
+        batch::forget_plan(workspace);
         const int rc = mx::run_plan(L, &op, 1, bufs, T, workspace, workspace_bytes, stream);
         if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_MX; return rc; }
     }
-    if (T > 2 && gemm::supported(L, T) && workspace && workspace_bytes >= gemm::workspace_bytes(L, T)) {
+    if (act_dtype == RB_F16 && out_dtype == RB_F16 && single_batch_applies(L, T) && workspace &&
+        workspace_bytes >= batch::plan_workspace_bytes(L, 1, 1, T)) {
+        const rb_stack_op op{0, 0, 1};
+        uint16_t *bufs[2] = {static_cast<uint16_t *>(const_cast<void *>(X)), static_cast<uint16_t *>(Y)};
+        int rc = batch::prepare_plan(L, &op, 1, bufs, T, workspace, workspace_bytes, stream);
+        if (rc == RB_OK) rc = batch::launch_plan(workspace, workspace_bytes, stream);
+        if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_BATCH; return rc; }
+    }
+    if (single_gemm_applies(L, T) && workspace && workspace_bytes >= gemm::workspace_bytes(L, T)) {
         g_last_path = RB_PATH_GEMM;
         return gemm::launch(L, X, Y, T, act_dtype, out_dtype, workspace, stream);
     }
@@ -213,6 +243,7 @@ int dispatch_stack(const rb_layer *layers, int n_layers, const rb_stack_op *ops,
     bool fused = workspace && workspace_bytes >= mx::plan_workspace_bytes(layers, n_layers, n_ops, T);
     for (int n = 0; n < n_ops && fused; ++n) fused = mx::layer_supported(&layers[ops[n].layer], T);
     if (fused) {
+        batch::forget_plan(workspace);
         const int rc = mx::run_plan(layers, ops, n_ops, bufs, T, workspace, workspace_bytes, stream);
         if (rc != RB_ERR_UNSUPPORTED) { g_last_path = RB_PATH_MX; return rc; }
     }

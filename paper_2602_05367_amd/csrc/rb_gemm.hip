@@ -846,7 +846,7 @@ struct Plan {
 static Plan make_plan(const rb_layer *L, int T)
 {
     Plan p;
-    p.small = T <= SMALL_TOKENS;
+    p.small = T <= SMALL_TOKENS && L->K == 2;       // three paths: the one-contraction kernel at any token count
     const int blk_tok = p.small ? SMALL_TOKENS : LARGE_TOKENS;
     p.T_pad = round_up(T, blk_tok);
     p.CT = col_tiles(L->in);
@@ -892,8 +892,7 @@ size_t workspace_bytes(const rb_layer *L, int T)
 
 bool supported(const rb_layer *L, int T)
 {
-    // three paths: the one-contraction kernel only (more than 32 tokens)
-    return (L->K == 2 && T >= 1) || (L->K == 3 && T > SMALL_TOKENS);
+    return (L->K == 2 || L->K == 3) && T >= 1;
 }
 
 int launch(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype, void *workspace,

@@ -17,6 +17,8 @@ int launch_signadd(const rb_layer *L, const void *X, void *Y, int T, int act_dty
 size_t workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int T);
 // stacks that run on the small-batch kernel (see rb_dispatch.hip)
 bool batch_applies(const rb_layer *layers, int n_layers, int T);
+// a single call of T tokens on this layer takes the many-token kernel (given the scratch memory it needs)
+bool single_gemm_applies(const rb_layer *L, int T);
 
 int dispatch_linear(const rb_layer *L, const void *X, void *Y, int T, int act_dtype, int out_dtype,
                     void *workspace, size_t workspace_bytes, hipStream_t stream);

@@ -54,7 +54,10 @@ extern "C" int rb_linear_gemm_noalloc(const rb_layer *L, const void *X, void *Y,
         rb::set_last_path(RB_PATH_MX);
         return rb::gemv1::launch(L, X, Y, stream);
     }
-    if (rb::gemm::supported(L, T)) {
+    // three paths at up to 32 tokens: the generic kernel, which needs no scratch memory, serves
+    // whatever the many-token kernel's scratch would not fit
+    const bool generic_instead = L->K == 3 && T <= 32 && rb::gemm::workspace_bytes(L, T) > SCRATCH_BYTES;
+    if (rb::single_gemm_applies(L, T) && !generic_instead) {
         // the only kernels here that need scratch memory: every byte of it that they read in a
         // call they have written earlier in the same call, so nothing has to be cleared
         if (rb::gemm::workspace_bytes(L, T) > SCRATCH_BYTES) return RB_ERR_WORKSPACE;

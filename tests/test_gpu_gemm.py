@@ -64,6 +64,31 @@ def test_three_path_gemm_matches_oracle(out, inn, T):
     assert err <= TOL
 
 
+@pytest.mark.parametrize("out,inn,T,bf16_in,path", [
+    (272, 544, 5, False, "generic"), (272, 544, 6, False, "batch"), (1000, 2080, 8, False, "batch"), (272, 544, 12, False, "batch"),
+    (272, 544, 13, False, "gemm"), (1000, 2080, 32, False, "gemm"), (272, 544, 3, True, "generic"), (48, 32, 7, True, "gemm")])
+def test_three_path_single_calls_at_few_tokens(out, inn, T, bf16_in, path):
+    """One call on a three-path layer at 6..32 tokens reads the weights once: the small-batch kernel
+    as a plan of one op up to 12 fp16 tokens, the one-contraction kernel beyond that and for bf16."""
+    rng = synth.child_rng(5, 111, out, inn, T)
+    signs, g, h = random_layer(rng, 3, out, inn)
+    g = g.copy(); h = h.copy()
+    g[1, ::6] *= -1; h[2, ::3] *= -1
+    X = synth.outlier_activations(rng, T, inn)
+    _say(f"three-path single call out={out} in={inn} T={T} bf16={bf16_in}")
+    L = to_device_layer(signs, g, h)
+    Xd = torch.from_numpy(X).cuda()
+    if bf16_in:
+        Xd = Xd.to(torch.bfloat16)
+        X = oracle.bf16_bits_to_f64(bf16_bits(Xd.cpu())).reshape(T, inn)
+    Y = rb.rb_linear_gemm(L, Xd)
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == {"batch": rb.RB_PATH_BATCH, "gemm": rb.RB_PATH_GEMM, "generic": rb.RB_PATH_SIGNADD}[path]
+    err = max_rel_l2(Y, oracle.forward(signs, g, h, X))
+    _say(f"  rel_l2={err:.3e}")
+    assert err <= TOL
+
+
 def test_gemm_negative_and_zero_scales():
     """Stored output scales of either sign and zero: the kernel folds the sign of g into the
     sign bits and keeps |g| as the magnitude of its left operand."""

@@ -56,18 +56,18 @@ def test_gemv_shapes_and_tails(K, out, inn):
 
 def test_three_paths_derived_and_batched():
     """K = 3 (the 3-bit variant of the paper's packing appendix): paths derived from a Gaussian
-    matrix, one token and a small batch, on the generic kernel."""
+    matrix, one token and a few on the generic kernel, a small batch on the small-batch kernel."""
     rng = synth.child_rng(0, 260)
     W = rng.standard_normal((160, 544)) * 0.02
     signs, g, h, norms = oracle.derive(W, 3)
     assert norms[3] < norms[2] < norms[1] < norms[0]
     L = to_device_layer(signs, g, h)
-    for T in (1, 4):
+    for T in (1, 4, 9):
         X = synth.outlier_activations(rng, T, 544)
         _say(f"K=3 derived 160x544 T={T}")
         Y = rb.rb_linear_gemm(L, torch.from_numpy(X).cuda())
         torch.cuda.synchronize()
-        assert rb.rb_last_path() == rb.RB_PATH_SIGNADD
+        assert rb.rb_last_path() == (rb.RB_PATH_SIGNADD if T <= 4 else rb.RB_PATH_BATCH)
         assert max_rel_l2(Y, oracle.forward(signs, g, h, X)) <= TOL
         # the third path refines the second: closer to the dense W x than the two-path layer
         dense = (X.astype(np.float64) @ W.T)
