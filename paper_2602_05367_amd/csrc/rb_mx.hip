@@ -58,7 +58,15 @@ constexpr int GO_PAUSE_1 = 24;      // between a workgroup's own stores and its 
 constexpr int GO_PAUSE_2 = 28;      // ... two tokens
 constexpr int TILE_PAUSE_1 = 32;    // per 16 sign tiles that a workgroup is ahead of the busiest one, one token
 constexpr int TILE_PAUSE_2 = 44;    // ... two tokens
-#define RB_REPOLL_SLEEP "8"         // between two looks at a tile that was not yet written
+// between two looks at a tile that was not yet written: the first 64 come quickly, the rest far
+// apart (wavefronts that look too often keep the stores they wait for from landing); %[left] counts
+// down from 0x40000
+#define RB_REPOLL_PAUSE                       \
+    "s_sleep 8\n\t"                           \
+    "s_cmp_gt_u32 %[left], 0x3ffc0\n\t"       \
+    "s_cbranch_scc1 3f\n\t"                   \
+    "s_sleep 56\n"                            \
+    "3:\n\t"
 
 // ---------------------------------------------------------------- helpers ---
 __device__ __forceinline__ uint32_t lds_addr(const void *p)
@@ -780,7 +788,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_or_b64 %[un], %[un], vcc\n\t"
                                              "s_cmp_eq_u64 %[un], 0\n\t"
                                              "s_cbranch_scc1 2f\n\t"
-                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             RB_REPOLL_PAUSE
                                              "s_sub_u32 %[left], %[left], 1\n\t"
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
@@ -792,6 +800,11 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              : [off] "v"(lane_off), [rs] "s"(rsrc), [cnt] "v"(waited_lds)
                                              : "vcc", "scc", "memory");
                             } else if constexpr (TT == 4) {
+                                // Four tokens: the looks read first words only, and further and further
+                                // apart; the tile follows once they all show data.  (A look that fetched
+                                // the 8 KB tile as well, from every wavefront that waits, kept the
+                                // producers' second store of a row tile from landing for as long as the
+                                // looks went on.)
                                 int c0, c1, c2, c3, c4, c5, c6, c7;
                                 asm volatile("s_mov_b32 %[left], 0x40000\n"
                                              "1:\n\t"
@@ -804,14 +817,6 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "buffer_load_dword %[c5], %[off2], %[rs], 0 offen offset:1024 sc1\n\t"
                                              "buffer_load_dword %[c6], %[off2], %[rs], 0 offen offset:2048 sc1\n\t"
                                              "buffer_load_dword %[c7], %[off2], %[rs], 0 offen offset:3072 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
-                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b4], %[off2], %[rs], 0 offen sc1\n\t"
-                                             "buffer_load_dwordx4 %[b5], %[off2], %[rs], 0 offen offset:1024 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b6], %[off2], %[rs], 0 offen offset:2048 sc1\n\t"
-                                             "buffer_load_dwordx4 %[b7], %[off2], %[rs], 0 offen offset:3072 sc1\n\t"
                                              "s_waitcnt vmcnt(0)\n\t"
                                              "v_and_b32 %[c0], 0xff, %[c0]\n\t"
                                              "v_and_b32 %[c1], 0xff, %[c1]\n\t"
@@ -829,11 +834,20 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_mov_b64 %[un], vcc\n\t"
                                              "s_cmp_eq_u64 %[un], 0\n\t"
                                              "s_cbranch_scc1 2f\n\t"
-                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             RB_REPOLL_PAUSE
                                              "s_sub_u32 %[left], %[left], 1\n\t"
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"
                                              "2:\n\t"
+                                             "buffer_load_dwordx4 %[b0], %[off], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b1], %[off], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b2], %[off], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b3], %[off], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b4], %[off2], %[rs], 0 offen sc1\n\t"
+                                             "buffer_load_dwordx4 %[b5], %[off2], %[rs], 0 offen offset:1024 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b6], %[off2], %[rs], 0 offen offset:2048 sc1\n\t"
+                                             "buffer_load_dwordx4 %[b7], %[off2], %[rs], 0 offen offset:3072 sc1\n\t"
+                                             "s_waitcnt vmcnt(0)\n\t"
                                              "v_mov_b32 %[c0], 1\n\t"
                                              "ds_add_u32 %[cnt], %[c0]"
                                              : [b0] "+v"(B[s].r[0]), [b1] "+v"(B[s].r[1]), [b2] "+v"(B[s].r[2 % KOP]),
@@ -871,7 +885,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                              "s_or_b64 %[un], %[un], vcc\n\t"
                                              "s_cmp_eq_u64 %[un], 0\n\t"
                                              "s_cbranch_scc1 2f\n\t"
-                                             "s_sleep " RB_REPOLL_SLEEP "\n\t"
+                                             RB_REPOLL_PAUSE
                                              "s_sub_u32 %[left], %[left], 1\n\t"
                                              "s_cmp_lg_u32 %[left], 0\n\t"
                                              "s_cbranch_scc1 1b\n"

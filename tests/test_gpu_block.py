@@ -259,6 +259,39 @@ def test_block_beyond_the_fused_kernel_is_refused():
     assert e.value.code == rb.RB_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("T", [1, 2, 4])
+def test_full_7b_block_stack_without_pause(T):
+    """The 32-block stack as bench.py builds it with the hand-over pause set to zero: at full width
+    every wavefront that waits looks again while all the others do the same and the producers still
+    store.  Same bits as the paced run, no wait given up."""
+    import bench
+    ops, layers, norms, bufs, x0, op_list, _ = bench.build_block_stack(rb, synth, torch, "7b", T)
+    block = rb.Block(layers, norms, 1e-5, op_list, bufs, T)
+    block.prepare()
+    bufs[0].copy_(x0)
+    block.run_prepared()
+    torch.cuda.synchronize()
+    assert block.status() == rb.RB_OK, f"gave up: reason {block.gave_up()}"
+    paced = [b.clone() for b in bufs]
+    before = block.waited()
+    try:
+        rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, 0)
+        print(f"no hand-over pause, full 7B-shaped block stack, T={T}", flush=True)
+        for run in range(4):
+            for b in bufs[1:]:
+                b.zero_()
+            bufs[0].copy_(x0)
+            block.run_prepared()
+            torch.cuda.synchronize()
+            assert block.status() == rb.RB_OK, f"run {run} gave up: reason {block.gave_up()}"
+            bad = [n for n, (a, b) in enumerate(zip(paced, bufs)) if not torch.equal(a, b)]
+            assert not bad, (run, bad[:5])
+    finally:
+        rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, -1)
+    print(f"  tiles read again: {block.waited() - before}", flush=True)
+    block.forget()
+
+
 def test_full_7b_block_stack_as_benchmarked_sampled_outputs():
     """The 32-block stack exactly as bench.py builds and times it (residual stream in one buffer):
     status clean, and bit for bit the run of the same ops with a buffer per op, whose sampled rows

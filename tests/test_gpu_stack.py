@@ -147,7 +147,7 @@ def test_non_finite_activation_propagates_and_ends():
         assert not torch.isfinite(dev_bufs[op.dst]).any(), op.name
 
 
-@pytest.mark.parametrize("T", [1, 2])
+@pytest.mark.parametrize("T", [1, 2, 3, 4])
 def test_requests_ahead_of_the_writes_are_caught(T):
     """With the hand-over pause set to zero every workgroup asks for a phase's inputs the moment its
     own part is stored, so many input tiles are requested before the other workgroups have written
@@ -354,6 +354,42 @@ def test_determinism_canary_and_hand_over_stress(T, runs):
     assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
     bad = [n for n, (a, b) in enumerate(zip(first, bufs)) if not torch.equal(a, b)]
     assert not bad, bad[:5]
+    stack.forget()
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4])
+def test_unpaced_hand_over_on_the_full_stack(T):
+    """The 7B-shaped stack as the benchmark builds it with the hand-over pause set to zero: at every
+    one of its 128 hand-overs nearly every wavefront asks for its inputs before they are written and
+    has to look again while the producers still store.  Same bits as the paced run, no wait given
+    up.  (With four tokens a waiting wavefront used to fetch its whole 8 KB tile with every look;
+    at this width those looks kept the second store of the producers' row tiles from landing until
+    the waits were given up.)"""
+    import bench
+    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T)
+    stack = rb.Stack(layers, op_list, bufs, T)
+    stack.prepare()
+    stack.run_prepared()
+    torch.cuda.synchronize()
+    assert stack.status() == rb.RB_OK, f"gave up: reason {stack.gave_up()}"
+    paced = [b.clone() for b in bufs]
+    waited_before = stack.waited()
+    try:
+        rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, 0)
+        print(f"no hand-over pause, full 7B-shaped stack, T={T}", flush=True)
+        for run in range(5):
+            for b in bufs[1:]:
+                b.zero_()
+            stack.run_prepared()
+            torch.cuda.synchronize()
+            assert stack.status() == rb.RB_OK, f"run {run} gave up: reason {stack.gave_up()}"
+            bad = [n for n, (a, b) in enumerate(zip(paced, bufs)) if not torch.equal(a, b)]
+            assert not bad, (run, bad[:5])
+    finally:
+        rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, DEFAULT_PAUSE)
+    waited = stack.waited() - waited_before
+    print(f"  tiles read again: {waited}", flush=True)
+    assert waited > 100000                                   # the unpaced runs did exercise the waits
     stack.forget()
 
 
