@@ -357,8 +357,8 @@ def test_determinism_canary_and_hand_over_stress(T, runs):
     stack.forget()
 
 
-@pytest.mark.parametrize("T", [1, 2, 3, 4])
-def test_unpaced_hand_over_on_the_full_stack(T):
+@pytest.mark.parametrize("T,K", [(1, 2), (2, 2), (3, 2), (4, 2), (1, 3)])
+def test_unpaced_hand_over_on_the_full_stack(T, K):
     """The 7B-shaped stack as the benchmark builds it with the hand-over pause set to zero: at every
     one of its 128 hand-overs nearly every wavefront asks for its inputs before they are written and
     has to look again while the producers still store.  Same bits as the paced run, no wait given
@@ -366,7 +366,7 @@ def test_unpaced_hand_over_on_the_full_stack(T):
     at this width those looks kept the second store of the producers' row tiles from landing until
     the waits were given up.)"""
     import bench
-    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T)
+    ops, layers, bufs, op_list, _ = bench.build_stack(rb, synth, torch, "7b", T, K=K)
     stack = rb.Stack(layers, op_list, bufs, T)
     stack.prepare()
     stack.run_prepared()
@@ -376,7 +376,7 @@ def test_unpaced_hand_over_on_the_full_stack(T):
     waited_before = stack.waited()
     try:
         rb.rb_stack_set_option(rb.RB_OPT_HANDOVER_PAUSE, 0)
-        print(f"no hand-over pause, full 7B-shaped stack, T={T}", flush=True)
+        print(f"no hand-over pause, full 7B-shaped stack, T={T}, K={K}", flush=True)
         for run in range(5):
             for b in bufs[1:]:
                 b.zero_()
