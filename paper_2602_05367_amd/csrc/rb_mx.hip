@@ -1094,7 +1094,9 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                             if (lane == 0) __hip_atomic_store(RB_GLOBAL(uint32_t, error), (uint32_t)GAVE_UP_BLOCK, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
+                        // like the looks at a late tile: the first 64 come quickly, the rest far apart
                         __builtin_amdgcn_s_sleep(8);
+                        if (left < BLOCK_POLLS - 64) __builtin_amdgcn_s_sleep(56);
                     }
                     // 1 / root mean square of the input, per token: the 32 lanes of this slot's half
                     // add up their shares in a fixed order
