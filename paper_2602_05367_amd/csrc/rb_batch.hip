@@ -49,14 +49,23 @@ constexpr int MAX_CONS = 3;            // ops that read one op's output inside a
 constexpr int WAVES = 16;              // wavefronts of a workgroup
 constexpr int THREADS = WAVES * 64;
 constexpr int MAX_STAGE_OPS = 8;       // independent ops that share a launch
-// S wavefronts share a row tile, each taking every S-th piece (128-column half x path) of a sign
-// tile; a workgroup owns R = 16 / S row tiles.  Few row tiles per workgroup make many workgroups
-// out of a small op; many row tiles share the staged right operands among more rows, which is what
-// counts when a launch has workgroups enough anyway (at 16 tokens the operands of a column tile
-// are 32 KB, a sign tile 1 KB).  S is chosen per launch (see prepare_plan).
-__host__ __device__ constexpr int max_split(int K) { return K == 2 ? 4 : 2; }
-__host__ __device__ constexpr int min_split(int K) { return K == 2 ? 1 : 2; }     // three paths, all pieces in one wavefront: too many accumulators
-__host__ __device__ constexpr int block_tiles(int S) { return WAVES / S; }      // row tiles of a workgroup
+// S wavefronts share P row tiles, each taking every S-th piece (128-column half x path) of their
+// sign tiles; a workgroup owns R = 16 / S * P row tiles.  Few row tiles per workgroup make many
+// workgroups out of a small op; many row tiles share the staged right operands among more rows,
+// which is what counts when a launch has workgroups enough anyway (at 16 tokens the operands of a
+// column tile are 32 KB, a sign tile 1 KB).  With P = 2 a wavefront reads an operand from LDS once
+// for two matrix instructions: at 16 tokens the reads of the operands, 2 KB per instruction, are
+// what a compute unit spends most of a column tile on.  The form is chosen per launch (see
+// prepare_plan): two paths (S, P) = (2, 2), (4, 2) or (4, 1), i.e. 16, 8 or 4 row tiles per
+// workgroup; three paths (2, 1) (two row tiles of three paths would need 96 accumulator registers
+// at 16 tokens).
+struct Form { int S, P; };
+__host__ __device__ constexpr int n_forms(int K) { return K == 2 ? 3 : 1; }
+__host__ __device__ constexpr Form form_of(int K, int i)     // by falling row tiles per workgroup
+{
+    return K == 2 ? (i == 0 ? Form{2, 2} : i == 1 ? Form{4, 2} : Form{4, 1}) : Form{2, 1};
+}
+__host__ __device__ constexpr int block_tiles(int S, int P) { return WAVES / S * P; }      // row tiles of a workgroup
 constexpr int WANT_GROUPS = 256;       // workgroups a launch should have before it takes larger row blocks
 constexpr size_t MAX_EXPAND = 1024;
 
@@ -167,10 +176,13 @@ __global__ __launch_bounds__(256) void expand_kernel(const Op *ops, const int *w
 // ------------------------------------------------------------------- kernel ---
 // LDS ring of column tiles: a slot holds the tile's right operands and the sign tiles of the
 // workgroup's row tiles; as many slots as fit (at most 16)
-__host__ __device__ constexpr int slot_bytes(int K, int G, int S) { return (int)tile_operand_bytes(K, G) + block_tiles(S) * tile_words(K) * 4; }
-__host__ __device__ constexpr int ring_depth(int K, int G, int S)
+__host__ __device__ constexpr int slot_bytes(int K, int G, int S, int P)
 {
-    return (144 * 1024) / slot_bytes(K, G, S) < 16 ? (144 * 1024) / slot_bytes(K, G, S) : 16;
+    return (int)tile_operand_bytes(K, G) + block_tiles(S, P) * tile_words(K) * 4;
+}
+__host__ __device__ constexpr int ring_depth(int K, int G, int S, int P)
+{
+    return (144 * 1024) / slot_bytes(K, G, S, P) < 16 ? (144 * 1024) / slot_bytes(K, G, S, P) : 16;
 }
 
 // "at most rem * LPI vector-memory loads outstanding" for a run-time rem in 0 .. R.  (KERNEL only
@@ -204,20 +216,20 @@ template <int KERNEL, int LPI> struct Copies {
     }
 };
 
-template <int K, int G, int S>
+template <int K, int G, int S, int P>
 __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict__ ops, int op0, int nops, int T)
 {
-    constexpr int R = block_tiles(S), NP = 2 * K / S;        // NP: pieces per wavefront and tile
+    constexpr int R = block_tiles(S, P), NP = 2 * K / S;     // NP: pieces per wavefront and tile
     static_assert(2 * K % S == 0 && WAVES % S == 0, "pieces and wavefronts go round");
     constexpr int OPB = (int)tile_operand_bytes(K, G);
     constexpr int TB = tile_words(K) * 4;                    // bytes of a sign tile
-    constexpr int SLOT = slot_bytes(K, G, S);                 // [operands OPB][sign tiles R x TB]
+    constexpr int SLOT = slot_bytes(K, G, S, P);              // [operands OPB][sign tiles R x TB]
     constexpr int COPIES = SLOT / 1024;                      // 1 KB per wavefront instruction
     constexpr int LPI = (COPIES + WAVES - 1) / WAVES;        // copies per wavefront and tile
-    constexpr int D = ring_depth(K, G, S);                    // slots in LDS; D - 1 tiles are requested ahead
+    constexpr int D = ring_depth(K, G, S, P);                 // slots in LDS; D - 1 tiles are requested ahead
     constexpr int PART = G * 4 * TILE_ROWS;                  // floats of one wavefront's partial outputs: [token][row]
     static_assert(SLOT % 1024 == 0 && D >= 2 && (D - 1) * LPI < 64, "the in-order wait counts on this");
-    static_assert(WAVES * PART * 4 <= D * SLOT, "the partial outputs reuse the ring");
+    static_assert(WAVES * P * PART * 4 <= D * SLOT, "the partial outputs reuse the ring");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // D slots
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -229,7 +241,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
     const Op &op = ops[o];
     wg -= op.wg0;
     const int CT = op.CT, RT = op.RT, out = op.out;
-    const int rt = wg * R + r;
+    const int rt = wg * R + r * P;                           // this wavefront's first row tile (of P)
     const bool live = rt < RT;
     const int col = lane & 15, qd = lane >> 4;
     const int scale_b = mx::term_scale(col);
@@ -243,7 +255,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
     // temporal) follow in the slot as they are in memory, so that lane l finds its 2 K words
     // (word c * K + k = path k, columns 128 c + 32 (l / 16) ..) at 8 K l.  A row tile past the
     // end of the matrix copies the last one (nobody reads it).
-    Copies<64 * K + 8 * G + S, LPI> copies;
+    Copies<64 * K + 8 * G + S + 128 * P, LPI> copies;
 #pragma unroll
     for (int i = 0; i < LPI; ++i) {
         const int piece = (wave + WAVES * i) % COPIES;
@@ -260,25 +272,27 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
         }
     }
 
-    v4f acc[NP][G];
+    v4f acc[P][NP][G];
 #pragma unroll
-    for (int j = 0; j < NP; ++j)
+    for (int p = 0; p < P; ++p)
 #pragma unroll
-        for (int g = 0; g < G; ++g) acc[j][g] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NP; ++j)
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[p][j][g] = (v4f){0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
     for (int d = 0; d < D - 1; ++d)
         if (d < CT) copies.request(lds + d * SLOT, d);
     const uint32_t lds_base = (uint32_t)(size_t)RB_LDS(lds);
     const uint32_t lds_lane = lds_base + (uint32_t)lane * 16u;
-    const uint32_t lds_sign = lds_base + (uint32_t)(OPB + r * TB + lane * 8 * K + 4 * sp);
+    const uint32_t lds_sign = lds_base + (uint32_t)(OPB + r * P * TB + lane * 8 * K + 4 * sp);
     int slot = 0;
     for (int ct = 0; ct < CT; ++ct) {
         // Copies complete in order and every tile costs this wavefront LPI of them: when at most
         // LPI times the number of younger tiles already requested are outstanding, tile ct is
         // here.  After the barrier it is here for every wavefront, and every wavefront is
         // through with the slot of tile ct - 1, which the next request overwrites.
-        WaitTiles<64 * K + 8 * G + S, LPI, D - 2>::run(min(CT - 1 - ct, D - 2));
+        WaitTiles<64 * K + 8 * G + S + 128 * P, LPI, D - 2>::run(min(CT - 1 - ct, D - 2));
         asm volatile("s_barrier" ::: "memory");               // the barrier alone: a fence would wait for every copy in flight
         if (ct + D - 1 < CT) copies.request(lds + (slot == 0 ? D - 1 : slot - 1) * SLOT, ct + D - 1);
         if (live) {
@@ -286,18 +300,21 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
             for (int j = 0; j < NP; ++j) {
                 // Reads of the ring are written as instructions: a read the compiler can see would
                 // wait for every copy still in flight.
-                uint32_t sw;
-                asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                             : "=v"(sw) : "v"(lds_sign + (uint32_t)(slot * SLOT + 4 * j * S)) : "memory");
-                v8i a;
-                a[0] = (int)(((sw << 3) & 0x88888888u) | c22);
-                a[1] = (int)(((sw << 2) & 0x88888888u) | c22);
-                a[2] = (int)(((sw << 1) & 0x88888888u) | c22);
-                a[3] = (int)((sw & 0x88888888u) | c22);
-                a[4] = 0; a[5] = 0; a[6] = 0; a[7] = 0;
+                v8i a[P];
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    uint32_t sw;
+                    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(sw) : "v"(lds_sign + (uint32_t)(slot * SLOT + p * TB + 4 * j * S)) : "memory");
+                    a[p][0] = (int)(((sw << 3) & 0x88888888u) | c22);
+                    a[p][1] = (int)(((sw << 2) & 0x88888888u) | c22);
+                    a[p][2] = (int)(((sw << 1) & 0x88888888u) | c22);
+                    a[p][3] = (int)((sw & 0x88888888u) | c22);
+                    a[p][4] = 0; a[p][5] = 0; a[p][6] = 0; a[p][7] = 0;
+                }
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    // the operand of piece c * K + k, token group g
+                    // the operand of piece c * K + k, token group g: read once for the P row tiles
                     const uint32_t addr = lds_lane + (uint32_t)(slot * SLOT + ((sp + j * S) * G + g) * 2048);
                     v4i lo, hi;
                     asm volatile("ds_read_b128 %0, %2\n\t"
@@ -310,7 +327,9 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
                     b[0] = lo[0]; b[1] = lo[1]; b[2] = lo[2]; b[3] = lo[3];
                     b[4] = hi[0]; b[5] = hi[1]; b[6] = hi[2]; b[7] = hi[3];
                     // A: fp4 (cbsz = 4), B: bf8 (blgp = 1); scale bytes are E8M0 exponents
-                    acc[j][g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[j][g], 4, 1, 0, 0x7f7f7f7f, 0, scale_b);
+#pragma unroll
+                    for (int p = 0; p < P; ++p)
+                        acc[p][j][g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p], b, acc[p][j][g], 4, 1, 0, 0x7f7f7f7f, 0, scale_b);
                 }
             }
         }
@@ -322,27 +341,30 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
     // ---- partial outputs of this wavefront's pieces, scaled by the output scales of their paths
     // (Section 4.1: y = sum_k g_k (.) (B_k u_k)).  Lane (col, q) holds rows 4q .. 4q+3 of operand
     // column col = 4 * (token % 4) + term; the four lanes of a quad hold the four terms.
-    float *const part = reinterpret_cast<float *>(lds);       // [wavefront][token][row]
+    float *const part = reinterpret_cast<float *>(lds);       // [wavefront][row tile of the wavefront][token][row]
     if (live) {
-        float gq[NP][4];
 #pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            const int k = (sp + j * S) % K;
+        for (int p = 0; p < P; ++p) {
+            float gq[NP][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = rt * TILE_ROWS + 4 * qd + i;
-                gq[j][i] = row < out ? (float)RB_GLOBAL(const _Float16, op.g)[(size_t)k * out + row] * op.inv_sc[k] : 0.f;
+            for (int j = 0; j < NP; ++j) {
+                const int k = (sp + j * S) % K;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = (rt + p) * TILE_ROWS + 4 * qd + i;
+                    gq[j][i] = row < out ? (float)RB_GLOBAL(const _Float16, op.g)[(size_t)k * out + row] * op.inv_sc[k] : 0.f;
+                }
             }
-        }
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            v4f p = {0.f, 0.f, 0.f, 0.f};
+            for (int g = 0; g < G; ++g) {
+                v4f v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < NP; ++j)
+                for (int j = 0; j < NP; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) p[i] = __builtin_fmaf(gq[j][i], mx::quad_sum(acc[j][g][i]), p[i]);
-            if ((col & 3) == 0)
-                *reinterpret_cast<v4f *>(part + wave * PART + (4 * g + (col >> 2)) * TILE_ROWS + 4 * qd) = p;
+                    for (int i = 0; i < 4; ++i) v[i] = __builtin_fmaf(gq[j][i], mx::quad_sum(acc[p][j][g][i]), v[i]);
+                if ((col & 3) == 0)
+                    *reinterpret_cast<v4f *>(part + (wave * P + p) * PART + (4 * g + (col >> 2)) * TILE_ROWS + 4 * qd) = v;
+            }
         }
     }
     __syncthreads();
@@ -356,7 +378,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
         if (row >= out) continue;
         float sum = 0.f;
 #pragma unroll
-        for (int q = 0; q < S; ++q) sum += part[(rr * S + q) * PART + tok * TILE_ROWS + i];
+        for (int q = 0; q < S; ++q) sum += part[(((rr / P) * S + q) * P + rr % P) * PART + tok * TILE_ROWS + i];
         const _Float16 y16 = (_Float16)sum;                   // round to nearest even
         RB_GLOBAL(_Float16, op.y)[(size_t)tok * out + row] = y16;
         const float yf = (float)y16;
@@ -375,7 +397,7 @@ __global__ __launch_bounds__(THREADS, 1) void batch_kernel(const Op *__restrict_
 }
 
 // ------------------------------------------------------------------ host ---
-struct Launch { int op0, nops, groups, K, S; };
+struct Launch { int op0, nops, groups, K, S, P; };
 struct Layout { size_t ops, cons, which, up, total; };
 
 static Layout make_layout(int n_ops, size_t up_total)
@@ -463,19 +485,20 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
             ++nops;
         }
         // the largest row blocks that still give the launch WANT_GROUPS workgroups, else the smallest
-        int S = max_split(K), groups = 0;
-        for (int s_try = min_split(K); s_try <= max_split(K); s_try *= 2) {
+        Form f = form_of(K, n_forms(K) - 1);
+        int groups = 0;
+        for (int i = 0; i < n_forms(K); ++i) {
+            f = form_of(K, i);
             groups = 0;
-            for (int n = op0; n < op0 + nops; ++n) groups += (ops[(size_t)n].RT + block_tiles(s_try) - 1) / block_tiles(s_try);
-            S = s_try;
+            for (int n = op0; n < op0 + nops; ++n) groups += (ops[(size_t)n].RT + block_tiles(f.S, f.P) - 1) / block_tiles(f.S, f.P);
             if (groups >= WANT_GROUPS) break;
         }
         groups = 0;
         for (int n = op0; n < op0 + nops; ++n) {
             ops[(size_t)n].wg0 = groups;
-            groups += (ops[(size_t)n].RT + block_tiles(S) - 1) / block_tiles(S);
+            groups += (ops[(size_t)n].RT + block_tiles(f.S, f.P) - 1) / block_tiles(f.S, f.P);
         }
-        pr.launches.push_back(Launch{op0, nops, groups, K, S});
+        pr.launches.push_back(Launch{op0, nops, groups, K, f.S, f.P});
         op0 += nops;
     }
     pr.n_expand = (int)expand_list.size();
@@ -501,29 +524,29 @@ int prepare_plan(const rb_layer *layers, const rb_stack_op *sops, int n_ops, uin
     return RB_OK;
 }
 
-template <int K, int G, int S>
+template <int K, int G, int S, int P>
 static int launch_one(const Op *d_ops, const Launch &l, int T, hipStream_t stream)
 {
-    const int lds_bytes = ring_depth(K, G, S) * slot_bytes(K, G, S);
+    const int lds_bytes = ring_depth(K, G, S, P) * slot_bytes(K, G, S, P);
     static std::atomic<bool> configured{false};
     if (!configured.load()) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(batch_kernel<K, G, S>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(batch_kernel<K, G, S, P>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 lds_bytes) != hipSuccess)
             return RB_ERR_HIP;
         configured.store(true);
     }
-    hipLaunchKernelGGL((batch_kernel<K, G, S>), dim3((unsigned)l.groups), dim3(THREADS), lds_bytes, stream, d_ops, l.op0, l.nops, T);
+    hipLaunchKernelGGL((batch_kernel<K, G, S, P>), dim3((unsigned)l.groups), dim3(THREADS), lds_bytes, stream, d_ops, l.op0, l.nops, T);
     return RB_OK;
 }
 
-template <int K, int S>
+template <int K, int S, int P>
 static int launch_groups(const Op *d_ops, const Launch &l, int T, hipStream_t stream)
 {
     switch (groups_of(T)) {
-    case 1: return launch_one<K, 1, S>(d_ops, l, T, stream);
-    case 2: return launch_one<K, 2, S>(d_ops, l, T, stream);
-    case 3: return launch_one<K, 3, S>(d_ops, l, T, stream);
-    default: return launch_one<K, 4, S>(d_ops, l, T, stream);
+    case 1: return launch_one<K, 1, S, P>(d_ops, l, T, stream);
+    case 2: return launch_one<K, 2, S, P>(d_ops, l, T, stream);
+    case 3: return launch_one<K, 3, S, P>(d_ops, l, T, stream);
+    default: return launch_one<K, 4, S, P>(d_ops, l, T, stream);
     }
 }
 
@@ -543,9 +566,9 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            stream, d_ops, reinterpret_cast<const int *>(ws + pr.lay.which), T);
     for (const Launch &l : pr.launches) {
         int rc = RB_ERR_UNSUPPORTED;
-        if (l.K == 2) rc = l.S == 1 ? launch_groups<2, 1>(d_ops, l, T, stream) : l.S == 2 ? launch_groups<2, 2>(d_ops, l, T, stream)
-                                    : launch_groups<2, 4>(d_ops, l, T, stream);
-        else if (l.K == 3) rc = launch_groups<3, 2>(d_ops, l, T, stream);
+        if (l.K == 2) rc = l.S == 2 ? launch_groups<2, 2, 2>(d_ops, l, T, stream) : l.P == 2 ? launch_groups<2, 4, 2>(d_ops, l, T, stream)
+                                    : launch_groups<2, 4, 1>(d_ops, l, T, stream);
+        else if (l.K == 3) rc = launch_groups<3, 2, 1>(d_ops, l, T, stream);
         if (rc != RB_OK) return rc;
     }
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
