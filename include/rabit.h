@@ -121,7 +121,10 @@ int rb_linear_gemm(const rb_layer *L, const void *X, void *Y, int T,
  * kernel is a device array inside the library (RB_NOALLOC_SCRATCH_BYTES per GPU that uses the
  * library, held until the process ends).  The call allocates nothing on host or device.  It returns
  * RB_ERR_WORKSPACE when rb_workspace_bytes(L, 1, 1, T) of the many-token kernel exceeds
- * RB_NOALLOC_SCRATCH_BYTES (roughly T_padded * in above 4 M elements).  Every call on one GPU
+ * RB_NOALLOC_SCRATCH_BYTES (roughly T_padded * in above 4 M elements; a three-path layer at up to
+ * 32 tokens takes the generic kernel then, which needs no scratch memory, and where the variant
+ * with a workspace takes the small-batch kernel this one takes the many-token kernel: same result
+ * to the tolerance, not bit for bit).  Every call on one GPU
  * shares that GPU's array: calls that may overlap in time on one GPU (different streams or
  * threads) race and must be ordered by the caller; calls on one stream are ordered already.
  * rb_noalloc_scratch_bytes returns RB_NOALLOC_SCRATCH_BYTES.

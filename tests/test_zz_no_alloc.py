@@ -37,6 +37,38 @@ def test_noalloc_matches_workspace_variant_twice_second_call_smaller():
         assert max_rel_l2(Y, oracle.forward(*host, X)) <= TOL
 
 
+def test_noalloc_three_paths_at_few_tokens():
+    """Three-path layers: from six tokens on the one-contraction kernel on the library's scratch
+    memory (the variant with a workspace may take the small-batch kernel instead: same result to
+    the tolerance); below, and where that kernel's scratch would not fit, the generic kernel, which
+    needs none."""
+    rng = synth.child_rng(7, 2)
+    host = random_layer(rng, 3, 272, 1056)
+    L = to_device_layer(*host)
+    for T, path in ((20, rb.RB_PATH_GEMM), (8, rb.RB_PATH_GEMM), (4, rb.RB_PATH_SIGNADD)):
+        X = synth.outlier_activations(rng, T, 1056)
+        Xd = torch.from_numpy(X).cuda()
+        Y = torch.full((T, 272), float("nan"), dtype=torch.float16, device="cuda")
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        print(f"three paths, T={T}", flush=True)
+        rb.rb_linear_gemm_noalloc(L, Xd, Y)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_allocated() == before and rb.rb_last_path() == path
+        assert max_rel_l2(Y, oracle.forward(*host, X)) <= TOL
+        if T == 20:
+            assert torch.equal(Y, rb.rb_linear_gemm(L, Xd))          # the same kernel on the caller's workspace
+    wide = random_layer(rng, 3, 16, 65536)                           # 256 x 65536 fp16 of scratch: more than the library holds
+    Lw = to_device_layer(*wide)
+    X = synth.gaussian_activations(rng, 8, 65536)
+    Y = torch.full((8, 16), float("nan"), dtype=torch.float16, device="cuda")
+    print("three paths, 65536 columns, T=8", flush=True)
+    rb.rb_linear_gemm_noalloc(Lw, torch.from_numpy(X).cuda(), Y)
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == rb.RB_PATH_SIGNADD
+    assert max_rel_l2(Y, oracle.forward(*wide, X)) <= TOL
+
+
 def test_noalloc_rejects_what_does_not_fit_and_bad_arguments():
     assert rb.rb_noalloc_scratch_bytes() == 32 << 20
     rng = synth.child_rng(7, 1)
