@@ -174,10 +174,10 @@ static_assert(sizeof(SlotRec) == 64, "four 16-byte loads");
 // per row of the slot: g_1 / sc_1, g_2 / sc_2 of the op (its output scales over the input scaling
 // it was fed with), then h_k * sc_k (k = 1, 2) of each reading op (its input scales times its input
 // scaling); for three paths g_3 / sc_3 and the readers' h_3 * sc_3 follow
-struct SlotVals {
-    float v[16][12];
-};
-static_assert(sizeof(SlotVals) == 768 && 12 >= 3 + 3 * MAX_CONS, "48 bytes per row");
+// (eight floats per row for two paths, twelve for three; a record is 16 rows)
+__host__ __device__ constexpr int vals_row_floats(int K) { return K == 3 ? 12 : 8; }
+__host__ __device__ constexpr size_t vals_record_bytes(int K) { return (size_t)16 * vals_row_floats(K) * sizeof(float); }
+static_assert(8 >= 2 + 2 * MAX_CONS && 12 >= 3 + 3 * MAX_CONS, "32 or 48 bytes per row");
 
 // More per slot, read only by the form of the kernel that runs decoder blocks.
 struct SlotExt {
@@ -213,7 +213,7 @@ struct Header {
 // workspace: [Header][Op x n_ops][Stage x n_stages][error u32][zero page 1 KB]
 //            [indices of the ops whose input is expanded by a kernel of its own]
 //            [sign lists, operand lists: blocks x n_groups x cwaves_of(T) each]
-//            [SlotRec x records][SlotVals x the same][up arrays]   (records: see Stage)
+//            [SlotRec x records][value records x the same][up arrays]   (records: see Stage)
 //            decoder blocks: [SlotExt x the same][sums of squares and output copies of ops]
 //                            [sums of squares of inputs from outside]
 struct Layout {

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(64) void desc_kernel(const Header *hdr, const Op *o
 // One workgroup per (stage, LINK_GROUPS workgroups of the stack kernel); a thread per (slot, row).
 constexpr int LINK_GROUPS = 8;
 __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *ops, const Stage *stages,
-                                                   SlotRec *slots, SlotVals *vals, SlotExt *ext)
+                                                   SlotRec *slots, float *vals, SlotExt *ext)
 {
     const int G = hdr->n_groups, T = hdr->T;
     const int st = blockIdx.x;
@@ -295,10 +295,11 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
             }
         }
     }
-    float4 *vrow = reinterpret_cast<float4 *>(&vals[idx].v[row][0]);      // 48 bytes per row: three 16-byte stores
+    // 32 bytes per row, 48 with three paths: two or three 16-byte stores
+    float4 *vrow = reinterpret_cast<float4 *>(vals + (idx * 16 + (size_t)row) * vals_row_floats(hdr->K));
     vrow[0] = make_float4(v[0], v[1], v[2], v[3]);
     vrow[1] = make_float4(v[4], v[5], v[6], v[7]);
-    vrow[2] = make_float4(v[8], v[9], v[10], v[11]);
+    if (hdr->K == 3) vrow[2] = make_float4(v[8], v[9], v[10], v[11]);
     if (row == 0) {
         slots[idx] = sr;
         if (ext) ext[idx] = sx;
@@ -421,7 +422,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                                                            const uint32_t *__restrict__ odesc_g,
                                                            uint32_t sblocks, uint32_t oblocks,
                                                            const SlotRec *__restrict__ slots_g,
-                                                           const SlotVals *__restrict__ vals_g, int go_pause,
+                                                           const float *__restrict__ vals_g, int go_pause,
                                                            const SlotExt *__restrict__ ext_g)
 {
     static_assert(KK == 2 || (KK == 3 && TT == 2), "three paths use the two-token layout");
@@ -1004,7 +1005,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             const size_t idx = (size_t)sg.rec0 + (size_t)grp * sg.n_slots + min(my_slot, sg.n_slots - 1);
             Fin f;
             f.r = slots_g[idx];
-            const v4f *pv = reinterpret_cast<const v4f *>(&vals_g[idx].v[row][0]);
+            const v4f *pv = reinterpret_cast<const v4f *>(vals_g + (idx * 16 + (size_t)row) * vals_row_floats(KK));
             f.a = pv[0];
             f.b = pv[1];
             if constexpr (KK == 3) f.c = pv[2];
@@ -1289,7 +1290,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
 }
 
 // ------------------------------------------------------------------ host ---
-static Layout make_layout(int n_ops, int n_stages, size_t n_records, int n_groups, int cwaves, size_t up_total,
+static Layout make_layout(int n_ops, int n_stages, size_t n_records, int n_groups, int cwaves, int K, size_t up_total,
                           size_t sblocks, size_t oblocks, bool block = false, size_t aux_poison = 0, size_t aux_rest = 0)
 {
     Layout L;
@@ -1302,7 +1303,7 @@ static Layout make_layout(int n_ops, int n_stages, size_t n_records, int n_group
     o = align_up(o, 256); L.sdesc = o; o += 4 * SIGN_FIELDS * DESC_BLOCK * sblocks * (size_t)n_groups * (size_t)cwaves;
     o = align_up(o, 256); L.odesc = o; o += 4 * OPND_FIELDS * DESC_BLOCK * oblocks * (size_t)n_groups * (size_t)cwaves;
     o = align_up(o, 128); L.slots = o; o += sizeof(SlotRec) * n_records;
-    o = align_up(o, 128); L.vals = o; o += sizeof(SlotVals) * n_records;
+    o = align_up(o, 128); L.vals = o; o += vals_record_bytes(K) * n_records;
     o = align_up(o, 256); L.up = o; o += up_total;
     L.ext = L.aux = o; L.aux_poison = 0;
     if (block) {
@@ -1368,7 +1369,9 @@ size_t plan_workspace_bytes(const rb_layer *layers, int n_layers, int n_ops, int
     for (int l = 0; l < n_layers; ++l) slots_per_op = std::max(slots_per_op, (row_tiles(layers[l].out) + G - 1) / G);
     if (block) slots_per_op = std::max(slots_per_op, MAXSLOT / 2);
     slots_per_op = std::min(slots_per_op, MAXSLOT);
-    return make_layout(n_ops, n_ops, (size_t)n_ops * (size_t)G * (size_t)slots_per_op, G, (int)CW, align_up(up_max, 256) * (size_t)n_ops,
+    int K = 2;
+    for (int l = 0; l < n_layers; ++l) K = std::max(K, layers[l].K);
+    return make_layout(n_ops, n_ops, (size_t)n_ops * (size_t)G * (size_t)slots_per_op, G, (int)CW, K, align_up(up_max, 256) * (size_t)n_ops,
                        desc_blocks((uint32_t)(steps + RING_D)), desc_blocks((uint32_t)(steps + (size_t)nb_of(T) * n_ops)),
                        block, block ? block_aux_bound(layers, n_layers, T_in) * (size_t)n_ops : 0, 0)
         .total;
@@ -1561,7 +1564,7 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
     }
     pr.block = block;
     if (n_records > 0xffffffffull) return RB_ERR_UNSUPPORTED;
-    pr.lay = make_layout(n_ops, pr.n_stages, n_records, G, cwaves_of(T), up_total, pr.sblocks, pr.oblocks, block, aux_poison,
+    pr.lay = make_layout(n_ops, pr.n_stages, n_records, G, cwaves_of(T), K, up_total, pr.sblocks, pr.oblocks, block, aux_poison,
                          aux_rest);
     const Layout &lay = pr.lay;
     if (workspace_bytes_ < lay.total) return RB_ERR_WORKSPACE;
@@ -1615,7 +1618,7 @@ static int prepare_any(const rb_layer *layers, const PlanOp *sops, int n_ops, ui
     hipLaunchKernelGGL(link_kernel, dim3(pr.n_stages, (G + LINK_GROUPS - 1) / LINK_GROUPS), dim3(256), 0, stream,
                        reinterpret_cast<const Header *>(ws), reinterpret_cast<const Op *>(ws + lay.ops),
                        reinterpret_cast<const Stage *>(ws + lay.stages), reinterpret_cast<SlotRec *>(ws + lay.slots),
-                       reinterpret_cast<SlotVals *>(ws + lay.vals), block ? reinterpret_cast<SlotExt *>(ws + lay.ext) : nullptr);
+                       reinterpret_cast<float *>(ws + lay.vals), block ? reinterpret_cast<SlotExt *>(ws + lay.ext) : nullptr);
     return hipGetLastError() == hipSuccess ? RB_OK : RB_ERR_HIP;
 }
 
@@ -1678,7 +1681,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
                            reinterpret_cast<uint32_t *>(ws + lay.error), reinterpret_cast<const uint32_t *>(ws + lay.zero),
                            reinterpret_cast<const uint32_t *>(ws + lay.sdesc), reinterpret_cast<const uint32_t *>(ws + lay.odesc),
                            pr.sblocks, pr.oblocks,
-                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const SlotVals *>(ws + lay.vals),
+                           reinterpret_cast<const SlotRec *>(ws + lay.slots), reinterpret_cast<const float *>(ws + lay.vals),
                            go_pause, pr.block ? reinterpret_cast<const SlotExt *>(ws + lay.ext) : nullptr);
         return RB_OK;
     };
