@@ -157,22 +157,43 @@ __global__ void link_kernel(Op *ops, const int *cons_index, int n_ops)
 }
 
 // Input scaling u_k = h_k (.) x (Section 4.1) for ops whose input comes from outside the stack,
-// as four bf8 terms in operand order.
+// as four bf8 terms in operand order.  A thread takes 16 consecutive columns of one token and path
+// (in % 32 == 0): 32 bytes of x and of h in, one 16-byte group per term out.
 __global__ __launch_bounds__(256) void expand_kernel(const Op *ops, const int *which, int T)
 {
     const Op &op = ops[which[blockIdx.z]];
     const int tok = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= op.in) return;
+    const int nblk = op.in / 16;
+    const int id = blockIdx.x * 256 + threadIdx.x;
+    if (id >= nblk * op.K) return;
+    const int p = id / nblk, j0 = (id - p * nblk) * 16;
     const int G = groups_of(T);
-    const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
-    for (int p = 0; p < op.K; ++p) {
-        const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
-        const uint32_t terms = mx::expand4(h * x * op.sc[p]);
+    const uint4 *xs = reinterpret_cast<const uint4 *>(reinterpret_cast<const __half *>(op.x) + (size_t)tok * op.in + j0);
+    const uint4 xq[2] = {xs[0], xs[1]};
+    const uint32_t xw[8] = {xq[0].x, xq[0].y, xq[0].z, xq[0].w, xq[1].x, xq[1].y, xq[1].z, xq[1].w};
+    uint32_t hw[8];
+    const uint16_t *hp = op.h + (size_t)p * op.in + j0;
+    if (((uintptr_t)hp & 15) == 0) {                          // the scales need only be 2-byte aligned
+        const uint4 h0 = reinterpret_cast<const uint4 *>(hp)[0], h1 = reinterpret_cast<const uint4 *>(hp)[1];
+        hw[0] = h0.x; hw[1] = h0.y; hw[2] = h0.z; hw[3] = h0.w; hw[4] = h1.x; hw[5] = h1.y; hw[6] = h1.z; hw[7] = h1.w;
+    } else {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            op.up[operand_group_offset(op.K, G, j & ~15, p, tok >> 2, 4 * (tok & 3) + t) + (size_t)(j & 15)] = (uint8_t)(terms >> (8 * t));
+        for (int e = 0; e < 8; ++e) hw[e] = (uint32_t)hp[2 * e] | ((uint32_t)hp[2 * e + 1] << 16);
     }
+    uint32_t out[4][4] = {};                                  // [term][word of the group]
+    const float sc = op.sc[p];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float x = __half2float(__ushort_as_half((unsigned short)(xw[e >> 1] >> (16 * (e & 1)))));
+        const float h = __half2float(__ushort_as_half((unsigned short)(hw[e >> 1] >> (16 * (e & 1)))));
+        const uint32_t terms = mx::expand4(h * x * sc);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) out[t][e >> 2] |= ((terms >> (8 * t)) & 0xffu) << (8 * (e & 3));
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        *reinterpret_cast<uint4 *>(op.up + operand_group_offset(op.K, G, j0, p, tok >> 2, 4 * (tok & 3) + t)) =
+            make_uint4(out[t][0], out[t][1], out[t][2], out[t][3]);
 }
 
 // ------------------------------------------------------------------- kernel ---
@@ -564,7 +585,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     const Op *d_ops = reinterpret_cast<const Op *>(ws + pr.lay.ops);
     const int T = pr.T;
     if (pr.n_expand > 0)
-        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, T, (unsigned)pr.n_expand), dim3(256), 0,
+        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in / 16 * RB_MAX_K + 255) / 256, T, (unsigned)pr.n_expand), dim3(256), 0,
                            stream, d_ops, reinterpret_cast<const int *>(ws + pr.lay.which), T);
     for (const Launch &l : pr.launches) {
         int rc = RB_ERR_UNSUPPORTED;

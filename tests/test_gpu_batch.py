@@ -194,6 +194,42 @@ def test_many_independent_rows_take_larger_row_blocks(n_ops, T):
     _check_stack(layers, op_list, (inn,) + (out,) * n_ops, x, T, f"{n_ops} independent ops of {out} rows", prepared=(T >= 8))
 
 
+@pytest.mark.parametrize("T", [1, 3, 8])
+def test_scales_that_are_only_two_byte_aligned(T):
+    """g and h need no more than the alignment of their elements: a two-op chain whose scale
+    vectors start two bytes past a 16-byte boundary, on the fused kernel (1 and 3 tokens) and on
+    the small-batch kernel (8 tokens; its input expansion reads h sixteen bytes at a time when it can)."""
+    rng = synth.child_rng(3, 507, T)
+    shapes = [(320, 544), (288, 320)]
+    layers = [random_layer(rng, 2, o, i, gain=30.0) for o, i in shapes]
+
+    def off_by_one(a):
+        flat = torch.zeros(a.size + 1, dtype=torch.float16, device="cuda")
+        flat[1:].copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float16)).flatten())
+        t = flat[1:].view(a.shape)
+        assert t.data_ptr() % 16 == 2
+        return t
+    dev_layers = []
+    for signs, g, h in layers:
+        aligned = to_device_layer(signs, g, h)
+        dev_layers.append(rb.Layer(aligned.bits, off_by_one(g), off_by_one(h), 2, signs.shape[1], signs.shape[2]))
+    x = synth.outlier_activations(rng, T, 544)
+    bufs = [torch.zeros((T, w), dtype=torch.float16, device="cuda") for w in (544, 320, 288)]
+    bufs[0].copy_(torch.from_numpy(x))
+    print(f"scales two bytes past a 16-byte boundary, T={T}", flush=True)
+    rb.rb_layer_stack(dev_layers, [(0, 0, 1), (1, 1, 2)], bufs, T)
+    torch.cuda.synchronize()
+    assert rb.rb_last_path() == (rb.RB_PATH_BATCH if T == 8 else rb.RB_PATH_MX)
+    got = [b.cpu().numpy() for b in bufs]
+    for n, (signs, g, h) in enumerate(layers):
+        ref = oracle.forward(signs, g, h, got[n])
+        assert np.abs(ref).max() > 0.05
+        assert oracle.relative_l2(got[n + 1].astype(np.float64), ref).max() <= TOL, n
+    y = rb.rb_linear_gemm(dev_layers[0], bufs[0])             # the single-call kernels take the same layers
+    torch.cuda.synchronize()
+    assert oracle.relative_l2(y.cpu().numpy().astype(np.float64), oracle.forward(*layers[0], got[0])).max() <= TOL
+
+
 @pytest.mark.parametrize("prepared", [True, False])
 def test_three_path_decode_kernel_one_token(prepared):
     """Three paths, one token: the fused decode kernel (its three paths take the place of two
