@@ -310,23 +310,36 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
 
 // --------------------------------------------------------- expand kernel ---
 // Input scaling u_k = h_k (.) x (Section 4.1) for ops whose input comes from
-// outside the fused ops, written as four bf8 terms in operand order.
+// outside the fused ops, written as four bf8 terms in operand order.  A thread takes 16 consecutive
+// columns of one token and path (in % 32 == 0) and stores one 16-byte group per term.
 __global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op *ops, const int *which)
 {
     const Op &op = ops[which[blockIdx.z]];
     const int tok = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= op.in) return;
+    const int nblk = op.in / 16;
+    const int id = blockIdx.x * 256 + threadIdx.x;
+    if (id >= nblk * op.K) return;
+    const int p = id / nblk, j0 = (id - p * nblk) * 16;
     const int T = hdr->T;
-    const float x = __half2float(reinterpret_cast<const __half *>(op.x)[(size_t)tok * op.in + j]);
-    for (int p = 0; p < op.K; ++p) {
-        const float h = __half2float(reinterpret_cast<const __half *>(op.h)[(size_t)p * op.in + j]);
-        const uint32_t terms = expand4(h * norm_weight(op, j) * x * op.sc[p]);
-        // where path p of this token sits in the layout: three paths use token 1's path 0 for path 2
-        const int ltok = op.K == 3 ? p >> 1 : tok, lp = op.K == 3 ? p & 1 : p;
+    const uint4 *xs = reinterpret_cast<const uint4 *>(op.x + (size_t)tok * op.in + j0);     // buffers are 16-byte aligned
+    const uint4 xq[2] = {xs[0], xs[1]};
+    const uint32_t xw[8] = {xq[0].x, xq[0].y, xq[0].z, xq[0].w, xq[1].x, xq[1].y, xq[1].z, xq[1].w};
+    const __half *hp = reinterpret_cast<const __half *>(op.h) + (size_t)p * op.in + j0;     // scales: 2-byte aligned
+    uint32_t out[4][4] = {};                                  // [term][word of the group]
+    const float sc = op.sc[p];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) op.up[up_offset(T, ltok, lp, t, j)] = (uint8_t)(terms >> (8 * t));
+    for (int e = 0; e < 16; ++e) {
+        const float x = __half2float(__ushort_as_half((unsigned short)(xw[e >> 1] >> (16 * (e & 1)))));
+        const uint32_t terms = expand4(__half2float(hp[e]) * norm_weight(op, j0 + e) * x * sc);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) out[t][e >> 2] |= ((terms >> (8 * t)) & 0xffu) << (8 * (e & 3));
     }
+    // where path p of this token sits in the layout: three paths use token 1's path 0 for path 2
+    const int ltok = op.K == 3 ? p >> 1 : tok, lp = op.K == 3 ? p & 1 : p;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        *reinterpret_cast<uint4 *>(op.up + up_group_offset(T, j0, 8 * ltok + 4 * lp + t)) =
+            make_uint4(out[t][0], out[t][1], out[t][2], out[t][3]);
 }
 
 // Sums of squares of an input from outside that an op normalises: 16 columns per entry, [token][entry], as the
@@ -1662,7 +1675,7 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     Header *d_hdr = reinterpret_cast<Header *>(ws);
     Op *d_ops = reinterpret_cast<Op *>(ws + lay.ops);
     if (pr.n_expand > 0)
-        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in + 255) / 256, pr.tokens, (unsigned)pr.n_expand),
+        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in / 16 * RB_MAX_K + 255) / 256, pr.tokens, (unsigned)pr.n_expand),
                            dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
     if (pr.ext_norm)
         hipLaunchKernelGGL(ssq_kernel, dim3((unsigned)pr.n_expand, pr.tokens), dim3(256), 0, stream, d_ops,
