@@ -298,7 +298,7 @@ def main() -> int:
         "traffic_source": "profiles/stack_kernel_7b_T1_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
                           "scaled by a plain copy of known size; counters cannot be read from inside this process)",
         "note": "one launch per step; duration = HIP events around rb_stack_run on its stream "
-                "(includes the ~4 us input-expansion kernel and the ~6 us kernel that marks inputs not yet written)",
+                "(includes the ~6 us kernel that expands the stack input and marks inputs not yet written)",
     }
 
     if args.calibrate_copy:

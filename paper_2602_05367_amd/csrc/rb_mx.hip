@@ -312,12 +312,11 @@ __global__ __launch_bounds__(256) void link_kernel(const Header *hdr, const Op *
 // Input scaling u_k = h_k (.) x (Section 4.1) for ops whose input comes from
 // outside the fused ops, written as four bf8 terms in operand order.  A thread takes 16 consecutive
 // columns of one token and path (in % 32 == 0) and stores one 16-byte group per term.
-__global__ __launch_bounds__(256) void expand_kernel(const Header *hdr, const Op *ops, const int *which)
+__device__ __forceinline__ void expand_part(const Header *hdr, const Op *ops, const int *which, int bx, int tok, int bz)
 {
-    const Op &op = ops[which[blockIdx.z]];
-    const int tok = blockIdx.y;
+    const Op &op = ops[which[bz]];
     const int nblk = op.in / 16;
-    const int id = blockIdx.x * 256 + threadIdx.x;
+    const int id = bx * 256 + (int)threadIdx.x;
     if (id >= nblk * op.K) return;
     const int p = id / nblk, j0 = (id - p * nblk) * 16;
     const int T = hdr->T;
@@ -365,20 +364,20 @@ __global__ __launch_bounds__(256) void ssq_kernel(const Op *ops, const int *whic
 // columns: no bf8 term of a finite value is 0xff; padding columns read as zero).  POISON_SPLIT
 // workgroups per op.
 constexpr int POISON_SPLIT = 4;
-__global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T, int n_ops, uint4 *aux, size_t aux16)
+__device__ __forceinline__ void poison_part(const Op *ops, int T, int n_ops, uint4 *aux, size_t aux16, int bx, int by)
 {
-    if ((int)blockIdx.x == n_ops) {
+    if (bx == n_ops) {
         // what finishing wavefronts hand to each other in a decoder block: no sum of squares and
         // no fp16 value in a word of its own is all ones
-        for (size_t i = blockIdx.y * 256 + threadIdx.x; i < aux16; i += 256 * POISON_SPLIT)
+        for (size_t i = by * 256 + threadIdx.x; i < aux16; i += 256 * POISON_SPLIT)
             aux[i] = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
         return;
     }
-    const Op &op = ops[blockIdx.x];
+    const Op &op = ops[bx];
     if (op.dep < 0) return;
     const int groups = (int)(up_bytes(op.in, T) / 16);
     uint4 *up = reinterpret_cast<uint4 *>(op.up);
-    for (int i = blockIdx.y * 256 + threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
+    for (int i = by * 256 + (int)threadIdx.x; i < groups; i += 256 * POISON_SPLIT) {
         // which 16 input columns group i holds (see up_group_offset): a block of 128 columns is
         // [q][half j][operand column 0..7] for one token, [half j][q][operand column 0..15] for two
         // and two such images for four
@@ -388,6 +387,21 @@ __global__ __launch_bounds__(256) void poison_kernel(const Op *ops, int T, int n
         const uint32_t v = b * 128 + j * 64 + q * 16 < op.in ? 0xffffffffu : 0u;
         up[i] = make_uint4(v, v, v, v);
     }
+}
+
+// What goes before the stack kernel in every run, as one launch: the first n_poison workgroups mark
+// inputs (they write the expanded inputs of ops fed from inside the launch), the rest expand the
+// inputs from outside (ex x ey x ez workgroups; they write those of the other ops).
+__global__ __launch_bounds__(256) void before_kernel(const Header *hdr, const Op *ops, const int *which, int n_poison, int ex,
+                                                     int ey, uint4 *aux, size_t aux16)
+{
+    const int b = (int)blockIdx.x;
+    if (b < n_poison) {
+        poison_part(ops, hdr->T, hdr->n_ops, aux, aux16, b / POISON_SPLIT, b % POISON_SPLIT);
+        return;
+    }
+    const int e = b - n_poison;
+    expand_part(hdr, ops, which, e % ex, (e / ex) % ey, e / (ex * ey));
 }
 
 // ---------------------------------------------------------- stack kernel ---
@@ -1674,15 +1688,16 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     const Layout &lay = pr.lay;
     Header *d_hdr = reinterpret_cast<Header *>(ws);
     Op *d_ops = reinterpret_cast<Op *>(ws + lay.ops);
-    if (pr.n_expand > 0)
-        hipLaunchKernelGGL(expand_kernel, dim3((pr.max_expand_in / 16 * RB_MAX_K + 255) / 256, pr.tokens, (unsigned)pr.n_expand),
-                           dim3(256), 0, stream, d_hdr, d_ops, reinterpret_cast<const int *>(ws + lay.which));
+    const int n_poison = pr.chained ? (pr.n_ops + (lay.aux_poison ? 1 : 0)) * POISON_SPLIT : 0;
+    const int ex = (pr.max_expand_in / 16 * RB_MAX_K + 255) / 256, ey = pr.tokens;
+    const int n_expand_groups = pr.n_expand > 0 ? ex * ey * pr.n_expand : 0;
+    if (n_poison + n_expand_groups > 0)
+        hipLaunchKernelGGL(before_kernel, dim3((unsigned)(n_poison + n_expand_groups)), dim3(256), 0, stream, d_hdr, d_ops,
+                           reinterpret_cast<const int *>(ws + lay.which), n_poison, ex, ey, reinterpret_cast<uint4 *>(ws + lay.aux),
+                           lay.aux_poison / 16);
     if (pr.ext_norm)
         hipLaunchKernelGGL(ssq_kernel, dim3((unsigned)pr.n_expand, pr.tokens), dim3(256), 0, stream, d_ops,
                            reinterpret_cast<const int *>(ws + lay.which));
-    if (pr.chained)
-        hipLaunchKernelGGL(poison_kernel, dim3(pr.n_ops + (lay.aux_poison ? 1 : 0), POISON_SPLIT), dim3(256), 0, stream, d_ops,
-                           pr.T, pr.n_ops, reinterpret_cast<uint4 *>(ws + lay.aux), lay.aux_poison / 16);
     const int pause_clks = g_pause_clks.load();
     const int go_pause = pause_clks < 0 ? -1 : pause_clks / 64;      // s_sleep units
     auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
