@@ -343,11 +343,10 @@ __device__ __forceinline__ void expand_part(const Header *hdr, const Op *ops, co
 
 // Sums of squares of an input from outside that an op normalises: 16 columns per entry, [token][entry], as the
 // finishing wavefronts file them for inputs written inside a launch.  One workgroup per (op, token).
-__global__ __launch_bounds__(256) void ssq_kernel(const Op *ops, const int *which)
+__device__ __forceinline__ void ssq_part(const Op *ops, const int *which, int bx, int tok)
 {
-    const Op &op = ops[which[blockIdx.x]];
+    const Op &op = ops[which[bx]];
     if (!op.norm_w || op.dep >= 0) return;
-    const int tok = blockIdx.y;
     float *out = const_cast<float *>(op.ssq_in);
     for (int e = threadIdx.x; e < op.n_part; e += 256) {
         float sum = 0.f;
@@ -390,10 +389,12 @@ __device__ __forceinline__ void poison_part(const Op *ops, int T, int n_ops, uin
 }
 
 // What goes before the stack kernel in every run, as one launch: the first n_poison workgroups mark
-// inputs (they write the expanded inputs of ops fed from inside the launch), the rest expand the
-// inputs from outside (ex x ey x ez workgroups; they write those of the other ops).
-__global__ __launch_bounds__(256) void before_kernel(const Header *hdr, const Op *ops, const int *which, int n_poison, int ex,
-                                                     int ey, uint4 *aux, size_t aux16)
+// inputs (they write the expanded inputs of ops fed from inside the launch), the next n_expand
+// expand the inputs from outside (ex x ey x ez workgroups; they write those of the other ops), and
+// in a decoder block the rest add up the squares of the inputs from outside that an op normalises
+// (one workgroup per such input and token).
+__global__ __launch_bounds__(256) void before_kernel(const Header *hdr, const Op *ops, const int *which, int n_poison,
+                                                     int n_expand, int ex, int ey, uint4 *aux, size_t aux16)
 {
     const int b = (int)blockIdx.x;
     if (b < n_poison) {
@@ -401,7 +402,12 @@ __global__ __launch_bounds__(256) void before_kernel(const Header *hdr, const Op
         return;
     }
     const int e = b - n_poison;
-    expand_part(hdr, ops, which, e % ex, (e / ex) % ey, e / (ex * ey));
+    if (e < n_expand) {
+        expand_part(hdr, ops, which, e % ex, (e / ex) % ey, e / (ex * ey));
+        return;
+    }
+    const int q = e - n_expand;
+    ssq_part(ops, which, q / ey, q % ey);
 }
 
 // ---------------------------------------------------------- stack kernel ---
@@ -1691,13 +1697,11 @@ int launch_plan(void *workspace, size_t workspace_bytes_, hipStream_t stream)
     const int n_poison = pr.chained ? (pr.n_ops + (lay.aux_poison ? 1 : 0)) * POISON_SPLIT : 0;
     const int ex = (pr.max_expand_in / 16 * RB_MAX_K + 255) / 256, ey = pr.tokens;
     const int n_expand_groups = pr.n_expand > 0 ? ex * ey * pr.n_expand : 0;
-    if (n_poison + n_expand_groups > 0)
-        hipLaunchKernelGGL(before_kernel, dim3((unsigned)(n_poison + n_expand_groups)), dim3(256), 0, stream, d_hdr, d_ops,
-                           reinterpret_cast<const int *>(ws + lay.which), n_poison, ex, ey, reinterpret_cast<uint4 *>(ws + lay.aux),
-                           lay.aux_poison / 16);
-    if (pr.ext_norm)
-        hipLaunchKernelGGL(ssq_kernel, dim3((unsigned)pr.n_expand, pr.tokens), dim3(256), 0, stream, d_ops,
-                           reinterpret_cast<const int *>(ws + lay.which));
+    const int n_ssq_groups = pr.ext_norm ? pr.n_expand * ey : 0;
+    if (n_poison + n_expand_groups + n_ssq_groups > 0)
+        hipLaunchKernelGGL(before_kernel, dim3((unsigned)(n_poison + n_expand_groups + n_ssq_groups)), dim3(256), 0, stream, d_hdr,
+                           d_ops, reinterpret_cast<const int *>(ws + lay.which), n_poison, n_expand_groups, ex, ey,
+                           reinterpret_cast<uint4 *>(ws + lay.aux), lay.aux_poison / 16);
     const int pause_clks = g_pause_clks.load();
     const int go_pause = pause_clks < 0 ? -1 : pause_clks / 64;      // s_sleep units
     auto launch = [&](auto kernel, int threads, int lds_bytes) -> int {
