@@ -1148,12 +1148,37 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     }
                 }
             }
+            // Where this lane's stores of the expanded outputs will go (it then acts for a (half,
+            // consumer, token, path, term) of its own, in two rounds): worked out while the compute
+            // wavefronts still work.  A slot's record is the same in all lanes of its half.
+            const int n_cons = have_slot ? cur.r.n_cons : 0;
+            uint64_t store_base[2];
+            bool store_here[2];
+#pragma unroll
+            for (int round = 0; round < 2; ++round) {
+                const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
+                const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vtok = (v % 16) >> 3;
+                const int nc = vh ? __builtin_amdgcn_readlane(n_cons, 32) : __builtin_amdgcn_readlane(n_cons, 0);
+                const bool has = (vh ? __builtin_amdgcn_readlane((int)have_slot, 32) : __builtin_amdgcn_readlane((int)have_slot, 0)) != 0;
+                uint64_t base = 0;
+#pragma unroll
+                for (int c = 0; c < MAX_CONS; ++c) {
+                    // the 16-byte group of operand column 0 that the slot's rows fill
+                    const uint64_t u = cur.r.up[c];
+                    const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, 0);
+                    const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), 0);
+                    const uint32_t lo1 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, 32);
+                    const uint32_t hi1 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), 32);
+                    if (c == vc) base = vh ? ((uint64_t)hi1 << 32) | lo1 : ((uint64_t)hi0 << 32) | lo0;
+                }
+                store_base[round] = base;
+                store_here[round] = v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T;
+            }
             lds_barrier();                                    // partial sums complete
             // One token: the lanes of a row's second-token position are free, so the two lanes of a
             // row split the paths between them (sub = which path) for the sums and the expansion.
             constexpr bool SPLIT = TT == 1;
             const int sub = tok;
-            const int n_cons = have_slot ? cur.r.n_cons : 0;
             // Three paths: the lane at a row's second-token position stands for path 2 (as that
             // token's path 0, see layout_tokens): its output scale and its readers' input scales
             // are the third path's, and its "path 1" is nothing.
@@ -1254,22 +1279,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
                     const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vrest = v % 16;
                     const int vtok = vrest >> 3, vpt = vrest & 7;
-                    // the slot's values live in the lanes of its half: take them from that half's lane 0
-                    const int src_lane = vh * 32;
-                    const int nc = __shfl(n_cons, src_lane);
-                    const bool has = __shfl((int)have_slot, src_lane) != 0;
-                    uint64_t base = 0;
-#pragma unroll
-                    for (int c = 0; c < MAX_CONS; ++c) {
-                        // the 16-byte group of operand column 0 that this slot's rows fill
-                        const uint64_t u = cur.r.up[c];
-                        const uint32_t lo = __shfl((uint32_t)u, src_lane), hi = __shfl((uint32_t)(u >> 32), src_lane);
-                        if (c == vc) base = ((uint64_t)hi << 32) | lo;
-                    }
-                    if (v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T) {
+                    if (store_here[round]) {
                         const v4i bytes = *reinterpret_cast<const v4i *>(
                             stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
-                        uint8_t *dst = reinterpret_cast<uint8_t *>(base) + pair * 2048 + (8 * vtok + vpt) * 16;
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(store_base[round]) + pair * 2048 + (8 * vtok + vpt) * 16;
                                                 asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
