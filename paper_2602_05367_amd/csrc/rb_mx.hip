@@ -1205,7 +1205,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     float mine = 0.f;
 #pragma unroll
                     for (int w = 0; w < CW; ++w) mine += P[w * (64 * PAIRS) + sub * 32];
-                    const float other = __shfl_xor(mine, 16);      // the lane with the same row and the other path
+                    const float other = xor16(mine);                // the lane with the same row and the other path
                     s0 = sub ? other : mine;
                     s1 = sub ? mine : other;
                 } else {
@@ -1216,7 +1216,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     }
                 }
                 ysum = path_sum(g_a, s0, g_b, s1);
-                if constexpr (KK == 3) ysum += __shfl_xor(ysum, 16);       // paths 0 and 1 in one lane of the row, path 2 in the other
+                if constexpr (KK == 3) ysum += xor16(ysum);                // paths 0 and 1 in one lane of the row, path 2 in the other
             }
             if constexpr (BLK) {
                 ysum *= rinv[pair];                                          // the input was x / rms(x) (.) w

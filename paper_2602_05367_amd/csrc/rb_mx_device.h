@@ -91,6 +91,17 @@ __device__ __forceinline__ v4f mfma_signs(uint32_t w, v8i b, v4f acc, uint32_t c
 // carries the factor 8^-t
 __device__ __forceinline__ int term_scale(int col) { return (127 - 3 * (col & 3)) * 0x01010101; }
 
+// the value of lane ^ 16: the 16-lane rows swapped in registers, no trip through LDS
+// (v_permlane16_swap_b32 with both operands v: its first result holds, in the odd rows, what the
+// even row before them had; its second result, in the even rows, what the odd row after them had).
+// A lane and its partner must both be active.
+__device__ __forceinline__ float xor16(float v)
+{
+    const unsigned x = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    return __uint_as_float((threadIdx.x & 16u) ? r[0] : r[1]);
+}
+
 // sum over the four lanes of a quad (the four terms of one path and token)
 __device__ __forceinline__ float quad_sum(float v)
 {
