@@ -61,14 +61,13 @@ static_assert(RING_D > nb_of(1) && RING_D > nb_of(2) && RING_D > nb_of(4) && wai
 constexpr int layout_tokens(int T, int K) { return K == 3 ? 2 : T == 3 ? 4 : T; }
 
 // LDS map of the stack kernel with CW compute wavefronts
-constexpr int LDS_STAGE_BYTES = 2 * MAX_CONS * 2 * 2 * 4 * 16;   // per finishing wavefront: bytes of expanded outputs
 template <int CW, int K = 2, int PAIRS = 1> struct LdsMap {
     static constexpr int RING_BYTES = CW * RING_D * 512 * K;
     // partial sums: [parity][slot][compute wavefront][token pair][path][token of the pair][row] fp32
     static constexpr int PART_SLOT_BYTES = CW * PAIRS * 2 * 2 * 16 * 4;
     static constexpr int PART_BYTES = 2 * MAXSLOT * PART_SLOT_BYTES;
-    // go words and a counter, per-wavefront target of the stand-in loads, staging of the finishing wavefronts
-    static constexpr int MISC_BYTES = 256 + CW * 256 + EWAVES * LDS_STAGE_BYTES;
+    // go words and a counter, per-wavefront target of the stand-in loads
+    static constexpr int MISC_BYTES = 256 + CW * 256;
     static constexpr int RING_OFF = 0;
     static constexpr int PART_OFF = RING_OFF + RING_BYTES;
     static constexpr int MISC_OFF = PART_OFF + PART_BYTES;

@@ -1020,8 +1020,6 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         const int my_slot = ew + EWAVES * half;
         const int row = lane & 15, tok = (lane >> 4) & 1;
         const int tokens = hdr_p->tokens;                 // of the activations (three use the layout of four)
-        // staging area for the bytes of the expanded outputs: [half][consumer][token][path][term][row]
-        uint8_t *stage_bytes = lds + Lds::MISC_OFF + 256 + CW * 256 + ew * (2 * MAX_CONS * 2 * 2 * 4 * 16);
 
         // Everything a stage's epilogue needs from memory sits in two flat tables indexed by
         // (stage, workgroup, slot) and is requested one stage ahead, while the compute wavefronts
@@ -1148,32 +1146,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     }
                 }
             }
-            // Where this lane's stores of the expanded outputs will go (it then acts for a (half,
-            // consumer, token, path, term) of its own, in two rounds): worked out while the compute
-            // wavefronts still work.  A slot's record is the same in all lanes of its half.
             const int n_cons = have_slot ? cur.r.n_cons : 0;
-            uint64_t store_base[2];
-            bool store_here[2];
-#pragma unroll
-            for (int round = 0; round < 2; ++round) {
-                const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
-                const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vtok = (v % 16) >> 3;
-                const int nc = vh ? __builtin_amdgcn_readlane(n_cons, 32) : __builtin_amdgcn_readlane(n_cons, 0);
-                const bool has = (vh ? __builtin_amdgcn_readlane((int)have_slot, 32) : __builtin_amdgcn_readlane((int)have_slot, 0)) != 0;
-                uint64_t base = 0;
-#pragma unroll
-                for (int c = 0; c < MAX_CONS; ++c) {
-                    // the 16-byte group of operand column 0 that the slot's rows fill
-                    const uint64_t u = cur.r.up[c];
-                    const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, 0);
-                    const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), 0);
-                    const uint32_t lo1 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, 32);
-                    const uint32_t hi1 = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), 32);
-                    if (c == vc) base = vh ? ((uint64_t)hi1 << 32) | lo1 : ((uint64_t)hi0 << 32) | lo0;
-                }
-                store_base[round] = base;
-                store_here[round] = v < 2 * MAX_CONS * 16 && has && vc < nc && vtok < T;
-            }
             lds_barrier();                                    // partial sums complete
             // One token: the lanes of a row's second-token position are free, so the two lanes of a
             // row split the paths between them (sub = which path) for the sums and the expansion.
@@ -1249,41 +1222,27 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                         store_sc1_u32(cur.x.ssq_out + (uint64_t)tk * (uint32_t)cur.x.ssq_stride * 4u, __float_as_uint(sq));
                 }
             }
-            // ---- expanded input of the ops that read y next: bytes of 16 rows -> one 16-byte store.
-            // Rows beyond the end of the matrix stage zero bytes (the padding columns of the reader).
-            if (__any(n_cons > 0)) {
-                if (have_slot && (SPLIT || tok < T)) {
+            // ---- expanded input of the ops that read y next: the term bytes of the 16 rows of a
+            // (token, path), one word per lane of a 16-lane row, are transposed in registers into one
+            // 16-byte group per term, which lanes 0..3 of the row store.  Rows beyond the end of the
+            // matrix give zero bytes (the padding columns of the reader).
+            if (have_slot) {
 #pragma unroll
-                    for (int c = 0; c < MAX_CONS; ++c) {
-                        if (c < n_cons) {
-                            if constexpr (SPLIT) {
-                                const uint32_t terms = active ? expand4(hsub[c] * yf) : 0u;
-                                uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2) * 2 + sub) * 4) * 16 + row;
+                for (int c = 0; c < MAX_CONS; ++c) {
+                    if (c < n_cons) {                               // the same in all lanes of the half (two whole rows)
+                        uint8_t *const base = reinterpret_cast<uint8_t *>(cur.r.up[c]) + pair * 2048;
+                        if constexpr (SPLIT) {
+                            const v4i bytes = transpose_16x4_bytes(active ? expand4(hsub[c] * yf) : 0u);
+                            uint8_t *dst = base + (4 * sub + row) * 16;
+                            if (row < 4) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
+                        } else {
 #pragma unroll
-                                for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
-                            } else {
-#pragma unroll
-                                for (int p = 0; p < 2; ++p) {
-                                    const uint32_t terms = active ? expand4(hs[c][p] * yf) : 0u;
-                                    uint8_t *dst = stage_bytes + ((((half * MAX_CONS + c) * 2 + tok) * 2 + p) * 4) * 16 + row;
-#pragma unroll
-                                    for (int t = 0; t < 4; ++t) dst[t * 16] = (uint8_t)(terms >> (8 * t));
-                                }
+                            for (int p = 0; p < 2; ++p) {
+                                const v4i bytes = transpose_16x4_bytes(active ? expand4(hs[c][p] * yf) : 0u);
+                                uint8_t *dst = base + (8 * tok + 4 * p + row) * 16;
+                                if (row < 4) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                             }
                         }
-                    }
-                }
-                // lanes now act as (half, consumer, token, path, term): 96 vectors, two rounds
-#pragma unroll
-                for (int round = 0; round < 2; ++round) {
-                    const int v = lane + 64 * round;                    // < 2 * MAX_CONS * 16 = 96
-                    const int vh = v / (MAX_CONS * 16), vc = (v / 16) % MAX_CONS, vrest = v % 16;
-                    const int vtok = vrest >> 3, vpt = vrest & 7;
-                    if (store_here[round]) {
-                        const v4i bytes = *reinterpret_cast<const v4i *>(
-                            stage_bytes + ((((vh * MAX_CONS + vc) * 2 + vtok) * 8) + vpt) * 16);
-                        uint8_t *dst = reinterpret_cast<uint8_t *>(store_base[round]) + pair * 2048 + (8 * vtok + vpt) * 16;
-                                                asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(bytes) : "memory");
                     }
                 }
             }

@@ -102,6 +102,29 @@ __device__ __forceinline__ float xor16(float v)
     return __uint_as_float((threadIdx.x & 16u) ? r[0] : r[1]);
 }
 
+// The 16 lanes of a row hold one word of four bytes each (lane r: bytes b_r0 .. b_r3); afterwards
+// lane t < 4 of the row holds the 16 bytes b_0t .. b_15t.  Two exchanges inside each quad with a
+// byte select each (a 4 x 4 byte transpose over four lanes), then three row shifts bring the
+// quads' words together.  The whole row must be active.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_move(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+__device__ __forceinline__ v4i transpose_16x4_bytes(uint32_t w)
+{
+    const uint32_t lane = threadIdx.x;
+    const uint32_t x = dpp_move<0xB1>(w);                                           // quad_perm [1,0,3,2]
+    const uint32_t a = __builtin_amdgcn_perm(x, w, (lane & 1) ? 0x03070105u : 0x06020400u);
+    const uint32_t y = dpp_move<0x4E>(a);                                           // quad_perm [2,3,0,1]
+    const uint32_t z = __builtin_amdgcn_perm(y, a, (lane & 2) ? 0x03020706u : 0x05040100u);
+    v4i v;
+    v[0] = (int)z;
+    v[1] = (int)dpp_move<0x104>(z);                                                 // row_shl:4: the lane four further on
+    v[2] = (int)dpp_move<0x108>(z);
+    v[3] = (int)dpp_move<0x10C>(z);
+    return v;
+}
+
 // sum over the four lanes of a quad (the four terms of one path and token)
 __device__ __forceinline__ float quad_sum(float v)
 {
