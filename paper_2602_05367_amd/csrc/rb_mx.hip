@@ -1196,7 +1196,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 const int role = have_slot ? cur.x.role : ROLE_PLAIN;
                 if (__any(role != ROLE_PLAIN)) {
                     // the same rows of the up projection sit in the other half of the wavefront
-                    const float other = __shfl_xor(ysum, 32);
+                    const float other = xor32(ysum);
                     if (role == ROLE_GATE) ysum = ysum / (1.f + __expf(-ysum)) * other;
                 }
                 ysum += radd[pair];
@@ -1214,9 +1214,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 // this row tile's sum of squares, for the ops that normalise what they read
                 const bool files = have_slot && cur.x.ssq_out != 0;
                 if (__any(files)) {
-                    float sq = yf * yf;
-#pragma unroll
-                    for (int m = 1; m < 16; m <<= 1) sq += __shfl_xor(sq, m);
+                    const float sq = row_sum(yf * yf);
                     const int tk = (SPLIT || KK == 3) ? 0 : 2 * pair + tok;
                     if (files && row == 0 && ((SPLIT || KK == 3) ? tok == 0 : true) && tk < tokens)
                         store_sc1_u32(cur.x.ssq_out + (uint64_t)tk * (uint32_t)cur.x.ssq_stride * 4u, __float_as_uint(sq));

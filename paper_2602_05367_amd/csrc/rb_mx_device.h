@@ -40,7 +40,9 @@ __device__ __forceinline__ uint32_t expand4(float u)
     for (int t = 0; t < 4; ++t) {
         const int pk = __builtin_amdgcn_cvt_pk_bf8_f32(r, 0.f, 0, false);
         out |= (uint32_t)(pk & 0xff) << (8 * t);
-        r = (r - __builtin_amdgcn_cvt_f32_bf8(pk, 0)) * 8.f;
+        // (r - term) * 8: the difference is exact (|u| < 2^15 never saturates a term), so one fused
+        // multiply-add on 8 r, which does not wait for the conversions, gives the same bits
+        r = __builtin_fmaf(-__builtin_amdgcn_cvt_f32_bf8(pk, 0), 8.f, r * 8.f);
     }
     // A value that is not finite (an fp16 overflow upstream) becomes four NaN terms of one fixed
     // pattern, so that the product is NaN whatever the conversion would have made of it and no
@@ -100,6 +102,23 @@ __device__ __forceinline__ float xor16(float v)
     const unsigned x = __float_as_uint(v);
     const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
     return __uint_as_float((threadIdx.x & 16u) ? r[0] : r[1]);
+}
+// the same for lane ^ 32: the halves of the wavefront swapped (v_permlane32_swap_b32)
+__device__ __forceinline__ float xor32(float v)
+{
+    const unsigned x = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return __uint_as_float((threadIdx.x & 32u) ? r[0] : r[1]);
+}
+// sum over the 16 lanes of a row, left in all of them: two exchanges inside the quad, then the
+// mirrored lane of the eight (in the other quad, whose four lanes hold the same sum) and of the row
+__device__ __forceinline__ float row_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));   // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));   // row_mirror
+    return v;
 }
 
 // The 16 lanes of a row hold one word of four bytes each (lane r: bytes b_r0 .. b_r3); afterwards
