@@ -1147,6 +1147,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 }
             }
             const int n_cons = have_slot ? cur.r.n_cons : 0;
+            // where this lane's partial sums are, worked out before the barrier (what follows it is
+            // on the path from the last matrix instruction of the stage to the stores)
+            uint32_t p_off = (uint32_t)(((st & 1) * MAXSLOT + my_slot) * CW * (64 * pairs_of(TT)) + (TT == 1 ? 0 : tok * 16) + row);
+            asm volatile("" : "+v"(p_off));
             lds_barrier();                                    // partial sums complete
             // One token: the lanes of a row's second-token position are free, so the two lanes of a
             // row split the paths between them (sub = which path) for the sums and the expansion.
@@ -1170,7 +1174,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
             const bool active = have_slot && (SPLIT || KK == 3 || 2 * pair + tok < tokens) && grow < cur.r.out;
             float yf = 0.f, ysum = 0.f;
             // partial sums of this lane's row: [run][token pair][path][token][row]
-            float *P = part + ((size_t)((st & 1) * MAXSLOT + my_slot) * CW) * (64 * PAIRS) + pair * 64 + (SPLIT ? 0 : tok * 16) + row;
+            float *P = part + p_off + pair * 64;
             if (active) {
                 // sum the partial sums of the runs in run order
                 float s0 = 0.f, s1 = 0.f;
