@@ -1014,6 +1014,10 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
         keep_blocks();
     } else {
         // ========================= finishing wavefront ======================
+        // What a finishing wavefront does after the barrier is on the path from one stage to the
+        // next; the three compute wavefronts it shares a SIMD with wake up at the same barrier and
+        // would take three of four issue slots for work that then waits for this one anyway.
+        __builtin_amdgcn_s_setprio(3);
         const int ew = wave - CW;
         // lane -> (slot, row, token): a wavefront finishes two slots per stage, one per half
         const int half = lane >> 5;
