@@ -1209,14 +1209,15 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                 }
                 ysum += radd[pair];
             }
+            _Float16 y16 = (_Float16)0.f;
+            const bool writes = active && (KK == 3 ? tok == 0 : (!SPLIT || sub == 0)) && (!BLK || cur.x.role != ROLE_UP);
+            const size_t y_at = (size_t)((SPLIT || KK == 3) ? 0 : 2 * pair + tok) * cur.r.out + grow;
             if (active) {
-                const _Float16 y16 = (_Float16)ysum;                         // round to nearest even
-                const bool writes = (KK == 3 ? tok == 0 : (!SPLIT || sub == 0)) && (!BLK || cur.x.role != ROLE_UP);
-                const size_t e = (size_t)((SPLIT || KK == 3) ? 0 : 2 * pair + tok) * cur.r.out + grow;
-                if (writes) RB_GLOBAL(_Float16, cur.r.y)[e] = y16;
+                y16 = (_Float16)ysum;                                        // round to nearest even
                 yf = (float)y16;
+                // (y itself is stored after what the next stage waits for)
                 if constexpr (BLK)
-                    if (writes && cur.x.rcopy != 0) store_sc1_u32(cur.x.rcopy + e * 4u, (uint32_t)__builtin_bit_cast(uint16_t, y16));
+                    if (writes && cur.x.rcopy != 0) store_sc1_u32(cur.x.rcopy + y_at * 4u, (uint32_t)__builtin_bit_cast(uint16_t, y16));
             }
             if constexpr (BLK) {
                 // this row tile's sum of squares, for the ops that normalise what they read
@@ -1252,6 +1253,7 @@ __global__ __launch_bounds__(threads_of(TT), 1) void stack_kernel(const Header *
                     }
                 }
             }
+            if (writes) RB_GLOBAL(_Float16, cur.r.y)[y_at] = y16;
             // clear the partial sums for the stage after next (a run without tiles writes nothing);
             // off the path from the barrier to the stores
             if (active) {
